@@ -1,0 +1,17 @@
+"""CPU oracle for the PTQ4VM quantized-linear path (test infrastructure only).
+
+Only tests, the smoke check and the benchmark's CPU-baseline leg may import this
+package; the product path (paper_2412_20386_amd) never does.
+"""
+from .ptq4vm_oracle import (  # noqa: F401
+    build,
+    threads,
+    half_to_float,
+    double_to_half,
+    fold_smoothing,
+    quantize_pts,
+    int8_gemm,
+    dequant,
+    w8a8_linear,
+    f16_linear,
+)

@@ -1,0 +1,161 @@
+"""ctypes front-end of the plain-C CPU oracle (test infrastructure only).
+
+Argument marshalling only: every function takes and returns dense NumPy arrays
+(fp16 as np.float16) and forwards to oracle/ptq4vm_oracle.c, which holds all of
+the arithmetic.  Nothing here imports the HIP package.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+import subprocess
+from typing import Optional, Tuple
+
+import numpy as np
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+_SRC = os.path.join(_HERE, "ptq4vm_oracle.c")
+_LIB = os.path.join(_HERE, "libptq4vm_oracle.so")
+_lib = None
+
+# No fast-math, no FMA contraction: the fp32 decision order in the C file is law.
+_CFLAGS = ["-O2", "-fopenmp", "-ffp-contract=off", "-fno-fast-math", "-fPIC", "-shared",
+           "-Wall", "-Wextra", "-std=c11"]
+
+
+def build(force: bool = False) -> str:
+    """Compile the oracle with gcc (always when force=True, else only if stale)."""
+    stale = (not os.path.exists(_LIB)) or os.path.getmtime(_LIB) < os.path.getmtime(_SRC)
+    if force or stale:
+        tmp = _LIB + f".tmp{os.getpid()}"
+        subprocess.run(["gcc", *_CFLAGS, _SRC, "-o", tmp, "-lm"], check=True)
+        os.replace(tmp, _LIB)
+    return _LIB
+
+
+def _load():
+    global _lib
+    if _lib is None:
+        build()
+        lib = ctypes.CDLL(_LIB)
+        i64, vp = ctypes.c_int64, ctypes.c_void_p
+        lib.oracle_half_to_float.restype = ctypes.c_float
+        lib.oracle_half_to_float.argtypes = [ctypes.c_uint16]
+        lib.oracle_double_to_half.restype = ctypes.c_uint16
+        lib.oracle_double_to_half.argtypes = [ctypes.c_double]
+        lib.oracle_threads.restype = ctypes.c_int
+        lib.oracle_fold_smoothing.restype = None
+        lib.oracle_fold_smoothing.argtypes = [vp, vp, vp, vp, vp, i64, i64]
+        lib.oracle_quantize_pts.restype = None
+        lib.oracle_quantize_pts.argtypes = [vp, vp, vp, vp, i64, i64, i64]
+        lib.oracle_int8_gemm.restype = i64
+        lib.oracle_int8_gemm.argtypes = [vp, vp, vp, i64, i64, i64]
+        lib.oracle_dequant.restype = None
+        lib.oracle_dequant.argtypes = [vp, vp, vp, vp, vp, vp, i64, i64, i64]
+        lib.oracle_f16_linear.restype = None
+        lib.oracle_f16_linear.argtypes = [vp, vp, vp, vp, vp, vp, i64, i64, i64]
+        _lib = lib
+    return _lib
+
+
+def _arr(a, dtype, shape=None) -> np.ndarray:
+    a = np.ascontiguousarray(a, dtype=dtype)
+    if shape is not None and tuple(a.shape) != tuple(shape):
+        raise ValueError(f"expected shape {shape}, got {a.shape}")
+    return a
+
+
+def _p(a: Optional[np.ndarray]):
+    return None if a is None else a.ctypes.data_as(ctypes.c_void_p)
+
+
+def threads() -> int:
+    return int(_load().oracle_threads())
+
+
+def half_to_float(bits: int) -> float:
+    return float(_load().oracle_half_to_float(int(bits) & 0xFFFF))
+
+
+def double_to_half(x: float) -> int:
+    return int(_load().oracle_double_to_half(float(x)))
+
+
+def fold_smoothing(w: np.ndarray, m: np.ndarray) -> Tuple[np.ndarray, np.ndarray, np.ndarray]:
+    """(Wq int8 [N,K], s_w fp32 [N], inv_m fp32 [K]) from W fp16 [N,K] and m fp32 [K]."""
+    w = _arr(w, np.float16)
+    N, K = w.shape
+    m = _arr(m, np.float32, (K,))
+    wq = np.empty((N, K), np.int8)
+    s_w = np.empty(N, np.float32)
+    inv_m = np.empty(K, np.float32)
+    _load().oracle_fold_smoothing(_p(w), _p(m), _p(wq), _p(s_w), _p(inv_m), N, K)
+    return wq, s_w, inv_m
+
+
+def quantize_pts(x: np.ndarray, inv_m: Optional[np.ndarray], s_tok: np.ndarray, B: int,
+                 L: int) -> np.ndarray:
+    """Xq int8 [B*L,K] from X fp16 [B*L,K], inv_m fp32 [K] (or None), s_tok fp32 [L]."""
+    x = _arr(x, np.float16)
+    M, K = x.shape
+    if M != B * L:
+        raise ValueError("x must have B*L rows")
+    inv_m = None if inv_m is None else _arr(inv_m, np.float32, (K,))
+    s_tok = _arr(s_tok, np.float32, (L,))
+    xq = np.empty((M, K), np.int8)
+    _load().oracle_quantize_pts(_p(x), _p(inv_m), _p(s_tok), _p(xq), B, L, K)
+    return xq
+
+
+def int8_gemm(xq: np.ndarray, wq: np.ndarray) -> np.ndarray:
+    """acc int32 [M,N] = Xq [M,K] . Wq[N,K]^T; raises if any exact sum overflows int32."""
+    xq = _arr(xq, np.int8)
+    wq = _arr(wq, np.int8)
+    M, K = xq.shape
+    N, K2 = wq.shape
+    if K != K2:
+        raise ValueError("K mismatch")
+    acc = np.empty((M, N), np.int32)
+    bad = _load().oracle_int8_gemm(_p(xq), _p(wq), _p(acc), M, K, N)
+    if bad:
+        raise OverflowError(f"{bad} accumulators exceed int32")
+    return acc
+
+
+def dequant(acc: np.ndarray, s_tok: np.ndarray, s_w: np.ndarray, bias: Optional[np.ndarray],
+            B: int, L: int) -> Tuple[np.ndarray, np.ndarray]:
+    """(Y fp16 [M,N], y64 double [M,N]) from int32 accumulators and the two step vectors."""
+    acc = _arr(acc, np.int32)
+    M, N = acc.shape
+    if M != B * L:
+        raise ValueError("acc must have B*L rows")
+    s_tok = _arr(s_tok, np.float32, (L,))
+    s_w = _arr(s_w, np.float32, (N,))
+    bias = None if bias is None else _arr(bias, np.float16, (N,))
+    y = np.empty((M, N), np.float16)
+    y64 = np.empty((M, N), np.float64)
+    _load().oracle_dequant(_p(acc), _p(s_tok), _p(s_w), _p(bias), _p(y), _p(y64), B, L, N)
+    return y, y64
+
+
+def w8a8_linear(xq, wq, s_tok, s_w, bias, B: int, L: int):
+    """Integer GEMM followed by dequantization: (Y fp16, y64, acc int32)."""
+    acc = int8_gemm(xq, wq)
+    y, y64 = dequant(acc, s_tok, s_w, bias, B, L)
+    return y, y64, acc
+
+
+def f16_linear(x: np.ndarray, w: np.ndarray, bias: Optional[np.ndarray]):
+    """(Y fp16, y64, sum|terms|) of the unquantized linear, double accumulation."""
+    x = _arr(x, np.float16)
+    w = _arr(w, np.float16)
+    M, K = x.shape
+    N, K2 = w.shape
+    if K != K2:
+        raise ValueError("K mismatch")
+    bias = None if bias is None else _arr(bias, np.float16, (N,))
+    y = np.empty((M, N), np.float16)
+    y64 = np.empty((M, N), np.float64)
+    asum = np.empty((M, N), np.float64)
+    _load().oracle_f16_linear(_p(x), _p(w), _p(bias), _p(y), _p(y64), _p(asum), M, K, N)
+    return y, y64, asum
