@@ -1,0 +1,125 @@
+/*
+ * ptq4vm.h - C ABI of the MI355X (gfx950) quantized-linear library for PTQ4VM
+ * ("Post-Training Quantization for Visual Mamba", arXiv 2412.20386).
+ *
+ * The library runs the paper's W8A8 linear layer with Per-Token Static (PTS) activation
+ * quantization (Sec. 5.1) and SmoothQuant-style smoothing (Sec. 2.4), i.e. the four stages of
+ * the paper's acceleration kernel (App. B.1: activation smoothing, quantization, INT GEMM,
+ * dequantization) as two fused launches, plus the offline weight preparation and an FP16
+ * linear used as the comparison baseline of the paper's latency table.
+ *
+ * Conventions shared by every entry point
+ *   - Storage is token-major: activations X[B*L, K], weights W[N, K] (same as a framework's
+ *     linear.weight and as the paper's W-bar in R^{Dout x Din}), outputs Y[B*L, N]; all
+ *     row-major, leading dimensions (ld*) counted in ELEMENTS and >= the row width.  Row r
+ *     belongs to token position t = r mod L.  The paper writes activations as Din x L
+ *     (token = column); this is the transpose, so diag(Delta_X) scales rows of Y and
+ *     diag(Delta_W) scales its columns.
+ *   - Every pointer is DEVICE memory owned by the caller.  The library allocates nothing,
+ *     keeps no state between calls and never synchronises: work is enqueued on `stream`
+ *     (a hipStream_t passed as void*, NULL = the default stream) and the call returns at once.
+ *     Inputs are only read; outputs must not overlap inputs.  fp16 buffers are passed as
+ *     void* (IEEE binary16).
+ *   - Alignment: base pointers of fp16 and int8 matrices must be 16-byte aligned, float
+ *     vectors 4-byte aligned (else PTQ4VM_ERR_ALIGN).  Rows need not be 16-byte multiples
+ *     (K = 12 with ld = 12, N = 44 with ld = 44 are valid); rows whose byte pitch is a multiple
+ *     of 16 take the fastest loads and stores.
+ *   - Return value: PTQ4VM_OK (0) or a negative ptq4vm_status.  All argument checks run on the
+ *     host before any launch.  A problem with zero rows or zero output columns is PTQ4VM_OK and
+ *     launches nothing.  Device-side values (steps <= 0, NaN scales) are the caller's
+ *     responsibility and are not inspected.
+ */
+#ifndef PTQ4VM_H
+#define PTQ4VM_H
+
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum {
+    PTQ4VM_OK = 0,
+    PTQ4VM_ERR_NULL = -1,   /* a required pointer is NULL */
+    PTQ4VM_ERR_SHAPE = -2,  /* a size is negative, zero where it must not be, or too large */
+    PTQ4VM_ERR_STRIDE = -3, /* a leading dimension is smaller than the row width */
+    PTQ4VM_ERR_ALIGN = -4,  /* a base pointer is not aligned as stated above */
+    PTQ4VM_ERR_HIP = -5     /* the HIP runtime refused a launch; see ptq4vm_last_hip_error() */
+} ptq4vm_status;
+
+/* Largest K for which sum_k (+-127)(+-127) is guaranteed to fit int32: floor((2^31-1)/127^2). */
+#define PTQ4VM_MAX_K 133143
+
+/*
+ * Offline weight preparation: fold the smoothing vector into the weight (Eq. (smooth),
+ * Sec. 2.4: Y = (W diag(s)) (diag(s)^-1 X)), then quantize each OUTPUT channel symmetrically to
+ * 8 bits (Sec. 2.3, Delta_W = max|W| / (2^(b-1) - 1), codes clipped to [-127, 127]; Sec. 5.1:
+ * Delta_W is per output channel).
+ *   w_f16 [N, ldw]  fp16 in   unsmoothed weight
+ *   m     [K]       f32  in   smoothing vector s of the paper, every entry > 0
+ *   wq    [N, ldwq] int8 out  wq[o,k] = clip(rne(W'[o,k] / s_w[o]), -127, 127), W' = f32(W)*m[k]
+ *   s_w   [N]       f32  out  max_k |W'[o,k]| / 127, or 1 for an all-zero row
+ *   inv_m [K]       f32  out  1 / m[k] (correctly rounded), what the activation side multiplies by
+ * All arithmetic is fp32 with IEEE division; rounding is to nearest, ties to even.
+ * Errors: NULL pointer, N < 0 or K <= 0, ld* < K, misaligned w_f16 / wq.
+ */
+int ptq4vm_fold_smoothing(const void *w_f16, const float *m, int8_t *wq, float *s_w, float *inv_m,
+                          int64_t N, int64_t K, int64_t ldw, int64_t ldwq, void *stream);
+
+/*
+ * Per-Token Static activation quantizer (Sec. 5.1) with the activation-smoothing multiply
+ * fused in front (App. B.1 "Activation smoothing" + "Quantization"):
+ *   xq[r,k] = clip(rne((f32(x[r,k]) * inv_m[k]) * (1 / s_tok[r mod L])), -127, 127)
+ * evaluated in fp32 in exactly this order, 1/s_tok correctly rounded, ties to even; the zero
+ * offset is omitted as in the paper's PTS equation.  NaN quantizes to 0, +-Inf to +-127.
+ *   x_f16 [B*L, ldx]  fp16 in
+ *   inv_m [K]         f32  in   may be NULL (no smoothing, all ones)
+ *   s_tok [L]         f32  in   static step per token position (Delta_X in R^{1 x L}), > 0
+ *   xq    [B*L, ldxq] int8 out
+ * Errors: NULL x_f16 / s_tok / xq, B < 0 or L <= 0 or K <= 0, ld* < K, misaligned x_f16 / xq.
+ */
+int ptq4vm_quantize_pts(const void *x_f16, const float *inv_m, const float *s_tok, int8_t *xq,
+                        int64_t B, int64_t L, int64_t K, int64_t ldx, int64_t ldxq, void *stream);
+
+/*
+ * W8A8 linear: integer GEMM and fused dequantization (PTS equation of Sec. 5.1,
+ * Y ~= diag(Delta_W) (W-bar X-bar) diag(Delta_X); App. B.1 "INT GEMM" + "Dequantization"):
+ *   acc[r,o] = sum_k xq[r,k] * wq[o,k]                                   (exact, int32)
+ *   y[r,o]   = fp16( f32(acc[r,o]) * (s_tok[r mod L] * s_w[o]) + f32(bias[o]) )   (fp32)
+ * The step-size outer product is never materialised.
+ *   xq       [B*L, ldxq] int8 in
+ *   wq       [N, ldwq]   int8 in
+ *   s_tok    [L]         f32  in
+ *   s_w      [N]         f32  in
+ *   bias_f16 [N]         fp16 in   may be NULL
+ *   y_f16    [B*L, ldy]  fp16 out
+ *   acc_out  [B*L, N]    int32 out, dense; may be NULL.  Exists so that the exact accumulators
+ *                        can be compared with a reference; leave NULL when timing.
+ * Errors: NULL xq / wq / s_tok / s_w / y_f16, B < 0, N < 0, L <= 0, K <= 0, K > PTQ4VM_MAX_K,
+ * ld* too small, misaligned xq / wq / y_f16 (y_f16 needs only 2-byte alignment; 16 is faster).
+ */
+int ptq4vm_w8a8_linear(const int8_t *xq, const int8_t *wq, const float *s_tok, const float *s_w,
+                       const void *bias_f16, void *y_f16, int32_t *acc_out, int64_t B, int64_t L,
+                       int64_t K, int64_t N, int64_t ldxq, int64_t ldwq, int64_t ldy, void *stream);
+
+/*
+ * Unquantized comparison linear (the "FP16" column of the paper's latency table, Sec. 6.3):
+ *   y[r,o] = fp16( sum_k x[r,k] * w[o,k]  (fp32 accumulation)  + bias[o] )
+ *   x_f16 [M, ldx], w_f16 [N, ldw], bias_f16 [N] or NULL, y_f16 [M, ldy]
+ * Errors as for ptq4vm_w8a8_linear.
+ */
+int ptq4vm_f16_linear(const void *x_f16, const void *w_f16, const void *bias_f16, void *y_f16,
+                      int64_t M, int64_t K, int64_t N, int64_t ldx, int64_t ldw, int64_t ldy,
+                      void *stream);
+
+/* Static, never freed. */
+const char *ptq4vm_status_string(int status);
+/* Thread-local text of the last HIP error that produced PTQ4VM_ERR_HIP on this thread. */
+const char *ptq4vm_last_hip_error(void);
+/* major * 10000 + minor * 100 + patch */
+int ptq4vm_version(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* PTQ4VM_H */

@@ -1,0 +1,12 @@
+"""MI355X-native PTQ4VM quantized-linear path (arXiv 2412.20386).
+
+`binding` exposes the C ABI of libptq4vm.so (hand-written HIP for gfx950); `synth` draws the
+seeded Vim-shaped inputs; `build` compiles the library.  Nothing is loaded at import time.
+"""
+from . import binding, synth  # noqa: F401
+from .binding import (  # noqa: F401
+    f16_linear,
+    fold_smoothing,
+    quantize_pts,
+    w8a8_linear,
+)

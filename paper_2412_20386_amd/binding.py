@@ -1,0 +1,165 @@
+"""Thin ctypes binding of libptq4vm.so: argument marshalling only.
+
+Every function takes torch CUDA tensors (used purely as device buffers), passes raw device
+pointers, sizes and the current HIP stream to the C ABI declared in include/ptq4vm.h, and
+returns the output tensors.  No arithmetic happens here and there is no fallback: if the
+library has not been built, loading raises.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+from typing import Optional, Tuple
+
+import torch
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_HERE, "libptq4vm.so")
+
+EXPORTS = (
+    "ptq4vm_fold_smoothing",
+    "ptq4vm_quantize_pts",
+    "ptq4vm_w8a8_linear",
+    "ptq4vm_f16_linear",
+    "ptq4vm_status_string",
+    "ptq4vm_last_hip_error",
+    "ptq4vm_version",
+)
+
+_lib = None
+
+
+class Ptq4vmError(RuntimeError):
+    def __init__(self, status: int, text: str):
+        super().__init__(f"ptq4vm status {status}: {text}")
+        self.status = status
+
+
+def load() -> ctypes.CDLL:
+    """Load libptq4vm.so (built by paper_2412_20386_amd.build). Raises if it is missing."""
+    global _lib
+    if _lib is not None:
+        return _lib
+    if not os.path.exists(LIB_PATH):
+        raise FileNotFoundError(
+            f"{LIB_PATH} not found: build it with `python -m paper_2412_20386_amd.build` "
+            "(there is no CPU or PyTorch fallback)")
+    lib = ctypes.CDLL(LIB_PATH)
+    i64, vp, ci = ctypes.c_int64, ctypes.c_void_p, ctypes.c_int
+    lib.ptq4vm_fold_smoothing.restype = ci
+    lib.ptq4vm_fold_smoothing.argtypes = [vp, vp, vp, vp, vp, i64, i64, i64, i64, vp]
+    lib.ptq4vm_quantize_pts.restype = ci
+    lib.ptq4vm_quantize_pts.argtypes = [vp, vp, vp, vp, i64, i64, i64, i64, i64, vp]
+    lib.ptq4vm_w8a8_linear.restype = ci
+    lib.ptq4vm_w8a8_linear.argtypes = [vp, vp, vp, vp, vp, vp, vp, i64, i64, i64, i64, i64, i64, i64, vp]
+    lib.ptq4vm_f16_linear.restype = ci
+    lib.ptq4vm_f16_linear.argtypes = [vp, vp, vp, vp, i64, i64, i64, i64, i64, i64, vp]
+    lib.ptq4vm_status_string.restype = ctypes.c_char_p
+    lib.ptq4vm_status_string.argtypes = [ci]
+    lib.ptq4vm_last_hip_error.restype = ctypes.c_char_p
+    lib.ptq4vm_last_hip_error.argtypes = []
+    lib.ptq4vm_version.restype = ci
+    lib.ptq4vm_version.argtypes = []
+    _lib = lib
+    return lib
+
+
+def status_string(status: int) -> str:
+    return load().ptq4vm_status_string(int(status)).decode()
+
+
+def check(status: int) -> None:
+    if status != 0:
+        text = status_string(status)
+        if status == -5:
+            text += ": " + load().ptq4vm_last_hip_error().decode()
+        raise Ptq4vmError(status, text)
+
+
+def _ptr(t: Optional[torch.Tensor]):
+    return None if t is None else ctypes.c_void_p(t.data_ptr())
+
+
+def _stream():
+    return ctypes.c_void_p(torch.cuda.current_stream().cuda_stream)
+
+
+def _matrix(t: torch.Tensor, dtype, name: str) -> Tuple[int, int, int]:
+    if not t.is_cuda or t.dtype != dtype or t.dim() != 2 or (t.shape[1] > 1 and t.stride(1) != 1):
+        raise TypeError(f"{name}: expected a 2-D CUDA tensor of {dtype} with unit inner stride")
+    return t.shape[0], t.shape[1], (t.stride(0) if t.shape[0] > 1 else max(t.stride(0), t.shape[1]))
+
+
+def _vector(t: Optional[torch.Tensor], dtype, n: int, name: str, optional=False):
+    if t is None:
+        if optional:
+            return
+        raise TypeError(f"{name} is required")
+    if not t.is_cuda or t.dtype != dtype or t.dim() != 1 or t.shape[0] != n or not t.is_contiguous():
+        raise TypeError(f"{name}: expected a contiguous CUDA vector of {n} x {dtype}")
+
+
+def fold_smoothing(w: torch.Tensor, m: torch.Tensor, wq: Optional[torch.Tensor] = None):
+    """ptq4vm_fold_smoothing: (wq int8 [N,K], s_w f32 [N], inv_m f32 [K])."""
+    N, K, ldw = _matrix(w, torch.float16, "w")
+    _vector(m, torch.float32, K, "m")
+    if wq is None:
+        wq = torch.empty((N, K), dtype=torch.int8, device=w.device)
+    _, _, ldwq = _matrix(wq, torch.int8, "wq")
+    s_w = torch.empty(N, dtype=torch.float32, device=w.device)
+    inv_m = torch.empty(K, dtype=torch.float32, device=w.device)
+    check(load().ptq4vm_fold_smoothing(_ptr(w), _ptr(m), _ptr(wq), _ptr(s_w), _ptr(inv_m), N, K, ldw, ldwq,
+                                       _stream()))
+    return wq, s_w, inv_m
+
+
+def quantize_pts(x: torch.Tensor, inv_m: Optional[torch.Tensor], s_tok: torch.Tensor, B: int, L: int,
+                 xq: Optional[torch.Tensor] = None) -> torch.Tensor:
+    """ptq4vm_quantize_pts: xq int8 [B*L, K]."""
+    M, K, ldx = _matrix(x, torch.float16, "x")
+    if M != B * L:
+        raise ValueError("x must have B*L rows")
+    _vector(inv_m, torch.float32, K, "inv_m", optional=True)
+    _vector(s_tok, torch.float32, L, "s_tok")
+    if xq is None:
+        xq = torch.empty((M, K), dtype=torch.int8, device=x.device)
+    _, _, ldxq = _matrix(xq, torch.int8, "xq")
+    check(load().ptq4vm_quantize_pts(_ptr(x), _ptr(inv_m), _ptr(s_tok), _ptr(xq), B, L, K, ldx, ldxq, _stream()))
+    return xq
+
+
+def w8a8_linear(xq: torch.Tensor, wq: torch.Tensor, s_tok: torch.Tensor, s_w: torch.Tensor,
+                bias: Optional[torch.Tensor], B: int, L: int, y: Optional[torch.Tensor] = None,
+                acc_out: Optional[torch.Tensor] = None) -> torch.Tensor:
+    """ptq4vm_w8a8_linear: y fp16 [B*L, N]; acc_out (int32 [B*L, N], dense) is filled if given."""
+    M, K, ldxq = _matrix(xq, torch.int8, "xq")
+    N, K2, ldwq = _matrix(wq, torch.int8, "wq")
+    if K != K2 or M != B * L:
+        raise ValueError("shape mismatch")
+    _vector(s_tok, torch.float32, L, "s_tok")
+    _vector(s_w, torch.float32, N, "s_w")
+    _vector(bias, torch.float16, N, "bias", optional=True)
+    if y is None:
+        y = torch.empty((M, N), dtype=torch.float16, device=xq.device)
+    _, _, ldy = _matrix(y, torch.float16, "y")
+    if acc_out is not None and (acc_out.dtype != torch.int32 or tuple(acc_out.shape) != (M, N)
+                                or not acc_out.is_contiguous() or not acc_out.is_cuda):
+        raise TypeError("acc_out: expected a dense CUDA int32 [M, N] tensor")
+    check(load().ptq4vm_w8a8_linear(_ptr(xq), _ptr(wq), _ptr(s_tok), _ptr(s_w), _ptr(bias), _ptr(y),
+                                    _ptr(acc_out), B, L, K, N, ldxq, ldwq, ldy, _stream()))
+    return y
+
+
+def f16_linear(x: torch.Tensor, w: torch.Tensor, bias: Optional[torch.Tensor],
+               y: Optional[torch.Tensor] = None) -> torch.Tensor:
+    """ptq4vm_f16_linear: y fp16 [M, N]."""
+    M, K, ldx = _matrix(x, torch.float16, "x")
+    N, K2, ldw = _matrix(w, torch.float16, "w")
+    if K != K2:
+        raise ValueError("shape mismatch")
+    _vector(bias, torch.float16, N, "bias", optional=True)
+    if y is None:
+        y = torch.empty((M, N), dtype=torch.float16, device=x.device)
+    _, _, ldy = _matrix(y, torch.float16, "y")
+    check(load().ptq4vm_f16_linear(_ptr(x), _ptr(w), _ptr(bias), _ptr(y), M, K, N, ldx, ldw, ldy, _stream()))
+    return y

@@ -1,0 +1,234 @@
+"""GPU parity: every entry point of libptq4vm.so, called through the C ABI, against the CPU
+oracle on the same seeded inputs.  int8 codes and int32 accumulators bit-exact; fp16 outputs
+within 1 fp16 ulp (see parity_util.check_dequantized_output for the exact bar)."""
+import numpy as np
+import pytest
+import torch
+
+import oracle
+import paper_2412_20386_amd as ptq
+from paper_2412_20386_amd import synth
+
+from parity_util import check_dequantized_output
+
+pytestmark = pytest.mark.gpu
+DEV = "cuda:0"
+
+
+def _np(t):
+    return t.detach().cpu().numpy()
+
+
+def _padded(rows, cols, ld, dtype, fill):
+    """A [rows, cols] view with row pitch ld inside a sentinel-filled buffer."""
+    buf = torch.full((rows, ld), fill, dtype=dtype, device=DEV)
+    return buf, buf[:, :cols]
+
+
+# ---------------------------------------------------------------------------------- quantizer
+QUANT_SHAPES = [  # B, L, K
+    (1, 197, 384),    # config 0
+    (3, 197, 768),
+    (2, 7, 12),       # dt_proj input: 24-byte rows -> 4-wide path
+    (5, 33, 44),
+    (4, 9, 13),       # odd K -> element path
+    (3, 5, 8),        # one chunk per row
+    (1, 3, 2056),     # more than 256 chunks per row
+    (257, 1, 48),     # L = 1: per-tensor static
+    (2, 785, 24),
+    (1, 1, 1536),
+]
+
+
+@pytest.mark.parametrize("B,L,K", QUANT_SHAPES)
+@pytest.mark.parametrize("use_m", [True, False])
+def test_quantize_pts_bit_exact(B, L, K, use_m):
+    print(f"quantize B={B} L={L} K={K} use_m={use_m}", flush=True)
+    c = synth.random_problem(1000 + B * 7 + K, B, L, K, 8, device=DEV)
+    _, _, inv_m = oracle.fold_smoothing(_np(c.w), _np(c.m))
+    inv_m_t = torch.from_numpy(inv_m).to(DEV) if use_m else None
+    xq = ptq.quantize_pts(c.x, inv_m_t, c.s_tok, B, L)
+    torch.cuda.synchronize()
+    want = oracle.quantize_pts(_np(c.x), inv_m if use_m else None, _np(c.s_tok), B, L)
+    assert np.array_equal(_np(xq), want)
+    assert np.abs(want.astype(np.int32)).max() > 16  # the case is not degenerate
+
+
+def test_quantize_pts_special_values_and_ties():
+    K = 16
+    row = [0.5, 1.5, 2.5, -0.5, -1.5, -2.5, 126.5, 127.5, 128.0, 1000.0, float("inf"), float("-inf"),
+           float("nan"), -127.49, -127.5, -60000.0]
+    x = torch.tensor([row, row[::-1]], dtype=torch.float16, device=DEV)
+    s_tok = torch.tensor([1.0, 0.5], dtype=torch.float32, device=DEV)
+    for inv_m in (None, torch.full((K,), 1.0, device=DEV), torch.full((K,), 0.25, device=DEV)):
+        xq = ptq.quantize_pts(x, inv_m, s_tok, 1, 2)
+        torch.cuda.synchronize()
+        want = oracle.quantize_pts(_np(x), None if inv_m is None else _np(inv_m), _np(s_tok), 1, 2)
+        assert np.array_equal(_np(xq), want)
+    assert _np(ptq.quantize_pts(x, None, s_tok, 1, 2))[0].tolist() == \
+        [0, 2, 2, 0, -2, -2, 126, 127, 127, 127, 127, -127, 0, -127, -127, -127]
+
+
+def test_quantize_pts_every_fp16_value():
+    bits = np.arange(65536, dtype=np.uint32).astype(np.uint16)
+    x = torch.from_numpy(bits.view(np.float16).reshape(64, 1024).copy()).to(DEV)
+    rng = np.random.default_rng(3)
+    inv_m = rng.uniform(0.01, 30, 1024).astype(np.float32)
+    s_tok = rng.uniform(0.001, 50, 8).astype(np.float32)
+    xq = ptq.quantize_pts(x, torch.from_numpy(inv_m).to(DEV), torch.from_numpy(s_tok).to(DEV), 8, 8)
+    torch.cuda.synchronize()
+    assert np.array_equal(_np(xq), oracle.quantize_pts(_np(x), inv_m, s_tok, 8, 8))
+
+
+@pytest.mark.parametrize("K,ldx,ldxq", [(384, 400, 416), (12, 20, 16), (13, 17, 19)])
+def test_quantize_pts_padded_rows_leave_padding_untouched(K, ldx, ldxq):
+    B, L = 3, 11
+    c = synth.random_problem(77 + K, B, L, K, 8, device=DEV)
+    xbuf, xv = _padded(B * L, K, ldx, torch.float16, 777.0)
+    xv.copy_(c.x)
+    qbuf, qv = _padded(B * L, K, ldxq, torch.int8, 0x55)
+    inv_m = (1.0 / c.m).contiguous()
+    ptq.quantize_pts(xv, inv_m, c.s_tok, B, L, xq=qv)
+    torch.cuda.synchronize()
+    want = oracle.quantize_pts(_np(c.x), _np(inv_m), _np(c.s_tok), B, L)
+    assert np.array_equal(_np(qv), want)
+    assert np.all(_np(qbuf[:, K:]) == 0x55)
+
+
+# ---------------------------------------------------------------------------------- fold
+@pytest.mark.parametrize("N,K,ldw,ldwq", [(192, 384, 384, 384), (44, 384, 384, 384), (384, 12, 12, 12),
+                                           (17, 1000, 1008, 1024), (3, 5, 8, 16), (3072, 768, 768, 768)])
+def test_fold_smoothing_bit_exact(N, K, ldw, ldwq):
+    print(f"fold N={N} K={K}", flush=True)
+    c = synth.random_problem(500 + N + K, 2, 5, K, N, device=DEV)
+    w = c.w.clone()
+    if N > 2:
+        w[1].zero_()  # dead output channel
+    wbuf, wv = _padded(N, K, ldw, torch.float16, 9.0)
+    wv.copy_(w)
+    qbuf, qv = _padded(N, K, ldwq, torch.int8, 0x55)
+    wq, s_w, inv_m = ptq.fold_smoothing(wv, c.m, wq=qv)
+    torch.cuda.synchronize()
+    wq_o, s_w_o, inv_m_o = oracle.fold_smoothing(_np(w), _np(c.m))
+    assert np.array_equal(_np(s_w).view(np.uint32), s_w_o.view(np.uint32))
+    assert np.array_equal(_np(inv_m).view(np.uint32), inv_m_o.view(np.uint32))
+    assert np.array_equal(_np(qv), wq_o)
+    if ldwq > K:
+        assert np.all(_np(qbuf[:, K:]) == 0x55)
+
+
+# ---------------------------------------------------------------------------------- W8A8 linear
+def _run_w8a8_case(c, use_bias=True, ldy=None, what=""):
+    """Full path on the GPU vs the oracle chain on the CPU, each from the same fp16 inputs."""
+    print(f"w8a8 {what} B={c.B} L={c.L} K={c.K} N={c.N} bias={use_bias} ldy={ldy}", flush=True)
+    M = c.B * c.L
+    wq, s_w, inv_m = ptq.fold_smoothing(c.w, c.m)
+    xq = ptq.quantize_pts(c.x, inv_m, c.s_tok, c.B, c.L)
+    acc = torch.full((M, c.N), -1, dtype=torch.int32, device=DEV)
+    bias = c.bias if use_bias else None
+    if ldy is None:
+        y = ptq.w8a8_linear(xq, wq, c.s_tok, s_w, bias, c.B, c.L, acc_out=acc)
+        ybuf = None
+    else:
+        ybuf, yv = _padded(M, c.N, ldy, torch.float16, 12345.0)
+        y = ptq.w8a8_linear(xq, wq, c.s_tok, s_w, bias, c.B, c.L, y=yv, acc_out=acc)
+    y2 = ptq.w8a8_linear(xq, wq, c.s_tok, s_w, bias, c.B, c.L)  # timed configuration: no acc_out
+    torch.cuda.synchronize()
+
+    wq_o, s_w_o, inv_m_o = oracle.fold_smoothing(_np(c.w), _np(c.m))
+    xq_o = oracle.quantize_pts(_np(c.x), inv_m_o, _np(c.s_tok), c.B, c.L)
+    b_o = _np(c.bias) if use_bias else None
+    y_o, y64, acc_o = oracle.w8a8_linear(xq_o, wq_o, _np(c.s_tok), s_w_o, b_o, c.B, c.L)
+
+    assert np.array_equal(_np(wq), wq_o) and np.array_equal(_np(xq), xq_o)
+    assert np.array_equal(_np(acc), acc_o), "int32 accumulators differ"
+    st = np.tile(_np(c.s_tok).astype(np.float64), c.B)[:, None]
+    prod_abs = np.abs(acc_o.astype(np.float64) * st * s_w_o.astype(np.float64)[None, :])
+    bias_abs = np.broadcast_to(np.abs(b_o.astype(np.float64))[None, :] if use_bias else 0.0, prod_abs.shape)
+    stats = check_dequantized_output(_np(y), y_o, y64, prod_abs, bias_abs, what)
+    assert np.array_equal(_np(y).view(np.uint16), _np(y2).view(np.uint16)), "acc_out changes the result"
+    if ybuf is not None:
+        assert np.all(_np(ybuf[:, c.N:]) == np.float16(12345.0))
+    return stats
+
+
+def test_w8a8_linear_config0():
+    c = synth.make_linear_case(0, device=DEV)
+    assert c.clipped > 0
+    _run_w8a8_case(c, what="config0")
+
+
+W8A8_SHAPES = [  # B, L, K, N
+    (3, 197, 384, 192),
+    (2, 197, 192, 768),
+    (2, 197, 384, 44),    # x_proj (Vim-Ti): 88-byte output rows
+    (3, 197, 12, 384),    # dt_proj (Vim-Ti): 12-byte activation rows
+    (2, 65, 24, 768),
+    (2, 50, 768, 56),
+    (1, 300, 1536, 80),
+    (1, 1, 64, 32),       # a single row
+    (1, 257, 100, 130),   # K, N multiples of 4 only
+    (2, 33, 13, 5),       # nothing aligned
+    (1, 129, 1000, 257),
+    (5, 7, 16, 1),
+]
+
+
+@pytest.mark.parametrize("B,L,K,N", W8A8_SHAPES)
+def test_w8a8_linear_shapes(B, L, K, N):
+    c = synth.random_problem(31 * K + N, B, L, K, N, device=DEV)
+    _run_w8a8_case(c, what="adhoc")
+
+
+def test_w8a8_linear_without_bias_and_padded_output():
+    c = synth.random_problem(5, 2, 197, 384, 192, device=DEV)
+    _run_w8a8_case(c, use_bias=False, what="nobias")
+    _run_w8a8_case(c, ldy=200, what="ldy200")
+    c = synth.random_problem(6, 2, 31, 384, 44, device=DEV)
+    _run_w8a8_case(c, ldy=45, what="ldy45")
+
+
+def test_w8a8_linear_extreme_codes():
+    """All codes at +-127 with the largest K of the workloads: |acc| = 1536 * 127^2."""
+    B, L, K, N = 1, 40, 1536, 96
+    xq = torch.full((B * L, K), 127, dtype=torch.int8, device=DEV)
+    xq[1::2] = -127
+    wq = torch.full((N, K), 127, dtype=torch.int8, device=DEV)
+    wq[::3] = -127
+    s_tok = torch.full((L,), 2.0 ** -12, device=DEV)
+    s_w = torch.full((N,), 2.0 ** -10, device=DEV)
+    acc = torch.empty((B * L, N), dtype=torch.int32, device=DEV)
+    y = ptq.w8a8_linear(xq, wq, s_tok, s_w, None, B, L, acc_out=acc)
+    torch.cuda.synchronize()
+    y_o, y64, acc_o = oracle.w8a8_linear(_np(xq), _np(wq), _np(s_tok), _np(s_w), None, B, L)
+    assert np.abs(acc_o).max() == 1536 * 16129
+    assert np.array_equal(_np(acc), acc_o)
+    assert np.array_equal(_np(y).view(np.uint16), y_o.view(np.uint16))  # exact: power-of-two steps
+
+
+def test_w8a8_linear_is_deterministic():
+    c = synth.random_problem(9, 4, 197, 768, 384, device=DEV)
+    wq, s_w, inv_m = ptq.fold_smoothing(c.w, c.m)
+    first_q = first_y = None
+    for _ in range(10):
+        xq = ptq.quantize_pts(c.x, inv_m, c.s_tok, c.B, c.L)
+        y = ptq.w8a8_linear(xq, wq, c.s_tok, s_w, c.bias, c.B, c.L)
+        torch.cuda.synchronize()
+        if first_q is None:
+            first_q, first_y = xq.clone(), y.clone()
+        assert torch.equal(xq, first_q) and torch.equal(y.view(torch.int16), first_y.view(torch.int16))
+
+
+# ---------------------------------------------------------------------------------- FP16 linear
+@pytest.mark.parametrize("M,K,N", [(197, 384, 192), (500, 768, 3072), (300, 1536, 80), (100, 12, 384),
+                                    (77, 50, 33), (64, 13, 7)])
+def test_f16_linear_within_accumulation_bound(M, K, N):
+    print(f"f16 M={M} K={K} N={N}", flush=True)
+    c = synth.random_problem(3 * M + K, 1, M, K, N, device=DEV)
+    y = ptq.f16_linear(c.x, c.w, c.bias)
+    torch.cuda.synchronize()
+    y_o, y64, asum = oracle.f16_linear(_np(c.x), _np(c.w), _np(c.bias))
+    g = _np(y).astype(np.float64)
+    # fp32 accumulation in any order: |err| <= (K+1) 2^-24 sum|terms|, then one fp16 rounding
+    tol = (K + 2) * 2.0 ** -24 * asum + 2.0 ** -11 * np.abs(y64) + 2.0 ** -24
+    assert np.all(np.abs(g - y64) <= tol)
