@@ -1,0 +1,226 @@
+#!/usr/bin/env python3
+"""Benchmark of the PTQ4VM W8A8 quantized-linear hot path on one MI355X.
+
+A "step" is one pass of the hot path over one synthetic batch of the Vim-B-shaped stack
+(benchmark configs[3]): for each of 24 layers and each of its four linears
+(in_proj 768->3072, x_proj 1536->80, dt_proj 48->1536, out_proj 1536->768; M = 256*197 rows)
+  ptq4vm_quantize_pts  (fp16 -> int8, per-token static step, smoothing folded in)
+  ptq4vm_w8a8_linear   (int8 MFMA GEMM + fused dequantization + bias -> fp16)
+i.e. 96 + 96 launches.  Weight folding/quantization is offline (done once in setup, like the
+paper's stored INT8 weights) and is not timed.  All inputs are resident in HBM before the
+timed region; every layer has its own buffers (~1.1 GB per layer), so the working set of a step
+(~27 GB) cannot sit in the 256 MB last-level cache.
+
+Prints ONE JSON line (see README for the fields).
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+PEAK_INT8_TOPS = 5000.0   # MI355X dense int8 MFMA, TOP/s
+PEAK_F16_TFLOPS = 2500.0  # dense fp16 MFMA
+PEAK_HBM_GBS = 8000.0     # HBM3E
+
+# HBM traffic of the dominant kernel from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE
+# (profiles/), bytes per launch; None until measured.
+DOMINANT_TRAFFIC_BYTES = None
+
+
+def main() -> int:
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=20)
+    ap.add_argument("--warmup", type=int, default=5)
+    ap.add_argument("--config", type=int, default=3, help="workload config (BASELINE.json configs index)")
+    ap.add_argument("--layers", type=int, default=None, help="override the number of layers (debug only)")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--cpu-sample-batch", type=int, default=256)
+    args = ap.parse_args()
+    if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
+        print("bench.py: this build runs on one GPU only (the path shards data-parallel over the batch "
+              "with no collectives, see DESIGN.md); run with --gpus 1", file=sys.stderr)
+        return 2
+
+    import torch
+
+    import paper_2412_20386_amd as ptq
+    from paper_2412_20386_amd import synth
+
+    if not torch.cuda.is_available():
+        print("bench.py: no GPU visible", file=sys.stderr)
+        return 2
+    ptq.binding.load()  # fail loudly if the HIP library is missing
+    dev = "cuda:0"
+    torch.cuda.set_device(0)
+    cfg = synth.CONFIGS[args.config]
+    n_layers = args.layers or cfg.layers
+    B, L, M = cfg.B, cfg.L, cfg.M
+
+    # ------------------------------------------------------------------ setup (untimed)
+    t0 = time.time()
+    layers = []
+    for layer in range(n_layers):
+        lin = []
+        for li, (name, K, N) in enumerate(cfg.linears):
+            c = synth.make_linear_case(args.config, layer, li, device=dev)
+            wq, s_w, inv_m = ptq.fold_smoothing(c.w, c.m)  # offline weight preparation
+            lin.append(dict(name=name, K=K, N=N, x=c.x, w=c.w, bias=c.bias, s_tok=c.s_tok, wq=wq, s_w=s_w,
+                            inv_m=inv_m, xq=torch.empty((M, K), dtype=torch.int8, device=dev),
+                            y=torch.empty((M, N), dtype=torch.float16, device=dev)))
+        layers.append(lin)
+    torch.cuda.synchronize()
+    setup_s = time.time() - t0
+
+    def step_w8a8(events=None):
+        for lin in layers:
+            for d in lin:
+                ptq.quantize_pts(d["x"], d["inv_m"], d["s_tok"], B, L, xq=d["xq"])
+                if events is not None and d["name"] == events["name"]:
+                    a = torch.cuda.Event(enable_timing=True)
+                    b = torch.cuda.Event(enable_timing=True)
+                    a.record()
+                    ptq.w8a8_linear(d["xq"], d["wq"], d["s_tok"], d["s_w"], d["bias"], B, L, y=d["y"])
+                    b.record()
+                    events["pairs"].append((a, b))
+                else:
+                    ptq.w8a8_linear(d["xq"], d["wq"], d["s_tok"], d["s_w"], d["bias"], B, L, y=d["y"])
+
+    def step_f16():
+        for lin in layers:
+            for d in lin:
+                ptq.f16_linear(d["x"], d["w"], d["bias"], y=d["y"])
+
+    # ------------------------------------------------------------------ timed region
+    dominant = max(cfg.linears, key=lambda t: t[1] * t[2])  # most MACs: in_proj
+    for _ in range(args.warmup):
+        step_w8a8()
+    torch.cuda.synchronize()
+    events = dict(name=dominant[0], pairs=[])
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        step_w8a8(events)
+    torch.cuda.synchronize()
+    elapsed = time.perf_counter() - t0
+    ms_per_step = elapsed / args.steps * 1e3
+    dom_us = sum(a.elapsed_time(b) for a, b in events["pairs"]) / len(events["pairs"]) * 1e3
+
+    # ------------------------------------------------------------------ per-kernel detail (untimed extras)
+    def time_launch(fn, reps=3):
+        """Average device time of fn over all layers (distinct buffers), HIP events on the launch stream."""
+        tot, n = 0.0, 0
+        for _ in range(reps):
+            for lin in layers:
+                a = torch.cuda.Event(enable_timing=True)
+                b = torch.cuda.Event(enable_timing=True)
+                a.record()
+                fn(lin)
+                b.record()
+                b.synchronize()
+                tot += a.elapsed_time(b)
+                n += 1
+        return tot / n * 1e3  # us
+
+    kernels = []
+    f16_total_us = w8_total_us = q_total_us = 0.0
+    for li, (name, K, N) in enumerate(cfg.linears):
+        tq = time_launch(lambda lin: ptq.quantize_pts(lin[li]["x"], lin[li]["inv_m"], lin[li]["s_tok"], B, L,
+                                                     xq=lin[li]["xq"]))
+        tg = time_launch(lambda lin: ptq.w8a8_linear(lin[li]["xq"], lin[li]["wq"], lin[li]["s_tok"], lin[li]["s_w"],
+                                                    lin[li]["bias"], B, L, y=lin[li]["y"]))
+        tf = time_launch(lambda lin: ptq.f16_linear(lin[li]["x"], lin[li]["w"], lin[li]["bias"], y=lin[li]["y"]))
+        ops = 2.0 * M * K * N
+        q_bytes = 3.0 * M * K + 4 * K + 4 * L
+        g_bytes = 1.0 * M * K + N * K + 2.0 * M * N + 4 * L + 6 * N
+        kernels.append(dict(
+            linear=name, K=K, N=N,
+            quantize_us=round(tq, 2), quantize_GBps=round(q_bytes / tq / 1e3, 1),
+            quantize_frac_hbm=round(q_bytes / tq / 1e3 / PEAK_HBM_GBS, 4),
+            w8a8_us=round(tg, 2), w8a8_TOPS=round(ops / tg / 1e6, 1),
+            w8a8_frac_int8_peak=round(ops / tg / 1e6 / PEAK_INT8_TOPS, 4),
+            w8a8_GBps=round(g_bytes / tg / 1e3, 1), w8a8_frac_hbm=round(g_bytes / tg / 1e3 / PEAK_HBM_GBS, 4),
+            f16_us=round(tf, 2), f16_TFLOPS=round(ops / tf / 1e6, 1),
+            speedup_gemm_only=round(tf / tg, 3), speedup_quant_plus_gemm=round(tf / (tq + tg), 3)))
+        f16_total_us += tf
+        w8_total_us += tg
+        q_total_us += tq
+    for _ in range(2):
+        step_f16()
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(max(1, args.steps // 2)):
+        step_f16()
+    torch.cuda.synchronize()
+    f16_ms_per_step = (time.perf_counter() - t0) / max(1, args.steps // 2) * 1e3
+
+    # ------------------------------------------------------------------ roofline of the dominant kernel
+    _, dK, dN = dominant
+    dom_ops = 2.0 * M * dK * dN                     # algorithmic int8 ops per launch
+    achieved = dom_ops / dom_us / 1e6               # TOP/s
+    roofline = dict(bound="mfma", kernel=f"linear_mfma<int8> {dominant[0]} {dK}->{dN}, M={M}",
+                    achieved=round(achieved, 1), peak=PEAK_INT8_TOPS, unit="TFLOP/s",
+                    frac=round(achieved / PEAK_INT8_TOPS, 4), avg_launch_us=round(dom_us, 2),
+                    launches_timed=len(events["pairs"]), traffic=DOMINANT_TRAFFIC_BYTES)
+
+    # ------------------------------------------------------------------ CPU oracle baseline (bounded sample)
+    cpu = None
+    if not args.no_cpu_baseline:
+        import numpy as np
+
+        import oracle
+
+        sb = min(args.cpu_sample_batch, B)
+        rows = sb * L
+        lin0 = layers[0]
+        host = [dict(x=d["x"][:rows].cpu().numpy(), w=d["w"].cpu().numpy(), bias=d["bias"].cpu().numpy(),
+                     s_tok=d["s_tok"].cpu().numpy(), inv_m=d["inv_m"].cpu().numpy()) for d in lin0]
+        folded = [oracle.fold_smoothing(h["w"], (np.float32(1) / h["inv_m"]).astype(np.float32)) for h in host]
+        t0 = time.perf_counter()
+        for h, (wq_o, s_w_o, _) in zip(host, folded):
+            xq_o = oracle.quantize_pts(h["x"], h["inv_m"], h["s_tok"], sb, L)
+            oracle.w8a8_linear(xq_o, wq_o, h["s_tok"], s_w_o, h["bias"], sb, L)
+        cpu_s = time.perf_counter() - t0
+        cpu = dict(value=round(rows / (cpu_s * n_layers), 2), unit="tokens/s", cores=oracle.threads(), kind="oracle",
+                   sample=f"layer 0, all four linears (quantize + int GEMM + dequantize), first {sb} of {B} images "
+                          f"({rows} rows) in {cpu_s:.2f} s; extrapolated to {n_layers} layers")
+
+    tokens_per_s = M / (ms_per_step * 1e-3)
+    total_ops = sum(2.0 * M * K * N for _, K, N in cfg.linears) * n_layers
+    out = {
+        "metric": "W8A8 linear TOPS + tokens/sec, Vim-B shapes batch 256; speedup vs fp16 GEMM",
+        "value": round(tokens_per_s, 1),
+        "unit": "tokens/s",
+        "n_gpus": 1,
+        "steps": args.steps,
+        "warmup": args.warmup,
+        "ms_per_step": round(ms_per_step, 4),
+        "higher_is_better": True,
+        "scaling": "weak",
+        "vs_baseline": None,
+        "dtype": "int8",
+        "data": "synthetic",
+        "config": {"workload": f"configs[{args.config}] {cfg.name}: {n_layers} layers x "
+                               f"{[f'{n} {k}->{o}' for n, k, o in cfg.linears]}, B={B}, L={L}, M={M}; "
+                               "step = 96 PTS-quantize + 96 W8A8-linear launches, fold offline"},
+        "tops": round(total_ops / (ms_per_step * 1e-3) / 1e12, 1),
+        "speedup_vs_f16_stack": round(f16_ms_per_step / ms_per_step, 3),
+        "f16_ms_per_step": round(f16_ms_per_step, 4),
+        "paper_context": "paper: up to 1.83x end-to-end at W4A4 on VMamba-B, batch 32, RTX 3090 (not this metric)",
+        "roofline": roofline,
+        "cpu_baseline": cpu,
+        "kernels": kernels,
+        "setup_s": round(setup_s, 1),
+    }
+    print(json.dumps(out))
+    return 0
+
+
+if __name__ == "__main__":
+    sys.exit(main())

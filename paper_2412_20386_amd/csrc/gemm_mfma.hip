@@ -11,14 +11,20 @@
 // a lane feeds 16 consecutive bytes of K per instruction (16 int8 for v_mfma_i32_32x32x32_i8,
 // 8 fp16 for v_mfma_f32_32x32x16_f16), so one 128-bit load from either matrix is one operand.
 // The weight is the MFMA "A" operand and the activation the "B" operand: the accumulator of a
-// lane then holds one token row r and runs of four consecutive output channels, which become
-// 8-byte fp16 stores, and the per-token step s_tok[r mod L] is one scalar per lane.
+// lane then holds one token row r and runs of four consecutive output channels, and the
+// per-token step s_tok[r mod L] is one scalar per lane.
 //
 // Tiling: a workgroup of 4 wavefronts owns BR token rows x BO output channels; K is walked in
-// slabs of 64 bytes, double buffered in LDS (register-staged global loads, one barrier per
-// slab).  LDS rows are 64 bytes with the 16-byte chunk index XOR-swizzled by the row so that
-// both the 128-bit writes and the MFMA-fragment reads spread over all banks.  Workgroup ids
-// are remapped so that the tiles sharing one activation strip run on the same XCD (shared L2).
+// slabs of 64 bytes.  LDS rows are 64 bytes with the 16-byte chunk index XOR-swizzled by the
+// row.  Workgroup ids are remapped so that the tiles sharing one activation strip run on the
+// same XCD (shared L2).  Two kernels share fragments, MFMA loop and epilogue:
+//   linear_mfma_dma      fast path (16-byte aligned pitches, K bytes a multiple of 64): slabs are
+//                        copied global -> LDS directly (global_load_lds_dwordx4), several slabs
+//                        in flight in a ring of LDS stages, one s_barrier per slab and explicit
+//                        s_waitcnt vmcnt so that younger slabs stay in flight across the barrier.
+//   linear_mfma_generic  any pitch, alignment and K: register-staged loads with zero fill.
+// The epilogue transposes each wavefront's results through a private LDS patch so that global
+// stores are 16 bytes per lane and cover whole contiguous row segments.
 #include <hip/hip_fp16.h>
 
 #include "common.hpp"
@@ -67,11 +73,249 @@ struct LinearArgs {
     int64_t ldy;         // elements
     int64_t L;
     int tiles_o, tiles_r;
-    int y_vec4_ok;       // rows of y are 8-byte aligned: runs of 4 outputs may use one 64-bit store
+    int y_vec;           // widest store the pitch and base of y allow, in fp16 elements: 8, 4 or 1
 };
+
+extern __shared__ __attribute__((aligned(16))) char lds_dyn[];
 
 __device__ __forceinline__ int swizzle(int row) { return ((row >> 1) ^ (row >> 2)) & 3; }
 
+// XCD-aware tile order: workgroup ids go round-robin over the 8 XCDs, so give each XCD a
+// contiguous range of tiles, output-channel tiles fastest (they share the activation strip).
+__device__ __forceinline__ bool tile_of_block(const LinearArgs &p, int &tile_r, int &tile_o) {
+    const int total_tiles = p.tiles_o * p.tiles_r;
+    const int per_xcd = (total_tiles + kXcds - 1) / kXcds;
+    const int tile = (int)(blockIdx.x % kXcds) * per_xcd + (int)(blockIdx.x / kXcds);
+    if (tile >= total_tiles) return false;
+    tile_o = tile % p.tiles_o;
+    tile_r = tile / p.tiles_o;
+    return true;
+}
+
+// MFMA work on one 64-byte slab held in LDS: x_rows/w_rows point at the wave's first row.
+template <class Path, int FO, int FR>
+__device__ __forceinline__ void mfma_slab(typename Path::Acc (&acc)[FO][FR], const char *x_rows, const char *w_rows,
+                                          int l32, int lhalf) {
+#pragma unroll
+    for (int s = 0; s < 2; s++) {
+        const int kc = 2 * s + lhalf;
+        v4i fw[FO], fx[FR];
+#pragma unroll
+        for (int i = 0; i < FO; i++) {
+            const int row = i * 32 + l32;  // wave row offsets are multiples of 32: swizzle(row) is unchanged
+            fw[i] = *reinterpret_cast<const v4i *>(w_rows + row * kSlabBytes + ((kc ^ swizzle(row)) << 4));
+        }
+#pragma unroll
+        for (int j = 0; j < FR; j++) {
+            const int row = j * 32 + l32;
+            fx[j] = *reinterpret_cast<const v4i *>(x_rows + row * kSlabBytes + ((kc ^ swizzle(row)) << 4));
+        }
+#pragma unroll
+        for (int i = 0; i < FO; i++)
+#pragma unroll
+            for (int j = 0; j < FR; j++) acc[i][j] = Path::mfma(fw[i], fx[j], acc[i][j]);
+    }
+}
+
+// Epilogue of one wavefront.  Accumulator register v of a lane in block (i, j):
+//   token row       r = r_base + 32 j + (lane mod 32)
+//   output channel  o = o_base + 32 i + 8 (v / 4) + 4 (lane / 32) + (v mod 4)
+// A lane therefore owns 8-byte runs scattered over 32 rows.  The wavefront transposes its
+// results through a private LDS patch (JB*32 rows x WAVE_O fp16 at a time, 16-byte chunks
+// XOR-swizzled by the row) so that the global stores are 16 bytes per lane with the lanes of a
+// row side by side: every store instruction writes whole, contiguous row segments.  Only this
+// wavefront touches `patch`, and the LDS executes a wavefront's instructions in order, so no
+// barrier is needed; the empty asm statements only stop the compiler from reordering LDS
+// accesses.  Column scales and biases are fetched per group of four channels (outer loops) so
+// that they do not have to live in registers next to the accumulators.
+template <class Path, int FO, int FR, int JB>
+__device__ __forceinline__ void epilogue(const typename Path::Acc (&acc)[FO][FR], const LinearArgs &p, char *patch,
+                                         int64_t r_base, int64_t o_base, int lane) {
+    constexpr int WAVE_O = FO * 32;
+    constexpr int CPR = WAVE_O / 8;           // 16-byte chunks per staged row
+    constexpr int ROWS_PER_STORE = 64 / CPR;  // rows covered by one store instruction
+    static_assert(CPR <= 64 && (CPR & (CPR - 1)) == 0, "wave tile width must be 32, 64 or 128 channels");
+    static_assert(FR % JB == 0, "row blocks are staged in equal groups");
+    const int l32 = lane & 31, lhalf = lane >> 5;
+    auto patch_chunk = [&](int row, int chunk) {  // byte offset of a 16-byte chunk
+        const int sw = CPR >= 8 ? (row & 7) : ((row / (8 / CPR)) & (CPR - 1));
+        return row * (WAVE_O * 2) + ((chunk ^ sw) << 4);
+    };
+
+#pragma unroll
+    for (int jb = 0; jb < FR; jb += JB) {
+        float row_scale[JB];
+#pragma unroll
+        for (int jj = 0; jj < JB; jj++) {
+            const int64_t r = r_base + (jb + jj) * 32 + l32;
+            row_scale[jj] = 1.0f;
+            if constexpr (Path::kElemBytes == 1) row_scale[jj] = p.s_tok[(r < p.M ? r : 0) % p.L];
+        }
+#pragma unroll
+        for (int i = 0; i < FO; i++) {
+#pragma unroll
+            for (int g = 0; g < 4; g++) {
+                float col_scale[4], col_bias[4];
+#pragma unroll
+                for (int c = 0; c < 4; c++) {
+                    const int64_t o = o_base + i * 32 + g * 8 + lhalf * 4 + c;
+                    const bool ok = o < p.N;
+                    col_bias[c] = (ok && p.bias) ? __half2float(p.bias[o]) : 0.0f;
+                    col_scale[c] = 1.0f;
+                    if constexpr (Path::kElemBytes == 1) col_scale[c] = ok ? p.s_w[o] : 0.0f;
+                }
+#pragma unroll
+                for (int jj = 0; jj < JB; jj++) {
+                    const int j = jb + jj;
+                    float out[4];
+#pragma unroll
+                    for (int c = 0; c < 4; c++) {
+                        if constexpr (Path::kElemBytes == 1) {
+                            const int a = acc[i][j][g * 4 + c];
+                            if (p.acc_out) {
+                                const int64_t r = r_base + j * 32 + l32;
+                                const int64_t o = o_base + i * 32 + g * 8 + lhalf * 4 + c;
+                                if (r < p.M && o < p.N) p.acc_out[r * p.N + o] = a;
+                            }
+                            out[c] = (float)a * (row_scale[jj] * col_scale[c]) + col_bias[c];
+                        } else {
+                            out[c] = acc[i][j][g * 4 + c] + col_bias[c];
+                        }
+                    }
+                    __half2 lo = __floats2half2_rn(out[0], out[1]);
+                    __half2 hi = __floats2half2_rn(out[2], out[3]);
+                    u32x2 packed = {*reinterpret_cast<uint32_t *>(&lo), *reinterpret_cast<uint32_t *>(&hi)};
+                    *reinterpret_cast<u32x2 *>(patch + patch_chunk(jj * 32 + l32, i * 4 + g) + lhalf * 8) = packed;
+                }
+            }
+        }
+        asm volatile("" ::: "memory");
+#pragma unroll
+        for (int s = 0; s < JB * 32 / ROWS_PER_STORE; s++) {
+            const int row = s * ROWS_PER_STORE + lane / CPR, chunk = lane % CPR;
+            const v4i data = *reinterpret_cast<const v4i *>(patch + patch_chunk(row, chunk));
+            const int64_t rr = r_base + jb * 32 + row;
+            const int64_t oc = o_base + chunk * 8;
+            if (rr < p.M && oc < p.N) {
+                __half *dst = p.y + rr * p.ldy + oc;
+                if (p.y_vec == 8 && oc + 8 <= p.N) {
+                    *reinterpret_cast<v4i *>(dst) = data;
+                } else if (p.y_vec >= 4 && oc + 8 <= p.N) {
+                    u32x2 a = {(uint32_t)data[0], (uint32_t)data[1]}, b = {(uint32_t)data[2], (uint32_t)data[3]};
+                    *reinterpret_cast<u32x2 *>(dst) = a;
+                    *reinterpret_cast<u32x2 *>(dst + 4) = b;
+                } else {
+#pragma unroll
+                    for (int e = 0; e < 8; e++)
+                        if (oc + e < p.N)
+                            reinterpret_cast<uint16_t *>(dst)[e] = (uint16_t)((uint32_t)data[e >> 1] >> (16 * (e & 1)));
+                }
+            }
+        }
+        asm volatile("" ::: "memory");
+    }
+}
+
+// ------------------------------------------------------------------------------------------
+// Fast path: direct global -> LDS copies, STAGES-deep ring.
+// Requirements (checked on the host): k_bytes % 64 == 0, pitches and bases 16-byte aligned,
+// 256 * pitch below 2^31.
+// A wavefront copies 1 KiB blocks (16 rows x 64 bytes): the LDS side of the copy is linear in the
+// lane index, so the swizzle is applied by choosing which global chunk each lane fetches.  Rows
+// beyond M or N are clamped to the last valid row; their results are never stored.
+// ------------------------------------------------------------------------------------------
+template <class Path, int BR, int BO, int WR, int WO, int STAGES>
+__global__ __launch_bounds__(kThreads, 2) void linear_mfma_dma(const LinearArgs p) {
+    static_assert(WR * WO == kWaves, "four wavefronts per workgroup");
+    constexpr int WAVE_R = BR / WR, WAVE_O = BO / WO;
+    constexpr int FR = WAVE_R / 32, FO = WAVE_O / 32;
+    static_assert(WAVE_R % 32 == 0 && WAVE_O % 32 == 0, "wave tile must be whole MFMA blocks");
+    static_assert(BR % 64 == 0 && BO % 64 == 0, "each wavefront copies whole 16-row blocks");
+    constexpr int X_BLOCKS = BR / 16 / kWaves, W_BLOCKS = BO / 16 / kWaves;  // 1 KiB copies per wave per slab
+    constexpr int LOADS_PER_SLAB = X_BLOCKS + W_BLOCKS;
+    constexpr int STAGE_BYTES = (BR + BO) * kSlabBytes;
+    static_assert((STAGES - 2) * LOADS_PER_SLAB <= 63, "vmcnt is a 6-bit counter");
+    static_assert(BR * BO * 2 <= STAGES * STAGE_BYTES, "the output tile must fit the LDS ring for the epilogue");
+    using Acc = typename Path::Acc;
+
+    int tile_r, tile_o;
+    if (!tile_of_block(p, tile_r, tile_o)) return;
+    const int64_t r0 = (int64_t)tile_r * BR, o0 = (int64_t)tile_o * BO;
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int wave_r = (wave / WO) * WAVE_R, wave_o = (wave % WO) * WAVE_O;
+    const int l32 = lane & 31, lhalf = lane >> 5;
+
+    // Per-lane source offsets (bytes from the tile's first row, slab 0) of the copies.
+    const char *x_tile = p.x + r0 * p.ldx_bytes;
+    const char *w_tile = p.w + o0 * p.ldw_bytes;
+    const int rows_x = (int)min((int64_t)BR, p.M - r0), rows_w = (int)min((int64_t)BO, p.N - o0);
+    uint32_t x_off[X_BLOCKS], w_off[W_BLOCKS];
+#pragma unroll
+    for (int i = 0; i < X_BLOCKS; i++) {
+        const int row = (wave + kWaves * i) * 16 + (lane >> 2);
+        const int kc = (lane & 3) ^ swizzle(row);
+        x_off[i] = (uint32_t)min(row, rows_x - 1) * (uint32_t)p.ldx_bytes + kc * 16;
+    }
+#pragma unroll
+    for (int i = 0; i < W_BLOCKS; i++) {
+        const int row = (wave + kWaves * i) * 16 + (lane >> 2);
+        const int kc = (lane & 3) ^ swizzle(row);
+        w_off[i] = (uint32_t)min(row, rows_w - 1) * (uint32_t)p.ldw_bytes + kc * 16;
+    }
+    auto issue = [&](int slab, int stage) {
+        char *sx = lds_dyn + stage * STAGE_BYTES;
+        char *sw = sx + BR * kSlabBytes;
+        const char *gx = x_tile + (int64_t)slab * kSlabBytes;
+        const char *gw = w_tile + (int64_t)slab * kSlabBytes;
+#pragma unroll
+        for (int i = 0; i < X_BLOCKS; i++)
+            __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void *)(gx + x_off[i]),
+                                             (__attribute__((address_space(3))) void *)(sx + (wave + kWaves * i) * 1024),
+                                             16, 0, 0);
+#pragma unroll
+        for (int i = 0; i < W_BLOCKS; i++)
+            __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void *)(gw + w_off[i]),
+                                             (__attribute__((address_space(3))) void *)(sw + (wave + kWaves * i) * 1024),
+                                             16, 0, 0);
+    };
+
+    Acc acc[FO][FR];
+#pragma unroll
+    for (int i = 0; i < FO; i++)
+#pragma unroll
+        for (int j = 0; j < FR; j++)
+#pragma unroll
+            for (int v = 0; v < 16; v++) acc[i][j][v] = 0;
+
+    const int n_slabs = (int)(p.k_bytes / kSlabBytes);
+#pragma unroll
+    for (int s = 0; s < STAGES - 1; s++)
+        if (s < n_slabs) issue(s, s);
+
+    int stage = 0;
+    for (int it = 0; it < n_slabs; it++) {
+        // Slab `it` must have landed; up to STAGES-2 younger slabs may stay in flight.
+        // s_waitcnt immediate on gfx9: vmcnt[3:0] | expcnt[6:4] | lgkmcnt[11:8] | vmcnt[5:4] << 14.
+        constexpr int KEEP = (STAGES - 2) * LOADS_PER_SLAB;
+        if (it + STAGES - 2 < n_slabs)
+            __builtin_amdgcn_s_waitcnt(0x0F70 | (KEEP & 15) | ((KEEP >> 4) << 14));
+        else
+            __builtin_amdgcn_s_waitcnt(0x0F70);
+        __builtin_amdgcn_s_barrier();  // everyone's copies of slab `it` are visible; slab it-1 is fully consumed
+        int refill = stage + STAGES - 1;
+        if (refill >= STAGES) refill -= STAGES;
+        if (it + STAGES - 1 < n_slabs) issue(it + STAGES - 1, refill);
+        const char *sx = lds_dyn + stage * STAGE_BYTES;
+        mfma_slab<Path, FO, FR>(acc, sx + wave_r * kSlabBytes, sx + (BR + wave_o) * kSlabBytes, l32, lhalf);
+        if (++stage == STAGES) stage = 0;
+    }
+    __syncthreads();  // all MFMA reads of LDS are done: the ring becomes the epilogue patches
+    epilogue<Path, FO, FR, FR>(acc, p, lds_dyn + wave * (WAVE_R * WAVE_O * 2), r0 + wave_r, o0 + wave_o, lane);
+}
+
+// ------------------------------------------------------------------------------------------
+// Generic path: register-staged loads, zero fill beyond M, N and K, any pitch.
+// ------------------------------------------------------------------------------------------
 __device__ __forceinline__ uint32_t keep_low_bytes(uint32_t v, int nbytes) {
     return nbytes >= 4 ? v : (nbytes <= 0 ? 0u : (v & ((1u << (8 * nbytes)) - 1u)));
 }
@@ -118,10 +362,10 @@ __device__ __forceinline__ v4i load_chunk(const char *row_ptr, int64_t kb, int64
 }
 
 template <class Path, int BR, int BO, int WR, int WO, int LOAD_ALIGN>
-__global__ __launch_bounds__(kThreads, 2) void linear_mfma(const LinearArgs p) {
+__global__ __launch_bounds__(kThreads, 2) void linear_mfma_generic(const LinearArgs p) {
     static_assert(WR * WO == kWaves, "four wavefronts per workgroup");
-    constexpr int WAVE_R = BR / WR, WAVE_O = BO / WO;  // wave tile
-    constexpr int FR = WAVE_R / 32, FO = WAVE_O / 32;  // 32x32 MFMA blocks per wave tile
+    constexpr int WAVE_R = BR / WR, WAVE_O = BO / WO;
+    constexpr int FR = WAVE_R / 32, FO = WAVE_O / 32;
     static_assert(WAVE_R % 32 == 0 && WAVE_O % 32 == 0, "wave tile must be whole MFMA blocks");
     constexpr int X_CHUNKS = (BR * 4 + kThreads - 1) / kThreads;  // 16-byte chunks per thread per slab
     constexpr int W_CHUNKS = (BO * 4 + kThreads - 1) / kThreads;
@@ -129,17 +373,12 @@ __global__ __launch_bounds__(kThreads, 2) void linear_mfma(const LinearArgs p) {
 
     __shared__ __attribute__((aligned(16))) char lds_x[2][BR * kSlabBytes];
     __shared__ __attribute__((aligned(16))) char lds_w[2][BO * kSlabBytes];
+    constexpr int JB = (FR % 2 == 0 && kWaves * 64 * WAVE_O * 2 <= 2 * BR * kSlabBytes) ? 2 : 1;
+    static_assert(kWaves * JB * 32 * WAVE_O * 2 <= 2 * BR * kSlabBytes, "epilogue patches must fit the activation buffers");
 
-    // XCD-aware tile order: workgroup ids go round-robin over the 8 XCDs, so give each XCD a
-    // contiguous range of tiles, output-channel tiles fastest (they share the activation strip).
-    const int total_tiles = p.tiles_o * p.tiles_r;
-    const int per_xcd = (total_tiles + kXcds - 1) / kXcds;
-    const int tile = (int)(blockIdx.x % kXcds) * per_xcd + (int)(blockIdx.x / kXcds);
-    if (tile >= total_tiles) return;
-    const int tile_o = tile % p.tiles_o, tile_r = tile / p.tiles_o;
-    const int64_t r0 = (int64_t)tile_r * BR;
-    const int64_t o0 = (int64_t)tile_o * BO;
-
+    int tile_r, tile_o;
+    if (!tile_of_block(p, tile_r, tile_o)) return;
+    const int64_t r0 = (int64_t)tile_r * BR, o0 = (int64_t)tile_o * BO;
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int wave_r = (wave / WO) * WAVE_R, wave_o = (wave % WO) * WAVE_O;
     const int l32 = lane & 31, lhalf = lane >> 5;
@@ -153,7 +392,6 @@ __global__ __launch_bounds__(kThreads, 2) void linear_mfma(const LinearArgs p) {
             for (int v = 0; v < 16; v++) acc[i][j][v] = 0;
 
     v4i stage_x[X_CHUNKS], stage_w[W_CHUNKS];
-
     auto fetch = [&](int64_t kb0) {
 #pragma unroll
         for (int i = 0; i < X_CHUNKS; i++) {
@@ -189,97 +427,58 @@ __global__ __launch_bounds__(kThreads, 2) void linear_mfma(const LinearArgs p) {
     fetch(0);
     commit(0);
     __syncthreads();
-
     for (int it = 0; it < n_slabs; it++) {
         const int buf = it & 1;
         const bool more = it + 1 < n_slabs;
         if (more) fetch((int64_t)(it + 1) * kSlabBytes);
-#pragma unroll
-        for (int s = 0; s < 2; s++) {
-            const int kc = 2 * s + lhalf;
-            v4i fw[FO], fx[FR];
-#pragma unroll
-            for (int i = 0; i < FO; i++) {
-                const int row = wave_o + i * 32 + l32;
-                fw[i] = *reinterpret_cast<const v4i *>(&lds_w[buf][row * kSlabBytes + ((kc ^ swizzle(row)) << 4)]);
-            }
-#pragma unroll
-            for (int j = 0; j < FR; j++) {
-                const int row = wave_r + j * 32 + l32;
-                fx[j] = *reinterpret_cast<const v4i *>(&lds_x[buf][row * kSlabBytes + ((kc ^ swizzle(row)) << 4)]);
-            }
-#pragma unroll
-            for (int i = 0; i < FO; i++)
-#pragma unroll
-                for (int j = 0; j < FR; j++) acc[i][j] = Path::mfma(fw[i], fx[j], acc[i][j]);
-        }
+        mfma_slab<Path, FO, FR>(acc, &lds_x[buf][wave_r * kSlabBytes], &lds_w[buf][wave_o * kSlabBytes], l32, lhalf);
         if (more) commit(buf ^ 1);
         __syncthreads();
     }
+    epilogue<Path, FO, FR, JB>(acc, p, &lds_x[0][0] + wave * (JB * 32 * WAVE_O * 2), r0 + wave_r, o0 + wave_o, lane);
+}
 
-    // Epilogue.  Accumulator register v of a lane in block (i, j):
-    //   token row       r = r0 + wave_r + 32 j + (lane mod 32)
-    //   output channel  o = o0 + wave_o + 32 i + 8 (v / 4) + 4 (lane / 32) + (v mod 4)
-#pragma unroll
-    for (int j = 0; j < FR; j++) {
-        const int64_t r = r0 + wave_r + j * 32 + l32;
-        if (r >= p.M) continue;
-        float row_scale = 1.0f;
-        if constexpr (Path::kElemBytes == 1) row_scale = p.s_tok[r % p.L];
-        __half *yrow = p.y + r * p.ldy;
-#pragma unroll
-        for (int i = 0; i < FO; i++) {
-#pragma unroll
-            for (int g = 0; g < 4; g++) {
-                const int64_t ob = o0 + wave_o + i * 32 + g * 8 + lhalf * 4;
-                if (ob >= p.N) continue;
-                float out[4];
-#pragma unroll
-                for (int c = 0; c < 4; c++) {
-                    const int64_t o = ob + c;
-                    float val = 0.0f;
-                    if (o < p.N) {
-                        const float b = p.bias ? __half2float(p.bias[o]) : 0.0f;
-                        if constexpr (Path::kElemBytes == 1) {
-                            const int a = acc[i][j][g * 4 + c];
-                            if (p.acc_out) p.acc_out[r * p.N + o] = a;
-                            val = (float)a * (row_scale * p.s_w[o]) + b;
-                        } else {
-                            val = acc[i][j][g * 4 + c] + b;
-                        }
-                    }
-                    out[c] = val;
-                }
-                if (p.y_vec4_ok && ob + 3 < p.N) {
-                    __half2 lo = __floats2half2_rn(out[0], out[1]);
-                    __half2 hi = __floats2half2_rn(out[2], out[3]);
-                    u32x2 packed = {*reinterpret_cast<uint32_t *>(&lo), *reinterpret_cast<uint32_t *>(&hi)};
-                    __builtin_nontemporal_store(packed, reinterpret_cast<u32x2 *>(yrow + ob));
-                } else {
-#pragma unroll
-                    for (int c = 0; c < 4; c++)
-                        if (ob + c < p.N) yrow[ob + c] = __float2half_rn(out[c]);
-                }
-            }
-        }
+// ------------------------------------------------------------------------------------------
+// Host side
+// ------------------------------------------------------------------------------------------
+template <int BR, int BO>
+bool set_grid(LinearArgs &a, dim3 &grid) {
+    const int64_t tiles_r = ptq4vm::ceil_div(a.M, BR), tiles_o = ptq4vm::ceil_div(a.N, BO);
+    if (tiles_r * tiles_o > 0x3fffffffLL) return false;
+    a.tiles_r = (int)tiles_r;
+    a.tiles_o = (int)tiles_o;
+    grid = dim3((unsigned)(ptq4vm::ceil_div(tiles_r * tiles_o, kXcds) * kXcds));
+    return true;
+}
+
+template <class Path, int BR, int BO, int WR, int WO, int STAGES>
+int launch_dma(LinearArgs a, hipStream_t stream) {
+    dim3 grid;
+    if (!set_grid<BR, BO>(a, grid)) return PTQ4VM_ERR_SHAPE;
+    constexpr int lds_bytes = STAGES * (BR + BO) * kSlabBytes;
+    auto kernel = linear_mfma_dma<Path, BR, BO, WR, WO, STAGES>;
+    static bool configured = false;  // raising the dynamic-LDS limit is a per-function, idempotent setting
+    if (!configured) {
+        hipError_t err = hipFuncSetAttribute(reinterpret_cast<const void *>(kernel),
+                                             hipFuncAttributeMaxDynamicSharedMemorySize, lds_bytes);
+        if (err != hipSuccess) return ptq4vm::record_hip_error(err, "hipFuncSetAttribute(linear_mfma_dma)");
+        configured = true;
     }
+    kernel<<<grid, dim3(kThreads), lds_bytes, stream>>>(a);
+    return ptq4vm::check_launch("linear_mfma_dma");
 }
 
 template <class Path, int BR, int BO, int WR, int WO>
-int launch_tiles(LinearArgs a, int load_align, hipStream_t stream) {
-    const int64_t tiles_r = ptq4vm::ceil_div(a.M, BR), tiles_o = ptq4vm::ceil_div(a.N, BO);
-    if (tiles_r * tiles_o > 0x3fffffffLL) return PTQ4VM_ERR_SHAPE;
-    a.tiles_r = (int)tiles_r;
-    a.tiles_o = (int)tiles_o;
-    const int64_t total = tiles_r * tiles_o;
-    dim3 grid((unsigned)(ptq4vm::ceil_div(total, kXcds) * kXcds)), block(kThreads);
+int launch_generic(LinearArgs a, int load_align, hipStream_t stream) {
+    dim3 grid;
+    if (!set_grid<BR, BO>(a, grid)) return PTQ4VM_ERR_SHAPE;
     if (load_align == 16)
-        linear_mfma<Path, BR, BO, WR, WO, 16><<<grid, block, 0, stream>>>(a);
+        linear_mfma_generic<Path, BR, BO, WR, WO, 16><<<grid, dim3(kThreads), 0, stream>>>(a);
     else if (load_align == 4)
-        linear_mfma<Path, BR, BO, WR, WO, 4><<<grid, block, 0, stream>>>(a);
+        linear_mfma_generic<Path, BR, BO, WR, WO, 4><<<grid, dim3(kThreads), 0, stream>>>(a);
     else
-        linear_mfma<Path, BR, BO, WR, WO, 0><<<grid, block, 0, stream>>>(a);
-    return ptq4vm::check_launch("linear_mfma");
+        linear_mfma_generic<Path, BR, BO, WR, WO, 0><<<grid, dim3(kThreads), 0, stream>>>(a);
+    return ptq4vm::check_launch("linear_mfma_generic");
 }
 
 // Widest load granularity that base pointers and pitches allow for both operands.
@@ -294,9 +493,16 @@ int pick_load_align(const LinearArgs &a) {
 template <class Path>
 int dispatch(LinearArgs a, hipStream_t stream) {
     const int la = pick_load_align(a);
-    a.y_vec4_ok = (a.ldy % 4 == 0 && ptq4vm::aligned_to(a.y, 8)) ? 1 : 0;
-    if (a.N > 64) return launch_tiles<Path, 256, 128, 2, 2>(a, la, stream);
-    return launch_tiles<Path, 256, 64, 4, 1>(a, la, stream);
+    a.y_vec = (a.ldy % 8 == 0 && ptq4vm::aligned_to(a.y, 16)) ? 8
+              : ((a.ldy % 4 == 0 && ptq4vm::aligned_to(a.y, 8)) ? 4 : 1);
+    const bool dma_ok = la == 16 && a.k_bytes % kSlabBytes == 0 && a.ldx_bytes * 256 < (1LL << 31) &&
+                        a.ldw_bytes * 256 < (1LL << 31);
+    if (a.N > 64) {
+        if (dma_ok) return launch_dma<Path, 256, 128, 2, 2, 3>(a, stream);
+        return launch_generic<Path, 256, 128, 2, 2>(a, la, stream);
+    }
+    if (dma_ok) return launch_dma<Path, 256, 64, 4, 1, 3>(a, stream);
+    return launch_generic<Path, 256, 64, 4, 1>(a, la, stream);
 }
 
 }  // namespace

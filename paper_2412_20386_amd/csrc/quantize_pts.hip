@@ -3,10 +3,13 @@
 //
 // The kernel is a pure stream (2 B read + 1 B written per element), so everything is arranged
 // for HBM: 128-bit loads, consecutive lanes on consecutive addresses, several loads in flight
-// per lane, and no per-element index arithmetic.  A thread keeps ONE column chunk (VEC
-// channels) for its whole life, so the smoothing factors sit in registers; a block owns a
-// contiguous band of rows and precomputes their reciprocal steps once into LDS (the only
-// place r mod L and the IEEE division appear).
+// per lane, and no per-element index arithmetic.  The grid is a fixed, small number of
+// workgroups per CU that stride over the rows together (measured: ~3 workgroups per CU stream
+// faster than a grid of many short-lived ones).  The total thread count is a multiple of the
+// chunks per row, so a thread keeps ONE column chunk (VEC channels) for its whole life: the
+// smoothing factors sit in registers and the row index advances by a constant.  The reciprocal
+// steps 1/s_tok[t] of all L token positions are computed once per workgroup into LDS (the only
+// place the IEEE division appears); the token position advances incrementally, without a modulo.
 #include <hip/hip_fp16.h>
 
 #include "common.hpp"
@@ -17,7 +20,7 @@ typedef unsigned int u32x2 __attribute__((ext_vector_type(2)));
 typedef unsigned int u32x4 __attribute__((ext_vector_type(4)));
 
 constexpr int kMaxThreads = 256;
-constexpr int kMaxBandRows = 1024;  // rows per block; bounds the LDS table of reciprocal steps
+constexpr int kMaxLdsTokens = 16384;  // reciprocal-step table of up to 64 KiB; longer sequences divide per row
 
 // fp32 -> int32 conversion with the hardware's defined behaviour for specials
 // (NaN -> 0, out-of-range saturates), which a C++ cast leaves undefined.
@@ -88,57 +91,60 @@ __device__ __forceinline__ uint32_t quantize_chunk<4>(u32x2 in, const float (&im
     return pack4(q[0], q[1], q[2], q[3]);
 }
 
-// Column-stationary streaming kernel.  blockDim.x = rows_per_pass * cols_per_pass.
-//   chunks        K / VEC
-//   cols_per_pass min(chunks, 256)           threads side by side along a row
-//   rows_per_pass blockDim.x / cols_per_pass rows covered by one pass of the block
-//   band          rows owned by one block (multiple of rows_per_pass, <= kMaxBandRows)
-template <int VEC, bool HAS_M, int UNROLL>
+// Column-stationary grid-stride stream.  gridDim.x * 256 is a multiple of `chunks` (= K / VEC),
+// so thread g owns column chunk g mod chunks and rows g / chunks + i * row_step, i = 0, 1, ...
+template <int VEC, bool HAS_M, bool LDS_TABLE, int UNROLL>
 __global__ __launch_bounds__(kMaxThreads) void quantize_pts_stream(
     const __half *__restrict__ x, const float *__restrict__ inv_m, const float *__restrict__ s_tok,
-    int8_t *__restrict__ xq, int64_t M, int L, int K, int64_t ldx, int64_t ldxq, int chunks,
-    int cols_per_pass, int rows_per_pass, int band) {
+    int8_t *__restrict__ xq, int64_t M, int L, int chunks, int64_t ldx, int64_t ldxq, int64_t row_step) {
     using In = typename Chunk<VEC>::In;
     using Out = typename Chunk<VEC>::Out;
-    __shared__ float inv_s_lds[kMaxBandRows];
-
-    const int64_t row0 = (int64_t)blockIdx.x * band;
-    const int rows_here = (int)min((int64_t)band, M - row0);
-    {
-        int t = (int)((row0 + threadIdx.x) % L);  // the only modulo: once per row, in the prologue
-        for (int i = threadIdx.x; i < rows_here; i += blockDim.x) {
-            inv_s_lds[i] = 1.0f / s_tok[t];  // IEEE-correct division (compiled without fast-math)
-            t = (int)((t + (int64_t)blockDim.x) % L);
-        }
+    extern __shared__ float inv_s_lds[];
+    if constexpr (LDS_TABLE) {
+        for (int i = threadIdx.x; i < L; i += kMaxThreads)
+            inv_s_lds[i] = 1.0f / s_tok[i];  // IEEE-correct division (compiled without fast-math)
+        __syncthreads();
     }
-    __syncthreads();
+    auto inv_step = [&](int t) { return LDS_TABLE ? inv_s_lds[t] : 1.0f / s_tok[t]; };
 
-    const int col = threadIdx.x % cols_per_pass;
-    const int row_in_pass = threadIdx.x / cols_per_pass;
+    const int64_t gtid = (int64_t)blockIdx.x * kMaxThreads + threadIdx.x;
+    const int col = (int)(gtid % chunks);
+    int64_t row = gtid / chunks;
+    int t = (int)(row % L);
+    const int t_step = (int)(row_step % L);
 
-    for (int c = col; c < chunks; c += cols_per_pass) {
-        float im[VEC];
+    float im[VEC];
 #pragma unroll
-        for (int i = 0; i < VEC; i++) im[i] = HAS_M ? inv_m[c * VEC + i] : 1.0f;
+    for (int i = 0; i < VEC; i++) im[i] = HAS_M ? inv_m[col * VEC + i] : 1.0f;
 
-        const __half *xcol = x + row0 * ldx + (int64_t)c * VEC;
-        int8_t *qcol = xq + row0 * ldxq + (int64_t)c * VEC;
-        for (int rb = row_in_pass; rb < rows_here; rb += rows_per_pass * UNROLL) {
-            In v[UNROLL];
+    const __half *xp = x + row * ldx + (int64_t)col * VEC;
+    int8_t *qp = xq + row * ldxq + (int64_t)col * VEC;
+    const int64_t x_step = row_step * ldx, q_step = row_step * ldxq;
+
+    for (; row + (UNROLL - 1) * row_step < M; row += UNROLL * row_step) {
+        In v[UNROLL];
+        float is[UNROLL];
 #pragma unroll
-            for (int u = 0; u < UNROLL; u++) {
-                int r = rb + u * rows_per_pass;
-                if (r < rows_here) v[u] = __builtin_nontemporal_load(reinterpret_cast<const In *>(xcol + (int64_t)r * ldx));
-            }
-#pragma unroll
-            for (int u = 0; u < UNROLL; u++) {
-                int r = rb + u * rows_per_pass;
-                if (r < rows_here) {
-                    Out o = quantize_chunk<VEC>(v[u], im, inv_s_lds[r]);
-                    __builtin_nontemporal_store(o, reinterpret_cast<Out *>(qcol + (int64_t)r * ldxq));
-                }
-            }
+        for (int u = 0; u < UNROLL; u++) {
+            v[u] = __builtin_nontemporal_load(reinterpret_cast<const In *>(xp + u * x_step));
+            is[u] = inv_step(t);
+            t += t_step;
+            if (t >= L) t -= L;
         }
+#pragma unroll
+        for (int u = 0; u < UNROLL; u++)
+            __builtin_nontemporal_store(quantize_chunk<VEC>(v[u], im, is[u]), reinterpret_cast<Out *>(qp + u * q_step));
+        xp += UNROLL * x_step;
+        qp += UNROLL * q_step;
+    }
+    for (; row < M; row += row_step) {
+        In v = __builtin_nontemporal_load(reinterpret_cast<const In *>(xp));
+        const float is = inv_step(t);
+        t += t_step;
+        if (t >= L) t -= L;
+        __builtin_nontemporal_store(quantize_chunk<VEC>(v, im, is), reinterpret_cast<Out *>(qp));
+        xp += x_step;
+        qp += q_step;
     }
 }
 
@@ -157,29 +163,42 @@ __global__ __launch_bounds__(kMaxThreads) void quantize_pts_generic(
     }
 }
 
+int64_t gcd64(int64_t a, int64_t b) {
+    while (b) {
+        int64_t t = a % b;
+        a = b;
+        b = t;
+    }
+    return a;
+}
+
 template <int VEC>
 int launch_stream(const __half *x, const float *inv_m, const float *s_tok, int8_t *xq, int64_t M, int64_t L,
                   int64_t K, int64_t ldx, int64_t ldxq, hipStream_t stream) {
-    const int chunks = (int)(K / VEC);
-    const int cols_per_pass = chunks < kMaxThreads ? chunks : kMaxThreads;
-    const int rows_per_pass = kMaxThreads / cols_per_pass;
-    const int threads = rows_per_pass * cols_per_pass;
-    constexpr int UNROLL = 4;
-    // A block streams about 64 KiB of input, but no fewer rows than one unrolled pass.
-    int64_t want_rows = (64 * 1024) / (K * 2);
-    int64_t pass_rows = (int64_t)rows_per_pass * UNROLL;
-    int64_t band = ptq4vm::ceil_div(want_rows > 1 ? want_rows : 1, pass_rows) * pass_rows;
-    if (band > kMaxBandRows) band = (kMaxBandRows / rows_per_pass) * rows_per_pass;
-    if (band < rows_per_pass) band = rows_per_pass;  // rows_per_pass <= 256 <= kMaxBandRows
-    const int64_t blocks = ptq4vm::ceil_div(M, band);
+    const int64_t chunks = K / VEC;
+    // Grid: a multiple of `unit` workgroups (so that threads % chunks == 0), about 3 per CU of
+    // the 256-CU part, fewer when the whole problem is smaller than that.
+    const int64_t unit = chunks / gcd64(chunks, kMaxThreads);
+    const int64_t total_chunks = M * chunks;
+    int64_t want = 768;
+    const int64_t needed = ptq4vm::ceil_div(total_chunks, kMaxThreads);
+    if (want > needed) want = needed;
+    int64_t blocks = ptq4vm::ceil_div(want, unit) * unit;
     if (blocks > 0x7fffffffLL) return PTQ4VM_ERR_SHAPE;
-    dim3 grid((unsigned)blocks), block((unsigned)threads);
-    if (inv_m)
-        quantize_pts_stream<VEC, true, UNROLL><<<grid, block, 0, stream>>>(
-            x, inv_m, s_tok, xq, M, (int)L, (int)K, ldx, ldxq, chunks, cols_per_pass, rows_per_pass, (int)band);
-    else
-        quantize_pts_stream<VEC, false, UNROLL><<<grid, block, 0, stream>>>(
-            x, inv_m, s_tok, xq, M, (int)L, (int)K, ldx, ldxq, chunks, cols_per_pass, rows_per_pass, (int)band);
+    const int64_t row_step = blocks * kMaxThreads / chunks;
+    const bool table = L <= kMaxLdsTokens;
+    const size_t lds = table ? (size_t)L * sizeof(float) : 0;
+    constexpr int UNROLL = 2;
+    dim3 grid((unsigned)blocks), block(kMaxThreads);
+#define PTQ4VM_LAUNCH(HAS_M, TABLE)                                                                         \
+    quantize_pts_stream<VEC, HAS_M, TABLE, UNROLL><<<grid, block, lds, stream>>>(x, inv_m, s_tok, xq, M, (int)L, \
+                                                                                 (int)chunks, ldx, ldxq, row_step)
+    if (inv_m) {
+        if (table) PTQ4VM_LAUNCH(true, true); else PTQ4VM_LAUNCH(true, false);
+    } else {
+        if (table) PTQ4VM_LAUNCH(false, true); else PTQ4VM_LAUNCH(false, false);
+    }
+#undef PTQ4VM_LAUNCH
     return ptq4vm::check_launch("quantize_pts_stream");
 }
 

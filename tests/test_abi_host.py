@@ -1,0 +1,113 @@
+"""Host-only checks of the C ABI: the library loads without a GPU, exports every symbol the
+header declares, and rejects bad arguments before any launch.  No kernel is launched here."""
+import ctypes
+import os
+import re
+
+import pytest
+
+import paper_2412_20386_amd as ptq
+from paper_2412_20386_amd import build as hip_build
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+HEADER = os.path.join(ROOT, "include", "ptq4vm.h")
+
+
+@pytest.fixture(scope="module")
+def lib():
+    if not os.path.exists(ptq.binding.LIB_PATH):
+        hip_build.build()
+    return ptq.binding.load()
+
+
+def _declared_functions():
+    text = open(HEADER).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"\b(ptq4vm_[a-z0-9_]+)\s*\(", text)))
+
+
+def test_header_declares_the_named_entry_points():
+    names = _declared_functions()
+    for required in ("ptq4vm_quantize_pts", "ptq4vm_w8a8_linear", "ptq4vm_fold_smoothing"):
+        assert required in names
+
+
+def test_library_exports_every_declared_symbol(lib):
+    names = _declared_functions()
+    assert set(names) == set(ptq.binding.EXPORTS)
+    for name in names:
+        assert getattr(lib, name) is not None
+
+
+def test_version_and_status_strings(lib):
+    assert lib.ptq4vm_version() >= 100
+    assert ptq.binding.status_string(0) == "ok"
+    for code in (-1, -2, -3, -4, -5):
+        assert ptq.binding.status_string(code) not in ("ok", "unknown status")
+    assert ptq.binding.status_string(-99) == "unknown status"
+
+
+P = ctypes.c_void_p(0x1000)   # never dereferenced: every check below fails before a launch
+ODD = ctypes.c_void_p(0x1002)
+NULL = None
+
+
+def test_quantize_pts_argument_checks(lib):
+    f = lib.ptq4vm_quantize_pts
+    assert f(NULL, P, P, P, 1, 1, 8, 8, 8, None) == -1
+    assert f(P, P, NULL, P, 1, 1, 8, 8, 8, None) == -1
+    assert f(P, P, P, NULL, 1, 1, 8, 8, 8, None) == -1
+    assert f(P, P, P, P, -1, 1, 8, 8, 8, None) == -2
+    assert f(P, P, P, P, 1, 0, 8, 8, 8, None) == -2
+    assert f(P, P, P, P, 1, 1, 0, 8, 8, None) == -2
+    assert f(P, P, P, P, 1, 1, 8, 7, 8, None) == -3
+    assert f(P, P, P, P, 1, 1, 8, 8, 7, None) == -3
+    assert f(ODD, P, P, P, 1, 1, 8, 8, 8, None) == -4
+    assert f(P, P, P, ODD, 1, 1, 8, 8, 8, None) == -4
+    assert f(P, NULL, P, P, 0, 197, 8, 8, 8, None) == 0      # empty batch: nothing to do
+
+
+def test_w8a8_linear_argument_checks(lib):
+    f = lib.ptq4vm_w8a8_linear
+    ok = [P, P, P, P, P, P, NULL, 1, 1, 16, 16, 16, 16, 16, None]
+
+    def call(**kw):
+        a = list(ok)
+        for i, v in kw.items():
+            a[int(i[1:])] = v
+        return f(*a)
+
+    assert call(a0=NULL) == -1 and call(a1=NULL) == -1 and call(a2=NULL) == -1
+    assert call(a3=NULL) == -1 and call(a5=NULL) == -1
+    assert call(a7=-1) == -2 and call(a8=0) == -2 and call(a9=0) == -2 and call(a10=-1) == -2
+    assert call(a9=133144, a11=133144, a12=133144) == -2     # int32 accumulator could overflow
+    assert call(a11=15) == -3 and call(a12=15) == -3 and call(a13=15) == -3
+    assert call(a0=ODD) == -4 and call(a1=ODD) == -4
+    assert call(a5=ctypes.c_void_p(0x1001)) == -4
+    assert call(a7=0) == 0 and call(a10=0, a13=0) == 0       # empty problem
+
+
+def test_fold_and_f16_argument_checks(lib):
+    f = lib.ptq4vm_fold_smoothing
+    assert f(NULL, P, P, P, P, 1, 8, 8, 8, None) == -1
+    assert f(P, P, P, P, NULL, 1, 8, 8, 8, None) == -1
+    assert f(P, P, P, P, P, -1, 8, 8, 8, None) == -2
+    assert f(P, P, P, P, P, 1, 0, 8, 8, None) == -2
+    assert f(P, P, P, P, P, 1, 8, 7, 8, None) == -3
+    assert f(ODD, P, P, P, P, 1, 8, 8, 8, None) == -4
+    g = lib.ptq4vm_f16_linear
+    assert g(NULL, P, P, P, 1, 8, 8, 8, 8, 8, None) == -1
+    assert g(P, P, NULL, NULL, 1, 8, 8, 8, 8, 8, None) == -1
+    assert g(P, P, P, P, 1, 0, 8, 8, 8, 8, None) == -2
+    assert g(P, P, P, P, 1, 8, 8, 7, 8, 8, None) == -3
+    assert g(P, P, P, P, 1, 8, 8, 8, 8, 7, None) == -3
+    assert g(P, ODD, P, P, 1, 8, 8, 8, 8, 8, None) == -4
+    assert g(P, P, P, P, 0, 8, 8, 8, 8, 8, None) == 0
+
+
+def test_binding_refuses_cpu_tensors():
+    import torch
+
+    x = torch.zeros((4, 8), dtype=torch.float16)
+    with pytest.raises(TypeError):
+        ptq.quantize_pts(x, None, torch.ones(4), 1, 4)

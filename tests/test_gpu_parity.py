@@ -37,6 +37,8 @@ QUANT_SHAPES = [  # B, L, K
     (257, 1, 48),     # L = 1: per-tensor static
     (2, 785, 24),
     (1, 1, 1536),
+    (1, 20000, 16),   # token table too long for LDS: per-row division path
+    (2, 3, 776),      # 97 chunks per row: grid rounded to a multiple of 97
 ]
 
 
