@@ -36,11 +36,17 @@ typedef int v16i __attribute__((ext_vector_type(16)));
 typedef float v16f __attribute__((ext_vector_type(16)));
 typedef _Float16 v8h __attribute__((ext_vector_type(8)));
 typedef unsigned int u32x2 __attribute__((ext_vector_type(2)));
+typedef float v4f __attribute__((ext_vector_type(4)));
+typedef float v2f __attribute__((ext_vector_type(2)));
 
 constexpr int kThreads = 256;
 constexpr int kWaves = 4;
 constexpr int kSlabBytes = 64;  // K bytes per LDS stage per row: two MFMA k-steps of 32 bytes
 constexpr int kXcds = 8;
+#ifndef PTQ4VM_PERSISTENT_SLAB
+#define PTQ4VM_PERSISTENT_SLAB 128   // K bytes per LDS row of the persistent kernel
+#define PTQ4VM_PERSISTENT_STAGES 2   // ring depth (stages of 512 rows x SLAB bytes)
+#endif
 
 struct Int8Path {
     static constexpr int kElemBytes = 1;
@@ -314,6 +320,346 @@ __global__ __launch_bounds__(kThreads, 2) void linear_mfma_dma(const LinearArgs 
 }
 
 // ------------------------------------------------------------------------------------------
+// Large-problem path: persistent workgroups, one per CU, 8 wavefronts on a 256 x 256 tile
+// (wave tile 128 token rows x 64 channels), LDS ring fed by direct global -> LDS copies.
+// Compared with linear_mfma_dma:
+//   * the 256 x 256 tile halves the L2 -> LDS traffic per MAC (the 256 x 128 tile needs more
+//     L2 bandwidth than the chip has once the MFMA pipes are kept busy); with SLAB = 128 every
+//     copied row segment is a whole 128-byte cache line (measured: 64-byte segments cap the
+//     L2 -> LDS path at ~16 TB/s, 128-byte ones reach 22 TB/s and more);
+//   * the slab pipeline never drains: a workgroup walks its tiles in a loop and the copies for
+//     the next tile's first slabs are issued during the current tile's last slabs and epilogue;
+//   * MFMA fragments are double buffered in registers: the LDS reads of k-step n+1 are issued
+//     before the MFMAs of k-step n, so LDS latency hides behind the matrix pipe even though all
+//     wavefronts of the workgroup run in lock step;
+//   * per-tile scale vectors (s_w, bias, s_tok[r mod L]) are copied into LDS by the same
+//     asynchronous path at the start of a tile (double buffered), so the epilogue issues no
+//     register loads and never forces the in-flight slabs to land early;
+//   * the epilogue stages fp16 results in the ring stage that was consumed last (free until
+//     the next refill), index arithmetic is 32-bit and tile-relative, full tiles take a
+//     branch-free path.
+// Ring discipline: barrier B(g) sits before the MFMAs of the LAST k-step of slab g-1, after the
+// fragments of that k-step have arrived in registers.  Passing it means (a) every wavefront's
+// copies of slab g have landed (each waited on its own vmcnt first) and (b) nobody will read slab
+// g-1's stage again, so that stage is refilled at once with slab g-1+STAGES (after a tile's last
+// slab the refill waits until the epilogue, which borrows the stage, has finished).
+// Requirements (host-checked): as linear_mfma_dma, plus k_bytes % SLAB == 0, k_bytes >= 2 SLAB,
+// N % 8 == 0, 16-byte aligned y pitch, 4-byte aligned bias, 256 * ldy * 2 < 2^31, L < 2^31.
+// ------------------------------------------------------------------------------------------
+// LDS accesses of the epilogue are written as inline asm: the compiler does not see them, so it
+// cannot tie them to the outstanding global -> LDS copies (for which it would insert a full
+// vmcnt(0) drain).  Every read block ends with its own s_waitcnt inside the same asm statement,
+// so the outputs are valid as soon as the compiler may touch them.  Outputs are float vectors:
+// this compiler reads every element of an integer-vector asm output from its first register.
+__device__ __forceinline__ uint32_t lds_addr(const void *p) { return (uint32_t)(uintptr_t)p; }
+
+// eight 16-byte reads at base + STEP n (n = 0..3) and base + JUMP + STEP n
+template <int STEP, int JUMP>
+__device__ __forceinline__ void lds_read_8x_b128(uint32_t base, v4f (&v)[8]) {
+    asm volatile(
+        "ds_read_b128 %0, %8 offset:%9\n ds_read_b128 %1, %8 offset:%10\n ds_read_b128 %2, %8 offset:%11\n"
+        "ds_read_b128 %3, %8 offset:%12\n ds_read_b128 %4, %8 offset:%13\n ds_read_b128 %5, %8 offset:%14\n"
+        "ds_read_b128 %6, %8 offset:%15\n ds_read_b128 %7, %8 offset:%16\n s_waitcnt lgkmcnt(0)"
+        : "=&v"(v[0]), "=&v"(v[1]), "=&v"(v[2]), "=&v"(v[3]), "=&v"(v[4]), "=&v"(v[5]), "=&v"(v[6]), "=&v"(v[7])
+        : "v"(base), "n"(0), "n"(STEP), "n"(2 * STEP), "n"(3 * STEP), "n"(JUMP), "n"(JUMP + STEP), "n"(JUMP + 2 * STEP),
+          "n"(JUMP + 3 * STEP)
+        : "memory");
+}
+// four 4-byte reads at base + 128 n
+__device__ __forceinline__ void lds_read_4x_b32(uint32_t base, float (&v)[4]) {
+    asm volatile(
+        "ds_read_b32 %0, %4\n ds_read_b32 %1, %4 offset:128\n ds_read_b32 %2, %4 offset:256\n"
+        "ds_read_b32 %3, %4 offset:384\n s_waitcnt lgkmcnt(0)"
+        : "=&v"(v[0]), "=&v"(v[1]), "=&v"(v[2]), "=&v"(v[3])
+        : "v"(base)
+        : "memory");
+}
+// four 16-byte reads at arbitrary addresses
+__device__ __forceinline__ void lds_read_4_b128(const uint32_t (&addr)[4], v4f (&v)[4]) {
+    asm volatile(
+        "ds_read_b128 %0, %4\n ds_read_b128 %1, %5\n ds_read_b128 %2, %6\n ds_read_b128 %3, %7\n"
+        "s_waitcnt lgkmcnt(0)"
+        : "=&v"(v[0]), "=&v"(v[1]), "=&v"(v[2]), "=&v"(v[3])
+        : "v"(addr[0]), "v"(addr[1]), "v"(addr[2]), "v"(addr[3])
+        : "memory");
+}
+__device__ __forceinline__ void lds_write_b64(uint32_t addr, u32x2 v) {
+    asm volatile("ds_write_b64 %0, %1" ::"v"(addr), "v"(v) : "memory");
+}
+
+template <int KEEP>
+__device__ __forceinline__ void wait_vmcnt_at_most() {
+    // s_waitcnt immediate on gfx9: vmcnt[3:0] | expcnt[6:4] | lgkmcnt[11:8] | vmcnt[5:4] << 14
+    static_assert(KEEP >= 0 && KEEP <= 63, "vmcnt is a 6-bit counter");
+    __builtin_amdgcn_s_waitcnt(0x0F70 | (KEEP & 15) | ((KEEP >> 4) << 14));
+}
+
+template <class Path, int SLAB, int STAGES, bool HAS_BIAS, bool DUMP_ACC>
+__global__ __launch_bounds__(512, 1) void linear_mfma_persistent(const LinearArgs p) {
+    constexpr int BR = 256, BO = 256, WO = 4, NW = 8;
+    constexpr int WAVE_R = 128, WAVE_O = 64, FR = 4, FO = 2;
+    constexpr int KS = SLAB / 32;             // MFMA k-steps per slab
+    constexpr int CHUNKS = SLAB / 16;         // 16-byte chunks per LDS row
+    constexpr int ROWS_PER_COPY = 64 / CHUNKS;  // rows in one wavefront-wide 1 KiB copy
+    constexpr int X_COPIES = BR / ROWS_PER_COPY / NW, W_COPIES = BO / ROWS_PER_COPY / NW;
+    constexpr int LOADS_PER_SLAB = X_COPIES + W_COPIES;
+    constexpr int STAGE_BYTES = (BR + BO) * SLAB;
+    constexpr int KEEP = (STAGES - 2) * LOADS_PER_SLAB;  // copies allowed in flight when a slab is needed
+    static_assert(SLAB == 64 || SLAB == 128, "LDS rows hold 64 or 128 bytes of K");
+    static_assert(NW * 32 * WAVE_O * 2 <= STAGE_BYTES, "epilogue patches must fit one stage");
+    constexpr bool kInt8 = Path::kElemBytes == 1;
+    using Acc = typename Path::Acc;
+
+    char *const ring = lds_dyn;
+    // per-tile scale vectors, double buffered by tile parity
+    constexpr int SCALE_BYTES = BO * 4 + BR * 4 + BO * 2;
+    char *const scales = lds_dyn + STAGES * STAGE_BYTES;
+
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int wave_r = (wave / WO) * WAVE_R, wave_o = (wave % WO) * WAVE_O;
+    const int l32 = lane & 31, lhalf = lane >> 5;
+    auto lds_chunk = [&](int row, int chunk) {  // byte offset of a 16-byte chunk inside a stage half
+        return row * SLAB + ((chunk ^ (SLAB == 64 ? swizzle(row) : (row & 7))) << 4);
+    };
+
+    // Tiles of this workgroup: XCD x owns a contiguous range, its workgroups interleave in it.
+    const int total_tiles = p.tiles_o * p.tiles_r;
+    const int per_xcd = (total_tiles + kXcds - 1) / kXcds;
+    const int wgs_per_xcd = (int)gridDim.x / kXcds;
+    const int first = (int)(blockIdx.x % kXcds) * per_xcd + (int)(blockIdx.x / kXcds);
+    const int last = min(((int)(blockIdx.x % kXcds) + 1) * per_xcd, total_tiles);
+    const int n_my = first < last ? (last - first + wgs_per_xcd - 1) / wgs_per_xcd : 0;
+    const int n_slabs = (int)(p.k_bytes / SLAB);
+    const int total_slabs = n_my * n_slabs;
+    if (total_slabs == 0) return;
+
+    // ---- producer: the next slab to copy, possibly of a later tile than the one being computed
+    int pf_tile = first, pf_slab = 0, pf_stage = 0, issued = 0;
+    const char *pf_x = nullptr, *pf_w = nullptr;
+    uint32_t x_off[X_COPIES], w_off[W_COPIES];
+    auto pf_setup = [&]() {
+        const int to = pf_tile % p.tiles_o, tr = pf_tile / p.tiles_o;
+        const int64_t r0 = (int64_t)tr * BR, o0 = (int64_t)to * BO;
+        pf_x = p.x + r0 * p.ldx_bytes;
+        pf_w = p.w + o0 * p.ldw_bytes;
+        const int rows_x = (int)min((int64_t)BR, p.M - r0), rows_w = (int)min((int64_t)BO, p.N - o0);
+#pragma unroll
+        for (int i = 0; i < X_COPIES; i++) {
+            const int row = (wave + NW * i) * ROWS_PER_COPY + lane / CHUNKS;
+            const int chunk = (lane % CHUNKS) ^ (SLAB == 64 ? swizzle(row) : (row & 7));
+            x_off[i] = (uint32_t)min(row, rows_x - 1) * (uint32_t)p.ldx_bytes + chunk * 16;
+        }
+#pragma unroll
+        for (int i = 0; i < W_COPIES; i++) {
+            const int row = (wave + NW * i) * ROWS_PER_COPY + lane / CHUNKS;
+            const int chunk = (lane % CHUNKS) ^ (SLAB == 64 ? swizzle(row) : (row & 7));
+            w_off[i] = (uint32_t)min(row, rows_w - 1) * (uint32_t)p.ldw_bytes + chunk * 16;
+        }
+    };
+    auto issue = [&]() {  // copy the producer's slab into ring stage pf_stage, then advance
+        char *sx = ring + pf_stage * STAGE_BYTES;
+        char *sw = sx + BR * SLAB;
+        const char *gx = pf_x + (int64_t)pf_slab * SLAB;
+        const char *gw = pf_w + (int64_t)pf_slab * SLAB;
+#pragma unroll
+        for (int i = 0; i < X_COPIES; i++)
+            __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void *)(gx + x_off[i]),
+                                             (__attribute__((address_space(3))) void *)(sx + (wave + NW * i) * 1024),
+                                             16, 0, 0);
+#pragma unroll
+        for (int i = 0; i < W_COPIES; i++)
+            __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void *)(gw + w_off[i]),
+                                             (__attribute__((address_space(3))) void *)(sw + (wave + NW * i) * 1024),
+                                             16, 0, 0);
+        issued++;
+        if (++pf_stage == STAGES) pf_stage = 0;
+        if (++pf_slab == n_slabs) {
+            pf_slab = 0;
+            pf_tile += wgs_per_xcd;
+            if (pf_tile < last) pf_setup();
+        }
+    };
+    // Slab g has landed for this wavefront once at most `younger` of its copies are outstanding.
+    auto wait_slab = [&](int g) {
+        if (g + STAGES - 2 < total_slabs)
+            wait_vmcnt_at_most<KEEP>();
+        else
+            wait_vmcnt_at_most<0>();
+    };
+
+    pf_setup();
+    while (issued < STAGES - 1 && issued < total_slabs) issue();
+    wait_slab(0);
+    __builtin_amdgcn_s_barrier();  // B(0)
+    if (issued < total_slabs) issue();
+
+    int stage = 0, g = 0, parity = 0;  // consumer: ring stage, running slab number, scale buffer
+    for (int tile = first; tile < last; tile += wgs_per_xcd, parity ^= 1) {
+        const int tile_o = tile % p.tiles_o, tile_r = tile / p.tiles_o;
+        const int64_t r0 = (int64_t)tile_r * BR, o0 = (int64_t)tile_o * BO;
+        const int rows_valid = (int)min((int64_t)BR, p.M - r0), cols_valid = (int)min((int64_t)BO, p.N - o0);
+        float *const cs_lds = reinterpret_cast<float *>(scales + parity * SCALE_BYTES);  // s_w of the tile's channels
+        float *const rs_lds = cs_lds + BO;                                              // s_tok of the tile's rows
+        uint32_t *const cb_lds = reinterpret_cast<uint32_t *>(rs_lds + BR);             // bias, two fp16 per word
+
+        // Scale vectors of this tile, one 4-byte element per lane, straight into LDS.  Indices
+        // beyond the matrix are clamped; those rows / channels are never stored.
+        if (kInt8 && wave < 4) {
+            const int c = min(wave * 64 + lane, cols_valid - 1);
+            __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void *)(p.s_w + o0 + c),
+                                             (__attribute__((address_space(3))) void *)(cs_lds + wave * 64), 4, 0, 0);
+        }
+        if (kInt8 && wave >= 4) {
+            const int r = min((wave - 4) * 64 + lane, rows_valid - 1);
+            const uint32_t t = ((uint32_t)(r0 % p.L) + (uint32_t)r) % (uint32_t)p.L;
+            __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void *)(p.s_tok + t),
+                                             (__attribute__((address_space(3))) void *)(rs_lds + (wave - 4) * 64), 4, 0, 0);
+        }
+        if (HAS_BIAS && wave >= 2 && wave < 4) {
+            const int c2 = min((wave - 2) * 64 + lane, cols_valid / 2 - 1);
+            __builtin_amdgcn_global_load_lds(
+                (const __attribute__((address_space(1))) void *)(reinterpret_cast<const uint32_t *>(p.bias + o0) + c2),
+                (__attribute__((address_space(3))) void *)(cb_lds + (wave - 2) * 64), 4, 0, 0);
+        }
+        int loads_after_scales = 0;
+
+        Acc acc[FO][FR];
+#pragma unroll
+        for (int i = 0; i < FO; i++)
+#pragma unroll
+            for (int j = 0; j < FR; j++)
+#pragma unroll
+                for (int v = 0; v < 16; v++) acc[i][j][v] = 0;
+
+        v4i fw[2][FO], fx[2][FR];
+        auto load_frags = [&](int buf, int stg, int ks) {
+            const char *sx = ring + stg * STAGE_BYTES + wave_r * SLAB;
+            const char *sw = ring + stg * STAGE_BYTES + (BR + wave_o) * SLAB;
+            const int chunk = 2 * ks + lhalf;
+#pragma unroll
+            for (int i = 0; i < FO; i++) fw[buf][i] = *reinterpret_cast<const v4i *>(sw + lds_chunk(i * 32 + l32, chunk));
+#pragma unroll
+            for (int j = 0; j < FR; j++) fx[buf][j] = *reinterpret_cast<const v4i *>(sx + lds_chunk(j * 32 + l32, chunk));
+        };
+        auto mfma_step = [&](int buf) {
+#pragma unroll
+            for (int i = 0; i < FO; i++)
+#pragma unroll
+                for (int j = 0; j < FR; j++) acc[i][j] = Path::mfma(fw[buf][i], fx[buf][j], acc[i][j]);
+        };
+
+        load_frags(0, stage, 0);  // B(g) for the tile's first slab was passed during the previous tile
+        for (int s = 0; s < n_slabs; s++, g++) {
+            int next_stage = stage + 1;
+            if (next_stage == STAGES) next_stage = 0;
+#pragma unroll
+            for (int ks = 0; ks < KS; ks++) {
+                const int cur = ks & 1;
+                if (ks + 1 < KS) {
+                    load_frags(cur ^ 1, stage, ks + 1);
+                } else if (g + 1 < total_slabs) {
+                    // B(g+1): this wavefront holds the last fragments of slab g in registers and its
+                    // copies of slab g+1 have landed.
+                    asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
+                    wait_slab(g + 1);
+                    __builtin_amdgcn_s_barrier();
+                    if (s + 1 < n_slabs) {
+                        if (issued < total_slabs) {
+                            issue();  // refills the stage of slab g
+                            loads_after_scales += LOADS_PER_SLAB;
+                        }
+                        load_frags(cur ^ 1, next_stage, 0);
+                    }  // after the tile's last slab that stage first serves the epilogue
+                }
+                mfma_step(cur);
+            }
+            stage = next_stage;
+        }
+
+        // ---- epilogue of this tile.  The ring stage of the tile's last slab is free: B(g) was passed
+        // with that slab's fragments in registers and its refill has been held back; it holds the
+        // wavefronts' fp16 patches until the barrier that ends the epilogue.
+        if (loads_after_scales >= KEEP && KEEP > 0)
+            wait_vmcnt_at_most<KEEP>();
+        else
+            wait_vmcnt_at_most<0>();
+        __builtin_amdgcn_s_barrier();  // scale vectors are visible to every wavefront
+        const int free_stage = stage == 0 ? STAGES - 1 : stage - 1;  // stage of the tile's last slab
+        char *patch = ring + free_stage * STAGE_BYTES + wave * (32 * WAVE_O * 2);
+        char *y_tile = reinterpret_cast<char *>(p.y + r0 * p.ldy + o0);
+        const uint32_t ldy_bytes = (uint32_t)p.ldy * 2;
+        auto patch_chunk = [&](int row, int chunk) { return row * (WAVE_O * 2) + ((chunk ^ (row & 7)) << 4); };
+        const bool full_tile = rows_valid == BR && cols_valid == BO;
+
+        // column scales / biases of this lane's 32 channels (index i * 4 + gq), row scales of its 4 rows
+        v4f cs_raw[8];
+        v4f cb_raw[8];  // eight fp16 biases of channels 8 gq .. 8 gq + 7; this lane needs half of them
+        float rs_raw[4];
+        if constexpr (kInt8) lds_read_8x_b128<32, 128>(lds_addr(cs_lds + wave_o + lhalf * 4), cs_raw);
+        if constexpr (HAS_BIAS) lds_read_8x_b128<16, 64>(lds_addr(cb_lds + wave_o / 2), cb_raw);
+        if constexpr (kInt8) lds_read_4x_b32(lds_addr(rs_lds + wave_r + l32), rs_raw);
+
+#pragma unroll
+        for (int j = 0; j < FR; j++) {
+#pragma unroll
+            for (int i = 0; i < FO; i++) {
+#pragma unroll
+                for (int gq = 0; gq < 4; gq++) {
+                    float bias4[4] = {0.0f, 0.0f, 0.0f, 0.0f};
+                    if constexpr (HAS_BIAS) {
+                        const v4f b8 = cb_raw[i * 4 + gq];
+                        const __half2 b01 = __builtin_bit_cast(__half2, lhalf ? b8.z : b8.x);
+                        const __half2 b23 = __builtin_bit_cast(__half2, lhalf ? b8.w : b8.y);
+                        bias4[0] = __low2float(b01), bias4[1] = __high2float(b01);
+                        bias4[2] = __low2float(b23), bias4[3] = __high2float(b23);
+                    }
+                    float out[4];
+#pragma unroll
+                    for (int c = 0; c < 4; c++) {
+                        if constexpr (kInt8) {
+                            const int a = acc[i][j][gq * 4 + c];
+                            if constexpr (DUMP_ACC) {
+                                const int64_t r = r0 + wave_r + j * 32 + l32;
+                                const int64_t o = o0 + wave_o + i * 32 + gq * 8 + lhalf * 4 + c;
+                                if (r < p.M && o < p.N) p.acc_out[r * p.N + o] = a;
+                            }
+                            out[c] = (float)a * (rs_raw[j] * cs_raw[i * 4 + gq][c]) + bias4[c];
+                        } else {
+                            out[c] = acc[i][j][gq * 4 + c] + bias4[c];
+                        }
+                    }
+                    __half2 lo = __floats2half2_rn(out[0], out[1]);
+                    __half2 hi = __floats2half2_rn(out[2], out[3]);
+                    u32x2 packed = {__builtin_bit_cast(uint32_t, lo), __builtin_bit_cast(uint32_t, hi)};
+                    lds_write_b64(lds_addr(patch + patch_chunk(l32, i * 4 + gq) + lhalf * 8), packed);
+                }
+            }
+            v4f data[4];
+            uint32_t src[4];
+#pragma unroll
+            for (int q = 0; q < 4; q++)  // 8 rows x 128 bytes per store instruction
+                src[q] = lds_addr(patch + patch_chunk(q * 8 + (lane >> 3), lane & 7));
+            lds_read_4_b128(src, data);
+            const uint32_t base = (uint32_t)(wave_r + j * 32 + (lane >> 3)) * ldy_bytes + (uint32_t)(wave_o + (lane & 7) * 8) * 2;
+            if (full_tile) {
+#pragma unroll
+                for (int q = 0; q < 4; q++)
+                    __builtin_nontemporal_store(data[q], reinterpret_cast<v4f *>(y_tile + base + (uint32_t)(q * 8) * ldy_bytes));
+            } else {
+#pragma unroll
+                for (int q = 0; q < 4; q++) {
+                    const int rr = wave_r + j * 32 + q * 8 + (lane >> 3), cc = wave_o + (lane & 7) * 8;
+                    if (rr < rows_valid && cc < cols_valid)
+                        *reinterpret_cast<v4f *>(y_tile + base + (uint32_t)(q * 8) * ldy_bytes) = data[q];
+                }
+            }
+        }
+        __builtin_amdgcn_s_barrier();  // every wavefront has read its patch back: the stage can be refilled
+        if (issued < total_slabs) issue();
+    }
+}
+
+// ------------------------------------------------------------------------------------------
 // Generic path: register-staged loads, zero fill beyond M, N and K, any pitch.
 // ------------------------------------------------------------------------------------------
 __device__ __forceinline__ uint32_t keep_low_bytes(uint32_t v, int nbytes) {
@@ -468,6 +814,38 @@ int launch_dma(LinearArgs a, hipStream_t stream) {
     return ptq4vm::check_launch("linear_mfma_dma");
 }
 
+template <class Path, int SLAB, int STAGES>
+int launch_persistent(LinearArgs a, hipStream_t stream) {
+    dim3 grid;
+    if (!set_grid<256, 256>(a, grid)) return PTQ4VM_ERR_SHAPE;
+    // One workgroup per CU (the LDS footprint allows no more), a multiple of the XCD count.
+    int device = 0, cus = 0;
+    hipError_t err = hipGetDevice(&device);
+    if (err == hipSuccess) err = hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, device);
+    if (err != hipSuccess) return ptq4vm::record_hip_error(err, "hipDeviceGetAttribute(multiprocessor count)");
+    unsigned wgs = (unsigned)(cus / kXcds * kXcds);
+    if (wgs == 0) wgs = kXcds;
+    if (wgs > grid.x) wgs = grid.x;  // grid.x is the tile count rounded up to a multiple of kXcds
+    constexpr int lds_bytes = STAGES * 512 * SLAB + 2 * (256 * 4 + 256 * 4 + 256 * 2);
+    using Kernel = void (*)(const LinearArgs);
+    // [has bias][also write the int32 accumulators]
+    static const Kernel kernels[2][2] = {
+        {linear_mfma_persistent<Path, SLAB, STAGES, false, false>, linear_mfma_persistent<Path, SLAB, STAGES, false, true>},
+        {linear_mfma_persistent<Path, SLAB, STAGES, true, false>, linear_mfma_persistent<Path, SLAB, STAGES, true, true>}};
+    static bool configured = false;  // raising the dynamic-LDS limit is a per-function, idempotent setting
+    if (!configured) {
+        for (int b = 0; b < 2; b++)
+            for (int d = 0; d < 2; d++) {
+                err = hipFuncSetAttribute(reinterpret_cast<const void *>(kernels[b][d]),
+                                          hipFuncAttributeMaxDynamicSharedMemorySize, lds_bytes);
+                if (err != hipSuccess) return ptq4vm::record_hip_error(err, "hipFuncSetAttribute(linear_mfma_persistent)");
+            }
+        configured = true;
+    }
+    kernels[a.bias ? 1 : 0][a.acc_out ? 1 : 0]<<<dim3(wgs), dim3(512), lds_bytes, stream>>>(a);
+    return ptq4vm::check_launch("linear_mfma_persistent");
+}
+
 template <class Path, int BR, int BO, int WR, int WO>
 int launch_generic(LinearArgs a, int load_align, hipStream_t stream) {
     dim3 grid;
@@ -497,6 +875,11 @@ int dispatch(LinearArgs a, hipStream_t stream) {
               : ((a.ldy % 4 == 0 && ptq4vm::aligned_to(a.y, 8)) ? 4 : 1);
     const bool dma_ok = la == 16 && a.k_bytes % kSlabBytes == 0 && a.ldx_bytes * 256 < (1LL << 31) &&
                         a.ldw_bytes * 256 < (1LL << 31);
+    const bool persistent_ok = dma_ok && a.N % 8 == 0 && a.y_vec == 8 && ptq4vm::aligned_to(a.bias, 4) &&
+                               a.ldy * 512 < (1LL << 31) && a.L < (1LL << 31) && a.N >= 256 &&
+                               a.k_bytes % PTQ4VM_PERSISTENT_SLAB == 0 && a.k_bytes >= 2 * PTQ4VM_PERSISTENT_SLAB &&
+                               ptq4vm::ceil_div(a.M, 256) * ptq4vm::ceil_div(a.N, 256) >= 256;
+    if (persistent_ok) return launch_persistent<Path, PTQ4VM_PERSISTENT_SLAB, PTQ4VM_PERSISTENT_STAGES>(a, stream);
     if (a.N > 64) {
         if (dma_ok) return launch_dma<Path, 256, 128, 2, 2, 3>(a, stream);
         return launch_generic<Path, 256, 128, 2, 2>(a, la, stream);

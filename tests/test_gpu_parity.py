@@ -234,3 +234,60 @@ def test_f16_linear_within_accumulation_bound(M, K, N):
     # fp32 accumulation in any order: |err| <= (K+1) 2^-24 sum|terms|, then one fp16 rounding
     tol = (K + 2) * 2.0 ** -24 * asum + 2.0 ** -11 * np.abs(y64) + 2.0 ** -24
     assert np.all(np.abs(g - y64) <= tol)
+
+
+# ---------------------------------------------------------------------------------- full-size workloads
+def _sampled_rows(M, step, L):
+    rows = np.unique(np.concatenate([np.arange(0, M, step), [0, 1, L - 1, L, M - 1, M - 2], np.arange(M - 300, M, 7)]))
+    return rows[(rows >= 0) & (rows < M)]
+
+
+def _check_case_on_sampled_rows(c, rows, what):
+    """Whole problem on the GPU in the benchmark's launch configuration (no accumulator dump),
+    plus one launch with the dump; the oracle recomputes the sampled rows from the fp16 inputs."""
+    print(f"full-size {what}: M={c.B * c.L} K={c.K} N={c.N}, {len(rows)} sampled rows", flush=True)
+    M = c.B * c.L
+    wq, s_w, inv_m = ptq.fold_smoothing(c.w, c.m)
+    xq = ptq.quantize_pts(c.x, inv_m, c.s_tok, c.B, c.L)
+    y = ptq.w8a8_linear(xq, wq, c.s_tok, s_w, c.bias, c.B, c.L)
+    acc = torch.empty((M, c.N), dtype=torch.int32, device=DEV)
+    y_dump = ptq.w8a8_linear(xq, wq, c.s_tok, s_w, c.bias, c.B, c.L, acc_out=acc)
+    torch.cuda.synchronize()
+    assert torch.equal(y.view(torch.int16), y_dump.view(torch.int16))
+    ridx = torch.from_numpy(rows).to(DEV)
+    x_s, xq_s, y_s, acc_s = _np(c.x[ridx]), _np(xq[ridx]), _np(y[ridx]), _np(acc[ridx])
+
+    wq_o, s_w_o, inv_m_o = oracle.fold_smoothing(_np(c.w), _np(c.m))
+    assert np.array_equal(_np(wq), wq_o) and np.array_equal(_np(s_w), s_w_o)
+    st_rows = _np(c.s_tok)[rows % c.L]                      # token position of each sampled row
+    n = len(rows)
+    xq_o = oracle.quantize_pts(x_s, inv_m_o, st_rows, 1, n)  # B=1, L=n: one step per sampled row
+    assert np.array_equal(xq_s, xq_o), "int8 codes differ"
+    b_o = _np(c.bias)
+    y_o, y64, acc_o = oracle.w8a8_linear(xq_o, wq_o, st_rows, s_w_o, b_o, 1, n)
+    assert np.array_equal(acc_s, acc_o), "int32 accumulators differ"
+    prod_abs = np.abs(acc_o.astype(np.float64) * st_rows.astype(np.float64)[:, None] * s_w_o.astype(np.float64)[None, :])
+    bias_abs = np.broadcast_to(np.abs(b_o.astype(np.float64))[None, :], prod_abs.shape)
+    return check_dequantized_output(y_s, y_o, y64, prod_abs, bias_abs, what)
+
+
+@pytest.mark.parametrize("linear", [0, 1, 2, 3])
+def test_vim_b_full_size_sampled(linear):
+    """BASELINE configs[3]: M = 256 * 197 rows, the launch configuration bench.py times."""
+    c = synth.make_linear_case(3, 0, linear, device=DEV)
+    assert c.clipped > 0
+    _check_case_on_sampled_rows(c, _sampled_rows(c.B * c.L, 97, c.L), f"vim_b {c.name}")
+
+
+@pytest.mark.parametrize("cfg,linear", [(1, 0), (1, 1), (1, 2), (1, 3), (2, 0), (2, 3), (4, 0), (4, 1), (4, 2), (4, 3)])
+def test_other_configs_sampled(cfg, linear):
+    c = synth.make_linear_case(cfg, 0, linear, device=DEV)
+    assert c.clipped > 0
+    _check_case_on_sampled_rows(c, _sampled_rows(c.B * c.L, 53, c.L), f"cfg{cfg} {c.name}")
+
+
+@pytest.mark.parametrize("B,L,K,N", [(41, 251, 192, 1544), (33, 300, 64, 2056), (20, 517, 128, 6400)])
+def test_large_ragged_shapes_sampled(B, L, K, N):
+    """Enough 256 x 256 tiles for the persistent kernel, with ragged last tiles in both directions."""
+    c = synth.random_problem(4242 + N, B, L, K, N, device=DEV)
+    _check_case_on_sampled_rows(c, _sampled_rows(B * L, 61, L), "ragged")
