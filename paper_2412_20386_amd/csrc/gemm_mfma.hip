@@ -660,6 +660,162 @@ __global__ __launch_bounds__(512, 1) void linear_mfma_persistent(const LinearArg
 }
 
 // ------------------------------------------------------------------------------------------
+// Small-K path (K bytes <= 128, e.g. dt_proj with K = dt_rank): the whole reduction is 1-4 MFMA
+// k-steps, so the kernel is a stream of output rows bound by the fp16 stores.  A wavefront owns
+// 64 output channels for its whole life and keeps their weight fragments, scales and biases in
+// registers; it walks over 32-row blocks, fetching the activation fragments straight from
+// global memory (no LDS staging of operands), and transposes results through a private LDS
+// patch so that every store instruction writes eight whole 128-byte row segments.
+// LOAD_ALIGN 16: pitches and bases are multiples of 16 bytes; 4: multiples of 4 bytes.
+// ------------------------------------------------------------------------------------------
+template <int LOAD_ALIGN>
+__device__ __forceinline__ v4i load_fragment_chunk(const char *row_ptr, int kb, int k_bytes) {
+    v4i out = {0, 0, 0, 0};
+    if (kb >= k_bytes) return out;
+    const int valid = min(16, k_bytes - kb);
+    if constexpr (LOAD_ALIGN == 16) {
+        out = *reinterpret_cast<const v4i *>(row_ptr + kb);
+    } else {
+#pragma unroll
+        for (int j = 0; j < 4; j++)
+            if (4 * j < valid) out[j] = *reinterpret_cast<const int *>(row_ptr + kb + 4 * j);
+    }
+    if (valid < 16) {
+#pragma unroll
+        for (int j = 0; j < 4; j++) {
+            const int nb = valid - 4 * j;
+            out[j] = nb >= 4 ? out[j] : (nb <= 0 ? 0 : (out[j] & ((1 << (8 * nb)) - 1)));
+        }
+    }
+    return out;
+}
+
+template <class Path, int KSTEPS, int LOAD_ALIGN, bool HAS_BIAS, bool DUMP_ACC>
+__global__ __launch_bounds__(kThreads) void linear_mfma_smallk(const LinearArgs p) {
+    constexpr bool kInt8 = Path::kElemBytes == 1;
+    using Acc = typename Path::Acc;
+    __shared__ __attribute__((aligned(16))) char patches[kWaves][32 * 64 * 2];
+
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int l32 = lane & 31, lhalf = lane >> 5;
+    const int k_bytes = (int)p.k_bytes;
+    const int64_t o_base = ((int64_t)blockIdx.y * kWaves + wave) * 64;
+    if (o_base >= p.N) return;  // whole wavefront out of range; no barriers are used below
+    const int cols_valid = (int)min((int64_t)64, p.N - o_base);
+
+    // weight fragments of the strip's 64 channels: block i covers channels 32 i .. 32 i + 31
+    v4i fw[2][KSTEPS];
+#pragma unroll
+    for (int i = 0; i < 2; i++) {
+        const int row = min(i * 32 + l32, cols_valid - 1);  // clamped rows are never stored
+        const char *wrow = p.w + (o_base + row) * p.ldw_bytes;
+#pragma unroll
+        for (int ks = 0; ks < KSTEPS; ks++) fw[i][ks] = load_fragment_chunk<LOAD_ALIGN>(wrow, (2 * ks + lhalf) * 16, k_bytes);
+    }
+    // scales and biases of this lane's channels: o_base + 32 i + 8 g + 4 lhalf + c
+    float cs[2][4][4], cb[2][4][4];
+#pragma unroll
+    for (int i = 0; i < 2; i++)
+#pragma unroll
+        for (int g = 0; g < 4; g++)
+#pragma unroll
+            for (int c = 0; c < 4; c++) {
+                const int col = min(i * 32 + g * 8 + lhalf * 4 + c, cols_valid - 1);
+                cs[i][g][c] = 1.0f;
+                if constexpr (kInt8) cs[i][g][c] = p.s_w[o_base + col];
+                cb[i][g][c] = 0.0f;
+                if constexpr (HAS_BIAS) cb[i][g][c] = __half2float(p.bias[o_base + col]);
+            }
+
+    const int64_t n_blocks = (p.M + 31) / 32;
+    int64_t rb = blockIdx.x;
+    uint32_t t = 0, t_step = 0;
+    if constexpr (kInt8) {
+        t = (uint32_t)((rb * 32 + l32) % p.L);
+        t_step = (uint32_t)(((int64_t)gridDim.x * 32) % p.L);
+    }
+    auto load_x = [&](int64_t block, v4i (&fx)[KSTEPS]) {
+        const int64_t row = min(block * 32 + l32, p.M - 1);
+        const char *xrow = p.x + row * p.ldx_bytes;
+#pragma unroll
+        for (int ks = 0; ks < KSTEPS; ks++) fx[ks] = load_fragment_chunk<LOAD_ALIGN>(xrow, (2 * ks + lhalf) * 16, k_bytes);
+    };
+    char *patch = patches[wave];
+    auto patch_chunk = [&](int row, int chunk) { return row * 128 + ((chunk ^ (row & 7)) << 4); };
+    const bool y_fast = p.y_vec == 8 && cols_valid == 64;
+
+    v4i fx[KSTEPS], fx_next[KSTEPS];
+    if (rb < n_blocks) load_x(rb, fx);
+    for (; rb < n_blocks; rb += gridDim.x) {
+        const int64_t nb = rb + gridDim.x;
+        if (nb < n_blocks) load_x(nb, fx_next);  // in flight while this block is computed and stored
+        Acc acc[2];
+#pragma unroll
+        for (int i = 0; i < 2; i++) {
+#pragma unroll
+            for (int v = 0; v < 16; v++) acc[i][v] = 0;
+#pragma unroll
+            for (int ks = 0; ks < KSTEPS; ks++) acc[i] = Path::mfma(fw[i][ks], fx[ks], acc[i]);
+        }
+        float rs = 1.0f;
+        if constexpr (kInt8) {
+            rs = p.s_tok[t];
+            t += t_step;
+            if (t >= (uint32_t)p.L) t -= (uint32_t)p.L;
+        }
+        const int64_t r = rb * 32 + l32;
+#pragma unroll
+        for (int i = 0; i < 2; i++)
+#pragma unroll
+            for (int g = 0; g < 4; g++) {
+                float out[4];
+#pragma unroll
+                for (int c = 0; c < 4; c++) {
+                    if constexpr (kInt8) {
+                        const int a = acc[i][g * 4 + c];
+                        if constexpr (DUMP_ACC) {
+                            const int col = i * 32 + g * 8 + lhalf * 4 + c;
+                            if (r < p.M && col < cols_valid) p.acc_out[r * p.N + o_base + col] = a;
+                        }
+                        out[c] = (float)a * (rs * cs[i][g][c]) + cb[i][g][c];
+                    } else {
+                        out[c] = acc[i][g * 4 + c] + cb[i][g][c];
+                    }
+                }
+                __half2 lo = __floats2half2_rn(out[0], out[1]);
+                __half2 hi = __floats2half2_rn(out[2], out[3]);
+                u32x2 packed = {__builtin_bit_cast(uint32_t, lo), __builtin_bit_cast(uint32_t, hi)};
+                *reinterpret_cast<u32x2 *>(patch + patch_chunk(l32, i * 4 + g) + lhalf * 8) = packed;
+            }
+        asm volatile("" ::: "memory");  // wavefront-private patch: LDS runs a wavefront's accesses in order
+#pragma unroll
+        for (int q = 0; q < 4; q++) {
+            const int row = q * 8 + (lane >> 3), chunk = lane & 7;
+            const v4i data = *reinterpret_cast<const v4i *>(patch + patch_chunk(row, chunk));
+            const int64_t rr = rb * 32 + row;
+            if (rr < p.M) {
+                __half *dst = p.y + rr * p.ldy + o_base + chunk * 8;
+                if (y_fast) {
+                    __builtin_nontemporal_store(data, reinterpret_cast<v4i *>(dst));
+                } else if (p.y_vec >= 4 && chunk * 8 + 8 <= cols_valid) {
+                    u32x2 a = {(uint32_t)data[0], (uint32_t)data[1]}, b = {(uint32_t)data[2], (uint32_t)data[3]};
+                    *reinterpret_cast<u32x2 *>(dst) = a;
+                    *reinterpret_cast<u32x2 *>(dst + 4) = b;
+                } else {
+#pragma unroll
+                    for (int e = 0; e < 8; e++)
+                        if (chunk * 8 + e < cols_valid)
+                            reinterpret_cast<uint16_t *>(dst)[e] = (uint16_t)((uint32_t)data[e >> 1] >> (16 * (e & 1)));
+                }
+            }
+        }
+        asm volatile("" ::: "memory");
+#pragma unroll
+        for (int ks = 0; ks < KSTEPS; ks++) fx[ks] = fx_next[ks];
+    }
+}
+
+// ------------------------------------------------------------------------------------------
 // Generic path: register-staged loads, zero fill beyond M, N and K, any pitch.
 // ------------------------------------------------------------------------------------------
 __device__ __forceinline__ uint32_t keep_low_bytes(uint32_t v, int nbytes) {
@@ -846,6 +1002,36 @@ int launch_persistent(LinearArgs a, hipStream_t stream) {
     return ptq4vm::check_launch("linear_mfma_persistent");
 }
 
+template <class Path, int KSTEPS, int LOAD_ALIGN>
+int launch_smallk(const LinearArgs &a, hipStream_t stream) {
+    const int64_t strips = ptq4vm::ceil_div(a.N, 64 * kWaves), blocks = ptq4vm::ceil_div(a.M, 32);
+    if (strips > 65535) return PTQ4VM_ERR_SHAPE;
+    // about 8 workgroups per CU in total, each walking over row blocks
+    int64_t gx = ptq4vm::ceil_div(2048, strips);
+    if (gx > blocks) gx = blocks;
+    dim3 grid((unsigned)gx, (unsigned)strips), block(kThreads);
+    const bool bias = a.bias != nullptr, dump = a.acc_out != nullptr;
+    if (bias && dump)
+        linear_mfma_smallk<Path, KSTEPS, LOAD_ALIGN, true, true><<<grid, block, 0, stream>>>(a);
+    else if (bias)
+        linear_mfma_smallk<Path, KSTEPS, LOAD_ALIGN, true, false><<<grid, block, 0, stream>>>(a);
+    else if (dump)
+        linear_mfma_smallk<Path, KSTEPS, LOAD_ALIGN, false, true><<<grid, block, 0, stream>>>(a);
+    else
+        linear_mfma_smallk<Path, KSTEPS, LOAD_ALIGN, false, false><<<grid, block, 0, stream>>>(a);
+    return ptq4vm::check_launch("linear_mfma_smallk");
+}
+
+template <class Path, int LOAD_ALIGN>
+int launch_smallk_ksteps(const LinearArgs &a, hipStream_t stream) {
+    switch ((int)ptq4vm::ceil_div(a.k_bytes, 32)) {
+        case 1: return launch_smallk<Path, 1, LOAD_ALIGN>(a, stream);
+        case 2: return launch_smallk<Path, 2, LOAD_ALIGN>(a, stream);
+        case 3: return launch_smallk<Path, 3, LOAD_ALIGN>(a, stream);
+        default: return launch_smallk<Path, 4, LOAD_ALIGN>(a, stream);
+    }
+}
+
 template <class Path, int BR, int BO, int WR, int WO>
 int launch_generic(LinearArgs a, int load_align, hipStream_t stream) {
     dim3 grid;
@@ -875,12 +1061,15 @@ int dispatch(LinearArgs a, hipStream_t stream) {
               : ((a.ldy % 4 == 0 && ptq4vm::aligned_to(a.y, 8)) ? 4 : 1);
     const bool dma_ok = la == 16 && a.k_bytes % kSlabBytes == 0 && a.ldx_bytes * 256 < (1LL << 31) &&
                         a.ldw_bytes * 256 < (1LL << 31);
+    if (a.k_bytes <= 128 && la >= 4 && a.L < (1LL << 31))
+        return la == 16 ? launch_smallk_ksteps<Path, 16>(a, stream) : launch_smallk_ksteps<Path, 4>(a, stream);
     const bool persistent_ok = dma_ok && a.N % 8 == 0 && a.y_vec == 8 && ptq4vm::aligned_to(a.bias, 4) &&
                                a.ldy * 512 < (1LL << 31) && a.L < (1LL << 31) && a.N >= 256 &&
                                a.k_bytes % PTQ4VM_PERSISTENT_SLAB == 0 && a.k_bytes >= 2 * PTQ4VM_PERSISTENT_SLAB &&
                                ptq4vm::ceil_div(a.M, 256) * ptq4vm::ceil_div(a.N, 256) >= 256;
     if (persistent_ok) return launch_persistent<Path, PTQ4VM_PERSISTENT_SLAB, PTQ4VM_PERSISTENT_STAGES>(a, stream);
     if (a.N > 64) {
+        if (dma_ok && a.N <= 128) return launch_dma<Path, 128, 128, 2, 2, 4>(a, stream);  // skinny N: many small tiles
         if (dma_ok) return launch_dma<Path, 256, 128, 2, 2, 3>(a, stream);
         return launch_generic<Path, 256, 128, 2, 2>(a, la, stream);
     }
