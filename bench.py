@@ -29,9 +29,10 @@ PEAK_INT8_TOPS = 5000.0   # MI355X dense int8 MFMA, TOP/s
 PEAK_F16_TFLOPS = 2500.0  # dense fp16 MFMA
 PEAK_HBM_GBS = 8000.0     # HBM3E
 
-# HBM traffic of the dominant kernel from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE
-# (profiles/), bytes per launch; None until measured.
-DOMINANT_TRAFFIC_BYTES = None
+# HBM traffic of the dominant kernel (in_proj GEMM of configs[3]) per launch, bytes, from two
+# rocprofv3 --pmc runs (FETCH_SIZE, WRITE_SIZE), each scaled by the 256 MiB copy this script also
+# issues: 107.4 MB fetched + 311.7 MB written (profiles/bench_vim_b_stack_kernel_trace_and_traffic.txt).
+DOMINANT_TRAFFIC_BYTES = {3: 419.1e6}
 
 
 def main() -> int:
@@ -114,19 +115,20 @@ def main() -> int:
 
     # ------------------------------------------------------------------ per-kernel detail (untimed extras)
     def time_launch(fn, reps=3):
-        """Average device time of fn over all layers (distinct buffers), HIP events on the launch stream."""
-        tot, n = 0.0, 0
+        """Average device time of fn: one HIP-event pair (on the launch stream) around a back-to-back
+        sweep over all layers' distinct buffers, so that launch latency is hidden as in the stack."""
+        fn(layers[0])
+        tot = 0.0
         for _ in range(reps):
+            a = torch.cuda.Event(enable_timing=True)
+            b = torch.cuda.Event(enable_timing=True)
+            a.record()
             for lin in layers:
-                a = torch.cuda.Event(enable_timing=True)
-                b = torch.cuda.Event(enable_timing=True)
-                a.record()
                 fn(lin)
-                b.record()
-                b.synchronize()
-                tot += a.elapsed_time(b)
-                n += 1
-        return tot / n * 1e3  # us
+            b.record()
+            b.synchronize()
+            tot += a.elapsed_time(b)
+        return tot / (reps * len(layers)) * 1e3  # us
 
     kernels = []
     f16_total_us = w8_total_us = q_total_us = 0.0
@@ -160,6 +162,14 @@ def main() -> int:
     torch.cuda.synchronize()
     f16_ms_per_step = (time.perf_counter() - t0) / max(1, args.steps // 2) * 1e3
 
+    # One plain device-to-device copy of known size (untimed): the reference against which the
+    # rocprofv3 FETCH_SIZE / WRITE_SIZE counters of the GEMM are scaled in profiles/.
+    calib_src = torch.empty(256 << 20, dtype=torch.uint8, device=dev).fill_(1)
+    calib_dst = torch.empty_like(calib_src)
+    calib_dst.copy_(calib_src)
+    torch.cuda.synchronize()
+    del calib_src, calib_dst
+
     # ------------------------------------------------------------------ roofline of the dominant kernel
     _, dK, dN = dominant
     dom_ops = 2.0 * M * dK * dN                     # algorithmic int8 ops per launch
@@ -167,7 +177,8 @@ def main() -> int:
     roofline = dict(bound="mfma", kernel=f"linear_mfma<int8> {dominant[0]} {dK}->{dN}, M={M}",
                     achieved=round(achieved, 1), peak=PEAK_INT8_TOPS, unit="TFLOP/s",
                     frac=round(achieved / PEAK_INT8_TOPS, 4), avg_launch_us=round(dom_us, 2),
-                    launches_timed=len(events["pairs"]), traffic=DOMINANT_TRAFFIC_BYTES)
+                    launches_timed=len(events["pairs"]), traffic=DOMINANT_TRAFFIC_BYTES.get(args.config),
+                    algorithmic_bytes=1.0 * M * dK + dN * dK + 2.0 * M * dN)
 
     # ------------------------------------------------------------------ CPU oracle baseline (bounded sample)
     cpu = None
