@@ -26,6 +26,7 @@
 // The epilogue transposes each wavefront's results through a private LDS patch so that global
 // stores are 16 bytes per lane and cover whole contiguous row segments.
 #include <hip/hip_fp16.h>
+#include <math.h>
 
 #include "common.hpp"
 
@@ -44,8 +45,7 @@ constexpr int kWaves = 4;
 constexpr int kSlabBytes = 64;  // K bytes per LDS stage per row: two MFMA k-steps of 32 bytes
 constexpr int kXcds = 8;
 #ifndef PTQ4VM_PERSISTENT_SLAB
-#define PTQ4VM_PERSISTENT_SLAB 128   // K bytes per LDS row of the persistent kernel
-#define PTQ4VM_PERSISTENT_STAGES 2   // ring depth (stages of 512 rows x SLAB bytes)
+#define PTQ4VM_PERSISTENT_SLAB 128   // K bytes per LDS row that the 256 x 256 persistent kernel needs K to divide by
 #endif
 
 struct Int8Path {
@@ -394,10 +394,12 @@ __device__ __forceinline__ void wait_vmcnt_at_most() {
     __builtin_amdgcn_s_waitcnt(0x0F70 | (KEEP & 15) | ((KEEP >> 4) << 14));
 }
 
-template <class Path, int SLAB, int STAGES, bool HAS_BIAS, bool DUMP_ACC>
-__global__ __launch_bounds__(512, 1) void linear_mfma_persistent(const LinearArgs p) {
-    constexpr int BR = 256, BO = 256, WO = 4, NW = 8;
+template <class Path, int BO, int SLAB, int STAGES, bool HAS_BIAS, bool DUMP_ACC>
+__global__ __launch_bounds__(BO * 2, 2) void linear_mfma_persistent(const LinearArgs p) {
+    // 256 x 256 tile on 8 wavefronts (one workgroup per CU) or 256 x 128 on 4 (two per CU)
+    constexpr int BR = 256, WO = BO / 64, NW = 2 * WO;
     constexpr int WAVE_R = 128, WAVE_O = 64, FR = 4, FO = 2;
+    static_assert(BO == 256 || BO == 128, "tile width");
     constexpr int KS = SLAB / 32;             // MFMA k-steps per slab
     constexpr int CHUNKS = SLAB / 16;         // 16-byte chunks per LDS row
     constexpr int ROWS_PER_COPY = 64 / CHUNKS;  // rows in one wavefront-wide 1 KiB copy
@@ -504,22 +506,32 @@ __global__ __launch_bounds__(512, 1) void linear_mfma_persistent(const LinearArg
 
         // Scale vectors of this tile, one 4-byte element per lane, straight into LDS.  Indices
         // beyond the matrix are clamped; those rows / channels are never stored.
-        if (kInt8 && wave < 4) {
-            const int c = min(wave * 64 + lane, cols_valid - 1);
-            __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void *)(p.s_w + o0 + c),
-                                             (__attribute__((address_space(3))) void *)(cs_lds + wave * 64), 4, 0, 0);
-        }
-        if (kInt8 && wave >= 4) {
-            const int r = min((wave - 4) * 64 + lane, rows_valid - 1);
-            const uint32_t t = ((uint32_t)(r0 % p.L) + (uint32_t)r) % (uint32_t)p.L;
-            __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void *)(p.s_tok + t),
-                                             (__attribute__((address_space(3))) void *)(rs_lds + (wave - 4) * 64), 4, 0, 0);
-        }
-        if (HAS_BIAS && wave >= 2 && wave < 4) {
-            const int c2 = min((wave - 2) * 64 + lane, cols_valid / 2 - 1);
-            __builtin_amdgcn_global_load_lds(
-                (const __attribute__((address_space(1))) void *)(reinterpret_cast<const uint32_t *>(p.bias + o0) + c2),
-                (__attribute__((address_space(3))) void *)(cb_lds + (wave - 2) * 64), 4, 0, 0);
+#pragma unroll
+        for (int task = 0; task < BO / 64 + BR / 64 + BO / 128; task++) {
+            if (task % NW != wave) continue;  // the copies are dealt round-robin to the wavefronts
+            if (task < BO / 64) {             // s_w of 64 channels
+                if constexpr (kInt8) {
+                    const int c = min(task * 64 + lane, cols_valid - 1);
+                    __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void *)(p.s_w + o0 + c),
+                                                     (__attribute__((address_space(3))) void *)(cs_lds + task * 64), 4, 0, 0);
+                }
+            } else if (task < BO / 64 + BR / 64) {  // s_tok of 64 rows
+                if constexpr (kInt8) {
+                    const int blk = task - BO / 64;
+                    const int r = min(blk * 64 + lane, rows_valid - 1);
+                    const uint32_t t = ((uint32_t)(r0 % p.L) + (uint32_t)r) % (uint32_t)p.L;
+                    __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void *)(p.s_tok + t),
+                                                     (__attribute__((address_space(3))) void *)(rs_lds + blk * 64), 4, 0, 0);
+                }
+            } else {  // bias of 128 channels, two fp16 per lane
+                if constexpr (HAS_BIAS) {
+                    const int blk = task - BO / 64 - BR / 64;
+                    const int c2 = min(blk * 64 + lane, cols_valid / 2 - 1);
+                    __builtin_amdgcn_global_load_lds(
+                        (const __attribute__((address_space(1))) void *)(reinterpret_cast<const uint32_t *>(p.bias + o0) + c2),
+                        (__attribute__((address_space(3))) void *)(cb_lds + blk * 64), 4, 0, 0);
+                }
+            }
         }
         int loads_after_scales = 0;
 
@@ -970,24 +982,25 @@ int launch_dma(LinearArgs a, hipStream_t stream) {
     return ptq4vm::check_launch("linear_mfma_dma");
 }
 
-template <class Path, int SLAB, int STAGES>
+template <class Path, int BO, int SLAB, int STAGES>
 int launch_persistent(LinearArgs a, hipStream_t stream) {
     dim3 grid;
-    if (!set_grid<256, 256>(a, grid)) return PTQ4VM_ERR_SHAPE;
-    // One workgroup per CU (the LDS footprint allows no more), a multiple of the XCD count.
+    if (!set_grid<256, BO>(a, grid)) return PTQ4VM_ERR_SHAPE;
+    // One 8-wavefront or two 4-wavefront workgroups per CU (all that LDS allows), a multiple of the XCD count.
     int device = 0, cus = 0;
     hipError_t err = hipGetDevice(&device);
     if (err == hipSuccess) err = hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, device);
     if (err != hipSuccess) return ptq4vm::record_hip_error(err, "hipDeviceGetAttribute(multiprocessor count)");
-    unsigned wgs = (unsigned)(cus / kXcds * kXcds);
+    unsigned wgs = (unsigned)(cus / kXcds * kXcds) * (BO == 256 ? 1 : 2);
     if (wgs == 0) wgs = kXcds;
     if (wgs > grid.x) wgs = grid.x;  // grid.x is the tile count rounded up to a multiple of kXcds
-    constexpr int lds_bytes = STAGES * 512 * SLAB + 2 * (256 * 4 + 256 * 4 + 256 * 2);
+    constexpr int lds_bytes = STAGES * (256 + BO) * SLAB + 2 * (BO * 4 + 256 * 4 + BO * 2);
     using Kernel = void (*)(const LinearArgs);
     // [has bias][also write the int32 accumulators]
-    static const Kernel kernels[2][2] = {
-        {linear_mfma_persistent<Path, SLAB, STAGES, false, false>, linear_mfma_persistent<Path, SLAB, STAGES, false, true>},
-        {linear_mfma_persistent<Path, SLAB, STAGES, true, false>, linear_mfma_persistent<Path, SLAB, STAGES, true, true>}};
+    static const Kernel kernels[2][2] = {{linear_mfma_persistent<Path, BO, SLAB, STAGES, false, false>,
+                                          linear_mfma_persistent<Path, BO, SLAB, STAGES, false, true>},
+                                         {linear_mfma_persistent<Path, BO, SLAB, STAGES, true, false>,
+                                          linear_mfma_persistent<Path, BO, SLAB, STAGES, true, true>}};
     static bool configured = false;  // raising the dynamic-LDS limit is a per-function, idempotent setting
     if (!configured) {
         for (int b = 0; b < 2; b++)
@@ -998,7 +1011,7 @@ int launch_persistent(LinearArgs a, hipStream_t stream) {
             }
         configured = true;
     }
-    kernels[a.bias ? 1 : 0][a.acc_out ? 1 : 0]<<<dim3(wgs), dim3(512), lds_bytes, stream>>>(a);
+    kernels[a.bias ? 1 : 0][a.acc_out ? 1 : 0]<<<dim3(wgs), dim3(BO * 2), lds_bytes, stream>>>(a);
     return ptq4vm::check_launch("linear_mfma_persistent");
 }
 
@@ -1067,7 +1080,10 @@ int dispatch(LinearArgs a, hipStream_t stream) {
                                a.ldy * 512 < (1LL << 31) && a.L < (1LL << 31) && a.N >= 256 &&
                                a.k_bytes % PTQ4VM_PERSISTENT_SLAB == 0 && a.k_bytes >= 2 * PTQ4VM_PERSISTENT_SLAB &&
                                ptq4vm::ceil_div(a.M, 256) * ptq4vm::ceil_div(a.N, 256) >= 256;
-    if (persistent_ok) return launch_persistent<Path, PTQ4VM_PERSISTENT_SLAB, PTQ4VM_PERSISTENT_STAGES>(a, stream);
+    // 256 x 256 tiles on one 8-wavefront workgroup per CU.  (The 256 x 128 / two 4-wavefront workgroups
+    // per CU instantiation balances few-tile problems better but moves 1.5x the bytes through L2; it
+    // measured 3 % slower on out_proj and 10 % slower on in_proj of the Vim-B stack.)
+    if (persistent_ok) return launch_persistent<Path, 256, PTQ4VM_PERSISTENT_SLAB, 2>(a, stream);
     if (a.N > 64) {
         if (dma_ok && a.N <= 128) return launch_dma<Path, 128, 128, 2, 2, 4>(a, stream);  // skinny N: many small tiles
         if (dma_ok) return launch_dma<Path, 256, 128, 2, 2, 3>(a, stream);
