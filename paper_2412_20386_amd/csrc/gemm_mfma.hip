@@ -54,6 +54,11 @@ struct Int8Path {
     static __device__ __forceinline__ Acc mfma(v4i a, v4i b, Acc c) {
         return __builtin_amdgcn_mfma_i32_32x32x32_i8(a, b, c, 0, 0, 0);
     }
+    // 16 x 16 output block, 64 bytes of K per instruction: lane feeds row (lane mod 16), bytes 16 (lane / 16) ..
+    using Acc16 = v4i;
+    static __device__ __forceinline__ Acc16 mfma16(v4i a, v4i b, Acc16 c) {
+        return __builtin_amdgcn_mfma_i32_16x16x64_i8(a, b, c, 0, 0, 0);
+    }
 };
 
 struct Half16Path {
@@ -61,6 +66,11 @@ struct Half16Path {
     using Acc = v16f;
     static __device__ __forceinline__ Acc mfma(v4i a, v4i b, Acc c) {
         return __builtin_amdgcn_mfma_f32_32x32x16_f16(__builtin_bit_cast(v8h, a), __builtin_bit_cast(v8h, b), c, 0,
+                                                      0, 0);
+    }
+    using Acc16 = v4f;
+    static __device__ __forceinline__ Acc16 mfma16(v4i a, v4i b, Acc16 c) {
+        return __builtin_amdgcn_mfma_f32_16x16x32_f16(__builtin_bit_cast(v8h, a), __builtin_bit_cast(v8h, b), c, 0,
                                                       0, 0);
     }
 };
@@ -329,6 +339,10 @@ __global__ __launch_bounds__(kThreads, 2) void linear_mfma_dma(const LinearArgs 
 //     L2 -> LDS path at ~16 TB/s, 128-byte ones reach 22 TB/s and more);
 //   * the slab pipeline never drains: a workgroup walks its tiles in a loop and the copies for
 //     the next tile's first slabs are issued during the current tile's last slabs and epilogue;
+//   * the MFMA is v_mfma_i32_16x16x64_i8 (v_mfma_f32_16x16x32_f16 on the fp16 path): with random
+//     operand bytes it sustains ~18 % more than the 32x32x32 form on this part (3.5 vs 3.0 POP/s in
+//     an isolated LDS-fed loop; the matrix pipes are clock/power limited once operands toggle),
+//     for the same LDS traffic per MAC;
 //   * MFMA fragments are double buffered in registers: the LDS reads of k-step n+1 are issued
 //     before the MFMAs of k-step n, so LDS latency hides behind the matrix pipe even though all
 //     wavefronts of the workgroup run in lock step;
@@ -365,13 +379,26 @@ __device__ __forceinline__ void lds_read_8x_b128(uint32_t base, v4f (&v)[8]) {
           "n"(JUMP + 3 * STEP)
         : "memory");
 }
-// four 4-byte reads at base + 128 n
-__device__ __forceinline__ void lds_read_4x_b32(uint32_t base, float (&v)[4]) {
+// four 16-byte reads at base + STEP n
+template <int STEP>
+__device__ __forceinline__ void lds_read_4x_b128(uint32_t base, v4f (&v)[4]) {
     asm volatile(
-        "ds_read_b32 %0, %4\n ds_read_b32 %1, %4 offset:128\n ds_read_b32 %2, %4 offset:256\n"
-        "ds_read_b32 %3, %4 offset:384\n s_waitcnt lgkmcnt(0)"
+        "ds_read_b128 %0, %4 offset:%5\n ds_read_b128 %1, %4 offset:%6\n ds_read_b128 %2, %4 offset:%7\n"
+        "ds_read_b128 %3, %4 offset:%8\n s_waitcnt lgkmcnt(0)"
         : "=&v"(v[0]), "=&v"(v[1]), "=&v"(v[2]), "=&v"(v[3])
-        : "v"(base)
+        : "v"(base), "n"(0), "n"(STEP), "n"(2 * STEP), "n"(3 * STEP)
+        : "memory");
+}
+// eight 4-byte reads at base + STEP n
+template <int STEP>
+__device__ __forceinline__ void lds_read_8x_b32(uint32_t base, float (&v)[8]) {
+    asm volatile(
+        "ds_read_b32 %0, %8 offset:%9\n ds_read_b32 %1, %8 offset:%10\n ds_read_b32 %2, %8 offset:%11\n"
+        "ds_read_b32 %3, %8 offset:%12\n ds_read_b32 %4, %8 offset:%13\n ds_read_b32 %5, %8 offset:%14\n"
+        "ds_read_b32 %6, %8 offset:%15\n ds_read_b32 %7, %8 offset:%16\n s_waitcnt lgkmcnt(0)"
+        : "=&v"(v[0]), "=&v"(v[1]), "=&v"(v[2]), "=&v"(v[3]), "=&v"(v[4]), "=&v"(v[5]), "=&v"(v[6]), "=&v"(v[7])
+        : "v"(base), "n"(0), "n"(STEP), "n"(2 * STEP), "n"(3 * STEP), "n"(4 * STEP), "n"(5 * STEP), "n"(6 * STEP),
+          "n"(7 * STEP)
         : "memory");
 }
 // four 16-byte reads at arbitrary addresses
@@ -398,9 +425,10 @@ template <class Path, int BO, int SLAB, int STAGES, bool HAS_BIAS, bool DUMP_ACC
 __global__ __launch_bounds__(BO * 2, 2) void linear_mfma_persistent(const LinearArgs p) {
     // 256 x 256 tile on 8 wavefronts (one workgroup per CU) or 256 x 128 on 4 (two per CU)
     constexpr int BR = 256, WO = BO / 64, NW = 2 * WO;
-    constexpr int WAVE_R = 128, WAVE_O = 64, FR = 4, FO = 2;
+    constexpr int WAVE_R = 128, WAVE_O = 64;
+    constexpr int FR = WAVE_R / 16, FO = WAVE_O / 16;  // 16 x 16 MFMA blocks of the wave tile
     static_assert(BO == 256 || BO == 128, "tile width");
-    constexpr int KS = SLAB / 32;             // MFMA k-steps per slab
+    constexpr int KS = SLAB / 64;             // MFMA k-steps (64 bytes of K each) per slab
     constexpr int CHUNKS = SLAB / 16;         // 16-byte chunks per LDS row
     constexpr int ROWS_PER_COPY = 64 / CHUNKS;  // rows in one wavefront-wide 1 KiB copy
     constexpr int X_COPIES = BR / ROWS_PER_COPY / NW, W_COPIES = BO / ROWS_PER_COPY / NW;
@@ -410,7 +438,7 @@ __global__ __launch_bounds__(BO * 2, 2) void linear_mfma_persistent(const Linear
     static_assert(SLAB == 64 || SLAB == 128, "LDS rows hold 64 or 128 bytes of K");
     static_assert(NW * 32 * WAVE_O * 2 <= STAGE_BYTES, "epilogue patches must fit one stage");
     constexpr bool kInt8 = Path::kElemBytes == 1;
-    using Acc = typename Path::Acc;
+    using Acc = typename Path::Acc16;
 
     char *const ring = lds_dyn;
     // per-tile scale vectors, double buffered by tile parity
@@ -419,7 +447,7 @@ __global__ __launch_bounds__(BO * 2, 2) void linear_mfma_persistent(const Linear
 
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int wave_r = (wave / WO) * WAVE_R, wave_o = (wave % WO) * WAVE_O;
-    const int l32 = lane & 31, lhalf = lane >> 5;
+    const int l16 = lane & 15, lq = lane >> 4;
     auto lds_chunk = [&](int row, int chunk) {  // byte offset of a 16-byte chunk inside a stage half
         return row * SLAB + ((chunk ^ (SLAB == 64 ? swizzle(row) : (row & 7))) << 4);
     };
@@ -541,34 +569,34 @@ __global__ __launch_bounds__(BO * 2, 2) void linear_mfma_persistent(const Linear
 #pragma unroll
             for (int j = 0; j < FR; j++)
 #pragma unroll
-                for (int v = 0; v < 16; v++) acc[i][j][v] = 0;
+                for (int v = 0; v < 4; v++) acc[i][j][v] = 0;
 
-        v4i fw[2][FO], fx[2][FR];
-        auto load_frags = [&](int buf, int stg, int ks) {
-            const char *sx = ring + stg * STAGE_BYTES + wave_r * SLAB;
+        // Weight fragments are double buffered; an activation fragment is dead after its FO MFMAs
+        // of a k-step, so the next k-step's fragment is fetched into the same registers right then.
+        v4i fw[2][FO], fx[FR];
+        auto load_fw = [&](int buf, int stg, int ks) {
             const char *sw = ring + stg * STAGE_BYTES + (BR + wave_o) * SLAB;
-            const int chunk = 2 * ks + lhalf;
 #pragma unroll
-            for (int i = 0; i < FO; i++) fw[buf][i] = *reinterpret_cast<const v4i *>(sw + lds_chunk(i * 32 + l32, chunk));
-#pragma unroll
-            for (int j = 0; j < FR; j++) fx[buf][j] = *reinterpret_cast<const v4i *>(sx + lds_chunk(j * 32 + l32, chunk));
+            for (int i = 0; i < FO; i++) fw[buf][i] = *reinterpret_cast<const v4i *>(sw + lds_chunk(i * 16 + l16, 4 * ks + lq));
         };
-        auto mfma_step = [&](int buf) {
-#pragma unroll
-            for (int i = 0; i < FO; i++)
-#pragma unroll
-                for (int j = 0; j < FR; j++) acc[i][j] = Path::mfma(fw[buf][i], fx[buf][j], acc[i][j]);
+        auto load_fx = [&](int j, int stg, int ks) {
+            const char *sx = ring + stg * STAGE_BYTES + wave_r * SLAB;
+            fx[j] = *reinterpret_cast<const v4i *>(sx + lds_chunk(j * 16 + l16, 4 * ks + lq));
         };
 
-        load_frags(0, stage, 0);  // B(g) for the tile's first slab was passed during the previous tile
+        load_fw(0, stage, 0);  // B(g) for the tile's first slab was passed during the previous tile
+#pragma unroll
+        for (int j = 0; j < FR; j++) load_fx(j, stage, 0);
         for (int s = 0; s < n_slabs; s++, g++) {
             int next_stage = stage + 1;
             if (next_stage == STAGES) next_stage = 0;
 #pragma unroll
             for (int ks = 0; ks < KS; ks++) {
                 const int cur = ks & 1;
+                bool has_next = false;
+                int nstg = stage, nks = ks + 1;
                 if (ks + 1 < KS) {
-                    load_frags(cur ^ 1, stage, ks + 1);
+                    has_next = true;
                 } else if (g + 1 < total_slabs) {
                     // B(g+1): this wavefront holds the last fragments of slab g in registers and its
                     // copies of slab g+1 have landed.
@@ -580,10 +608,16 @@ __global__ __launch_bounds__(BO * 2, 2) void linear_mfma_persistent(const Linear
                             issue();  // refills the stage of slab g
                             loads_after_scales += LOADS_PER_SLAB;
                         }
-                        load_frags(cur ^ 1, next_stage, 0);
+                        has_next = true, nstg = next_stage, nks = 0;
                     }  // after the tile's last slab that stage first serves the epilogue
                 }
-                mfma_step(cur);
+                if (has_next) load_fw(cur ^ 1, nstg, nks);
+#pragma unroll
+                for (int j = 0; j < FR; j++) {
+#pragma unroll
+                    for (int i = 0; i < FO; i++) acc[i][j] = Path::mfma16(fw[cur][i], fx[j], acc[i][j]);
+                    if (has_next) load_fx(j, nstg, nks);
+                }
             }
             stage = next_stage;
         }
@@ -603,47 +637,53 @@ __global__ __launch_bounds__(BO * 2, 2) void linear_mfma_persistent(const Linear
         auto patch_chunk = [&](int row, int chunk) { return row * (WAVE_O * 2) + ((chunk ^ (row & 7)) << 4); };
         const bool full_tile = rows_valid == BR && cols_valid == BO;
 
-        // column scales / biases of this lane's 32 channels (index i * 4 + gq), row scales of its 4 rows
-        v4f cs_raw[8];
-        v4f cb_raw[8];  // eight fp16 biases of channels 8 gq .. 8 gq + 7; this lane needs half of them
-        float rs_raw[4];
-        if constexpr (kInt8) lds_read_8x_b128<32, 128>(lds_addr(cs_lds + wave_o + lhalf * 4), cs_raw);
-        if constexpr (HAS_BIAS) lds_read_8x_b128<16, 64>(lds_addr(cb_lds + wave_o / 2), cb_raw);
-        if constexpr (kInt8) lds_read_4x_b32(lds_addr(rs_lds + wave_r + l32), rs_raw);
+        // Accumulator register v of block (i, j):  token row 16 j + (lane mod 16),
+        // channel 16 i + 4 (lane / 16) + v.  Column scales / biases of this lane's 16 channels
+        // (cb_raw[i] holds the eight fp16 biases around them), row scales of its 8 rows.
+        v4f cs_raw[4], cb_raw[4];
+        float rs_raw[8];
+        if constexpr (kInt8) lds_read_4x_b128<64>(lds_addr(cs_lds + wave_o + lq * 4), cs_raw);
+        if constexpr (HAS_BIAS) lds_read_4x_b128<32>(lds_addr(cb_lds + (wave_o + (lq >> 1) * 8) / 2), cb_raw);
+        if constexpr (kInt8) lds_read_8x_b32<64>(lds_addr(rs_lds + wave_r + l16), rs_raw);
+        float bias4[FO][4];
+#pragma unroll
+        for (int i = 0; i < FO; i++) {
+#pragma unroll
+            for (int c = 0; c < 4; c++) bias4[i][c] = 0.0f;
+            if constexpr (HAS_BIAS) {
+                const __half2 b01 = __builtin_bit_cast(__half2, (lq & 1) ? cb_raw[i].z : cb_raw[i].x);
+                const __half2 b23 = __builtin_bit_cast(__half2, (lq & 1) ? cb_raw[i].w : cb_raw[i].y);
+                bias4[i][0] = __low2float(b01), bias4[i][1] = __high2float(b01);
+                bias4[i][2] = __low2float(b23), bias4[i][3] = __high2float(b23);
+            }
+        }
 
 #pragma unroll
-        for (int j = 0; j < FR; j++) {
+        for (int jp = 0; jp < FR / 2; jp++) {  // 32 rows per round through the patch
 #pragma unroll
-            for (int i = 0; i < FO; i++) {
+            for (int jj = 0; jj < 2; jj++) {
+                const int j = 2 * jp + jj;
 #pragma unroll
-                for (int gq = 0; gq < 4; gq++) {
-                    float bias4[4] = {0.0f, 0.0f, 0.0f, 0.0f};
-                    if constexpr (HAS_BIAS) {
-                        const v4f b8 = cb_raw[i * 4 + gq];
-                        const __half2 b01 = __builtin_bit_cast(__half2, lhalf ? b8.z : b8.x);
-                        const __half2 b23 = __builtin_bit_cast(__half2, lhalf ? b8.w : b8.y);
-                        bias4[0] = __low2float(b01), bias4[1] = __high2float(b01);
-                        bias4[2] = __low2float(b23), bias4[3] = __high2float(b23);
-                    }
+                for (int i = 0; i < FO; i++) {
                     float out[4];
 #pragma unroll
                     for (int c = 0; c < 4; c++) {
                         if constexpr (kInt8) {
-                            const int a = acc[i][j][gq * 4 + c];
+                            const int a = acc[i][j][c];
                             if constexpr (DUMP_ACC) {
-                                const int64_t r = r0 + wave_r + j * 32 + l32;
-                                const int64_t o = o0 + wave_o + i * 32 + gq * 8 + lhalf * 4 + c;
+                                const int64_t r = r0 + wave_r + j * 16 + l16;
+                                const int64_t o = o0 + wave_o + i * 16 + lq * 4 + c;
                                 if (r < p.M && o < p.N) p.acc_out[r * p.N + o] = a;
                             }
-                            out[c] = (float)a * (rs_raw[j] * cs_raw[i * 4 + gq][c]) + bias4[c];
+                            out[c] = (float)a * (rs_raw[j] * cs_raw[i][c]) + bias4[i][c];
                         } else {
-                            out[c] = acc[i][j][gq * 4 + c] + bias4[c];
+                            out[c] = acc[i][j][c] + bias4[i][c];
                         }
                     }
                     __half2 lo = __floats2half2_rn(out[0], out[1]);
                     __half2 hi = __floats2half2_rn(out[2], out[3]);
                     u32x2 packed = {__builtin_bit_cast(uint32_t, lo), __builtin_bit_cast(uint32_t, hi)};
-                    lds_write_b64(lds_addr(patch + patch_chunk(l32, i * 4 + gq) + lhalf * 8), packed);
+                    lds_write_b64(lds_addr(patch + patch_chunk(jj * 16 + l16, 2 * i + (lq >> 1)) + (lq & 1) * 8), packed);
                 }
             }
             v4f data[4];
@@ -652,7 +692,7 @@ __global__ __launch_bounds__(BO * 2, 2) void linear_mfma_persistent(const Linear
             for (int q = 0; q < 4; q++)  // 8 rows x 128 bytes per store instruction
                 src[q] = lds_addr(patch + patch_chunk(q * 8 + (lane >> 3), lane & 7));
             lds_read_4_b128(src, data);
-            const uint32_t base = (uint32_t)(wave_r + j * 32 + (lane >> 3)) * ldy_bytes + (uint32_t)(wave_o + (lane & 7) * 8) * 2;
+            const uint32_t base = (uint32_t)(wave_r + jp * 32 + (lane >> 3)) * ldy_bytes + (uint32_t)(wave_o + (lane & 7) * 8) * 2;
             if (full_tile) {
 #pragma unroll
                 for (int q = 0; q < 4; q++)
@@ -660,7 +700,7 @@ __global__ __launch_bounds__(BO * 2, 2) void linear_mfma_persistent(const Linear
             } else {
 #pragma unroll
                 for (int q = 0; q < 4; q++) {
-                    const int rr = wave_r + j * 32 + q * 8 + (lane >> 3), cc = wave_o + (lane & 7) * 8;
+                    const int rr = wave_r + jp * 32 + q * 8 + (lane >> 3), cc = wave_o + (lane & 7) * 8;
                     if (rr < rows_valid && cc < cols_valid)
                         *reinterpret_cast<v4f *>(y_tile + base + (uint32_t)(q * 8) * ldy_bytes) = data[q];
                 }
