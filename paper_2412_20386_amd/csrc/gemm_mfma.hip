@@ -436,6 +436,7 @@ __global__ __launch_bounds__(BO * 2, 2) void linear_mfma_persistent(const Linear
     constexpr int STAGE_BYTES = (BR + BO) * SLAB;
     constexpr int KEEP = (STAGES - 2) * LOADS_PER_SLAB;  // copies allowed in flight when a slab is needed
     static_assert(SLAB == 64 || SLAB == 128, "LDS rows hold 64 or 128 bytes of K");
+    static_assert(KS % 2 == 0, "the register double buffer of the weight fragments alternates per k-step");
     static_assert(NW * 32 * WAVE_O * 2 <= STAGE_BYTES, "epilogue patches must fit one stage");
     constexpr bool kInt8 = Path::kElemBytes == 1;
     using Acc = typename Path::Acc16;
@@ -868,6 +869,236 @@ __global__ __launch_bounds__(kThreads) void linear_mfma_smallk(const LinearArgs 
 }
 
 // ------------------------------------------------------------------------------------------
+// Skinny-N path (N <= 128 over very many rows, e.g. x_proj 1536 -> 80): the activation is read
+// exactly once from HBM and is almost all of the traffic, the weight is small.  One workgroup of 8
+// wavefronts per CU keeps the WHOLE weight in LDS (row pitch K bytes + 16, so the 16 rows of an
+// MFMA operand read start 4 banks apart and never conflict) together with s_w and the bias as
+// fp32.  A wavefront owns units of 32 token rows (two 16 x 16 MFMA row blocks against all
+// ceil(N / 16) channel blocks): its activation fragments go from global memory straight into
+// registers in MFMA operand layout (16 rows x 64 contiguous bytes per load instruction),
+// kWresDepth k-steps ahead, and there is no barrier after the weight has landed.  Results leave
+// through a wavefront-private LDS patch laid out like the output rows; when the output is dense
+// (ldy == N, N a multiple of 4, 16-byte aligned base) a 16-row block is one contiguous span and is
+// written with 16-byte stores.
+// Requirements (host-checked): pitches and bases 16-byte aligned, k_bytes % 64 == 0, N <= 128,
+// M, L < 2^31, everything fits the 160 KiB of LDS.
+// ------------------------------------------------------------------------------------------
+constexpr int kWresWaves = 8;
+constexpr int kWresDepth = 8;      // k-steps of activation fragments in flight per row block
+constexpr int kWresMaxBlocks = 8;  // 16-channel blocks: N <= 128
+constexpr int kLdsBytes = 160 * 1024;
+constexpr int64_t kWresMinRows = 16384;  // below this the one-off weight copy per workgroup does not pay
+
+struct WresLayout {
+    int nb, n4, pw, w_bytes, scale_bytes, patch_bytes, total;
+};
+__host__ __device__ __forceinline__ WresLayout wres_layout(int N, int k_bytes) {
+    WresLayout l;
+    l.nb = (N + 15) >> 4;
+    l.n4 = (N + 3) & ~3;
+    l.pw = k_bytes + 16;
+    l.w_bytes = (l.nb * 16 * l.pw + 1023) & ~1023;  // whole 1 KiB wavefront copies
+    l.scale_bytes = l.nb * 16 * 4 * 2;
+    l.patch_bytes = 16 * l.n4 * 2;                   // one 16-row block of fp16 results
+    l.total = l.w_bytes + l.scale_bytes + kWresWaves * l.patch_bytes;
+    return l;
+}
+
+template <class Path, int NB>
+__global__ __launch_bounds__(kWresWaves * 64) void linear_mfma_wres(const LinearArgs p) {
+    constexpr bool kInt8 = Path::kElemBytes == 1;
+    constexpr int D = kWresDepth;
+    using Acc = typename Path::Acc16;
+
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int l16 = lane & 15, lq = lane >> 4;
+    const int N = (int)p.N, k_bytes = (int)p.k_bytes, n_ksteps = k_bytes >> 6;
+    const WresLayout lay = wres_layout(N, k_bytes);
+    const int n4 = lay.n4, pw = lay.pw;
+    char *const w_lds = lds_dyn;
+    float *const cs_lds = reinterpret_cast<float *>(lds_dyn + lay.w_bytes);
+    float *const cb_lds = cs_lds + NB * 16;
+    char *const patch = lds_dyn + lay.w_bytes + lay.scale_bytes + wave * lay.patch_bytes;
+
+    // Units are dealt wavefront-major, so that a launch with fewer units than wavefronts still
+    // spreads them over all workgroups.
+    const int64_t units = (p.M + 31) >> 5;
+    const int64_t unit_step = (int64_t)gridDim.x * kWresWaves;
+    int64_t unit = (int64_t)wave * gridDim.x + blockIdx.x;
+
+    v4i fx[2][D];
+    const char *xrow[2];
+    auto load_x = [&](int d, int ks) {
+#pragma unroll
+        for (int j = 0; j < 2; j++)
+            fx[j][d] = __builtin_nontemporal_load(reinterpret_cast<const v4i *>(xrow[j] + ks * 64));
+    };
+    auto start_unit = [&](int64_t u) {  // first D k-steps of the unit's two row blocks
+#pragma unroll
+        for (int j = 0; j < 2; j++)
+            xrow[j] = p.x + min(u * 32 + j * 16 + l16, p.M - 1) * p.ldx_bytes + lq * 16;  // clamped rows are never stored
+#pragma unroll
+        for (int d = 0; d < D; d++)
+            if (d < n_ksteps) load_x(d, d);
+    };
+    if (unit < units) start_unit(unit);
+
+    // The weight, once: 1 KiB copies, linear on the LDS side; the lane picks the global chunk that
+    // belongs at its LDS position (pad chunks and pad rows re-read a valid neighbour).
+    {
+        const int chunks_per_row = pw >> 4;
+        for (int c = wave; c < (lay.w_bytes >> 10); c += kWresWaves) {
+            const int chunk = c * 64 + lane;
+            const int row = chunk / chunks_per_row, cc = chunk - row * chunks_per_row;
+            const char *src = p.w + (int64_t)min(row, N - 1) * p.ldw_bytes + min(cc, chunks_per_row - 2) * 16;
+            __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void *)src,
+                                             (__attribute__((address_space(3))) void *)(w_lds + c * 1024), 16, 0, 0);
+        }
+        for (int o = tid; o < NB * 16; o += kWresWaves * 64) {
+            float s = 0.0f, b = 0.0f;
+            if (o < N) {
+                s = 1.0f;
+                if constexpr (kInt8) s = p.s_w[o];
+                if (p.bias) b = __half2float(p.bias[o]);
+            }
+            cs_lds[o] = s;
+            cb_lds[o] = b;
+        }
+    }
+    __builtin_amdgcn_s_waitcnt(0);  // vmcnt(0) expcnt(0) lgkmcnt(0): this wavefront's copies have landed
+    __syncthreads();
+
+    const bool dense_y = n4 == N && p.ldy == p.N && (reinterpret_cast<uintptr_t>(p.y) & 15) == 0;
+    const int chunks8_per_row = n4 >> 2;  // 8-byte groups of four channels per patch row
+    const char *const w_lane = w_lds + l16 * pw + lq * 16;
+
+    for (; unit < units; unit += unit_step) {
+        Acc acc[2][NB];
+#pragma unroll
+        for (int j = 0; j < 2; j++)
+#pragma unroll
+            for (int i = 0; i < NB; i++)
+#pragma unroll
+                for (int v = 0; v < 4; v++) acc[j][i][v] = 0;
+        auto compute = [&](int d, int ks) {
+            v4i fw[NB];
+#pragma unroll
+            for (int i = 0; i < NB; i++) fw[i] = *reinterpret_cast<const v4i *>(w_lane + i * 16 * pw + ks * 64);
+            __builtin_amdgcn_sched_barrier(0);  // all LDS reads of the k-step in flight before its first MFMA
+#pragma unroll
+            for (int i = 0; i < NB; i++) {
+                acc[0][i] = Path::mfma16(fw[i], fx[0][d], acc[0][i]);
+                acc[1][i] = Path::mfma16(fw[i], fx[1][d], acc[1][i]);
+            }
+        };
+        // The scheduling barriers keep each refill right behind the MFMAs that free its registers;
+        // left alone the scheduler sinks all loads of a group to its end and the wavefront then
+        // waits for the whole group before every pass.
+
+        int ks0 = 0;
+        for (; ks0 + 2 * D <= n_ksteps; ks0 += D) {  // steady state: every register slot is refilled
+#pragma unroll
+            for (int d = 0; d < D; d++) {
+                compute(d, ks0 + d);
+                load_x(d, ks0 + d + D);
+                __builtin_amdgcn_sched_barrier(0);
+            }
+        }
+#pragma unroll
+        for (int d = 0; d < D; d++) {  // last refills
+            if (ks0 + d < n_ksteps) {
+                compute(d, ks0 + d);
+                if (ks0 + d + D < n_ksteps) load_x(d, ks0 + d + D);
+            }
+            __builtin_amdgcn_sched_barrier(0);
+        }
+        ks0 += D;
+#pragma unroll
+        for (int d = 0; d < D; d++) {  // drain
+            if (ks0 + d < n_ksteps) compute(d, ks0 + d);
+            __builtin_amdgcn_sched_barrier(0);
+        }
+
+        // Accumulator register v of block (j, i): token row 16 j + (lane mod 16), channel 16 i + 4 (lane / 16) + v.
+        const int64_t r_unit = unit * 32;
+        float rs[2] = {1.0f, 1.0f};
+        if constexpr (kInt8) {
+#pragma unroll
+            for (int j = 0; j < 2; j++)
+                rs[j] = p.s_tok[(uint32_t)min(r_unit + j * 16 + l16, p.M - 1) % (uint32_t)p.L];
+        }
+        const int64_t next = unit + unit_step;
+        if (next < units) start_unit(next);  // in flight while this unit's results are written
+
+#pragma unroll
+        for (int j = 0; j < 2; j++) {
+            const int64_t r0 = r_unit + j * 16;
+            const int rows_valid = (int)min((int64_t)16, p.M - r0);
+            if (rows_valid <= 0) break;
+#pragma unroll
+            for (int i = 0; i < NB; i++) {
+                const int col = i * 16 + lq * 4;
+                if (col < n4) {
+                    const v4f cs = *reinterpret_cast<const v4f *>(cs_lds + col);
+                    const v4f cb = *reinterpret_cast<const v4f *>(cb_lds + col);
+                    float out[4];
+#pragma unroll
+                    for (int c = 0; c < 4; c++) {
+                        if constexpr (kInt8) {
+                            const int a = acc[j][i][c];
+                            if (p.acc_out && l16 < rows_valid && col + c < N) p.acc_out[(r0 + l16) * p.N + col + c] = a;
+                            out[c] = (float)a * (rs[j] * cs[c]) + cb[c];
+                        } else {
+                            out[c] = acc[j][i][c] + cb[c];
+                        }
+                    }
+                    __half2 lo = __floats2half2_rn(out[0], out[1]);
+                    __half2 hi = __floats2half2_rn(out[2], out[3]);
+                    u32x2 packed = {__builtin_bit_cast(uint32_t, lo), __builtin_bit_cast(uint32_t, hi)};
+                    *reinterpret_cast<u32x2 *>(patch + l16 * (n4 * 2) + col * 2) = packed;
+                }
+            }
+            asm volatile("" ::: "memory");  // wavefront-private patch: LDS runs a wavefront's accesses in order
+            if (dense_y) {
+                const int valid_bytes = rows_valid * N * 2, block_bytes = 32 * N;
+                char *dst = reinterpret_cast<char *>(p.y + r0 * p.N);
+                for (int off = lane * 16; off < block_bytes; off += 64 * 16) {
+                    const v4i data = *reinterpret_cast<const v4i *>(patch + off);
+                    if (off + 16 <= valid_bytes) {
+                        __builtin_nontemporal_store(data, reinterpret_cast<v4i *>(dst + off));
+                    } else {
+#pragma unroll
+                        for (int e = 0; e < 8; e++)
+                            if (off + 2 * e < valid_bytes)
+                                reinterpret_cast<uint16_t *>(dst + off)[e] = (uint16_t)((uint32_t)data[e >> 1] >> (16 * (e & 1)));
+                    }
+                }
+            } else {
+                for (int idx = lane; idx < 16 * chunks8_per_row; idx += 64) {
+                    const int row = idx / chunks8_per_row, cc = idx - row * chunks8_per_row;
+                    if (row >= rows_valid) continue;
+                    const u32x2 data = *reinterpret_cast<const u32x2 *>(patch + row * (n4 * 2) + cc * 8);
+                    __half *dst = p.y + (r0 + row) * p.ldy + cc * 4;
+                    if (p.y_vec >= 4 && cc * 4 + 4 <= N) {
+                        *reinterpret_cast<u32x2 *>(dst) = data;
+                    } else {
+#pragma unroll
+                        for (int e = 0; e < 4; e++)
+                            if (cc * 4 + e < N)
+                                reinterpret_cast<uint16_t *>(dst)[e] = (uint16_t)(data[e >> 1] >> (16 * (e & 1)));
+                    }
+                }
+            }
+            asm volatile("" ::: "memory");
+        }
+        // Stores and loads share the vmcnt counter and complete out of order with each other, so with
+        // stores possibly outstanding every wait on a fragment would have to be a full drain.  Drain
+        // once here instead: the next unit's first fragments were fetched during the epilogue.
+        wait_vmcnt_at_most<0>();
+    }
+}
+
+// ------------------------------------------------------------------------------------------
 // Generic path: register-staged loads, zero fill beyond M, N and K, any pitch.
 // ------------------------------------------------------------------------------------------
 __device__ __forceinline__ uint32_t keep_low_bytes(uint32_t v, int nbytes) {
@@ -1085,6 +1316,34 @@ int launch_smallk_ksteps(const LinearArgs &a, hipStream_t stream) {
     }
 }
 
+template <class Path>
+int launch_wres(const LinearArgs &a, hipStream_t stream) {
+    const WresLayout lay = wres_layout((int)a.N, (int)a.k_bytes);
+    int device = 0, cus = 0;
+    hipError_t err = hipGetDevice(&device);
+    if (err == hipSuccess) err = hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, device);
+    if (err != hipSuccess) return ptq4vm::record_hip_error(err, "hipDeviceGetAttribute(multiprocessor count)");
+    if (cus < 1) cus = 1;
+    const int64_t units = ptq4vm::ceil_div(a.M, 32);
+    int64_t wgs = ptq4vm::ceil_div(units, kWresWaves);
+    if (wgs > cus) wgs = cus;  // one workgroup per CU: the resident weight takes most of its LDS
+    using Kernel = void (*)(const LinearArgs);
+    static const Kernel kernels[kWresMaxBlocks] = {  // by the number of 16-channel blocks
+        linear_mfma_wres<Path, 1>, linear_mfma_wres<Path, 2>, linear_mfma_wres<Path, 3>, linear_mfma_wres<Path, 4>,
+        linear_mfma_wres<Path, 5>, linear_mfma_wres<Path, 6>, linear_mfma_wres<Path, 7>, linear_mfma_wres<Path, 8>};
+    static bool configured = false;  // raising the dynamic-LDS limit is a per-function, idempotent setting
+    if (!configured) {
+        for (int i = 0; i < kWresMaxBlocks; i++) {
+            err = hipFuncSetAttribute(reinterpret_cast<const void *>(kernels[i]),
+                                      hipFuncAttributeMaxDynamicSharedMemorySize, kLdsBytes);
+            if (err != hipSuccess) return ptq4vm::record_hip_error(err, "hipFuncSetAttribute(linear_mfma_wres)");
+        }
+        configured = true;
+    }
+    kernels[lay.nb - 1]<<<dim3((unsigned)wgs), dim3(kWresWaves * 64), lay.total, stream>>>(a);
+    return ptq4vm::check_launch("linear_mfma_wres");
+}
+
 template <class Path, int BR, int BO, int WR, int WO>
 int launch_generic(LinearArgs a, int load_align, hipStream_t stream) {
     dim3 grid;
@@ -1124,6 +1383,11 @@ int dispatch(LinearArgs a, hipStream_t stream) {
     // per CU instantiation balances few-tile problems better but moves 1.5x the bytes through L2; it
     // measured 3 % slower on out_proj and 10 % slower on in_proj of the Vim-B stack.)
     if (persistent_ok) return launch_persistent<Path, 256, PTQ4VM_PERSISTENT_SLAB, 2>(a, stream);
+    // Few output channels over many rows: weight resident in LDS, activations streamed once.
+    const bool wres_ok = dma_ok && a.N <= 16 * kWresMaxBlocks && a.M >= kWresMinRows && a.M < (1LL << 31) &&
+                         a.L < (1LL << 31) && a.k_bytes < (1LL << 20) &&
+                         wres_layout((int)a.N, (int)a.k_bytes).total <= kLdsBytes;
+    if (wres_ok) return launch_wres<Path>(a, stream);
     if (a.N > 64) {
         if (dma_ok && a.N <= 128) return launch_dma<Path, 128, 128, 2, 2, 4>(a, stream);  // skinny N: many small tiles
         if (dma_ok) return launch_dma<Path, 256, 128, 2, 2, 3>(a, stream);

@@ -242,18 +242,27 @@ def _sampled_rows(M, step, L):
     return rows[(rows >= 0) & (rows < M)]
 
 
-def _check_case_on_sampled_rows(c, rows, what):
+def _check_case_on_sampled_rows(c, rows, what, ldy=None, use_bias=True):
     """Whole problem on the GPU in the benchmark's launch configuration (no accumulator dump),
     plus one launch with the dump; the oracle recomputes the sampled rows from the fp16 inputs."""
-    print(f"full-size {what}: M={c.B * c.L} K={c.K} N={c.N}, {len(rows)} sampled rows", flush=True)
+    print(f"full-size {what}: M={c.B * c.L} K={c.K} N={c.N} ldy={ldy} bias={use_bias}, {len(rows)} sampled rows",
+          flush=True)
     M = c.B * c.L
+    bias = c.bias if use_bias else None
     wq, s_w, inv_m = ptq.fold_smoothing(c.w, c.m)
     xq = ptq.quantize_pts(c.x, inv_m, c.s_tok, c.B, c.L)
-    y = ptq.w8a8_linear(xq, wq, c.s_tok, s_w, c.bias, c.B, c.L)
-    acc = torch.empty((M, c.N), dtype=torch.int32, device=DEV)
-    y_dump = ptq.w8a8_linear(xq, wq, c.s_tok, s_w, c.bias, c.B, c.L, acc_out=acc)
+    ybuf = None
+    if ldy is None:
+        y = ptq.w8a8_linear(xq, wq, c.s_tok, s_w, bias, c.B, c.L)
+    else:
+        ybuf, yv = _padded(M, c.N, ldy, torch.float16, 12345.0)
+        y = ptq.w8a8_linear(xq, wq, c.s_tok, s_w, bias, c.B, c.L, y=yv)
+    acc = torch.full((M, c.N), -1, dtype=torch.int32, device=DEV)
+    y_dump = ptq.w8a8_linear(xq, wq, c.s_tok, s_w, bias, c.B, c.L, acc_out=acc)
     torch.cuda.synchronize()
-    assert torch.equal(y.view(torch.int16), y_dump.view(torch.int16))
+    assert torch.equal(y.contiguous().view(torch.int16), y_dump.view(torch.int16))
+    if ybuf is not None:
+        assert bool((ybuf[:, c.N:] == 12345.0).all())
     ridx = torch.from_numpy(rows).to(DEV)
     x_s, xq_s, y_s, acc_s = _np(c.x[ridx]), _np(xq[ridx]), _np(y[ridx]), _np(acc[ridx])
 
@@ -263,11 +272,11 @@ def _check_case_on_sampled_rows(c, rows, what):
     n = len(rows)
     xq_o = oracle.quantize_pts(x_s, inv_m_o, st_rows, 1, n)  # B=1, L=n: one step per sampled row
     assert np.array_equal(xq_s, xq_o), "int8 codes differ"
-    b_o = _np(c.bias)
+    b_o = _np(c.bias) if use_bias else None
     y_o, y64, acc_o = oracle.w8a8_linear(xq_o, wq_o, st_rows, s_w_o, b_o, 1, n)
     assert np.array_equal(acc_s, acc_o), "int32 accumulators differ"
     prod_abs = np.abs(acc_o.astype(np.float64) * st_rows.astype(np.float64)[:, None] * s_w_o.astype(np.float64)[None, :])
-    bias_abs = np.broadcast_to(np.abs(b_o.astype(np.float64))[None, :], prod_abs.shape)
+    bias_abs = np.broadcast_to(np.abs(b_o.astype(np.float64))[None, :] if use_bias else 0.0, prod_abs.shape)
     return check_dequantized_output(y_s, y_o, y64, prod_abs, bias_abs, what)
 
 
@@ -291,3 +300,31 @@ def test_large_ragged_shapes_sampled(B, L, K, N):
     """Enough 256 x 256 tiles for the persistent kernel, with ragged last tiles in both directions."""
     c = synth.random_problem(4242 + N, B, L, K, N, device=DEV)
     _check_case_on_sampled_rows(c, _sampled_rows(B * L, 61, L), "ragged")
+
+
+SKINNY_SHAPES = [  # B, L, K, N, ldy, bias: few output channels over >= 16384 rows (weight-resident kernel)
+    (83, 199, 192, 44, None, True),     # 3 k-steps; 88-byte dense rows; M mod 32 = 5
+    (64, 257, 320, 80, None, False),    # 5 k-steps, fewer than the fragments kept in flight
+    (70, 241, 1024, 128, None, True),   # exactly two register groups of k-steps; 8 channel blocks; M mod 32 = 6
+    (83, 199, 704, 50, None, True),     # 11 k-steps; N not a multiple of 4: 2-byte stores
+    (83, 199, 1536, 72, 80, True),      # padded output rows
+    (66, 250, 1600, 16, None, True),    # 25 k-steps; one channel block; M mod 32 = 20
+    (65, 253, 448, 97, 100, False),     # odd N with padded rows
+]
+
+
+@pytest.mark.parametrize("B,L,K,N,ldy,bias", SKINNY_SHAPES)
+def test_skinny_output_shapes_sampled(B, L, K, N, ldy, bias):
+    c = synth.random_problem(777 + K + N, B, L, K, N, device=DEV)
+    _check_case_on_sampled_rows(c, _sampled_rows(B * L, 37, L), "skinny", ldy=ldy, use_bias=bias)
+
+
+def test_skinny_output_whole_result():
+    """Every element of a weight-resident launch, not a sample: 83 * 199 rows, 192 -> 44."""
+    c = synth.random_problem(99, 83, 199, 192, 44, device=DEV)
+    _run_w8a8_case(c, what="skinny-whole")
+
+
+@pytest.mark.parametrize("M,K,N", [(16517, 192, 44), (16400, 512, 80)])
+def test_f16_linear_skinny_output(M, K, N):
+    test_f16_linear_within_accumulation_bound(M, K, N)
