@@ -103,6 +103,31 @@ int ptq4vm_w8a8_linear(const int8_t *xq, const int8_t *wq, const float *s_tok, c
                        int64_t K, int64_t N, int64_t ldxq, int64_t ldwq, int64_t ldy, void *stream);
 
 /*
+ * Fused activation quantizer + W8A8 linear: the stages "Activation smoothing", "Quantization",
+ * "INT GEMM" and "Dequantization" of App. B.1 in one launch (PTS equation of Sec. 5.1).
+ * Computes exactly, bit for bit, what ptq4vm_quantize_pts followed by ptq4vm_w8a8_linear
+ * compute; the int8 codes stay on chip.  Worth using when the output is narrow (N <= 128 over
+ * >= 16384 rows, e.g. x_proj: every activation element is read and quantized once); for wide
+ * outputs a tiled GEMM would re-quantize each element once per tile column and the two separate
+ * calls are faster, but every shape is accepted.
+ *   x_f16    [B*L, ldx]  fp16 in
+ *   inv_m    [K]         f32  in   may be NULL (no smoothing)
+ *   s_tok    [L]         f32  in
+ *   wq       [N, ldwq]   int8 in
+ *   s_w      [N]         f32  in
+ *   bias_f16 [N]         fp16 in   may be NULL
+ *   y_f16    [B*L, ldy]  fp16 out
+ *   acc_out  [B*L, N]    int32 out, dense; may be NULL (parity aid, leave NULL when timing)
+ *   xq_out   [B*L, ldxq] int8 out; may be NULL (parity aid: the codes the GEMM consumed)
+ * Errors: NULL x_f16 / s_tok / wq / s_w / y_f16, B < 0, N < 0, L <= 0, K <= 0, K > PTQ4VM_MAX_K,
+ * ld* too small, misaligned x_f16 / wq (16 bytes) or y_f16 (2 bytes).
+ */
+int ptq4vm_w8a8_linear_fused(const void *x_f16, const float *inv_m, const float *s_tok, const int8_t *wq,
+                             const float *s_w, const void *bias_f16, void *y_f16, int32_t *acc_out,
+                             int8_t *xq_out, int64_t B, int64_t L, int64_t K, int64_t N, int64_t ldx,
+                             int64_t ldwq, int64_t ldy, int64_t ldxq, void *stream);
+
+/*
  * Unquantized comparison linear (the "FP16" column of the paper's latency table, Sec. 6.3):
  *   y[r,o] = fp16( sum_k x[r,k] * w[o,k]  (fp32 accumulation)  + bias[o] )
  *   x_f16 [M, ldx], w_f16 [N, ldw], bias_f16 [N] or NULL, y_f16 [M, ldy]

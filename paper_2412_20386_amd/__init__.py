@@ -9,4 +9,5 @@ from .binding import (  # noqa: F401
     fold_smoothing,
     quantize_pts,
     w8a8_linear,
+    w8a8_linear_fused,
 )

@@ -1,0 +1,274 @@
+// Shared pieces of the MFMA linear kernels for gfx950: operand/accumulator types of the int8 and
+// fp16 paths, the kernel argument block, the LDS swizzle, the XCD-aware tile order, the MFMA loop over
+// one 64-byte slab, the fused dequantization epilogue and the zero-filling chunk loader.
+#pragma once
+#include <hip/hip_fp16.h>
+#include <math.h>
+
+#include "common.hpp"
+
+namespace ptq4vm {
+namespace mfma {
+
+typedef int v4i __attribute__((ext_vector_type(4)));
+typedef int v16i __attribute__((ext_vector_type(16)));
+typedef float v16f __attribute__((ext_vector_type(16)));
+typedef _Float16 v8h __attribute__((ext_vector_type(8)));
+typedef unsigned int u32x2 __attribute__((ext_vector_type(2)));
+typedef float v4f __attribute__((ext_vector_type(4)));
+typedef float v2f __attribute__((ext_vector_type(2)));
+
+constexpr int kThreads = 256;
+constexpr int kWaves = 4;
+constexpr int kSlabBytes = 64;  // K bytes per LDS stage per row: two MFMA k-steps of 32 bytes
+constexpr int kXcds = 8;
+#ifndef PTQ4VM_PERSISTENT_SLAB
+#define PTQ4VM_PERSISTENT_SLAB 128   // K bytes per LDS row that the 256 x 256 persistent kernel needs K to divide by
+#endif
+
+struct Int8Path {
+    static constexpr int kElemBytes = 1;
+    using Acc = v16i;
+    static __device__ __forceinline__ Acc mfma(v4i a, v4i b, Acc c) {
+        return __builtin_amdgcn_mfma_i32_32x32x32_i8(a, b, c, 0, 0, 0);
+    }
+    // 16 x 16 output block, 64 bytes of K per instruction: lane feeds row (lane mod 16), bytes 16 (lane / 16) ..
+    using Acc16 = v4i;
+    static __device__ __forceinline__ Acc16 mfma16(v4i a, v4i b, Acc16 c) {
+        return __builtin_amdgcn_mfma_i32_16x16x64_i8(a, b, c, 0, 0, 0);
+    }
+};
+
+struct Half16Path {
+    static constexpr int kElemBytes = 2;
+    using Acc = v16f;
+    static __device__ __forceinline__ Acc mfma(v4i a, v4i b, Acc c) {
+        return __builtin_amdgcn_mfma_f32_32x32x16_f16(__builtin_bit_cast(v8h, a), __builtin_bit_cast(v8h, b), c, 0,
+                                                      0, 0);
+    }
+    using Acc16 = v4f;
+    static __device__ __forceinline__ Acc16 mfma16(v4i a, v4i b, Acc16 c) {
+        return __builtin_amdgcn_mfma_f32_16x16x32_f16(__builtin_bit_cast(v8h, a), __builtin_bit_cast(v8h, b), c, 0,
+                                                      0, 0);
+    }
+};
+
+struct LinearArgs {
+    const char *x;       // [M, ldx] activations (B operand), K-contiguous
+    const char *w;       // [N, ldw] weights (A operand), K-contiguous
+    const float *s_tok;  // [L] or nullptr (fp16 path)
+    const float *s_w;    // [N] or nullptr (fp16 path)
+    const __half *bias;  // [N] or nullptr
+    __half *y;           // [M, ldy]
+    int32_t *acc_out;    // [M, N] dense or nullptr (int8 path only)
+    int64_t M, N;
+    int64_t k_bytes;     // K * element size
+    int64_t ldx_bytes, ldw_bytes;
+    int64_t ldy;         // elements
+    int64_t L;
+    int tiles_o, tiles_r;
+    int y_vec;           // widest store the pitch and base of y allow, in fp16 elements: 8, 4 or 1
+    // Fused activation quantizer only: x then holds fp16 activations (ldx_bytes = 2 * pitch) and k_bytes
+    // is still K, the reduction length in int8 codes.
+    const float *inv_m;  // [K] reciprocal smoothing factors or nullptr (no smoothing)
+    int8_t *xq_out;      // [M, ldxq_out] optional copy of the int8 codes, or nullptr
+    int64_t ldxq_out;
+};
+
+extern __shared__ __attribute__((aligned(16))) char lds_dyn[];
+
+__device__ __forceinline__ int swizzle(int row) { return ((row >> 1) ^ (row >> 2)) & 3; }
+
+// XCD-aware tile order: workgroup ids go round-robin over the 8 XCDs, so give each XCD a
+// contiguous range of tiles, output-channel tiles fastest (they share the activation strip).
+__device__ __forceinline__ bool tile_of_block(const LinearArgs &p, int &tile_r, int &tile_o) {
+    const int total_tiles = p.tiles_o * p.tiles_r;
+    const int per_xcd = (total_tiles + kXcds - 1) / kXcds;
+    const int tile = (int)(blockIdx.x % kXcds) * per_xcd + (int)(blockIdx.x / kXcds);
+    if (tile >= total_tiles) return false;
+    tile_o = tile % p.tiles_o;
+    tile_r = tile / p.tiles_o;
+    return true;
+}
+
+// MFMA work on one 64-byte slab held in LDS: x_rows/w_rows point at the wave's first row.
+template <class Path, int FO, int FR>
+__device__ __forceinline__ void mfma_slab(typename Path::Acc (&acc)[FO][FR], const char *x_rows, const char *w_rows,
+                                          int l32, int lhalf) {
+#pragma unroll
+    for (int s = 0; s < 2; s++) {
+        const int kc = 2 * s + lhalf;
+        v4i fw[FO], fx[FR];
+#pragma unroll
+        for (int i = 0; i < FO; i++) {
+            const int row = i * 32 + l32;  // wave row offsets are multiples of 32: swizzle(row) is unchanged
+            fw[i] = *reinterpret_cast<const v4i *>(w_rows + row * kSlabBytes + ((kc ^ swizzle(row)) << 4));
+        }
+#pragma unroll
+        for (int j = 0; j < FR; j++) {
+            const int row = j * 32 + l32;
+            fx[j] = *reinterpret_cast<const v4i *>(x_rows + row * kSlabBytes + ((kc ^ swizzle(row)) << 4));
+        }
+#pragma unroll
+        for (int i = 0; i < FO; i++)
+#pragma unroll
+            for (int j = 0; j < FR; j++) acc[i][j] = Path::mfma(fw[i], fx[j], acc[i][j]);
+    }
+}
+
+// Epilogue of one wavefront.  Accumulator register v of a lane in block (i, j):
+//   token row       r = r_base + 32 j + (lane mod 32)
+//   output channel  o = o_base + 32 i + 8 (v / 4) + 4 (lane / 32) + (v mod 4)
+// A lane therefore owns 8-byte runs scattered over 32 rows.  The wavefront transposes its
+// results through a private LDS patch (JB*32 rows x WAVE_O fp16 at a time, 16-byte chunks
+// XOR-swizzled by the row) so that the global stores are 16 bytes per lane with the lanes of a
+// row side by side: every store instruction writes whole, contiguous row segments.  Only this
+// wavefront touches `patch`, and the LDS executes a wavefront's instructions in order, so no
+// barrier is needed; the empty asm statements only stop the compiler from reordering LDS
+// accesses.  Column scales and biases are fetched per group of four channels (outer loops) so
+// that they do not have to live in registers next to the accumulators.
+template <class Path, int FO, int FR, int JB>
+__device__ __forceinline__ void epilogue(const typename Path::Acc (&acc)[FO][FR], const LinearArgs &p, char *patch,
+                                         int64_t r_base, int64_t o_base, int lane) {
+    constexpr int WAVE_O = FO * 32;
+    constexpr int CPR = WAVE_O / 8;           // 16-byte chunks per staged row
+    constexpr int ROWS_PER_STORE = 64 / CPR;  // rows covered by one store instruction
+    static_assert(CPR <= 64 && (CPR & (CPR - 1)) == 0, "wave tile width must be 32, 64 or 128 channels");
+    static_assert(FR % JB == 0, "row blocks are staged in equal groups");
+    const int l32 = lane & 31, lhalf = lane >> 5;
+    auto patch_chunk = [&](int row, int chunk) {  // byte offset of a 16-byte chunk
+        const int sw = CPR >= 8 ? (row & 7) : ((row / (8 / CPR)) & (CPR - 1));
+        return row * (WAVE_O * 2) + ((chunk ^ sw) << 4);
+    };
+
+#pragma unroll
+    for (int jb = 0; jb < FR; jb += JB) {
+        float row_scale[JB];
+#pragma unroll
+        for (int jj = 0; jj < JB; jj++) {
+            const int64_t r = r_base + (jb + jj) * 32 + l32;
+            row_scale[jj] = 1.0f;
+            if constexpr (Path::kElemBytes == 1) row_scale[jj] = p.s_tok[(r < p.M ? r : 0) % p.L];
+        }
+#pragma unroll
+        for (int i = 0; i < FO; i++) {
+#pragma unroll
+            for (int g = 0; g < 4; g++) {
+                float col_scale[4], col_bias[4];
+#pragma unroll
+                for (int c = 0; c < 4; c++) {
+                    const int64_t o = o_base + i * 32 + g * 8 + lhalf * 4 + c;
+                    const bool ok = o < p.N;
+                    col_bias[c] = (ok && p.bias) ? __half2float(p.bias[o]) : 0.0f;
+                    col_scale[c] = 1.0f;
+                    if constexpr (Path::kElemBytes == 1) col_scale[c] = ok ? p.s_w[o] : 0.0f;
+                }
+#pragma unroll
+                for (int jj = 0; jj < JB; jj++) {
+                    const int j = jb + jj;
+                    float out[4];
+#pragma unroll
+                    for (int c = 0; c < 4; c++) {
+                        if constexpr (Path::kElemBytes == 1) {
+                            const int a = acc[i][j][g * 4 + c];
+                            if (p.acc_out) {
+                                const int64_t r = r_base + j * 32 + l32;
+                                const int64_t o = o_base + i * 32 + g * 8 + lhalf * 4 + c;
+                                if (r < p.M && o < p.N) p.acc_out[r * p.N + o] = a;
+                            }
+                            out[c] = (float)a * (row_scale[jj] * col_scale[c]) + col_bias[c];
+                        } else {
+                            out[c] = acc[i][j][g * 4 + c] + col_bias[c];
+                        }
+                    }
+                    __half2 lo = __floats2half2_rn(out[0], out[1]);
+                    __half2 hi = __floats2half2_rn(out[2], out[3]);
+                    u32x2 packed = {*reinterpret_cast<uint32_t *>(&lo), *reinterpret_cast<uint32_t *>(&hi)};
+                    *reinterpret_cast<u32x2 *>(patch + patch_chunk(jj * 32 + l32, i * 4 + g) + lhalf * 8) = packed;
+                }
+            }
+        }
+        asm volatile("" ::: "memory");
+#pragma unroll
+        for (int s = 0; s < JB * 32 / ROWS_PER_STORE; s++) {
+            const int row = s * ROWS_PER_STORE + lane / CPR, chunk = lane % CPR;
+            const v4i data = *reinterpret_cast<const v4i *>(patch + patch_chunk(row, chunk));
+            const int64_t rr = r_base + jb * 32 + row;
+            const int64_t oc = o_base + chunk * 8;
+            if (rr < p.M && oc < p.N) {
+                __half *dst = p.y + rr * p.ldy + oc;
+                if (p.y_vec == 8 && oc + 8 <= p.N) {
+                    *reinterpret_cast<v4i *>(dst) = data;
+                } else if (p.y_vec >= 4 && oc + 8 <= p.N) {
+                    u32x2 a = {(uint32_t)data[0], (uint32_t)data[1]}, b = {(uint32_t)data[2], (uint32_t)data[3]};
+                    *reinterpret_cast<u32x2 *>(dst) = a;
+                    *reinterpret_cast<u32x2 *>(dst + 4) = b;
+                } else {
+#pragma unroll
+                    for (int e = 0; e < 8; e++)
+                        if (oc + e < p.N)
+                            reinterpret_cast<uint16_t *>(dst)[e] = (uint16_t)((uint32_t)data[e >> 1] >> (16 * (e & 1)));
+                }
+            }
+        }
+        asm volatile("" ::: "memory");
+    }
+}
+
+__device__ __forceinline__ uint32_t keep_low_bytes(uint32_t v, int nbytes) {
+    return nbytes >= 4 ? v : (nbytes <= 0 ? 0u : (v & ((1u << (8 * nbytes)) - 1u)));
+}
+
+// One 16-byte chunk of row `row_ptr` at byte offset `kb`; bytes at or beyond k_bytes read as 0.
+// LOAD_ALIGN 16: pitch and base are multiples of 16, so the full chunk is inside the row's pitch.
+// LOAD_ALIGN 4:  same with 4.  LOAD_ALIGN 0: element-wise (ELEM bytes each), any pitch.
+template <int LOAD_ALIGN, int ELEM>
+__device__ __forceinline__ v4i load_chunk(const char *row_ptr, int64_t kb, int64_t k_bytes, bool row_ok) {
+    v4i out = {0, 0, 0, 0};
+    if (!row_ok || kb >= k_bytes) return out;
+    const int valid = (int)min((int64_t)16, k_bytes - kb);
+    if constexpr (LOAD_ALIGN == 16) {
+        out = *reinterpret_cast<const v4i *>(row_ptr + kb);
+        if (valid < 16) {
+#pragma unroll
+            for (int j = 0; j < 4; j++) out[j] = (int)keep_low_bytes((uint32_t)out[j], valid - 4 * j);
+        }
+    } else if constexpr (LOAD_ALIGN == 4) {
+#pragma unroll
+        for (int j = 0; j < 4; j++) {
+            if (4 * j < valid) {
+                uint32_t v = *reinterpret_cast<const uint32_t *>(row_ptr + kb + 4 * j);
+                out[j] = (int)keep_low_bytes(v, valid - 4 * j);
+            }
+        }
+    } else {
+#pragma unroll
+        for (int j = 0; j < 4; j++) {
+            uint32_t v = 0;
+#pragma unroll
+            for (int b = 0; b < 4; b += ELEM) {
+                if (4 * j + b < valid) {
+                    if constexpr (ELEM == 1)
+                        v |= (uint32_t) * reinterpret_cast<const uint8_t *>(row_ptr + kb + 4 * j + b) << (8 * b);
+                    else
+                        v |= (uint32_t) * reinterpret_cast<const uint16_t *>(row_ptr + kb + 4 * j + b) << (8 * b);
+                }
+            }
+            out[j] = (int)v;
+        }
+    }
+    return out;
+}
+
+template <int BR, int BO>
+inline bool set_grid(LinearArgs &a, dim3 &grid) {
+    const int64_t tiles_r = ptq4vm::ceil_div(a.M, BR), tiles_o = ptq4vm::ceil_div(a.N, BO);
+    if (tiles_r * tiles_o > 0x3fffffffLL) return false;
+    a.tiles_r = (int)tiles_r;
+    a.tiles_o = (int)tiles_o;
+    grid = dim3((unsigned)(ptq4vm::ceil_div(tiles_r * tiles_o, kXcds) * kXcds));
+    return true;
+}
+
+}  // namespace mfma
+}  // namespace ptq4vm

@@ -1,0 +1,551 @@
+// ptq4vm_w8a8_linear_fused: Per-Token-Static activation quantizer and W8A8 linear in ONE launch
+// (App. B.1 lists "Activation smoothing", "Quantization", "INT GEMM" and "Dequantization" as four
+// kernels; PTS equation of Sec. 5.1).  The int8 activation codes exist only in registers / LDS:
+//   q[r,k]   = clip(rne((f32(x[r,k]) * inv_m[k]) * (1 / s_tok[r mod L])), -127, 127)
+//   y[r,o]   = fp16(f32(sum_k q[r,k] wq[o,k]) * (s_tok[r mod L] * s_w[o]) + bias[o])
+// i.e. bit for bit what ptq4vm_quantize_pts followed by ptq4vm_w8a8_linear produce, without the
+// 1 byte written + 1 byte read per activation element in between.
+//
+// Fusing pays when an activation element is quantized once or a few times: a tiled GEMM quantizes
+// every element once per tile column (N / tile width times), so for wide outputs the separate
+// quantizer is cheaper.  Kernels:
+//   pts_linear_wres     N <= 128 over many rows (x_proj): weight resident in LDS, every fp16
+//                       activation read once from HBM in whole 128-byte lines, quantized once.
+//   pts_linear_generic  every other shape: the register-staged tiled kernel with the quantizer in
+//                       its loader (correct everywhere, re-quantizes per tile column).
+#include "mfma_linear.hpp"
+
+namespace {
+
+using namespace ptq4vm::mfma;
+
+// fp32 -> int32 conversion with the hardware's defined behaviour for specials
+// (NaN -> 0, out-of-range saturates), which a C++ cast leaves undefined.
+__device__ __forceinline__ int cvt_i32_f32(float v) {
+    int i;
+    asm("v_cvt_i32_f32 %0, %1" : "=v"(i) : "v"(v));
+    return i;
+}
+
+// One PTS code (Sec. 5.1): smoothing multiply, step multiply, round half to even, clip.  Two
+// separate fp32 multiplies in this order: the codes must equal the stand-alone quantizer's.
+__device__ __forceinline__ int quantize_one(float x, float inv_m, float inv_s) {
+    float v = x * inv_m;
+    v = v * inv_s;
+    const int q = cvt_i32_f32(__builtin_rintf(v));
+    return min(max(q, -127), 127);
+}
+
+__device__ __forceinline__ uint32_t pack4(int a, int b, int c, int d) {
+    const uint32_t lo = __builtin_amdgcn_perm((uint32_t)b, (uint32_t)a, 0x0c0c0400u);  // a.b0 | b.b0 << 8
+    const uint32_t hi = __builtin_amdgcn_perm((uint32_t)d, (uint32_t)c, 0x0c0c0400u);
+    return __builtin_amdgcn_perm(hi, lo, 0x05040100u);
+}
+
+// Eight fp16 values (one 16-byte load) -> eight int8 codes.
+__device__ __forceinline__ u32x2 quantize_8(v4i raw, const float (&im)[8], float inv_s) {
+    int q[8];
+#pragma unroll
+    for (int e = 0; e < 4; e++) {
+        const int word = raw[e];  // (a bit_cast applied directly to a vector element reads element 0 with this compiler)
+        const __half2 h = __builtin_bit_cast(__half2, word);
+        q[2 * e] = quantize_one(__low2float(h), im[2 * e], inv_s);
+        q[2 * e + 1] = quantize_one(__high2float(h), im[2 * e + 1], inv_s);
+    }
+    u32x2 out = {pack4(q[0], q[1], q[2], q[3]), pack4(q[4], q[5], q[6], q[7])};
+    return out;
+}
+
+// ------------------------------------------------------------------------------------------
+// Skinny-N fused kernel.  One workgroup of 8 wavefronts per CU; LDS holds, for the whole kernel,
+//   the int8 weight (row pitch K + 16 bytes: the 16 rows of an MFMA operand read start 4 banks apart),
+//   inv_m[K], 1 / s_tok[L] (the only place the IEEE division appears), s_w[N] and the bias as fp32.
+// A wavefront owns units of 32 token rows.  Per k-step (64 codes = one 128-byte line of fp16 per
+// row) it fetches the unit's 32 lines with four loads (lane s: row 8 i + s / 8, 16-byte piece s mod 8,
+// so every request is a whole cache line), D k-steps ahead (D = 4, 2 or 1, the largest that divides K / 64); at consumption the eight fp16 of a
+// lane become eight codes, go through a wavefront-private 32 x 64-byte LDS tile (chunks XOR-swizzled
+// by the row) and come back as two MFMA operands (lane t: row t mod 16, 16 codes t / 16), which
+// meet the weight fragments of all ceil(N / 16) channel blocks in v_mfma_i32_16x16x64_i8.
+// There is no barrier after the set-up.  The epilogue is the dequantization of the PTS equation,
+// staged through the same private LDS region and written as whole contiguous row segments.
+// Requirements (host-checked): K % 64 == 0, 16-byte aligned fp16 rows and weight rows, N <= 128,
+// M, L < 2^31, all tables fit the LDS.
+// ------------------------------------------------------------------------------------------
+constexpr int kFusedWaves = 8;
+constexpr int kFusedMaxBlocks = 8;   // 16-channel blocks: N <= 128
+constexpr int kLdsBytes = 160 * 1024;
+constexpr int64_t kFusedMinRows = 16384;  // below this the one-off table copies per workgroup do not pay
+
+struct FusedLayout {
+    int nb, n4, pw, w_bytes, inv_m_off, inv_s_off, scale_off, tile_off, tile_bytes, total;
+};
+__host__ __device__ __forceinline__ FusedLayout fused_layout(int N, int K, int L) {
+    FusedLayout l;
+    l.nb = (N + 15) >> 4;
+    l.n4 = (N + 3) & ~3;
+    l.pw = K + 16;
+    l.w_bytes = (l.nb * 16 * l.pw + 1023) & ~1023;  // whole 1 KiB wavefront copies
+    l.inv_m_off = l.w_bytes;
+    l.inv_s_off = l.inv_m_off + K * 4;
+    l.scale_off = l.inv_s_off + ((L * 4 + 15) & ~15);
+    l.tile_off = l.scale_off + l.nb * 16 * 4 * 2;
+    const int patch = 16 * l.n4 * 2;                 // one 16-row block of fp16 results
+    l.tile_bytes = patch > 2048 ? patch : 2048;      // or the 32 x 64-byte tile of codes
+    l.total = l.tile_off + kFusedWaves * l.tile_bytes;
+    return l;
+}
+
+template <int NB, int D>
+__global__ __launch_bounds__(kFusedWaves * 64) void pts_linear_wres(const LinearArgs p) {
+    using Acc = v4i;
+
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int l16 = lane & 15, lq = lane >> 4;  // MFMA operand position: row, 16-code chunk
+    const int rr = lane >> 3, pc = lane & 7;    // load position: row within a group of 8, 16-byte piece
+    const int N = (int)p.N, K = (int)p.k_bytes, L = (int)p.L, n_ksteps = K >> 6;
+    const FusedLayout lay = fused_layout(N, K, L);
+    const int n4 = lay.n4, pw = lay.pw;
+    char *const w_lds = lds_dyn;
+    float *const inv_m_lds = reinterpret_cast<float *>(lds_dyn + lay.inv_m_off);
+    float *const inv_s_lds = reinterpret_cast<float *>(lds_dyn + lay.inv_s_off);
+    float *const cs_lds = reinterpret_cast<float *>(lds_dyn + lay.scale_off);
+    float *const cb_lds = cs_lds + NB * 16;
+    char *const tile = lds_dyn + lay.tile_off + wave * lay.tile_bytes;  // codes in the K loop, results after it
+
+    // Units are dealt wavefront-major, so that a launch with fewer units than wavefronts still
+    // spreads them over all workgroups.
+    const int64_t units = (p.M + 31) >> 5;
+    const int64_t unit_step = (int64_t)gridDim.x * kFusedWaves;
+    int64_t unit = (int64_t)wave * gridDim.x + blockIdx.x;
+
+    v4i raw[D][4];
+    const char *xrow[4];
+    uint32_t tok[4];
+    auto load_x = [&](int d, int ks) {
+#pragma unroll
+        for (int i = 0; i < 4; i++)
+            raw[d][i] = __builtin_nontemporal_load(reinterpret_cast<const v4i *>(xrow[i] + ks * 128));
+    };
+    auto start_unit = [&](int64_t u) {  // first D k-steps of the unit's 32 rows
+#pragma unroll
+        for (int i = 0; i < 4; i++) {
+            const int64_t r = min(u * 32 + i * 8 + rr, p.M - 1);  // clamped rows are never stored
+            xrow[i] = p.x + r * p.ldx_bytes + pc * 16;
+            tok[i] = (uint32_t)r % (uint32_t)L;
+        }
+#pragma unroll
+        for (int d = 0; d < D; d++) load_x(d, d);
+    };
+    if (unit < units) start_unit(unit);
+
+    // Tables, once per workgroup.  The weight goes global -> LDS in 1 KiB copies, linear on the LDS
+    // side; the lane picks the global chunk that belongs at its LDS position (pad chunks and pad
+    // rows re-read a valid neighbour).
+    {
+        const int chunks_per_row = pw >> 4;
+        for (int c = wave; c < (lay.w_bytes >> 10); c += kFusedWaves) {
+            const int chunk = c * 64 + lane;
+            const int row = chunk / chunks_per_row, cc = chunk - row * chunks_per_row;
+            const char *src = p.w + (int64_t)min(row, N - 1) * p.ldw_bytes + min(cc, chunks_per_row - 2) * 16;
+            __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void *)src,
+                                             (__attribute__((address_space(3))) void *)(w_lds + c * 1024), 16, 0, 0);
+        }
+        for (int k = tid; k < K; k += kFusedWaves * 64) inv_m_lds[k] = p.inv_m ? p.inv_m[k] : 1.0f;
+        for (int t = tid; t < L; t += kFusedWaves * 64) inv_s_lds[t] = 1.0f / p.s_tok[t];  // IEEE division
+        for (int o = tid; o < NB * 16; o += kFusedWaves * 64) {
+            cs_lds[o] = o < N ? p.s_w[o] : 0.0f;
+            cb_lds[o] = (o < N && p.bias) ? __half2float(p.bias[o]) : 0.0f;
+        }
+    }
+    __builtin_amdgcn_s_waitcnt(0);  // vmcnt(0) expcnt(0) lgkmcnt(0): this wavefront's copies have landed
+    __syncthreads();
+
+    const bool dense_y = n4 == N && p.ldy == p.N && (reinterpret_cast<uintptr_t>(p.y) & 15) == 0;
+    const int chunks8_per_row = n4 >> 2;  // 8-byte groups of four channels per result row
+    const char *const w_lane = w_lds + l16 * pw + lq * 16;
+    // Code tile: row pitch 64 bytes, 16-byte chunk c of row r stored at chunk position c ^ ((r >> 2) & 3).
+    uint32_t tile_wr[4];
+#pragma unroll
+    for (int i = 0; i < 4; i++) {
+        const int row = i * 8 + rr;
+        tile_wr[i] = row * 64 + (((pc >> 1) ^ ((row >> 2) & 3)) << 4) + (pc & 1) * 8;
+    }
+    const uint32_t tile_rd = l16 * 64 + ((lq ^ ((l16 >> 2) & 3)) << 4);  // + 1024 for rows 16..31
+
+    for (; unit < units; unit += unit_step) {
+        Acc acc[2][NB];
+#pragma unroll
+        for (int j = 0; j < 2; j++)
+#pragma unroll
+            for (int i = 0; i < NB; i++)
+#pragma unroll
+                for (int v = 0; v < 4; v++) acc[j][i][v] = 0;
+        float inv_s[4];
+#pragma unroll
+        for (int i = 0; i < 4; i++) inv_s[i] = inv_s_lds[tok[i]];
+        const int64_t r_unit = unit * 32;
+
+        auto compute = [&](int d, int ks) {
+            float im[8];
+            const v4f im_lo = *reinterpret_cast<const v4f *>(inv_m_lds + ks * 64 + pc * 8);
+            const v4f im_hi = *reinterpret_cast<const v4f *>(inv_m_lds + ks * 64 + pc * 8 + 4);
+#pragma unroll
+            for (int e = 0; e < 4; e++) im[e] = im_lo[e], im[4 + e] = im_hi[e];
+#pragma unroll
+            for (int i = 0; i < 4; i++) {
+                const u32x2 codes = quantize_8(raw[d][i], im, inv_s[i]);
+                *reinterpret_cast<u32x2 *>(tile + tile_wr[i]) = codes;
+                if (p.xq_out) {  // parity aid: the codes exactly as the MFMA will see them
+                    const int64_t r = r_unit + i * 8 + rr;
+                    if (r < p.M) *reinterpret_cast<u32x2 *>(p.xq_out + r * p.ldxq_out + ks * 64 + pc * 8) = codes;
+                }
+                __builtin_amdgcn_sched_barrier(0);  // one load's eight codes at a time: bounds the live registers
+            }
+            v4i fw[NB], fb[2];
+            fb[0] = *reinterpret_cast<const v4i *>(tile + tile_rd);
+            fb[1] = *reinterpret_cast<const v4i *>(tile + tile_rd + 1024);
+#pragma unroll
+            for (int i = 0; i < NB; i++) fw[i] = *reinterpret_cast<const v4i *>(w_lane + i * 16 * pw + ks * 64);
+            __builtin_amdgcn_sched_barrier(0);  // all LDS traffic of the k-step in flight before its first MFMA
+#pragma unroll
+            for (int i = 0; i < NB; i++) {
+                acc[0][i] = __builtin_amdgcn_mfma_i32_16x16x64_i8(fw[i], fb[0], acc[0][i], 0, 0, 0);
+                acc[1][i] = __builtin_amdgcn_mfma_i32_16x16x64_i8(fw[i], fb[1], acc[1][i], 0, 0, 0);
+            }
+        };
+        // The scheduling barriers keep each refill right behind the work that frees its registers;
+        // left alone the scheduler sinks all loads of a group to its end and the wavefront then
+        // waits for the whole group before every pass.
+        int ks0 = 0;
+        for (; ks0 + D < n_ksteps; ks0 += D) {  // every register slot is refilled (K is a multiple of 64 D)
+#pragma unroll
+            for (int d = 0; d < D; d++) {
+                compute(d, ks0 + d);
+                load_x(d, ks0 + d + D);
+                __builtin_amdgcn_sched_barrier(0);
+            }
+        }
+#pragma unroll
+        for (int d = 0; d < D; d++) {  // last group: drain
+            compute(d, ks0 + d);
+            __builtin_amdgcn_sched_barrier(0);
+        }
+
+        // Accumulator register v of block (j, i): token row 16 j + (lane mod 16), channel 16 i + 4 (lane / 16) + v.
+        float rs[2];
+#pragma unroll
+        for (int j = 0; j < 2; j++) rs[j] = p.s_tok[(uint32_t)min(r_unit + j * 16 + l16, p.M - 1) % (uint32_t)L];
+        const int64_t next = unit + unit_step;
+        if (next < units) start_unit(next);  // in flight while this unit's results are written
+
+#pragma unroll
+        for (int j = 0; j < 2; j++) {
+            const int64_t r0 = r_unit + j * 16;
+            const int rows_valid = (int)min((int64_t)16, p.M - r0);
+            if (rows_valid <= 0) break;
+#pragma unroll
+            for (int i = 0; i < NB; i++) {
+                const int col = i * 16 + lq * 4;
+                if (col < n4) {
+                    const v4f cs = *reinterpret_cast<const v4f *>(cs_lds + col);
+                    const v4f cb = *reinterpret_cast<const v4f *>(cb_lds + col);
+                    float out[4];
+#pragma unroll
+                    for (int c = 0; c < 4; c++) {
+                        const int a = acc[j][i][c];
+                        if (p.acc_out && l16 < rows_valid && col + c < N) p.acc_out[(r0 + l16) * p.N + col + c] = a;
+                        out[c] = (float)a * (rs[j] * cs[c]) + cb[c];
+                    }
+                    __half2 lo = __floats2half2_rn(out[0], out[1]);
+                    __half2 hi = __floats2half2_rn(out[2], out[3]);
+                    u32x2 packed = {__builtin_bit_cast(uint32_t, lo), __builtin_bit_cast(uint32_t, hi)};
+                    *reinterpret_cast<u32x2 *>(tile + l16 * (n4 * 2) + col * 2) = packed;
+                }
+            }
+            asm volatile("" ::: "memory");  // wavefront-private region: LDS runs a wavefront's accesses in order
+            if (dense_y) {
+                const int valid_bytes = rows_valid * N * 2, block_bytes = 32 * N;
+                char *dst = reinterpret_cast<char *>(p.y + r0 * p.N);
+                for (int off = lane * 16; off < block_bytes; off += 64 * 16) {
+                    const v4i data = *reinterpret_cast<const v4i *>(tile + off);
+                    if (off + 16 <= valid_bytes) {
+                        __builtin_nontemporal_store(data, reinterpret_cast<v4i *>(dst + off));
+                    } else {
+#pragma unroll
+                        for (int e = 0; e < 8; e++)
+                            if (off + 2 * e < valid_bytes)
+                                reinterpret_cast<uint16_t *>(dst + off)[e] = (uint16_t)((uint32_t)data[e >> 1] >> (16 * (e & 1)));
+                    }
+                }
+            } else {
+                for (int idx = lane; idx < 16 * chunks8_per_row; idx += 64) {
+                    const int row = idx / chunks8_per_row, cc = idx - row * chunks8_per_row;
+                    if (row >= rows_valid) continue;
+                    const u32x2 data = *reinterpret_cast<const u32x2 *>(tile + row * (n4 * 2) + cc * 8);
+                    __half *dst = p.y + (r0 + row) * p.ldy + cc * 4;
+                    if (p.y_vec >= 4 && cc * 4 + 4 <= N) {
+                        *reinterpret_cast<u32x2 *>(dst) = data;
+                    } else {
+#pragma unroll
+                        for (int e = 0; e < 4; e++)
+                            if (cc * 4 + e < N)
+                                reinterpret_cast<uint16_t *>(dst)[e] = (uint16_t)(data[e >> 1] >> (16 * (e & 1)));
+                    }
+                }
+            }
+            asm volatile("" ::: "memory");
+        }
+        // Stores and loads share the vmcnt counter and complete out of order with each other, so with
+        // stores possibly outstanding every wait on a fetched line would have to be a full drain.
+        // Drain once here instead: the next unit's first lines were fetched during the epilogue.
+        __builtin_amdgcn_s_waitcnt(0x0F70);  // vmcnt(0)
+    }
+}
+
+// ------------------------------------------------------------------------------------------
+// Generic fused kernel: the register-staged tiled kernel (4 wavefronts, BR x BO tile, 64-code
+// slabs, double-buffered LDS) whose activation loader reads fp16 and quantizes on the way to LDS.
+// Any shape, pitch and alignment (X_ALIGN / W_ALIGN: 16, 4 or 0 = element-wise).
+// ------------------------------------------------------------------------------------------
+// Sixteen codes of row `row_ptr` (fp16) starting at code index k0; codes at or beyond K are 0.
+template <int X_ALIGN>
+__device__ __forceinline__ v4i load_quantized_chunk(const char *row_ptr, int64_t k0, int64_t K, bool row_ok,
+                                                    const float *inv_m, float inv_s) {
+    v4i out = {0, 0, 0, 0};
+    if (!row_ok || k0 >= K) return out;
+    const int valid = (int)min((int64_t)16, K - k0);
+    uint32_t h2[8];  // 16 fp16 values, two per word
+#pragma unroll
+    for (int j = 0; j < 8; j++) h2[j] = 0;
+    const char *src = row_ptr + k0 * 2;
+    if constexpr (X_ALIGN == 16) {
+#pragma unroll
+        for (int j = 0; j < 2; j++)
+            if (8 * j < valid) {
+                const v4i v = *reinterpret_cast<const v4i *>(src + 16 * j);
+#pragma unroll
+                for (int e = 0; e < 4; e++) h2[4 * j + e] = (uint32_t)v[e];
+            }
+    } else if constexpr (X_ALIGN == 4) {
+#pragma unroll
+        for (int j = 0; j < 8; j++)
+            if (2 * j < valid) h2[j] = *reinterpret_cast<const uint32_t *>(src + 4 * j);
+    } else {
+#pragma unroll
+        for (int j = 0; j < 16; j++)
+            if (j < valid) h2[j >> 1] |= (uint32_t) * reinterpret_cast<const uint16_t *>(src + 2 * j) << (16 * (j & 1));
+    }
+    int q[16];
+#pragma unroll
+    for (int j = 0; j < 16; j++) {
+        const float m = (inv_m && j < valid) ? inv_m[k0 + j] : 1.0f;
+        const __half h = __builtin_bit_cast(__half, (uint16_t)(h2[j >> 1] >> (16 * (j & 1))));
+        q[j] = j < valid ? quantize_one(__half2float(h), m, inv_s) : 0;
+    }
+#pragma unroll
+    for (int j = 0; j < 4; j++) out[j] = (int)pack4(q[4 * j], q[4 * j + 1], q[4 * j + 2], q[4 * j + 3]);
+    return out;
+}
+
+template <int BR, int BO, int WR, int WO, int X_ALIGN, int W_ALIGN>
+__global__ __launch_bounds__(kThreads, 2) void pts_linear_generic(const LinearArgs p) {
+    using Path = Int8Path;
+    static_assert(WR * WO == kWaves, "four wavefronts per workgroup");
+    constexpr int WAVE_R = BR / WR, WAVE_O = BO / WO;
+    constexpr int FR = WAVE_R / 32, FO = WAVE_O / 32;
+    static_assert(WAVE_R % 32 == 0 && WAVE_O % 32 == 0, "wave tile must be whole MFMA blocks");
+    static_assert(BR * 4 % kThreads == 0, "every thread stages the same rows in every slab");
+    constexpr int X_CHUNKS = BR * 4 / kThreads;  // 16-code chunks per thread per slab
+    constexpr int W_CHUNKS = (BO * 4 + kThreads - 1) / kThreads;
+    using Acc = typename Path::Acc;
+
+    __shared__ __attribute__((aligned(16))) char lds_x[2][BR * kSlabBytes];
+    __shared__ __attribute__((aligned(16))) char lds_w[2][BO * kSlabBytes];
+    constexpr int JB = (FR % 2 == 0 && kWaves * 64 * WAVE_O * 2 <= 2 * BR * kSlabBytes) ? 2 : 1;
+    static_assert(kWaves * JB * 32 * WAVE_O * 2 <= 2 * BR * kSlabBytes, "epilogue patches must fit the activation buffers");
+
+    int tile_r, tile_o;
+    if (!tile_of_block(p, tile_r, tile_o)) return;
+    const int64_t r0 = (int64_t)tile_r * BR, o0 = (int64_t)tile_o * BO;
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int wave_r = (wave / WO) * WAVE_R, wave_o = (wave % WO) * WAVE_O;
+    const int l32 = lane & 31, lhalf = lane >> 5;
+
+    Acc acc[FO][FR];
+#pragma unroll
+    for (int i = 0; i < FO; i++)
+#pragma unroll
+        for (int j = 0; j < FR; j++)
+#pragma unroll
+            for (int v = 0; v < 16; v++) acc[i][j][v] = 0;
+
+    // A thread stages the same X_CHUNKS rows in every slab: their reciprocal steps are computed once.
+    float inv_s[X_CHUNKS];
+#pragma unroll
+    for (int i = 0; i < X_CHUNKS; i++) {
+        const int64_t r = r0 + ((tid + kThreads * i) >> 2);
+        inv_s[i] = 1.0f / p.s_tok[(r < p.M ? r : 0) % p.L];  // IEEE division
+    }
+
+    v4i stage_x[X_CHUNKS], stage_w[W_CHUNKS];
+    auto fetch = [&](int64_t kb0) {
+#pragma unroll
+        for (int i = 0; i < X_CHUNKS; i++) {
+            const int cid = tid + kThreads * i, row = cid >> 2, kc = cid & 3;
+            const bool ok = r0 + row < p.M;
+            stage_x[i] = load_quantized_chunk<X_ALIGN>(p.x + (r0 + row) * p.ldx_bytes, kb0 + kc * 16, p.k_bytes, ok,
+                                                       p.inv_m, inv_s[i]);
+            if (p.xq_out && tile_o == 0 && ok) {  // parity aid: the codes exactly as the MFMA will see them
+#pragma unroll
+                for (int b = 0; b < 16; b++)
+                    if (kb0 + kc * 16 + b < p.k_bytes)
+                        p.xq_out[(r0 + row) * p.ldxq_out + kb0 + kc * 16 + b] = (int8_t)((uint32_t)stage_x[i][b >> 2] >> (8 * (b & 3)));
+            }
+        }
+#pragma unroll
+        for (int i = 0; i < W_CHUNKS; i++) {
+            const int cid = tid + kThreads * i, row = cid >> 2, kc = cid & 3;
+            const bool ok = (cid < BO * 4) && (o0 + row < p.N);
+            stage_w[i] = load_chunk<W_ALIGN, 1>(p.w + (o0 + row) * p.ldw_bytes, kb0 + kc * 16, p.k_bytes, ok);
+        }
+    };
+    auto commit = [&](int buf) {
+#pragma unroll
+        for (int i = 0; i < X_CHUNKS; i++) {
+            const int cid = tid + kThreads * i, row = cid >> 2, kc = cid & 3;
+            *reinterpret_cast<v4i *>(&lds_x[buf][row * kSlabBytes + ((kc ^ swizzle(row)) << 4)]) = stage_x[i];
+        }
+#pragma unroll
+        for (int i = 0; i < W_CHUNKS; i++) {
+            const int cid = tid + kThreads * i, row = cid >> 2, kc = cid & 3;
+            if (cid < BO * 4)
+                *reinterpret_cast<v4i *>(&lds_w[buf][row * kSlabBytes + ((kc ^ swizzle(row)) << 4)]) = stage_w[i];
+        }
+    };
+
+    const int n_slabs = (int)((p.k_bytes + kSlabBytes - 1) / kSlabBytes);
+    fetch(0);
+    commit(0);
+    __syncthreads();
+    for (int it = 0; it < n_slabs; it++) {
+        const int buf = it & 1;
+        const bool more = it + 1 < n_slabs;
+        if (more) fetch((int64_t)(it + 1) * kSlabBytes);
+        mfma_slab<Path, FO, FR>(acc, &lds_x[buf][wave_r * kSlabBytes], &lds_w[buf][wave_o * kSlabBytes], l32, lhalf);
+        if (more) commit(buf ^ 1);
+        __syncthreads();
+    }
+    epilogue<Path, FO, FR, JB>(acc, p, &lds_x[0][0] + wave * (JB * 32 * WAVE_O * 2), r0 + wave_r, o0 + wave_o, lane);
+}
+
+// ------------------------------------------------------------------------------------------
+// Host side
+// ------------------------------------------------------------------------------------------
+int launch_wres(const LinearArgs &a, hipStream_t stream) {
+    const FusedLayout lay = fused_layout((int)a.N, (int)a.k_bytes, (int)a.L);
+    int device = 0, cus = 0;
+    hipError_t err = hipGetDevice(&device);
+    if (err == hipSuccess) err = hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, device);
+    if (err != hipSuccess) return ptq4vm::record_hip_error(err, "hipDeviceGetAttribute(multiprocessor count)");
+    if (cus < 1) cus = 1;
+    const int64_t units = ptq4vm::ceil_div(a.M, 32);
+    int64_t wgs = ptq4vm::ceil_div(units, kFusedWaves);
+    if (wgs > cus) wgs = cus;  // one workgroup per CU: the resident tables take most of its LDS
+    using Kernel = void (*)(const LinearArgs);
+#define PTQ4VM_WRES_ROW(D) \
+    {pts_linear_wres<1, D>, pts_linear_wres<2, D>, pts_linear_wres<3, D>, pts_linear_wres<4, D>, \
+     pts_linear_wres<5, D>, pts_linear_wres<6, D>, pts_linear_wres<7, D>, pts_linear_wres<8, D>}
+    // [k-steps in flight: 4, 2, 1][number of 16-channel blocks - 1]
+    static const Kernel kernels[3][kFusedMaxBlocks] = {PTQ4VM_WRES_ROW(4), PTQ4VM_WRES_ROW(2), PTQ4VM_WRES_ROW(1)};
+#undef PTQ4VM_WRES_ROW
+    static bool configured = false;  // raising the dynamic-LDS limit is a per-function, idempotent setting
+    if (!configured) {
+        for (int d = 0; d < 3; d++)
+            for (int i = 0; i < kFusedMaxBlocks; i++) {
+                err = hipFuncSetAttribute(reinterpret_cast<const void *>(kernels[d][i]),
+                                          hipFuncAttributeMaxDynamicSharedMemorySize, kLdsBytes);
+                if (err != hipSuccess) return ptq4vm::record_hip_error(err, "hipFuncSetAttribute(pts_linear_wres)");
+            }
+        configured = true;
+    }
+    const int n_ksteps = (int)(a.k_bytes / 64);
+    // four k-steps in flight need too many registers next to the accumulators of 7 or 8 channel blocks
+    const int depth_row = (n_ksteps % 4 == 0 && lay.nb <= 6) ? 0 : (n_ksteps % 2 == 0 ? 1 : 2);
+    kernels[depth_row][lay.nb - 1]<<<dim3((unsigned)wgs), dim3(kFusedWaves * 64), lay.total, stream>>>(a);
+    return ptq4vm::check_launch("pts_linear_wres");
+}
+
+template <int BR, int BO, int WR, int WO>
+int launch_generic(LinearArgs a, int x_align, int w_align, hipStream_t stream) {
+    dim3 grid;
+    if (!set_grid<BR, BO>(a, grid)) return PTQ4VM_ERR_SHAPE;
+    const dim3 block(kThreads);
+#define PTQ4VM_LAUNCH(XA, WA) pts_linear_generic<BR, BO, WR, WO, XA, WA><<<grid, block, 0, stream>>>(a)
+    if (x_align == 16 && w_align == 16) PTQ4VM_LAUNCH(16, 16);
+    else if (x_align == 16 && w_align == 4) PTQ4VM_LAUNCH(16, 4);
+    else if (x_align == 16) PTQ4VM_LAUNCH(16, 0);
+    else if (x_align == 4 && w_align == 16) PTQ4VM_LAUNCH(4, 16);
+    else if (x_align == 4 && w_align == 4) PTQ4VM_LAUNCH(4, 4);
+    else if (x_align == 4) PTQ4VM_LAUNCH(4, 0);
+    else if (w_align == 16) PTQ4VM_LAUNCH(0, 16);
+    else if (w_align == 4) PTQ4VM_LAUNCH(0, 4);
+    else PTQ4VM_LAUNCH(0, 0);
+#undef PTQ4VM_LAUNCH
+    return ptq4vm::check_launch("pts_linear_generic");
+}
+
+int dispatch(LinearArgs a, hipStream_t stream) {
+    auto align_of = [](const void *base, int64_t pitch_bytes) {
+        if (ptq4vm::aligned_to(base, 16) && pitch_bytes % 16 == 0) return 16;
+        if (ptq4vm::aligned_to(base, 4) && pitch_bytes % 4 == 0) return 4;
+        return 0;
+    };
+    const int xa = align_of(a.x, a.ldx_bytes), wa = align_of(a.w, a.ldw_bytes);
+    a.y_vec = (a.ldy % 8 == 0 && ptq4vm::aligned_to(a.y, 16)) ? 8
+              : ((a.ldy % 4 == 0 && ptq4vm::aligned_to(a.y, 8)) ? 4 : 1);
+    const bool small = a.M < (1LL << 31) && a.L < (1LL << 31) && a.k_bytes < (1LL << 20);
+    const bool wres_ok = small && xa == 16 && wa == 16 && a.k_bytes % 64 == 0 && a.N <= 16 * kFusedMaxBlocks &&
+                         a.M >= kFusedMinRows && a.L <= 65536 &&
+                         (!a.xq_out || (ptq4vm::aligned_to(a.xq_out, 8) && a.ldxq_out % 8 == 0)) &&
+                         fused_layout((int)a.N, (int)a.k_bytes, (int)a.L).total <= kLdsBytes;
+    if (wres_ok) return launch_wres(a, stream);
+    if (a.N > 64) return launch_generic<256, 128, 2, 2>(a, xa, wa, stream);
+    return launch_generic<256, 64, 4, 1>(a, xa, wa, stream);
+}
+
+}  // namespace
+
+extern "C" int ptq4vm_w8a8_linear_fused(const void *x_f16, const float *inv_m, const float *s_tok, const int8_t *wq,
+                                        const float *s_w, const void *bias_f16, void *y_f16, int32_t *acc_out,
+                                        int8_t *xq_out, int64_t B, int64_t L, int64_t K, int64_t N, int64_t ldx,
+                                        int64_t ldwq, int64_t ldy, int64_t ldxq, void *stream_) {
+    if (!x_f16 || !s_tok || !wq || !s_w || !y_f16) return PTQ4VM_ERR_NULL;
+    if (B < 0 || N < 0 || L <= 0 || K <= 0 || K > PTQ4VM_MAX_K) return PTQ4VM_ERR_SHAPE;
+    if (B > 0 && L > INT64_MAX / B) return PTQ4VM_ERR_SHAPE;
+    if (ldx < K || ldwq < K || ldy < N || (xq_out && ldxq < K)) return PTQ4VM_ERR_STRIDE;
+    if (!ptq4vm::aligned_to(x_f16, 16) || !ptq4vm::aligned_to(wq, 16) || !ptq4vm::aligned_to(y_f16, 2) ||
+        !ptq4vm::aligned_to(inv_m, 4) || !ptq4vm::aligned_to(s_tok, 4) || !ptq4vm::aligned_to(s_w, 4) ||
+        !ptq4vm::aligned_to(bias_f16, 2) || !ptq4vm::aligned_to(acc_out, 4))
+        return PTQ4VM_ERR_ALIGN;
+    const int64_t M = B * L;
+    if (M == 0 || N == 0) return PTQ4VM_OK;
+    LinearArgs a{};
+    a.x = static_cast<const char *>(x_f16);
+    a.w = reinterpret_cast<const char *>(wq);
+    a.s_tok = s_tok;
+    a.s_w = s_w;
+    a.bias = static_cast<const __half *>(bias_f16);
+    a.y = static_cast<__half *>(y_f16);
+    a.acc_out = acc_out;
+    a.M = M;
+    a.N = N;
+    a.k_bytes = K;
+    a.ldx_bytes = ldx * 2;
+    a.ldw_bytes = ldwq;
+    a.ldy = ldy;
+    a.L = L;
+    a.inv_m = inv_m;
+    a.xq_out = xq_out;
+    a.ldxq_out = ldxq;
+    return dispatch(a, static_cast<hipStream_t>(stream_));
+}

@@ -87,6 +87,28 @@ def test_w8a8_linear_argument_checks(lib):
     assert call(a7=0) == 0 and call(a10=0, a13=0) == 0       # empty problem
 
 
+def test_w8a8_linear_fused_argument_checks(lib):
+    f = lib.ptq4vm_w8a8_linear_fused
+    #     x  inv_m s_tok wq s_w bias y acc  xq   B  L  K   N   ldx ldwq ldy ldxq stream
+    ok = [P, P, P, P, P, P, P, NULL, NULL, 1, 1, 16, 16, 16, 16, 16, 0, None]
+
+    def call(**kw):
+        a = list(ok)
+        for i, v in kw.items():
+            a[int(i[1:])] = v
+        return f(*a)
+
+    assert call(a0=NULL) == -1 and call(a2=NULL) == -1 and call(a3=NULL) == -1
+    assert call(a4=NULL) == -1 and call(a6=NULL) == -1
+    assert call(a9=-1) == -2 and call(a10=0) == -2 and call(a11=0) == -2 and call(a12=-1) == -2
+    assert call(a11=133144, a13=133144, a14=133144) == -2    # int32 accumulator could overflow
+    assert call(a13=15) == -3 and call(a14=15) == -3 and call(a15=15) == -3
+    assert call(a8=P, a16=15) == -3                          # copy of the codes requested with too small a pitch
+    assert call(a0=ODD) == -4 and call(a3=ODD) == -4 and call(a1=ctypes.c_void_p(0x1002)) == -4
+    assert call(a6=ctypes.c_void_p(0x1001)) == -4
+    assert call(a9=0) == 0 and call(a12=0, a15=0) == 0       # empty problem
+
+
 def test_fold_and_f16_argument_checks(lib):
     f = lib.ptq4vm_fold_smoothing
     assert f(NULL, P, P, P, P, 1, 8, 8, 8, None) == -1

@@ -328,3 +328,107 @@ def test_skinny_output_whole_result():
 @pytest.mark.parametrize("M,K,N", [(16517, 192, 44), (16400, 512, 80)])
 def test_f16_linear_skinny_output(M, K, N):
     test_f16_linear_within_accumulation_bound(M, K, N)
+
+
+# ---------------------------------------------------------------------------------- fused quantizer + linear
+def _run_fused_case(c, use_bias=True, use_m=True, ldy=None, what=""):
+    """ptq4vm_w8a8_linear_fused on the GPU vs the oracle's quantizer -> GEMM -> dequantization chain."""
+    print(f"fused {what} B={c.B} L={c.L} K={c.K} N={c.N} bias={use_bias} m={use_m} ldy={ldy}", flush=True)
+    M = c.B * c.L
+    m = c.m if use_m else torch.ones_like(c.m)
+    wq, s_w, inv_m = ptq.fold_smoothing(c.w, m)
+    bias = c.bias if use_bias else None
+    acc = torch.full((M, c.N), -1, dtype=torch.int32, device=DEV)
+    xq = torch.full((M, c.K), 0x55, dtype=torch.int8, device=DEV)
+    ybuf = None
+    if ldy is None:
+        y = ptq.w8a8_linear_fused(c.x, inv_m if use_m else None, c.s_tok, wq, s_w, bias, c.B, c.L, acc_out=acc, xq_out=xq)
+    else:
+        ybuf, yv = _padded(M, c.N, ldy, torch.float16, 12345.0)
+        y = ptq.w8a8_linear_fused(c.x, inv_m if use_m else None, c.s_tok, wq, s_w, bias, c.B, c.L, y=yv, acc_out=acc,
+                                  xq_out=xq)
+    y2 = ptq.w8a8_linear_fused(c.x, inv_m if use_m else None, c.s_tok, wq, s_w, bias, c.B, c.L)  # timed configuration
+    torch.cuda.synchronize()
+
+    wq_o, s_w_o, inv_m_o = oracle.fold_smoothing(_np(c.w), _np(m))
+    xq_o = oracle.quantize_pts(_np(c.x), inv_m_o if use_m else None, _np(c.s_tok), c.B, c.L)
+    b_o = _np(c.bias) if use_bias else None
+    y_o, y64, acc_o = oracle.w8a8_linear(xq_o, wq_o, _np(c.s_tok), s_w_o, b_o, c.B, c.L)
+    assert np.array_equal(_np(wq), wq_o)
+    assert np.array_equal(_np(xq), xq_o), "int8 codes differ"
+    assert np.array_equal(_np(acc), acc_o), "int32 accumulators differ"
+    st = np.tile(_np(c.s_tok).astype(np.float64), c.B)[:, None]
+    prod_abs = np.abs(acc_o.astype(np.float64) * st * s_w_o.astype(np.float64)[None, :])
+    bias_abs = np.broadcast_to(np.abs(b_o.astype(np.float64))[None, :] if use_bias else 0.0, prod_abs.shape)
+    stats = check_dequantized_output(_np(y), y_o, y64, prod_abs, bias_abs, what)
+    assert np.array_equal(_np(y).view(np.uint16), _np(y2).view(np.uint16)), "the parity outputs change the result"
+    if ybuf is not None:
+        assert np.all(_np(ybuf[:, c.N:]) == np.float16(12345.0))
+    return stats
+
+
+FUSED_SHAPES = [  # B, L, K, N: the tiled kernel with the quantizer in its loader
+    (3, 197, 384, 192),
+    (2, 197, 384, 44),
+    (3, 197, 12, 384),    # dt_proj (Vim-Ti): 24-byte fp16 rows
+    (2, 50, 768, 56),
+    (1, 1, 64, 32),
+    (1, 257, 100, 130),   # K a multiple of 4 only
+    (2, 33, 13, 5),       # nothing aligned
+    (1, 129, 1000, 257),
+    (5, 7, 16, 1),
+]
+
+
+@pytest.mark.parametrize("B,L,K,N", FUSED_SHAPES)
+def test_fused_linear_shapes(B, L, K, N):
+    c = synth.random_problem(57 * K + N, B, L, K, N, device=DEV)
+    _run_fused_case(c, what="fused-adhoc")
+
+
+def test_fused_linear_config0_and_options():
+    c = synth.make_linear_case(0, device=DEV)
+    assert c.clipped > 0
+    _run_fused_case(c, what="fused-config0")
+    _run_fused_case(c, use_bias=False, use_m=False, what="fused-plain")
+    _run_fused_case(c, ldy=c.N + 8, what="fused-ldy")
+
+
+FUSED_SKINNY = [  # B, L, K, N, ldy, bias, m: weight-resident fused kernel (N <= 128, >= 16384 rows)
+    (83, 199, 128, 44, None, True, True),     # 2 k-steps (depth 2); 88-byte dense rows; M mod 32 = 5
+    (64, 257, 320, 80, None, False, True),    # 5 k-steps (depth 1)
+    (70, 241, 1024, 128, None, True, True),   # 16 k-steps, 8 channel blocks (depth 2); M mod 32 = 6
+    (83, 199, 768, 50, None, True, False),    # 12 k-steps (depth 4); N not a multiple of 4; no smoothing
+    (83, 199, 1536, 72, 80, True, True),      # padded output rows
+    (66, 250, 1600, 16, None, True, True),    # 25 k-steps (depth 1); one channel block; M mod 32 = 20
+]
+
+
+@pytest.mark.parametrize("B,L,K,N,ldy,bias,use_m", FUSED_SKINNY)
+def test_fused_linear_skinny_whole_result(B, L, K, N, ldy, bias, use_m):
+    """Every code, accumulator and output of a weight-resident fused launch against the oracle."""
+    c = synth.random_problem(1234 + K + N, B, L, K, N, device=DEV)
+    _run_fused_case(c, use_bias=bias, use_m=use_m, ldy=ldy, what="fused-skinny")
+
+
+@pytest.mark.parametrize("cfg,linear", [(3, 1), (3, 2), (1, 1), (2, 1), (4, 1)])
+def test_fused_linear_full_size_matches_two_call_path(cfg, linear):
+    """Full-size x_proj / dt_proj: the fused launch must reproduce, bit for bit, the two-call path
+    (itself checked against the oracle above on sampled rows), and the oracle on sampled rows."""
+    c = synth.make_linear_case(cfg, 0, linear, device=DEV)
+    print(f"fused full-size cfg{cfg} {c.name}: M={c.B * c.L} K={c.K} N={c.N}", flush=True)
+    wq, s_w, inv_m = ptq.fold_smoothing(c.w, c.m)
+    xq = ptq.quantize_pts(c.x, inv_m, c.s_tok, c.B, c.L)
+    y_two = ptq.w8a8_linear(xq, wq, c.s_tok, s_w, c.bias, c.B, c.L)
+    y = ptq.w8a8_linear_fused(c.x, inv_m, c.s_tok, wq, s_w, c.bias, c.B, c.L)
+    torch.cuda.synchronize()
+    assert torch.equal(y.view(torch.int16), y_two.view(torch.int16))
+    rows = _sampled_rows(c.B * c.L, 97, c.L)
+    ridx = torch.from_numpy(rows).to(DEV)
+    wq_o, s_w_o, inv_m_o = oracle.fold_smoothing(_np(c.w), _np(c.m))
+    st_rows = _np(c.s_tok)[rows % c.L]
+    xq_o = oracle.quantize_pts(_np(c.x[ridx]), inv_m_o, st_rows, 1, len(rows))
+    y_o, y64, acc_o = oracle.w8a8_linear(xq_o, wq_o, st_rows, s_w_o, _np(c.bias), 1, len(rows))
+    prod_abs = np.abs(acc_o.astype(np.float64) * st_rows.astype(np.float64)[:, None] * s_w_o.astype(np.float64)[None, :])
+    bias_abs = np.broadcast_to(np.abs(_np(c.bias).astype(np.float64))[None, :], prod_abs.shape)
+    check_dequantized_output(_np(y[ridx]), y_o, y64, prod_abs, bias_abs, f"fused cfg{cfg} {c.name}")
