@@ -6,8 +6,11 @@ A "step" is one pass of the hot path over one synthetic batch of the Vim-B-shape
 (in_proj 768->3072, x_proj 1536->80, dt_proj 48->1536, out_proj 1536->768; M = 256*197 rows)
   ptq4vm_quantize_pts  (fp16 -> int8, per-token static step, smoothing folded in)
   ptq4vm_w8a8_linear   (int8 MFMA GEMM + fused dequantization + bias -> fp16)
-i.e. 96 + 96 launches.  Weight folding/quantization is offline (done once in setup, like the
-paper's stored INT8 weights) and is not timed.  All inputs are resident in HBM before the
+or, where an activation element is quantized exactly once anyway (K <= 128 or N <= 128: x_proj,
+dt_proj), the single launch ptq4vm_w8a8_linear_fused, which computes the same codes and outputs
+bit for bit without writing the codes to memory (--fused off times the two-launch form
+everywhere).  Weight folding/quantization is offline (done once in setup, like the paper's stored
+INT8 weights) and is not timed.  All inputs are resident in HBM before the
 timed region; every layer has its own buffers (~1.1 GB per layer), so the working set of a step
 (~27 GB) cannot sit in the 256 MB last-level cache.
 
@@ -42,6 +45,8 @@ def main() -> int:
     ap.add_argument("--warmup", type=int, default=5)
     ap.add_argument("--config", type=int, default=3, help="workload config (BASELINE.json configs index)")
     ap.add_argument("--layers", type=int, default=None, help="override the number of layers (debug only)")
+    ap.add_argument("--fused", choices=("auto", "off"), default="auto",
+                    help="auto: one fused quantize+linear launch for linears with K <= 128 or N <= 128")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-sample-batch", type=int, default=256)
     args = ap.parse_args()
@@ -73,7 +78,8 @@ def main() -> int:
         for li, (name, K, N) in enumerate(cfg.linears):
             c = synth.make_linear_case(args.config, layer, li, device=dev)
             wq, s_w, inv_m = ptq.fold_smoothing(c.w, c.m)  # offline weight preparation
-            lin.append(dict(name=name, K=K, N=N, x=c.x, w=c.w, bias=c.bias, s_tok=c.s_tok, wq=wq, s_w=s_w,
+            lin.append(dict(name=name, K=K, N=N, fused=(args.fused == "auto" and (K <= 128 or N <= 128)),
+                            x=c.x, w=c.w, bias=c.bias, s_tok=c.s_tok, wq=wq, s_w=s_w,
                             inv_m=inv_m, xq=torch.empty((M, K), dtype=torch.int8, device=dev),
                             y=torch.empty((M, N), dtype=torch.float16, device=dev)))
         layers.append(lin)
@@ -83,6 +89,9 @@ def main() -> int:
     def step_w8a8(events=None):
         for lin in layers:
             for d in lin:
+                if d["fused"]:
+                    ptq.w8a8_linear_fused(d["x"], d["inv_m"], d["s_tok"], d["wq"], d["s_w"], d["bias"], B, L, y=d["y"])
+                    continue
                 ptq.quantize_pts(d["x"], d["inv_m"], d["s_tok"], B, L, xq=d["xq"])
                 if events is not None and d["name"] == events["name"]:
                     a = torch.cuda.Event(enable_timing=True)
@@ -138,6 +147,11 @@ def main() -> int:
         tg = time_launch(lambda lin: ptq.w8a8_linear(lin[li]["xq"], lin[li]["wq"], lin[li]["s_tok"], lin[li]["s_w"],
                                                     lin[li]["bias"], B, L, y=lin[li]["y"]))
         tf = time_launch(lambda lin: ptq.f16_linear(lin[li]["x"], lin[li]["w"], lin[li]["bias"], y=lin[li]["y"]))
+        tfu = None
+        if layers[0][li]["fused"]:
+            tfu = time_launch(lambda lin: ptq.w8a8_linear_fused(lin[li]["x"], lin[li]["inv_m"], lin[li]["s_tok"],
+                                                                lin[li]["wq"], lin[li]["s_w"], lin[li]["bias"], B, L,
+                                                                y=lin[li]["y"]))
         ops = 2.0 * M * K * N
         q_bytes = 3.0 * M * K + 4 * K + 4 * L
         g_bytes = 1.0 * M * K + N * K + 2.0 * M * N + 4 * L + 6 * N
@@ -150,6 +164,13 @@ def main() -> int:
             w8a8_GBps=round(g_bytes / tg / 1e3, 1), w8a8_frac_hbm=round(g_bytes / tg / 1e3 / PEAK_HBM_GBS, 4),
             f16_us=round(tf, 2), f16_TFLOPS=round(ops / tf / 1e6, 1),
             speedup_gemm_only=round(tf / tg, 3), speedup_quant_plus_gemm=round(tf / (tq + tg), 3)))
+        if tfu is not None:  # the form the timed step uses for this linear
+            f_bytes = 2.0 * M * K + N * K + 2.0 * M * N + 4 * K + 4 * L + 6 * N
+            kernels[-1].update(in_timed_step="fused", fused_us=round(tfu, 2), fused_GBps=round(f_bytes / tfu / 1e3, 1),
+                               fused_frac_hbm=round(f_bytes / tfu / 1e3 / PEAK_HBM_GBS, 4),
+                               speedup_fused=round(tf / tfu, 3))
+        else:
+            kernels[-1].update(in_timed_step="quantize + w8a8")
         f16_total_us += tf
         w8_total_us += tg
         q_total_us += tq
@@ -219,7 +240,11 @@ def main() -> int:
         "data": "synthetic",
         "config": {"workload": f"configs[{args.config}] {cfg.name}: {n_layers} layers x "
                                f"{[f'{n} {k}->{o}' for n, k, o in cfg.linears]}, B={B}, L={L}, M={M}; "
-                               "step = 96 PTS-quantize + 96 W8A8-linear launches, fold offline"},
+                               + ("step = per layer PTS-quantize + W8A8-linear for in_proj and out_proj, one fused "
+                                  "quantize+linear launch for x_proj and dt_proj (same codes and outputs, bit for bit); "
+                                  if args.fused == "auto" else "step = 96 PTS-quantize + 96 W8A8-linear launches; ")
+                               + "fold offline",
+                   "fused_linears": [d["name"] for d in layers[0] if d["fused"]]},
         "tops": round(total_ops / (ms_per_step * 1e-3) / 1e12, 1),
         "speedup_vs_f16_stack": round(f16_ms_per_step / ms_per_step, 3),
         "f16_ms_per_step": round(f16_ms_per_step, 4),

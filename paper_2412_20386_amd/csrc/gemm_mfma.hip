@@ -27,6 +27,10 @@
 // stores are 16 bytes per lane and cover whole contiguous row segments.
 #include "mfma_linear.hpp"
 
+#ifndef PTQ4VM_STREAM_SMALLK
+#define PTQ4VM_STREAM_SMALLK 1
+#endif
+
 namespace {
 
 using namespace ptq4vm::mfma;
@@ -1117,6 +1121,14 @@ int dispatch(LinearArgs a, hipStream_t stream) {
               : ((a.ldy % 4 == 0 && ptq4vm::aligned_to(a.y, 8)) ? 4 : 1);
     const bool dma_ok = la == 16 && a.k_bytes % kSlabBytes == 0 && a.ldx_bytes * 256 < (1LL << 31) &&
                         a.ldw_bytes * 256 < (1LL << 31);
+#if PTQ4VM_STREAM_SMALLK
+    if constexpr (Path::kElemBytes == 1) {
+        if (a.k_bytes <= 128) {  // many rows: whole rows of y streamed out by one wavefront each
+            const int rc = launch_stream_smallk(a, false, stream);
+            if (rc <= 0) return rc;
+        }
+    }
+#endif
     if (a.k_bytes <= 128 && la >= 4 && a.L < (1LL << 31))
         return la == 16 ? launch_smallk_ksteps<Path, 16>(a, stream) : launch_smallk_ksteps<Path, 4>(a, stream);
     const bool persistent_ok = dma_ok && a.N % 8 == 0 && a.y_vec == 8 && ptq4vm::aligned_to(a.bias, 4) &&

@@ -270,5 +270,12 @@ inline bool set_grid(LinearArgs &a, dim3 &grid) {
     return true;
 }
 
+
+// Row-streaming kernel for short reductions (K <= 128), defined next to the fused kernels.
+// quantize: x holds fp16 activations and inv_m / xq_out are honoured; otherwise x holds int8 codes.
+// Returns PTQ4VM_OK after a launch, a negative status on error, or 1 if the shape does not fit
+// this kernel (nothing was launched; the caller picks another one).
+int launch_stream_smallk(const LinearArgs &a, bool quantize, hipStream_t stream);
+
 }  // namespace mfma
 }  // namespace ptq4vm

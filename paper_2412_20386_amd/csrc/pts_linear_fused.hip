@@ -99,7 +99,8 @@ template <int NB, int D>
 __global__ __launch_bounds__(kFusedWaves * 64) void pts_linear_wres(const LinearArgs p) {
     using Acc = v4i;
 
-    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int tid = threadIdx.x, lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);  // scalar: unit numbers and row bounds stay in SGPRs
     const int l16 = lane & 15, lq = lane >> 4;  // MFMA operand position: row, 16-code chunk
     const int rr = lane >> 3, pc = lane & 7;    // load position: row within a group of 8, 16-byte piece
     const int N = (int)p.N, K = (int)p.k_bytes, L = (int)p.L, n_ksteps = K >> 6;
@@ -302,11 +303,6 @@ __global__ __launch_bounds__(kFusedWaves * 64) void pts_linear_wres(const Linear
     }
 }
 
-// ------------------------------------------------------------------------------------------
-// Generic fused kernel: the register-staged tiled kernel (4 wavefronts, BR x BO tile, 64-code
-// slabs, double-buffered LDS) whose activation loader reads fp16 and quantizes on the way to LDS.
-// Any shape, pitch and alignment (X_ALIGN / W_ALIGN: 16, 4 or 0 = element-wise).
-// ------------------------------------------------------------------------------------------
 // Sixteen codes of row `row_ptr` (fp16) starting at code index k0; codes at or beyond K are 0.
 template <int X_ALIGN>
 __device__ __forceinline__ v4i load_quantized_chunk(const char *row_ptr, int64_t k0, int64_t K, bool row_ok,
@@ -347,6 +343,192 @@ __device__ __forceinline__ v4i load_quantized_chunk(const char *row_ptr, int64_t
     return out;
 }
 
+// ------------------------------------------------------------------------------------------
+// Short-reduction kernel (K <= 128, e.g. dt_proj 48 -> 1536): almost all traffic is the fp16
+// output, so the kernel is arranged around the stores.  One workgroup of 8 wavefronts per CU; LDS
+// holds the whole int8 weight (64 or 128 bytes per channel, 16-byte chunks XOR-swizzled by the row),
+// s_w and the bias as fp32.  A wavefront owns units of 16 token rows and ALL output channels of
+// them: it reads (and, fused, quantizes) the unit's activations once into two MFMA operands, then
+// walks over the channels 64 at a time - weight fragments and scales from LDS, v_mfma_i32_16x16x64_i8,
+// dequantization, transposition through a private 4 KiB LDS patch, 16-byte non-temporal stores of
+// whole 128-byte lines.  A unit's output is one contiguous 32-row span of y written by one
+// wavefront within a few microseconds.  No barrier after the set-up.
+// QUANT: activations are fp16 and pass through the PTS quantizer; otherwise they are int8 codes.
+// Any pitch and alignment (X_ALIGN / W_ALIGN: 16, 4 or 0 = element-wise loads).
+// ------------------------------------------------------------------------------------------
+#ifndef PTQ4VM_STREAM_RB
+#define PTQ4VM_STREAM_RB 1
+#endif
+constexpr int kStreamRB = PTQ4VM_STREAM_RB;       // 16-row MFMA blocks per unit
+constexpr int kStreamWaves = 16 / kStreamRB;      // wavefronts per workgroup
+constexpr int kStreamPatch = 2048 * kStreamRB;    // bytes of the per-wavefront transposition patch
+constexpr int64_t kStreamMinRows = 4096;
+
+struct StreamLayout {
+    int groups, rows, pitch, w_bytes, scale_off, patch_off, total;
+};
+__host__ __device__ __forceinline__ StreamLayout stream_layout(int N, int ksteps) {
+    StreamLayout l;
+    l.groups = (N + 63) >> 6;      // 64-channel groups
+    l.rows = l.groups * 64;        // weight rows in LDS, zero beyond N
+    l.pitch = 64 * ksteps;
+    l.w_bytes = l.rows * l.pitch;
+    l.scale_off = l.w_bytes;
+    l.patch_off = l.scale_off + l.rows * 8;
+    l.total = l.patch_off + kStreamWaves * kStreamPatch;
+    return l;
+}
+
+template <int KSTEPS, bool QUANT, int X_ALIGN, int W_ALIGN>
+__global__ __launch_bounds__(kStreamWaves * 64) void linear_stream_smallk(const LinearArgs p) {
+    const int tid = threadIdx.x, lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);  // scalar: unit numbers and row bounds stay in SGPRs
+    const int l16 = lane & 15, lq = lane >> 4;
+    const int N = (int)p.N, K = (int)p.k_bytes;
+    const StreamLayout lay = stream_layout(N, KSTEPS);
+    char *const w_lds = lds_dyn;
+    float *const cs_lds = reinterpret_cast<float *>(lds_dyn + lay.scale_off);
+    float *const cb_lds = cs_lds + lay.rows;
+    char *const patch = lds_dyn + lay.patch_off + wave * kStreamPatch;
+    constexpr int RB = kStreamRB, UNIT = 16 * RB;
+    auto swz = [](int row) { return KSTEPS == 1 ? ((row >> 2) & 3) : ((row >> 1) & 3); };
+
+    // Set-up: weight (zero beyond N and K), scales, bias.
+    {
+        constexpr int CPR = 4 * KSTEPS;  // 16-byte chunks per weight row
+        for (int idx = tid; idx < lay.rows * CPR; idx += kStreamWaves * 64) {
+            const int row = idx / CPR, c = idx - row * CPR;
+            const v4i v = load_chunk<W_ALIGN, 1>(p.w + (int64_t)min(row, N - 1) * p.ldw_bytes, c * 16, K, row < N);
+            *reinterpret_cast<v4i *>(w_lds + row * lay.pitch + ((c ^ swz(row)) << 4)) = v;
+        }
+        for (int o = tid; o < lay.rows; o += kStreamWaves * 64) {
+            cs_lds[o] = o < N ? p.s_w[o] : 0.0f;
+            cb_lds[o] = (o < N && p.bias) ? __half2float(p.bias[o]) : 0.0f;
+        }
+    }
+    __syncthreads();
+
+    const int64_t units = (p.M + UNIT - 1) / UNIT;
+    const int64_t unit_step = (int64_t)gridDim.x * kStreamWaves;
+    const bool y_wide = p.y_vec == 8;
+    auto patch_chunk = [&](int row, int chunk) { return row * 128 + ((chunk ^ (row & 7)) << 4); };
+
+    for (int64_t unit = (int64_t)wave * gridDim.x + blockIdx.x; unit < units; unit += unit_step) {
+        const int64_t r_unit = unit * UNIT;
+        // ---- the unit's two activation operands (lane: row 16 jb + lane mod 16, codes 64 ks + 16 (lane / 16) ..)
+        v4i fx[RB][KSTEPS];
+        float rs[RB];
+#pragma unroll
+        for (int jb = 0; jb < RB; jb++) {
+            const int64_t r = min(r_unit + jb * 16 + l16, p.M - 1);  // clamped rows are never stored
+            const float step = p.s_tok[(uint32_t)r % (uint32_t)p.L];
+            rs[jb] = step;
+            const char *xrow = p.x + r * p.ldx_bytes;
+#pragma unroll
+            for (int ks = 0; ks < KSTEPS; ks++) {
+                const int k0 = 64 * ks + 16 * lq;
+                if constexpr (QUANT) {
+                    const float inv_s = 1.0f / step;  // IEEE division
+                    const v4i codes = load_quantized_chunk<X_ALIGN>(xrow, k0, K, true, p.inv_m, inv_s);
+                    if (p.xq_out && r_unit + jb * 16 + l16 < p.M) {  // parity aid
+#pragma unroll
+                        for (int b = 0; b < 16; b++)
+                            if (k0 + b < K) p.xq_out[r * p.ldxq_out + k0 + b] = (int8_t)((uint32_t)codes[b >> 2] >> (8 * (b & 3)));
+                    }
+                    fx[jb][ks] = codes;
+                } else {
+                    fx[jb][ks] = load_chunk<X_ALIGN, 1>(xrow, k0, K, true);
+                }
+            }
+        }
+
+        // ---- all output channels, 64 at a time
+        for (int g = 0; g < lay.groups; g++) {
+            v4i acc[RB][4];
+            v4f cs[4], cb[4];
+#pragma unroll
+            for (int i = 0; i < 4; i++) {
+                const int row = g * 64 + i * 16 + l16;
+                v4i fw[KSTEPS];
+#pragma unroll
+                for (int ks = 0; ks < KSTEPS; ks++)
+                    fw[ks] = *reinterpret_cast<const v4i *>(w_lds + row * lay.pitch + (((4 * ks + lq) ^ swz(row)) << 4));
+                cs[i] = *reinterpret_cast<const v4f *>(cs_lds + g * 64 + i * 16 + lq * 4);
+                cb[i] = *reinterpret_cast<const v4f *>(cb_lds + g * 64 + i * 16 + lq * 4);
+#pragma unroll
+                for (int jb = 0; jb < RB; jb++) {
+                    v4i a = {0, 0, 0, 0};
+#pragma unroll
+                    for (int ks = 0; ks < KSTEPS; ks++) a = __builtin_amdgcn_mfma_i32_16x16x64_i8(fw[ks], fx[jb][ks], a, 0, 0, 0);
+                    acc[jb][i] = a;
+                }
+            }
+            const int cols_valid = min(64, N - g * 64);
+            // Accumulator register v of block (jb, i): token row 16 jb + (lane mod 16), channel 64 g + 16 i + 4 (lane / 16) + v.
+            if (p.acc_out) {  // parity aid, off the timed path
+#pragma unroll
+                for (int jb = 0; jb < RB; jb++)
+#pragma unroll
+                    for (int i = 0; i < 4; i++)
+#pragma unroll
+                        for (int c = 0; c < 4; c++) {
+                            const int64_t r = r_unit + jb * 16 + l16;
+                            const int col = i * 16 + lq * 4 + c;
+                            if (r < p.M && col < cols_valid) p.acc_out[r * p.N + g * 64 + col] = acc[jb][i][c];
+                        }
+            }
+#pragma unroll
+            for (int jb = 0; jb < RB; jb++)
+#pragma unroll
+                for (int i = 0; i < 4; i++) {
+                    float out[4];
+#pragma unroll
+                    for (int c = 0; c < 4; c++) out[c] = (float)acc[jb][i][c] * (rs[jb] * cs[i][c]) + cb[i][c];
+                    __half2 lo = __floats2half2_rn(out[0], out[1]);
+                    __half2 hi = __floats2half2_rn(out[2], out[3]);
+                    u32x2 packed = {__builtin_bit_cast(uint32_t, lo), __builtin_bit_cast(uint32_t, hi)};
+                    *reinterpret_cast<u32x2 *>(patch + patch_chunk(jb * 16 + l16, 2 * i + (lq >> 1)) + (lq & 1) * 8) = packed;
+                }
+            asm volatile("" ::: "memory");  // wavefront-private patch: LDS runs a wavefront's accesses in order
+            if (y_wide && cols_valid == 64 && r_unit + UNIT <= p.M) {  // uniform: whole lines, no per-lane tests
+                __half *dst = p.y + (r_unit + (lane >> 3)) * p.ldy + g * 64 + (lane & 7) * 8;
+#pragma unroll
+                for (int s = 0; s < 2 * RB; s++) {  // 8 rows x 128 bytes per store instruction
+                    const v4i data = *reinterpret_cast<const v4i *>(patch + patch_chunk(s * 8 + (lane >> 3), lane & 7));
+                    __builtin_nontemporal_store(data, reinterpret_cast<v4i *>(dst + s * 8 * p.ldy));
+                }
+            } else
+#pragma unroll
+            for (int s = 0; s < 2 * RB; s++) {
+                const int row = s * 8 + (lane >> 3), chunk = lane & 7;
+                const v4i data = *reinterpret_cast<const v4i *>(patch + patch_chunk(row, chunk));
+                const int64_t rr = r_unit + row;
+                if (rr < p.M) {
+                    __half *dst = p.y + rr * p.ldy + g * 64 + chunk * 8;
+                    if (y_wide && chunk * 8 + 8 <= cols_valid) {
+                        __builtin_nontemporal_store(data, reinterpret_cast<v4i *>(dst));
+                    } else if (p.y_vec >= 4 && chunk * 8 + 8 <= cols_valid) {
+                        u32x2 a = {(uint32_t)data[0], (uint32_t)data[1]}, b = {(uint32_t)data[2], (uint32_t)data[3]};
+                        *reinterpret_cast<u32x2 *>(dst) = a;
+                        *reinterpret_cast<u32x2 *>(dst + 4) = b;
+                    } else {
+#pragma unroll
+                        for (int e = 0; e < 8; e++)
+                            if (chunk * 8 + e < cols_valid)
+                                reinterpret_cast<uint16_t *>(dst)[e] = (uint16_t)((uint32_t)data[e >> 1] >> (16 * (e & 1)));
+                    }
+                }
+            }
+            asm volatile("" ::: "memory");
+        }
+    }
+}
+
+// ------------------------------------------------------------------------------------------
+// Generic fused kernel: the register-staged tiled kernel (4 wavefronts, BR x BO tile, 64-code
+// slabs, double-buffered LDS) whose activation loader reads fp16 and quantizes on the way to LDS.
+// Any shape, pitch and alignment (X_ALIGN / W_ALIGN: 16, 4 or 0 = element-wise).
+// ------------------------------------------------------------------------------------------
 template <int BR, int BO, int WR, int WO, int X_ALIGN, int W_ALIGN>
 __global__ __launch_bounds__(kThreads, 2) void pts_linear_generic(const LinearArgs p) {
     using Path = Int8Path;
@@ -441,6 +623,32 @@ __global__ __launch_bounds__(kThreads, 2) void pts_linear_generic(const LinearAr
 // ------------------------------------------------------------------------------------------
 // Host side
 // ------------------------------------------------------------------------------------------
+template <int KSTEPS, bool QUANT>
+int launch_stream_aligned(const LinearArgs &a, int xa, int wa, const StreamLayout &lay, unsigned wgs, hipStream_t stream) {
+    using Kernel = void (*)(const LinearArgs);
+    // [activation alignment 16 / 4 / 0][weight alignment 16 / 4 / 0]
+    static const Kernel kernels[3][3] = {
+        {linear_stream_smallk<KSTEPS, QUANT, 16, 16>, linear_stream_smallk<KSTEPS, QUANT, 16, 4>,
+         linear_stream_smallk<KSTEPS, QUANT, 16, 0>},
+        {linear_stream_smallk<KSTEPS, QUANT, 4, 16>, linear_stream_smallk<KSTEPS, QUANT, 4, 4>,
+         linear_stream_smallk<KSTEPS, QUANT, 4, 0>},
+        {linear_stream_smallk<KSTEPS, QUANT, 0, 16>, linear_stream_smallk<KSTEPS, QUANT, 0, 4>,
+         linear_stream_smallk<KSTEPS, QUANT, 0, 0>}};
+    static bool configured = false;  // raising the dynamic-LDS limit is a per-function, idempotent setting
+    if (!configured) {
+        for (int i = 0; i < 3; i++)
+            for (int j = 0; j < 3; j++) {
+                hipError_t err = hipFuncSetAttribute(reinterpret_cast<const void *>(kernels[i][j]),
+                                                     hipFuncAttributeMaxDynamicSharedMemorySize, kLdsBytes);
+                if (err != hipSuccess) return ptq4vm::record_hip_error(err, "hipFuncSetAttribute(linear_stream_smallk)");
+            }
+        configured = true;
+    }
+    auto idx = [](int al) { return al == 16 ? 0 : (al == 4 ? 1 : 2); };
+    kernels[idx(xa)][idx(wa)]<<<dim3(wgs), dim3(kStreamWaves * 64), lay.total, stream>>>(a);
+    return ptq4vm::check_launch("linear_stream_smallk");
+}
+
 int launch_wres(const LinearArgs &a, hipStream_t stream) {
     const FusedLayout lay = fused_layout((int)a.N, (int)a.k_bytes, (int)a.L);
     int device = 0, cus = 0;
@@ -509,11 +717,40 @@ int dispatch(LinearArgs a, hipStream_t stream) {
                          (!a.xq_out || (ptq4vm::aligned_to(a.xq_out, 8) && a.ldxq_out % 8 == 0)) &&
                          fused_layout((int)a.N, (int)a.k_bytes, (int)a.L).total <= kLdsBytes;
     if (wres_ok) return launch_wres(a, stream);
+    if (a.k_bytes <= 128) {
+        const int rc = launch_stream_smallk(a, true, stream);
+        if (rc <= 0) return rc;
+    }
     if (a.N > 64) return launch_generic<256, 128, 2, 2>(a, xa, wa, stream);
     return launch_generic<256, 64, 4, 1>(a, xa, wa, stream);
 }
 
 }  // namespace
+
+int ptq4vm::mfma::launch_stream_smallk(const LinearArgs &a, bool quantize, hipStream_t stream) {
+    auto align_of = [](const void *base, int64_t pitch_bytes) {
+        if (ptq4vm::aligned_to(base, 16) && pitch_bytes % 16 == 0) return 16;
+        if (ptq4vm::aligned_to(base, 4) && pitch_bytes % 4 == 0) return 4;
+        return 0;
+    };
+    const int xa = align_of(a.x, a.ldx_bytes), wa = align_of(a.w, a.ldw_bytes);
+    if (a.k_bytes > 128 || a.M < kStreamMinRows || a.M >= (1LL << 31) || a.L >= (1LL << 31) || a.N > 8192) return 1;
+    const int ksteps = a.k_bytes <= 64 ? 1 : 2;
+    const StreamLayout lay = stream_layout((int)a.N, ksteps);
+    if (lay.total > kLdsBytes) return 1;
+    int device = 0, cus = 0;
+    hipError_t err = hipGetDevice(&device);
+    if (err == hipSuccess) err = hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, device);
+    if (err != hipSuccess) return ptq4vm::record_hip_error(err, "hipDeviceGetAttribute(multiprocessor count)");
+    if (cus < 1) cus = 1;
+    int64_t wgs = ptq4vm::ceil_div(ptq4vm::ceil_div(a.M, 16 * kStreamRB), kStreamWaves);
+    if (wgs > cus) wgs = cus;  // one workgroup per CU: the resident weight takes most of its LDS
+    if (quantize)
+        return ksteps == 1 ? launch_stream_aligned<1, true>(a, xa, wa, lay, (unsigned)wgs, stream)
+                           : launch_stream_aligned<2, true>(a, xa, wa, lay, (unsigned)wgs, stream);
+    return ksteps == 1 ? launch_stream_aligned<1, false>(a, xa, wa, lay, (unsigned)wgs, stream)
+                       : launch_stream_aligned<2, false>(a, xa, wa, lay, (unsigned)wgs, stream);
+}
 
 extern "C" int ptq4vm_w8a8_linear_fused(const void *x_f16, const float *inv_m, const float *s_tok, const int8_t *wq,
                                         const float *s_w, const void *bias_f16, void *y_f16, int32_t *acc_out,
