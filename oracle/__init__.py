@@ -14,4 +14,12 @@ from .ptq4vm_oracle import (  # noqa: F401
     dequant,
     w8a8_linear,
     f16_linear,
+    quantize_dynamic,
+    fold_smoothing_bits,
+    quantize_pts_bits,
+    pack_int4,
+    unpack_int4,
+    quantize_pts_offset,
+    weight_rowsum,
+    dequant_offset,
 )

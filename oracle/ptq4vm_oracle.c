@@ -20,6 +20,22 @@
  *                           (+ bias), evaluated in double, rounded once to fp16.
  *   oracle_f16_linear       the unquantized FP16 linear the paper's latency table compares to.
  *
+ *   oracle_quantize_dynamic per-token dynamic quantization, the comparison scheme of Sec. 4 and of the
+ *                           latency table of Sec. 6.3: the step of a token row is computed online
+ *                           from that row (after smoothing), s_r = max_k|v| / 127.
+ *   oracle_fold_smoothing_bits / oracle_quantize_pts_bits
+ *                           the same quantizers at b bits (Sec. 2.3: clip to +-(2^(b-1) - 1)); b = 4
+ *                           is the W4A4 setting of the paper's latency table.
+ *   oracle_pack_int4 / oracle_unpack_int4
+ *                           two adjacent 4-bit codes per byte, the even index in the low nibble
+ *                           (App. B.1 "Quantization").
+ *   oracle_quantize_pts_offset / oracle_weight_rowsum / oracle_dequant_offset
+ *                           PTS with the per-token zero offset that Sec. 5.1 mentions and then
+ *                           omits; the offset form is the activation quantizer of Sec. 2.3
+ *                           (clip(round(X / Delta) + eps, 0, 2^b - 1)) with the code range shifted
+ *                           by 128 so that codes are int8: q = clip(rint(v) + z, -128, 127),
+ *                           x-hat = s (q - z), and sum_k (q - z) w = acc - z * rowsum(w).
+ *
  * Readings where the paper is silent (all stated again in the design notes):
  *   - rounding is round-half-to-even; clip range is [-127, 127] for weights and activations;
  *   - the integer decision of the activation quantizer is taken in fp32 in this exact order:
@@ -221,6 +237,158 @@ void oracle_f16_linear(const uint16_t *x_f16, const uint16_t *w_f16, const uint1
             if (y64_out) y64_out[r * N + o] = s;
             if (abs_sum_out) abs_sum_out[r * N + o] = a;
             y_f16[r * N + o] = double_to_half_bits(s);
+        }
+    }
+}
+
+
+/* ---- per-token dynamic activation quantizer (Sec. 4; the "Per-token dynamic" rows of the latency
+ * table, Sec. 6.3).  Every row gets its own step from its own smoothed values:
+ *   v[k] = f32(x[r,k]) * inv_m[k];  s_r = max_k |v[k]| / 127 (1 if the row is all zero; NaNs do not
+ *   take part in the maximum);  q = clip(rint(v * (1 / s_r)), -127, 127), all in fp32. ---- */
+void oracle_quantize_dynamic(const uint16_t *x_f16, const float *inv_m /* NULL => all ones */,
+                             int8_t *xq, float *s_row, int64_t M, int64_t K) {
+#pragma omp parallel for schedule(static)
+    for (int64_t r = 0; r < M; r++) {
+        float amax = 0.0f;
+        for (int64_t k = 0; k < K; k++) {
+            float v = half_bits_to_float(x_f16[r * K + k]);
+            if (inv_m) v = v * inv_m[k];
+            float a = fabsf(v);
+            if (a > amax) amax = a;
+        }
+        float step = (amax == 0.0f) ? 1.0f : amax / 127.0f;
+        float inv_s = 1.0f / step;
+        s_row[r] = step;
+        for (int64_t k = 0; k < K; k++) {
+            float v = half_bits_to_float(x_f16[r * K + k]);
+            if (inv_m) v = v * inv_m[k];
+            v = v * inv_s;
+            float q = rintf(v);
+            if (q != q) q = 0.0f;
+            if (q > 127.0f) q = 127.0f;
+            if (q < -127.0f) q = -127.0f;
+            xq[r * K + k] = (int8_t)q;
+        }
+    }
+}
+
+/* ---- b-bit forms of a0 and a1 (Sec. 2.3: codes clipped to +-qmax, qmax = 2^(b-1) - 1).  Codes are
+ * returned one per int8; packing is a separate step. ---- */
+void oracle_fold_smoothing_bits(const uint16_t *w_f16, const float *m, int8_t *wq, float *s_w,
+                                float *inv_m, int64_t N, int64_t K, int qmax) {
+    const float fq = (float)qmax;
+    for (int64_t k = 0; k < K; k++) inv_m[k] = 1.0f / m[k];
+#pragma omp parallel for schedule(static)
+    for (int64_t o = 0; o < N; o++) {
+        float amax = 0.0f;
+        for (int64_t k = 0; k < K; k++) {
+            float a = fabsf(half_bits_to_float(w_f16[o * K + k]) * m[k]);
+            if (a > amax) amax = a;
+        }
+        float step = (amax == 0.0f) ? 1.0f : amax / fq;
+        s_w[o] = step;
+        for (int64_t k = 0; k < K; k++) {
+            float wf = half_bits_to_float(w_f16[o * K + k]) * m[k];
+            float q = rintf(wf / step);
+            if (q != q) q = 0.0f;
+            if (q > fq) q = fq;
+            if (q < -fq) q = -fq;
+            wq[o * K + k] = (int8_t)q;
+        }
+    }
+}
+
+void oracle_quantize_pts_bits(const uint16_t *x_f16, const float *inv_m, const float *s_tok,
+                              int8_t *xq, int64_t B, int64_t L, int64_t K, int qmax) {
+    const float fq = (float)qmax;
+    int64_t M = B * L;
+#pragma omp parallel for schedule(static)
+    for (int64_t r = 0; r < M; r++) {
+        float inv_s = 1.0f / s_tok[r % L];
+        for (int64_t k = 0; k < K; k++) {
+            float v = half_bits_to_float(x_f16[r * K + k]);
+            if (inv_m) v = v * inv_m[k];
+            v = v * inv_s;
+            float q = rintf(v);
+            if (q != q) q = 0.0f;
+            if (q > fq) q = fq;
+            if (q < -fq) q = -fq;
+            xq[r * K + k] = (int8_t)q;
+        }
+    }
+}
+
+/* ---- INT4 packing (App. B.1): byte j of a row holds codes 2j (low nibble) and 2j + 1 (high
+ * nibble), each in two's complement.  K must be even. ---- */
+void oracle_pack_int4(const int8_t *codes, uint8_t *packed, int64_t rows, int64_t K) {
+    for (int64_t r = 0; r < rows; r++)
+        for (int64_t j = 0; j < K / 2; j++) {
+            int lo = codes[r * K + 2 * j], hi = codes[r * K + 2 * j + 1];
+            packed[r * (K / 2) + j] = (uint8_t)(((hi & 15) << 4) | (lo & 15));
+        }
+}
+
+void oracle_unpack_int4(const uint8_t *packed, int8_t *codes, int64_t rows, int64_t K) {
+    for (int64_t r = 0; r < rows; r++)
+        for (int64_t j = 0; j < K / 2; j++) {
+            int b = packed[r * (K / 2) + j];
+            int lo = b & 15, hi = b >> 4;
+            codes[r * K + 2 * j] = (int8_t)(lo >= 8 ? lo - 16 : lo);
+            codes[r * K + 2 * j + 1] = (int8_t)(hi >= 8 ? hi - 16 : hi);
+        }
+}
+
+/* ---- PTS with a per-token zero offset (Sec. 5.1 names it, the PTS equation omits it; Sec. 2.3
+ * gives the offset quantizer).  z_tok[t] is the int8-range offset of token position t:
+ *   q = clip(rint((f32(x) * inv_m[k]) * (1 / s_tok[t])) + z_tok[t], -128, 127),  x-hat = s_tok[t] (q - z_tok[t]). ---- */
+void oracle_quantize_pts_offset(const uint16_t *x_f16, const float *inv_m, const float *s_tok,
+                                const int32_t *z_tok, int8_t *xq, int64_t B, int64_t L, int64_t K) {
+    int64_t M = B * L;
+#pragma omp parallel for schedule(static)
+    for (int64_t r = 0; r < M; r++) {
+        float inv_s = 1.0f / s_tok[r % L];
+        int64_t z = z_tok[r % L];
+        for (int64_t k = 0; k < K; k++) {
+            float v = half_bits_to_float(x_f16[r * K + k]);
+            if (inv_m) v = v * inv_m[k];
+            v = v * inv_s;
+            float q = rintf(v);
+            if (q != q) q = 0.0f;
+            if (q > 1.0e6f) q = 1.0e6f;   /* keep the integer sum below in range; the clip follows */
+            if (q < -1.0e6f) q = -1.0e6f;
+            int64_t c = (int64_t)q + z;
+            if (c > 127) c = 127;
+            if (c < -128) c = -128;
+            xq[r * K + k] = (int8_t)c;
+        }
+    }
+}
+
+/* rowsum[o] = sum_k wq[o,k]: what the offset multiplies in  sum_k (q - z) w = sum_k q w - z rowsum. */
+void oracle_weight_rowsum(const int8_t *wq, int32_t *rowsum, int64_t N, int64_t K) {
+    for (int64_t o = 0; o < N; o++) {
+        int64_t s = 0;
+        for (int64_t k = 0; k < K; k++) s += wq[o * K + k];
+        rowsum[o] = (int32_t)s;
+    }
+}
+
+/* Y[r,o] = fp16( (acc - z_tok[r mod L] * rowsum[o]) * s_tok[r mod L] * s_w[o] + bias[o] ), in double. */
+void oracle_dequant_offset(const int32_t *acc, const float *s_tok, const int32_t *z_tok,
+                           const int32_t *rowsum, const float *s_w, const uint16_t *bias_f16,
+                           uint16_t *y_f16, double *y64_out, int64_t B, int64_t L, int64_t N) {
+    int64_t M = B * L;
+#pragma omp parallel for schedule(static)
+    for (int64_t r = 0; r < M; r++) {
+        double st = (double)s_tok[r % L];
+        int64_t z = z_tok[r % L];
+        for (int64_t o = 0; o < N; o++) {
+            int64_t corrected = (int64_t)acc[r * N + o] - z * (int64_t)rowsum[o];
+            double y = (double)corrected * st * (double)s_w[o];
+            if (bias_f16) y += (double)half_bits_to_float(bias_f16[o]);
+            if (y64_out) y64_out[r * N + o] = y;
+            y_f16[r * N + o] = double_to_half_bits(y);
         }
     }
 }

@@ -54,6 +54,22 @@ def _load():
         lib.oracle_dequant.argtypes = [vp, vp, vp, vp, vp, vp, i64, i64, i64]
         lib.oracle_f16_linear.restype = None
         lib.oracle_f16_linear.argtypes = [vp, vp, vp, vp, vp, vp, i64, i64, i64]
+        lib.oracle_quantize_dynamic.restype = None
+        lib.oracle_quantize_dynamic.argtypes = [vp, vp, vp, vp, i64, i64]
+        lib.oracle_fold_smoothing_bits.restype = None
+        lib.oracle_fold_smoothing_bits.argtypes = [vp, vp, vp, vp, vp, i64, i64, ctypes.c_int]
+        lib.oracle_quantize_pts_bits.restype = None
+        lib.oracle_quantize_pts_bits.argtypes = [vp, vp, vp, vp, i64, i64, i64, ctypes.c_int]
+        lib.oracle_pack_int4.restype = None
+        lib.oracle_pack_int4.argtypes = [vp, vp, i64, i64]
+        lib.oracle_unpack_int4.restype = None
+        lib.oracle_unpack_int4.argtypes = [vp, vp, i64, i64]
+        lib.oracle_quantize_pts_offset.restype = None
+        lib.oracle_quantize_pts_offset.argtypes = [vp, vp, vp, vp, vp, i64, i64, i64]
+        lib.oracle_weight_rowsum.restype = None
+        lib.oracle_weight_rowsum.argtypes = [vp, vp, i64, i64]
+        lib.oracle_dequant_offset.restype = None
+        lib.oracle_dequant_offset.argtypes = [vp, vp, vp, vp, vp, vp, vp, vp, i64, i64, i64]
         _lib = lib
     return _lib
 
@@ -159,3 +175,101 @@ def f16_linear(x: np.ndarray, w: np.ndarray, bias: Optional[np.ndarray]):
     asum = np.empty((M, N), np.float64)
     _load().oracle_f16_linear(_p(x), _p(w), _p(bias), _p(y), _p(y64), _p(asum), M, K, N)
     return y, y64, asum
+
+
+# ---------------------------------------------------------------------------------- widened rows
+def quantize_dynamic(x: np.ndarray, inv_m: Optional[np.ndarray]) -> Tuple[np.ndarray, np.ndarray]:
+    """Per-token dynamic quantizer: (Xq int8 [M,K], s_row fp32 [M]) from X fp16 [M,K]."""
+    x = _arr(x, np.float16)
+    M, K = x.shape
+    inv_m = None if inv_m is None else _arr(inv_m, np.float32, (K,))
+    xq = np.empty((M, K), np.int8)
+    s_row = np.empty(M, np.float32)
+    _load().oracle_quantize_dynamic(_p(x), _p(inv_m), _p(xq), _p(s_row), M, K)
+    return xq, s_row
+
+
+def fold_smoothing_bits(w: np.ndarray, m: np.ndarray, bits: int) -> Tuple[np.ndarray, np.ndarray, np.ndarray]:
+    """b-bit weight fold: codes (one per int8) in [-(2^(b-1)-1), 2^(b-1)-1], s_w, inv_m."""
+    w = _arr(w, np.float16)
+    N, K = w.shape
+    m = _arr(m, np.float32, (K,))
+    wq = np.empty((N, K), np.int8)
+    s_w = np.empty(N, np.float32)
+    inv_m = np.empty(K, np.float32)
+    _load().oracle_fold_smoothing_bits(_p(w), _p(m), _p(wq), _p(s_w), _p(inv_m), N, K, (1 << (bits - 1)) - 1)
+    return wq, s_w, inv_m
+
+
+def quantize_pts_bits(x: np.ndarray, inv_m: Optional[np.ndarray], s_tok: np.ndarray, B: int, L: int,
+                      bits: int) -> np.ndarray:
+    """b-bit PTS codes, one per int8."""
+    x = _arr(x, np.float16)
+    M, K = x.shape
+    if M != B * L:
+        raise ValueError("x must have B*L rows")
+    inv_m = None if inv_m is None else _arr(inv_m, np.float32, (K,))
+    s_tok = _arr(s_tok, np.float32, (L,))
+    xq = np.empty((M, K), np.int8)
+    _load().oracle_quantize_pts_bits(_p(x), _p(inv_m), _p(s_tok), _p(xq), B, L, K, (1 << (bits - 1)) - 1)
+    return xq
+
+
+def pack_int4(codes: np.ndarray) -> np.ndarray:
+    """[rows, K] int8 codes in [-8, 7] -> [rows, K/2] bytes, even index in the low nibble."""
+    codes = _arr(codes, np.int8)
+    rows, K = codes.shape
+    if K % 2:
+        raise ValueError("K must be even")
+    packed = np.empty((rows, K // 2), np.uint8)
+    _load().oracle_pack_int4(_p(codes), _p(packed), rows, K)
+    return packed
+
+
+def unpack_int4(packed: np.ndarray) -> np.ndarray:
+    packed = _arr(packed, np.uint8)
+    rows, half = packed.shape
+    codes = np.empty((rows, 2 * half), np.int8)
+    _load().oracle_unpack_int4(_p(packed), _p(codes), rows, 2 * half)
+    return codes
+
+
+def quantize_pts_offset(x: np.ndarray, inv_m: Optional[np.ndarray], s_tok: np.ndarray, z_tok: np.ndarray,
+                        B: int, L: int) -> np.ndarray:
+    """PTS codes with a per-token zero offset z_tok int32 [L] (int8 range): clip(rint(v) + z, -128, 127)."""
+    x = _arr(x, np.float16)
+    M, K = x.shape
+    if M != B * L:
+        raise ValueError("x must have B*L rows")
+    inv_m = None if inv_m is None else _arr(inv_m, np.float32, (K,))
+    s_tok = _arr(s_tok, np.float32, (L,))
+    z_tok = _arr(z_tok, np.int32, (L,))
+    xq = np.empty((M, K), np.int8)
+    _load().oracle_quantize_pts_offset(_p(x), _p(inv_m), _p(s_tok), _p(z_tok), _p(xq), B, L, K)
+    return xq
+
+
+def weight_rowsum(wq: np.ndarray) -> np.ndarray:
+    wq = _arr(wq, np.int8)
+    N, K = wq.shape
+    out = np.empty(N, np.int32)
+    _load().oracle_weight_rowsum(_p(wq), _p(out), N, K)
+    return out
+
+
+def dequant_offset(acc: np.ndarray, s_tok: np.ndarray, z_tok: np.ndarray, rowsum: np.ndarray, s_w: np.ndarray,
+                   bias: Optional[np.ndarray], B: int, L: int) -> Tuple[np.ndarray, np.ndarray]:
+    """(Y fp16, y64) = (acc - z_tok[r mod L] * rowsum[o]) * s_tok[r mod L] * s_w[o] + bias[o]."""
+    acc = _arr(acc, np.int32)
+    M, N = acc.shape
+    if M != B * L:
+        raise ValueError("acc must have B*L rows")
+    s_tok = _arr(s_tok, np.float32, (L,))
+    z_tok = _arr(z_tok, np.int32, (L,))
+    rowsum = _arr(rowsum, np.int32, (N,))
+    s_w = _arr(s_w, np.float32, (N,))
+    bias = None if bias is None else _arr(bias, np.float16, (N,))
+    y = np.empty((M, N), np.float16)
+    y64 = np.empty((M, N), np.float64)
+    _load().oracle_dequant_offset(_p(acc), _p(s_tok), _p(z_tok), _p(rowsum), _p(s_w), _p(bias), _p(y), _p(y64), B, L, N)
+    return y, y64

@@ -500,6 +500,7 @@ __global__ __launch_bounds__(BO * 2, 2) void linear_mfma_persistent(const Linear
             if (full_tile) {
 #pragma unroll
                 for (int q = 0; q < 4; q++)
+                    // non-temporal: measured 4-8 % faster than write-back stores here
                     __builtin_nontemporal_store(data[q], reinterpret_cast<v4f *>(y_tile + base + (uint32_t)(q * 8) * ldy_bytes));
             } else {
 #pragma unroll
