@@ -83,6 +83,7 @@ def main() -> int:
                             inv_m=inv_m, xq=torch.empty((M, K), dtype=torch.int8, device=dev),
                             y=torch.empty((M, N), dtype=torch.float16, device=dev)))
         layers.append(lin)
+    s_row = torch.empty(M, dtype=torch.float32, device=dev)
     torch.cuda.synchronize()
     setup_s = time.time() - t0
 
@@ -102,6 +103,13 @@ def main() -> int:
                     events["pairs"].append((a, b))
                 else:
                     ptq.w8a8_linear(d["xq"], d["wq"], d["s_tok"], d["s_w"], d["bias"], B, L, y=d["y"])
+
+    def step_dynamic():
+        """The per-token dynamic comparison scheme (Sec. 4, latency table of Sec. 6.3): steps computed online."""
+        for lin in layers:
+            for d in lin:
+                ptq.quantize_dynamic(d["x"], d["inv_m"], xq=d["xq"], s_row=s_row)
+                ptq.w8a8_linear(d["xq"], d["wq"], s_row, d["s_w"], d["bias"], 1, M, y=d["y"])
 
     def step_f16():
         for lin in layers:
@@ -147,6 +155,7 @@ def main() -> int:
         tg = time_launch(lambda lin: ptq.w8a8_linear(lin[li]["xq"], lin[li]["wq"], lin[li]["s_tok"], lin[li]["s_w"],
                                                     lin[li]["bias"], B, L, y=lin[li]["y"]))
         tf = time_launch(lambda lin: ptq.f16_linear(lin[li]["x"], lin[li]["w"], lin[li]["bias"], y=lin[li]["y"]))
+        td = time_launch(lambda lin: ptq.quantize_dynamic(lin[li]["x"], lin[li]["inv_m"], xq=lin[li]["xq"], s_row=s_row))
         tfu = None
         if layers[0][li]["fused"]:
             tfu = time_launch(lambda lin: ptq.w8a8_linear_fused(lin[li]["x"], lin[li]["inv_m"], lin[li]["s_tok"],
@@ -162,6 +171,7 @@ def main() -> int:
             w8a8_us=round(tg, 2), w8a8_TOPS=round(ops / tg / 1e6, 1),
             w8a8_frac_int8_peak=round(ops / tg / 1e6 / PEAK_INT8_TOPS, 4),
             w8a8_GBps=round(g_bytes / tg / 1e3, 1), w8a8_frac_hbm=round(g_bytes / tg / 1e3 / PEAK_HBM_GBS, 4),
+            dynamic_quantize_us=round(td, 2), dynamic_quantize_GBps=round((q_bytes + 4.0 * M) / td / 1e3, 1),
             f16_us=round(tf, 2), f16_TFLOPS=round(ops / tf / 1e6, 1),
             speedup_gemm_only=round(tf / tg, 3), speedup_quant_plus_gemm=round(tf / (tq + tg), 3)))
         if tfu is not None:  # the form the timed step uses for this linear
@@ -182,6 +192,14 @@ def main() -> int:
         step_f16()
     torch.cuda.synchronize()
     f16_ms_per_step = (time.perf_counter() - t0) / max(1, args.steps // 2) * 1e3
+    for _ in range(2):
+        step_dynamic()
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(max(1, args.steps // 2)):
+        step_dynamic()
+    torch.cuda.synchronize()
+    dynamic_ms_per_step = (time.perf_counter() - t0) / max(1, args.steps // 2) * 1e3
 
     # One plain device-to-device copy of known size (untimed): the reference against which the
     # rocprofv3 FETCH_SIZE / WRITE_SIZE counters of the GEMM are scaled in profiles/.
@@ -248,6 +266,8 @@ def main() -> int:
         "tops": round(total_ops / (ms_per_step * 1e-3) / 1e12, 1),
         "speedup_vs_f16_stack": round(f16_ms_per_step / ms_per_step, 3),
         "f16_ms_per_step": round(f16_ms_per_step, 4),
+        "dynamic_ms_per_step": round(dynamic_ms_per_step, 4),
+        "speedup_pts_vs_per_token_dynamic": round(dynamic_ms_per_step / ms_per_step, 3),
         "paper_context": "paper: up to 1.83x end-to-end at W4A4 on VMamba-B, batch 32, RTX 3090 (not this metric)",
         "roofline": roofline,
         "cpu_baseline": cpu,

@@ -82,6 +82,19 @@ int ptq4vm_quantize_pts(const void *x_f16, const float *inv_m, const float *s_to
                         int64_t B, int64_t L, int64_t K, int64_t ldx, int64_t ldxq, void *stream);
 
 /*
+ * Per-token dynamic activation quantizer: the comparison scheme of Sec. 4 and of the "Per-token
+ * dynamic" rows of the latency table (Sec. 6.3).  The step of every token row is computed online
+ * from the row itself, after smoothing (fp32, in this order):
+ *   v[k] = f32(x[r,k]) * inv_m[k];  s_row[r] = max_k |v[k]| / 127  (1 for an all-zero row; NaNs
+ *   do not take part in the maximum);  xq[r,k] = clip(rne(v[k] * (1 / s_row[r])), -127, 127).
+ * The linear that follows is ptq4vm_w8a8_linear(..., s_tok = s_row, B = 1, L = M).
+ *   x_f16 [M, ldx] fp16 in;  inv_m [K] f32 in, may be NULL;  xq [M, ldxq] int8 out;  s_row [M] f32 out
+ * Errors: NULL x_f16 / xq / s_row, M < 0, K <= 0, ld* < K, misaligned x_f16 / xq (16 bytes).
+ */
+int ptq4vm_quantize_dynamic(const void *x_f16, const float *inv_m, int8_t *xq, float *s_row, int64_t M,
+                            int64_t K, int64_t ldx, int64_t ldxq, void *stream);
+
+/*
  * W8A8 linear: integer GEMM and fused dequantization (PTS equation of Sec. 5.1,
  * Y ~= diag(Delta_W) (W-bar X-bar) diag(Delta_X); App. B.1 "INT GEMM" + "Dequantization"):
  *   acc[r,o] = sum_k xq[r,k] * wq[o,k]                                   (exact, int32)

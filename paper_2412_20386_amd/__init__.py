@@ -7,6 +7,7 @@ from . import binding, synth  # noqa: F401
 from .binding import (  # noqa: F401
     f16_linear,
     fold_smoothing,
+    quantize_dynamic,
     quantize_pts,
     w8a8_linear,
     w8a8_linear_fused,

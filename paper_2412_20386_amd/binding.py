@@ -19,6 +19,7 @@ LIB_PATH = os.path.join(_HERE, "libptq4vm.so")
 EXPORTS = (
     "ptq4vm_fold_smoothing",
     "ptq4vm_quantize_pts",
+    "ptq4vm_quantize_dynamic",
     "ptq4vm_w8a8_linear",
     "ptq4vm_w8a8_linear_fused",
     "ptq4vm_f16_linear",
@@ -51,6 +52,8 @@ def load() -> ctypes.CDLL:
     lib.ptq4vm_fold_smoothing.argtypes = [vp, vp, vp, vp, vp, i64, i64, i64, i64, vp]
     lib.ptq4vm_quantize_pts.restype = ci
     lib.ptq4vm_quantize_pts.argtypes = [vp, vp, vp, vp, i64, i64, i64, i64, i64, vp]
+    lib.ptq4vm_quantize_dynamic.restype = ci
+    lib.ptq4vm_quantize_dynamic.argtypes = [vp, vp, vp, vp, i64, i64, i64, i64, vp]
     lib.ptq4vm_w8a8_linear.restype = ci
     lib.ptq4vm_w8a8_linear.argtypes = [vp, vp, vp, vp, vp, vp, vp, i64, i64, i64, i64, i64, i64, i64, vp]
     lib.ptq4vm_w8a8_linear_fused.restype = ci
@@ -130,6 +133,21 @@ def quantize_pts(x: torch.Tensor, inv_m: Optional[torch.Tensor], s_tok: torch.Te
     _, _, ldxq = _matrix(xq, torch.int8, "xq")
     check(load().ptq4vm_quantize_pts(_ptr(x), _ptr(inv_m), _ptr(s_tok), _ptr(xq), B, L, K, ldx, ldxq, _stream()))
     return xq
+
+
+def quantize_dynamic(x: torch.Tensor, inv_m: Optional[torch.Tensor], xq: Optional[torch.Tensor] = None,
+                     s_row: Optional[torch.Tensor] = None) -> Tuple[torch.Tensor, torch.Tensor]:
+    """ptq4vm_quantize_dynamic: (xq int8 [M, K], s_row f32 [M])."""
+    M, K, ldx = _matrix(x, torch.float16, "x")
+    _vector(inv_m, torch.float32, K, "inv_m", optional=True)
+    if xq is None:
+        xq = torch.empty((M, K), dtype=torch.int8, device=x.device)
+    _, _, ldxq = _matrix(xq, torch.int8, "xq")
+    if s_row is None:
+        s_row = torch.empty(M, dtype=torch.float32, device=x.device)
+    _vector(s_row, torch.float32, M, "s_row")
+    check(load().ptq4vm_quantize_dynamic(_ptr(x), _ptr(inv_m), _ptr(xq), _ptr(s_row), M, K, ldx, ldxq, _stream()))
+    return xq, s_row
 
 
 def w8a8_linear(xq: torch.Tensor, wq: torch.Tensor, s_tok: torch.Tensor, s_w: torch.Tensor,

@@ -67,6 +67,20 @@ def test_quantize_pts_argument_checks(lib):
     assert f(P, NULL, P, P, 0, 197, 8, 8, 8, None) == 0      # empty batch: nothing to do
 
 
+def test_quantize_dynamic_argument_checks(lib):
+    f = lib.ptq4vm_quantize_dynamic
+    assert f(NULL, P, P, P, 1, 8, 8, 8, None) == -1
+    assert f(P, P, NULL, P, 1, 8, 8, 8, None) == -1
+    assert f(P, P, P, NULL, 1, 8, 8, 8, None) == -1
+    assert f(P, P, P, P, -1, 8, 8, 8, None) == -2
+    assert f(P, P, P, P, 1, 0, 8, 8, None) == -2
+    assert f(P, P, P, P, 1, 8, 7, 8, None) == -3
+    assert f(P, P, P, P, 1, 8, 8, 7, None) == -3
+    assert f(ODD, P, P, P, 1, 8, 8, 8, None) == -4
+    assert f(P, P, ODD, P, 1, 8, 8, 8, None) == -4
+    assert f(P, NULL, P, P, 0, 8, 8, 8, None) == 0           # no rows: nothing to do
+
+
 def test_w8a8_linear_argument_checks(lib):
     f = lib.ptq4vm_w8a8_linear
     ok = [P, P, P, P, P, P, NULL, 1, 1, 16, 16, 16, 16, 16, None]

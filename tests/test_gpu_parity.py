@@ -432,3 +432,67 @@ def test_fused_linear_full_size_matches_two_call_path(cfg, linear):
     prod_abs = np.abs(acc_o.astype(np.float64) * st_rows.astype(np.float64)[:, None] * s_w_o.astype(np.float64)[None, :])
     bias_abs = np.broadcast_to(np.abs(_np(c.bias).astype(np.float64))[None, :], prod_abs.shape)
     check_dequantized_output(_np(y[ridx]), y_o, y64, prod_abs, bias_abs, f"fused cfg{cfg} {c.name}")
+
+
+# ---------------------------------------------------------------------------------- per-token dynamic quantizer
+DYNAMIC_SHAPES = [  # M, K
+    (197, 384), (591, 768), (300, 1536), (257, 48), (100, 2048),   # register-resident rows: 1..4 chunks per lane
+    (64, 8), (33, 24), (130, 1000), (50, 776),                      # ragged chunk counts
+    (40, 12), (9, 13), (21, 2056), (7, 4100),                       # element-wise kernel
+    (1, 64), (3, 1),
+]
+
+
+@pytest.mark.parametrize("M,K", DYNAMIC_SHAPES)
+@pytest.mark.parametrize("use_m", [True, False])
+def test_quantize_dynamic_bit_exact(M, K, use_m):
+    print(f"dynamic M={M} K={K} m={use_m}", flush=True)
+    c = synth.random_problem(91 * K + M, 1, M, K, 8, device=DEV)
+    x = c.x.clone()
+    if M > 2:
+        x[1] = 0                                              # an all-zero row: step 1
+    inv_m = (1.0 / c.m) if use_m else None
+    xq, s_row = ptq.quantize_dynamic(x, inv_m)
+    torch.cuda.synchronize()
+    xq_o, s_o = oracle.quantize_dynamic(_np(x), None if inv_m is None else _np(inv_m))
+    assert np.array_equal(_np(s_row).view(np.uint32), s_o.view(np.uint32))
+    assert np.array_equal(_np(xq), xq_o)
+
+
+def test_quantize_dynamic_specials_and_padded_rows():
+    M, K, ldx, ldxq = 70, 384, 400, 416
+    c = synth.random_problem(17, 1, M, K, 8, device=DEV)
+    xbuf, xv = _padded(M, K, ldx, torch.float16, 3.0)
+    xv.copy_(c.x)
+    xv[0, 5] = float("nan")
+    xv[2, 7] = float("inf")
+    xv[3, :] = 65504.0
+    xv[4, 9] = -65504.0
+    qbuf, qv = _padded(M, K, ldxq, torch.int8, 0x55)
+    xq, s_row = ptq.quantize_dynamic(xv, 1.0 / c.m, xq=qv)
+    torch.cuda.synchronize()
+    xq_o, s_o = oracle.quantize_dynamic(_np(xv), _np(1.0 / c.m))
+    assert np.array_equal(_np(s_row).view(np.uint32), s_o.view(np.uint32))
+    assert np.array_equal(_np(qv), xq_o)
+    assert np.all(_np(qbuf[:, K:]) == 0x55)
+
+
+@pytest.mark.parametrize("cfg,linear", [(3, 0), (3, 1), (3, 2)])
+def test_dynamic_path_full_size(cfg, linear):
+    """Dynamic quantizer + W8A8 linear (one step per row) at the benchmark's size, sampled rows vs the oracle."""
+    c = synth.make_linear_case(cfg, 0, linear, device=DEV)
+    M = c.B * c.L
+    print(f"dynamic full-size cfg{cfg} {c.name}: M={M} K={c.K} N={c.N}", flush=True)
+    wq, s_w, inv_m = ptq.fold_smoothing(c.w, c.m)
+    xq, s_row = ptq.quantize_dynamic(c.x, inv_m)
+    y = ptq.w8a8_linear(xq, wq, s_row, s_w, c.bias, 1, M)
+    torch.cuda.synchronize()
+    rows = _sampled_rows(M, 97, c.L)
+    ridx = torch.from_numpy(rows).to(DEV)
+    wq_o, s_w_o, inv_m_o = oracle.fold_smoothing(_np(c.w), _np(c.m))
+    xq_o, s_o = oracle.quantize_dynamic(_np(c.x[ridx]), inv_m_o)
+    assert np.array_equal(_np(xq[ridx]), xq_o) and np.array_equal(_np(s_row[ridx]), s_o)
+    y_o, y64, acc_o = oracle.w8a8_linear(xq_o, wq_o, s_o, s_w_o, _np(c.bias), 1, len(rows))
+    prod_abs = np.abs(acc_o.astype(np.float64) * s_o.astype(np.float64)[:, None] * s_w_o.astype(np.float64)[None, :])
+    bias_abs = np.broadcast_to(np.abs(_np(c.bias).astype(np.float64))[None, :], prod_abs.shape)
+    check_dequantized_output(_np(y[ridx]), y_o, y64, prod_abs, bias_abs, f"dynamic cfg{cfg} {c.name}")
