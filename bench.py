@@ -156,6 +156,15 @@ def main() -> int:
                                                     lin[li]["bias"], B, L, y=lin[li]["y"]))
         tf = time_launch(lambda lin: ptq.f16_linear(lin[li]["x"], lin[li]["w"], lin[li]["bias"], y=lin[li]["y"]))
         td = time_launch(lambda lin: ptq.quantize_dynamic(lin[li]["x"], lin[li]["inv_m"], xq=lin[li]["xq"], s_row=s_row))
+        # per-token zero offset variant (tiled kernels): timing only, offsets drawn at random
+        z_tok = torch.randint(-20, 21, (L,), dtype=torch.int32, device=dev)
+        rowsums = [ptq.weight_rowsum(lin[li]["wq"]) for lin in layers]
+        tzq = time_launch(lambda lin: ptq.quantize_pts_offset(lin[li]["x"], lin[li]["inv_m"], lin[li]["s_tok"], z_tok, B, L,
+                                                              xq=lin[li]["xq"]))
+        rs_of = {id(lin): r for lin, r in zip(layers, rowsums)}
+        tzg = time_launch(lambda lin: ptq.w8a8_linear_offset(lin[li]["xq"], lin[li]["wq"], lin[li]["s_tok"], z_tok,
+                                                             rs_of[id(lin)], lin[li]["s_w"], lin[li]["bias"], B, L,
+                                                             y=lin[li]["y"]))
         tfu = None
         if layers[0][li]["fused"]:
             tfu = time_launch(lambda lin: ptq.w8a8_linear_fused(lin[li]["x"], lin[li]["inv_m"], lin[li]["s_tok"],
@@ -171,6 +180,7 @@ def main() -> int:
             w8a8_us=round(tg, 2), w8a8_TOPS=round(ops / tg / 1e6, 1),
             w8a8_frac_int8_peak=round(ops / tg / 1e6 / PEAK_INT8_TOPS, 4),
             w8a8_GBps=round(g_bytes / tg / 1e3, 1), w8a8_frac_hbm=round(g_bytes / tg / 1e3 / PEAK_HBM_GBS, 4),
+            offset_quantize_us=round(tzq, 2), offset_w8a8_us=round(tzg, 2),
             dynamic_quantize_us=round(td, 2), dynamic_quantize_GBps=round((q_bytes + 4.0 * M) / td / 1e3, 1),
             f16_us=round(tf, 2), f16_TFLOPS=round(ops / tf / 1e6, 1),
             speedup_gemm_only=round(tf / tg, 3), speedup_quant_plus_gemm=round(tf / (tq + tg), 3)))

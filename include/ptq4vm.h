@@ -116,6 +116,30 @@ int ptq4vm_w8a8_linear(const int8_t *xq, const int8_t *wq, const float *s_tok, c
                        int64_t K, int64_t N, int64_t ldxq, int64_t ldwq, int64_t ldy, void *stream);
 
 /*
+ * PTS with a per-token zero offset.  Sec. 5.1 allocates "the step size and zero offset for each
+ * token" and then omits the offset from its equation; the offset form is the activation quantizer
+ * of Sec. 2.3, clip(round(X / Delta) + eps, 0, 2^b - 1), here with the code range shifted by 128
+ * so that codes are int8 (z_tok = eps - 128):
+ *   xq[r,k] = clip(rne((f32(x[r,k]) * inv_m[k]) * (1 / s_tok[t])) + z_tok[t], -128, 127),  t = r mod L
+ *   x-hat   = s_tok[t] * (xq - z_tok[t])
+ *   y[r,o]  = fp16( f32(acc[r,o] - z_tok[t] * rowsum[o]) * (s_tok[t] * s_w[o]) + f32(bias[o]) ),
+ *             acc = sum_k xq[r,k] wq[o,k],  rowsum[o] = sum_k wq[o,k]
+ * ptq4vm_weight_rowsum prepares rowsum once per weight (offline, like the fold).
+ * Arguments as in ptq4vm_quantize_pts / ptq4vm_w8a8_linear, plus z_tok [L] int32 in (values in
+ * [-128, 127]) and rowsum [N] int32.  acc_out receives the raw accumulators (before the correction).
+ * K <= PTQ4VM_MAX_K_OFFSET keeps acc - z * rowsum inside int32.  The linear runs on the tiled
+ * kernels (no persistent / weight-resident variant yet).
+ */
+#define PTQ4VM_MAX_K_OFFSET 65536
+int ptq4vm_quantize_pts_offset(const void *x_f16, const float *inv_m, const float *s_tok, const int32_t *z_tok,
+                               int8_t *xq, int64_t B, int64_t L, int64_t K, int64_t ldx, int64_t ldxq, void *stream);
+int ptq4vm_weight_rowsum(const int8_t *wq, int32_t *rowsum, int64_t N, int64_t K, int64_t ldwq, void *stream);
+int ptq4vm_w8a8_linear_offset(const int8_t *xq, const int8_t *wq, const float *s_tok, const int32_t *z_tok,
+                              const int32_t *rowsum, const float *s_w, const void *bias_f16, void *y_f16,
+                              int32_t *acc_out, int64_t B, int64_t L, int64_t K, int64_t N, int64_t ldxq,
+                              int64_t ldwq, int64_t ldy, void *stream);
+
+/*
  * Fused activation quantizer + W8A8 linear: the stages "Activation smoothing", "Quantization",
  * "INT GEMM" and "Dequantization" of App. B.1 in one launch (PTS equation of Sec. 5.1).
  * Computes exactly, bit for bit, what ptq4vm_quantize_pts followed by ptq4vm_w8a8_linear

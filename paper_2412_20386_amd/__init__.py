@@ -9,6 +9,9 @@ from .binding import (  # noqa: F401
     fold_smoothing,
     quantize_dynamic,
     quantize_pts,
+    quantize_pts_offset,
+    weight_rowsum,
+    w8a8_linear_offset,
     w8a8_linear,
     w8a8_linear_fused,
 )

@@ -20,6 +20,9 @@ EXPORTS = (
     "ptq4vm_fold_smoothing",
     "ptq4vm_quantize_pts",
     "ptq4vm_quantize_dynamic",
+    "ptq4vm_quantize_pts_offset",
+    "ptq4vm_weight_rowsum",
+    "ptq4vm_w8a8_linear_offset",
     "ptq4vm_w8a8_linear",
     "ptq4vm_w8a8_linear_fused",
     "ptq4vm_f16_linear",
@@ -54,6 +57,12 @@ def load() -> ctypes.CDLL:
     lib.ptq4vm_quantize_pts.argtypes = [vp, vp, vp, vp, i64, i64, i64, i64, i64, vp]
     lib.ptq4vm_quantize_dynamic.restype = ci
     lib.ptq4vm_quantize_dynamic.argtypes = [vp, vp, vp, vp, i64, i64, i64, i64, vp]
+    lib.ptq4vm_quantize_pts_offset.restype = ci
+    lib.ptq4vm_quantize_pts_offset.argtypes = [vp, vp, vp, vp, vp, i64, i64, i64, i64, i64, vp]
+    lib.ptq4vm_weight_rowsum.restype = ci
+    lib.ptq4vm_weight_rowsum.argtypes = [vp, vp, i64, i64, i64, vp]
+    lib.ptq4vm_w8a8_linear_offset.restype = ci
+    lib.ptq4vm_w8a8_linear_offset.argtypes = [vp, vp, vp, vp, vp, vp, vp, vp, vp, i64, i64, i64, i64, i64, i64, i64, vp]
     lib.ptq4vm_w8a8_linear.restype = ci
     lib.ptq4vm_w8a8_linear.argtypes = [vp, vp, vp, vp, vp, vp, vp, i64, i64, i64, i64, i64, i64, i64, vp]
     lib.ptq4vm_w8a8_linear_fused.restype = ci
@@ -169,6 +178,55 @@ def w8a8_linear(xq: torch.Tensor, wq: torch.Tensor, s_tok: torch.Tensor, s_w: to
         raise TypeError("acc_out: expected a dense CUDA int32 [M, N] tensor")
     check(load().ptq4vm_w8a8_linear(_ptr(xq), _ptr(wq), _ptr(s_tok), _ptr(s_w), _ptr(bias), _ptr(y),
                                     _ptr(acc_out), B, L, K, N, ldxq, ldwq, ldy, _stream()))
+    return y
+
+
+def quantize_pts_offset(x: torch.Tensor, inv_m: Optional[torch.Tensor], s_tok: torch.Tensor, z_tok: torch.Tensor,
+                        B: int, L: int, xq: Optional[torch.Tensor] = None) -> torch.Tensor:
+    """ptq4vm_quantize_pts_offset: xq int8 [B*L, K] with the per-token zero offset z_tok (int32 [L])."""
+    M, K, ldx = _matrix(x, torch.float16, "x")
+    if M != B * L:
+        raise ValueError("x must have B*L rows")
+    _vector(inv_m, torch.float32, K, "inv_m", optional=True)
+    _vector(s_tok, torch.float32, L, "s_tok")
+    _vector(z_tok, torch.int32, L, "z_tok")
+    if xq is None:
+        xq = torch.empty((M, K), dtype=torch.int8, device=x.device)
+    _, _, ldxq = _matrix(xq, torch.int8, "xq")
+    check(load().ptq4vm_quantize_pts_offset(_ptr(x), _ptr(inv_m), _ptr(s_tok), _ptr(z_tok), _ptr(xq), B, L, K, ldx,
+                                            ldxq, _stream()))
+    return xq
+
+
+def weight_rowsum(wq: torch.Tensor) -> torch.Tensor:
+    """ptq4vm_weight_rowsum: int32 [N] = sum_k wq[o, k]."""
+    N, K, ldwq = _matrix(wq, torch.int8, "wq")
+    out = torch.empty(N, dtype=torch.int32, device=wq.device)
+    check(load().ptq4vm_weight_rowsum(_ptr(wq), _ptr(out), N, K, ldwq, _stream()))
+    return out
+
+
+def w8a8_linear_offset(xq: torch.Tensor, wq: torch.Tensor, s_tok: torch.Tensor, z_tok: torch.Tensor,
+                       rowsum: torch.Tensor, s_w: torch.Tensor, bias: Optional[torch.Tensor], B: int, L: int,
+                       y: Optional[torch.Tensor] = None, acc_out: Optional[torch.Tensor] = None) -> torch.Tensor:
+    """ptq4vm_w8a8_linear_offset: y fp16 [B*L, N] with the zero-offset correction in the epilogue."""
+    M, K, ldxq = _matrix(xq, torch.int8, "xq")
+    N, K2, ldwq = _matrix(wq, torch.int8, "wq")
+    if K != K2 or M != B * L:
+        raise ValueError("shape mismatch")
+    _vector(s_tok, torch.float32, L, "s_tok")
+    _vector(z_tok, torch.int32, L, "z_tok")
+    _vector(rowsum, torch.int32, N, "rowsum")
+    _vector(s_w, torch.float32, N, "s_w")
+    _vector(bias, torch.float16, N, "bias", optional=True)
+    if y is None:
+        y = torch.empty((M, N), dtype=torch.float16, device=xq.device)
+    _, _, ldy = _matrix(y, torch.float16, "y")
+    if acc_out is not None and (acc_out.dtype != torch.int32 or tuple(acc_out.shape) != (M, N)
+                                or not acc_out.is_contiguous() or not acc_out.is_cuda):
+        raise TypeError("acc_out: expected a dense CUDA int32 [M, N] tensor")
+    check(load().ptq4vm_w8a8_linear_offset(_ptr(xq), _ptr(wq), _ptr(s_tok), _ptr(z_tok), _ptr(rowsum), _ptr(s_w),
+                                           _ptr(bias), _ptr(y), _ptr(acc_out), B, L, K, N, ldxq, ldwq, ldy, _stream()))
     return y
 
 

@@ -51,7 +51,36 @@ __global__ __launch_bounds__(kThreads) void fold_smoothing_rows(const __half *__
     }
 }
 
+// rowsum[o] = sum_k wq[o,k], one wavefront per output channel: the factor of the per-token zero
+// offset in  sum_k (q - z) w = sum_k q w - z rowsum  (offset quantizer of Sec. 2.3 in the linear of Sec. 5.1).
+__global__ __launch_bounds__(kThreads) void weight_rowsum_rows(const int8_t *__restrict__ wq,
+                                                               int32_t *__restrict__ rowsum, int64_t N, int64_t K,
+                                                               int64_t ldwq) {
+    const int lane = threadIdx.x & 63;
+    const int64_t o = (int64_t)blockIdx.x * (kThreads / 64) + (threadIdx.x >> 6);
+    if (o >= N) return;
+    int sum = 0;
+    for (int64_t k = lane; k < K; k += 64) sum += wq[o * ldwq + k];
+#pragma unroll
+    for (int off = 32; off > 0; off >>= 1) sum += __shfl_xor(sum, off, 64);
+    if (lane == 0) rowsum[o] = sum;
+}
+
 }  // namespace
+
+extern "C" int ptq4vm_weight_rowsum(const int8_t *wq, int32_t *rowsum, int64_t N, int64_t K, int64_t ldwq,
+                                    void *stream_) {
+    if (!wq || !rowsum) return PTQ4VM_ERR_NULL;
+    if (N < 0 || K <= 0 || K > PTQ4VM_MAX_K) return PTQ4VM_ERR_SHAPE;
+    if (ldwq < K) return PTQ4VM_ERR_STRIDE;
+    if (!ptq4vm::aligned_to(rowsum, 4)) return PTQ4VM_ERR_ALIGN;
+    if (N == 0) return PTQ4VM_OK;
+    const int64_t blocks = ptq4vm::ceil_div(N, kThreads / 64);
+    if (blocks > 0x7fffffffLL) return PTQ4VM_ERR_SHAPE;
+    weight_rowsum_rows<<<dim3((unsigned)blocks), dim3(kThreads), 0, static_cast<hipStream_t>(stream_)>>>(wq, rowsum, N,
+                                                                                                         K, ldwq);
+    return ptq4vm::check_launch("weight_rowsum_rows");
+}
 
 extern "C" int ptq4vm_fold_smoothing(const void *w_f16, const float *m, int8_t *wq, float *s_w, float *inv_m,
                                      int64_t N, int64_t K, int64_t ldw, int64_t ldwq, void *stream_) {

@@ -28,6 +28,7 @@ constexpr int kXcds = 8;
 
 struct Int8Path {
     static constexpr int kElemBytes = 1;
+    static constexpr bool kOffset = false;
     using Acc = v16i;
     static __device__ __forceinline__ Acc mfma(v4i a, v4i b, Acc c) {
         return __builtin_amdgcn_mfma_i32_32x32x32_i8(a, b, c, 0, 0, 0);
@@ -39,8 +40,15 @@ struct Int8Path {
     }
 };
 
+// int8 codes carrying a per-token zero offset: the epilogue subtracts z_tok[r mod L] * rowsum[o]
+// from the accumulator (sum_k (q - z) w = sum_k q w - z sum_k w) before the rescale.
+struct Int8OffsetPath : Int8Path {
+    static constexpr bool kOffset = true;
+};
+
 struct Half16Path {
     static constexpr int kElemBytes = 2;
+    static constexpr bool kOffset = false;
     using Acc = v16f;
     static __device__ __forceinline__ Acc mfma(v4i a, v4i b, Acc c) {
         return __builtin_amdgcn_mfma_f32_32x32x16_f16(__builtin_bit_cast(v8h, a), __builtin_bit_cast(v8h, b), c, 0,
@@ -70,6 +78,9 @@ struct LinearArgs {
     int y_vec;           // widest store the pitch and base of y allow, in fp16 elements: 8, 4 or 1
     // Fused activation quantizer only: x then holds fp16 activations (ldx_bytes = 2 * pitch) and k_bytes
     // is still K, the reduction length in int8 codes.
+    // Per-token zero offset only (Int8OffsetPath):
+    const int32_t *z_tok;   // [L] offsets in the int8 range
+    const int32_t *rowsum;  // [N] sum_k wq[o,k]
     const float *inv_m;  // [K] reciprocal smoothing factors or nullptr (no smoothing)
     int8_t *xq_out;      // [M, ldxq_out] optional copy of the int8 codes, or nullptr
     int64_t ldxq_out;
@@ -144,24 +155,30 @@ __device__ __forceinline__ void epilogue(const typename Path::Acc (&acc)[FO][FR]
 #pragma unroll
     for (int jb = 0; jb < FR; jb += JB) {
         float row_scale[JB];
+        int row_z[JB];
 #pragma unroll
         for (int jj = 0; jj < JB; jj++) {
             const int64_t r = r_base + (jb + jj) * 32 + l32;
             row_scale[jj] = 1.0f;
+            row_z[jj] = 0;
             if constexpr (Path::kElemBytes == 1) row_scale[jj] = p.s_tok[(r < p.M ? r : 0) % p.L];
+            if constexpr (Path::kOffset) row_z[jj] = p.z_tok[(r < p.M ? r : 0) % p.L];
         }
 #pragma unroll
         for (int i = 0; i < FO; i++) {
 #pragma unroll
             for (int g = 0; g < 4; g++) {
                 float col_scale[4], col_bias[4];
+                int col_sum[4];
 #pragma unroll
                 for (int c = 0; c < 4; c++) {
                     const int64_t o = o_base + i * 32 + g * 8 + lhalf * 4 + c;
                     const bool ok = o < p.N;
                     col_bias[c] = (ok && p.bias) ? __half2float(p.bias[o]) : 0.0f;
                     col_scale[c] = 1.0f;
+                    col_sum[c] = 0;
                     if constexpr (Path::kElemBytes == 1) col_scale[c] = ok ? p.s_w[o] : 0.0f;
+                    if constexpr (Path::kOffset) col_sum[c] = ok ? p.rowsum[o] : 0;
                 }
 #pragma unroll
                 for (int jj = 0; jj < JB; jj++) {
@@ -176,7 +193,9 @@ __device__ __forceinline__ void epilogue(const typename Path::Acc (&acc)[FO][FR]
                                 const int64_t o = o_base + i * 32 + g * 8 + lhalf * 4 + c;
                                 if (r < p.M && o < p.N) p.acc_out[r * p.N + o] = a;
                             }
-                            out[c] = (float)a * (row_scale[jj] * col_scale[c]) + col_bias[c];
+                            int corrected = a;
+                            if constexpr (Path::kOffset) corrected = a - row_z[jj] * col_sum[c];
+                            out[c] = (float)corrected * (row_scale[jj] * col_scale[c]) + col_bias[c];
                         } else {
                             out[c] = acc[i][j][g * 4 + c] + col_bias[c];
                         }

@@ -30,10 +30,17 @@ __device__ __forceinline__ int cvt_i32_f32(float v) {
     return i;
 }
 
-__device__ __forceinline__ int quantize_one(float x, float inv_m, float inv_s) {
+// HAS_Z: per-token zero offset (Sec. 5.1 names it; quantizer form of Sec. 2.3 with the code range shifted
+// into int8): the offset is added to the rounded value and the clip range is [-128, 127].
+template <bool HAS_Z>
+__device__ __forceinline__ int quantize_one(float x, float inv_m, float inv_s, int z) {
     float v = x * inv_m;  // smoothing first (two separate fp32 multiplies, never fused or reordered)
     v = v * inv_s;
     int q = cvt_i32_f32(__builtin_rintf(v));  // round half to even, then NaN -> 0, Inf -> +-INT_MAX
+    if constexpr (HAS_Z) {
+        q = min(max(q, -(1 << 20)), 1 << 20);  // room for the offset without integer overflow
+        return min(max(q + z, -128), 127);
+    }
     return min(max(q, -127), 127);
 }
 
@@ -62,12 +69,8 @@ __device__ __forceinline__ void half2_to_floats(uint32_t packed, float &lo, floa
     hi = __high2float(h);
 }
 
-template <int VEC>
-__device__ __forceinline__ typename Chunk<VEC>::Out quantize_chunk(typename Chunk<VEC>::In in,
-                                                                   const float (&im)[VEC], float inv_s);
-
-template <>
-__device__ __forceinline__ u32x2 quantize_chunk<8>(u32x4 in, const float (&im)[8], float inv_s) {
+template <bool HAS_Z>
+__device__ __forceinline__ u32x2 quantize_chunk(u32x4 in, const float (&im)[8], float inv_s, int z) {
     float f[8];
     half2_to_floats(in.x, f[0], f[1]);
     half2_to_floats(in.y, f[2], f[3]);
@@ -75,37 +78,42 @@ __device__ __forceinline__ u32x2 quantize_chunk<8>(u32x4 in, const float (&im)[8
     half2_to_floats(in.w, f[6], f[7]);
     int q[8];
 #pragma unroll
-    for (int i = 0; i < 8; i++) q[i] = quantize_one(f[i], im[i], inv_s);
+    for (int i = 0; i < 8; i++) q[i] = quantize_one<HAS_Z>(f[i], im[i], inv_s, z);
     u32x2 out = {pack4(q[0], q[1], q[2], q[3]), pack4(q[4], q[5], q[6], q[7])};
     return out;
 }
 
-template <>
-__device__ __forceinline__ uint32_t quantize_chunk<4>(u32x2 in, const float (&im)[4], float inv_s) {
+template <bool HAS_Z>
+__device__ __forceinline__ uint32_t quantize_chunk(u32x2 in, const float (&im)[4], float inv_s, int z) {
     float f[4];
     half2_to_floats(in.x, f[0], f[1]);
     half2_to_floats(in.y, f[2], f[3]);
     int q[4];
 #pragma unroll
-    for (int i = 0; i < 4; i++) q[i] = quantize_one(f[i], im[i], inv_s);
+    for (int i = 0; i < 4; i++) q[i] = quantize_one<HAS_Z>(f[i], im[i], inv_s, z);
     return pack4(q[0], q[1], q[2], q[3]);
 }
 
 // Column-stationary grid-stride stream.  gridDim.x * 256 is a multiple of `chunks` (= K / VEC),
 // so thread g owns column chunk g mod chunks and rows g / chunks + i * row_step, i = 0, 1, ...
-template <int VEC, bool HAS_M, bool LDS_TABLE, int UNROLL>
+template <int VEC, bool HAS_M, bool LDS_TABLE, bool HAS_Z, int UNROLL>
 __global__ __launch_bounds__(kMaxThreads) void quantize_pts_stream(
     const __half *__restrict__ x, const float *__restrict__ inv_m, const float *__restrict__ s_tok,
-    int8_t *__restrict__ xq, int64_t M, int L, int chunks, int64_t ldx, int64_t ldxq, int64_t row_step) {
+    const int32_t *__restrict__ z_tok, int8_t *__restrict__ xq, int64_t M, int L, int chunks, int64_t ldx,
+    int64_t ldxq, int64_t row_step) {
     using In = typename Chunk<VEC>::In;
     using Out = typename Chunk<VEC>::Out;
-    extern __shared__ float inv_s_lds[];
+    extern __shared__ float inv_s_lds[];  // [L] reciprocal steps, then (HAS_Z) [L] offsets
+    int *const z_lds = reinterpret_cast<int *>(inv_s_lds + L);
     if constexpr (LDS_TABLE) {
-        for (int i = threadIdx.x; i < L; i += kMaxThreads)
+        for (int i = threadIdx.x; i < L; i += kMaxThreads) {
             inv_s_lds[i] = 1.0f / s_tok[i];  // IEEE-correct division (compiled without fast-math)
+            if constexpr (HAS_Z) z_lds[i] = z_tok[i];
+        }
         __syncthreads();
     }
     auto inv_step = [&](int t) { return LDS_TABLE ? inv_s_lds[t] : 1.0f / s_tok[t]; };
+    auto offset = [&](int t) { return HAS_Z ? (LDS_TABLE ? z_lds[t] : z_tok[t]) : 0; };
 
     const int64_t gtid = (int64_t)blockIdx.x * kMaxThreads + threadIdx.x;
     const int col = (int)(gtid % chunks);
@@ -124,42 +132,47 @@ __global__ __launch_bounds__(kMaxThreads) void quantize_pts_stream(
     for (; row + (UNROLL - 1) * row_step < M; row += UNROLL * row_step) {
         In v[UNROLL];
         float is[UNROLL];
+        int zs[UNROLL];
 #pragma unroll
         for (int u = 0; u < UNROLL; u++) {
             v[u] = __builtin_nontemporal_load(reinterpret_cast<const In *>(xp + u * x_step));
             is[u] = inv_step(t);
+            zs[u] = offset(t);
             t += t_step;
             if (t >= L) t -= L;
         }
 #pragma unroll
         for (int u = 0; u < UNROLL; u++)
-            __builtin_nontemporal_store(quantize_chunk<VEC>(v[u], im, is[u]), reinterpret_cast<Out *>(qp + u * q_step));
+            __builtin_nontemporal_store(quantize_chunk<HAS_Z>(v[u], im, is[u], zs[u]), reinterpret_cast<Out *>(qp + u * q_step));
         xp += UNROLL * x_step;
         qp += UNROLL * q_step;
     }
     for (; row < M; row += row_step) {
         In v = __builtin_nontemporal_load(reinterpret_cast<const In *>(xp));
         const float is = inv_step(t);
+        const int z = offset(t);
         t += t_step;
         if (t >= L) t -= L;
-        __builtin_nontemporal_store(quantize_chunk<VEC>(v, im, is), reinterpret_cast<Out *>(qp));
+        __builtin_nontemporal_store(quantize_chunk<HAS_Z>(v, im, is, z), reinterpret_cast<Out *>(qp));
         xp += x_step;
         qp += q_step;
     }
 }
 
 // Any shape and pitch: one element per thread-iteration, index arithmetic per element.
-template <bool HAS_M>
+template <bool HAS_M, bool HAS_Z>
 __global__ __launch_bounds__(kMaxThreads) void quantize_pts_generic(
     const __half *__restrict__ x, const float *__restrict__ inv_m, const float *__restrict__ s_tok,
-    int8_t *__restrict__ xq, int64_t M, int64_t L, int64_t K, int64_t ldx, int64_t ldxq) {
+    const int32_t *__restrict__ z_tok, int8_t *__restrict__ xq, int64_t M, int64_t L, int64_t K, int64_t ldx,
+    int64_t ldxq) {
     const int64_t total = M * K;
     for (int64_t e = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; e < total;
          e += (int64_t)gridDim.x * blockDim.x) {
         int64_t r = e / K, k = e - r * K;
         float inv_s = 1.0f / s_tok[r % L];
         float m = HAS_M ? inv_m[k] : 1.0f;
-        xq[r * ldxq + k] = (int8_t)quantize_one(__half2float(x[r * ldx + k]), m, inv_s);
+        const int z = HAS_Z ? z_tok[r % L] : 0;
+        xq[r * ldxq + k] = (int8_t)quantize_one<HAS_Z>(__half2float(x[r * ldx + k]), m, inv_s, z);
     }
 }
 
@@ -173,8 +186,8 @@ int64_t gcd64(int64_t a, int64_t b) {
 }
 
 template <int VEC>
-int launch_stream(const __half *x, const float *inv_m, const float *s_tok, int8_t *xq, int64_t M, int64_t L,
-                  int64_t K, int64_t ldx, int64_t ldxq, hipStream_t stream) {
+int launch_stream(const __half *x, const float *inv_m, const float *s_tok, const int32_t *z_tok, int8_t *xq, int64_t M,
+                  int64_t L, int64_t K, int64_t ldx, int64_t ldxq, hipStream_t stream) {
     const int64_t chunks = K / VEC;
     // Grid: a multiple of `unit` workgroups (so that threads % chunks == 0), about 3 per CU of
     // the 256-CU part, fewer when the whole problem is smaller than that.
@@ -186,32 +199,35 @@ int launch_stream(const __half *x, const float *inv_m, const float *s_tok, int8_
     int64_t blocks = ptq4vm::ceil_div(want, unit) * unit;
     if (blocks > 0x7fffffffLL) return PTQ4VM_ERR_SHAPE;
     const int64_t row_step = blocks * kMaxThreads / chunks;
-    const bool table = L <= kMaxLdsTokens;
-    const size_t lds = table ? (size_t)L * sizeof(float) : 0;
+    const bool table = L <= (z_tok ? kMaxLdsTokens / 2 : kMaxLdsTokens);
+    const size_t lds = table ? (size_t)L * sizeof(float) * (z_tok ? 2 : 1) : 0;
     constexpr int UNROLL = 2;
     dim3 grid((unsigned)blocks), block(kMaxThreads);
-#define PTQ4VM_LAUNCH(HAS_M, TABLE)                                                                         \
-    quantize_pts_stream<VEC, HAS_M, TABLE, UNROLL><<<grid, block, lds, stream>>>(x, inv_m, s_tok, xq, M, (int)L, \
-                                                                                 (int)chunks, ldx, ldxq, row_step)
-    if (inv_m) {
-        if (table) PTQ4VM_LAUNCH(true, true); else PTQ4VM_LAUNCH(true, false);
-    } else {
-        if (table) PTQ4VM_LAUNCH(false, true); else PTQ4VM_LAUNCH(false, false);
+#define PTQ4VM_LAUNCH(HAS_M, TABLE, HAS_Z)                                                                       \
+    quantize_pts_stream<VEC, HAS_M, TABLE, HAS_Z, UNROLL><<<grid, block, lds, stream>>>(                          \
+        x, inv_m, s_tok, z_tok, xq, M, (int)L, (int)chunks, ldx, ldxq, row_step)
+    const int variant = (inv_m ? 4 : 0) | (table ? 2 : 0) | (z_tok ? 1 : 0);
+    switch (variant) {
+        case 0: PTQ4VM_LAUNCH(false, false, false); break;
+        case 1: PTQ4VM_LAUNCH(false, false, true); break;
+        case 2: PTQ4VM_LAUNCH(false, true, false); break;
+        case 3: PTQ4VM_LAUNCH(false, true, true); break;
+        case 4: PTQ4VM_LAUNCH(true, false, false); break;
+        case 5: PTQ4VM_LAUNCH(true, false, true); break;
+        case 6: PTQ4VM_LAUNCH(true, true, false); break;
+        default: PTQ4VM_LAUNCH(true, true, true); break;
     }
 #undef PTQ4VM_LAUNCH
     return ptq4vm::check_launch("quantize_pts_stream");
 }
 
-}  // namespace
-
-extern "C" int ptq4vm_quantize_pts(const void *x_f16, const float *inv_m, const float *s_tok, int8_t *xq,
-                                   int64_t B, int64_t L, int64_t K, int64_t ldx, int64_t ldxq, void *stream_) {
-    if (!x_f16 || !s_tok || !xq) return PTQ4VM_ERR_NULL;
+int quantize_entry(const void *x_f16, const float *inv_m, const float *s_tok, const int32_t *z_tok, int8_t *xq, int64_t B,
+                   int64_t L, int64_t K, int64_t ldx, int64_t ldxq, void *stream_) {
     if (B < 0 || L <= 0 || K <= 0) return PTQ4VM_ERR_SHAPE;
     if (L > 0x7fffffffLL || K > 0x7fffffffLL || (B > 0 && L > INT64_MAX / B)) return PTQ4VM_ERR_SHAPE;
     if (ldx < K || ldxq < K) return PTQ4VM_ERR_STRIDE;
     if (!ptq4vm::aligned_to(x_f16, 16) || !ptq4vm::aligned_to(xq, 16) || !ptq4vm::aligned_to(s_tok, 4) ||
-        (inv_m && !ptq4vm::aligned_to(inv_m, 4)))
+        !ptq4vm::aligned_to(z_tok, 4) || (inv_m && !ptq4vm::aligned_to(inv_m, 4)))
         return PTQ4VM_ERR_ALIGN;
     const int64_t M = B * L;
     if (M == 0) return PTQ4VM_OK;
@@ -219,17 +235,35 @@ extern "C" int ptq4vm_quantize_pts(const void *x_f16, const float *inv_m, const 
     const __half *x = static_cast<const __half *>(x_f16);
 
     if (K % 8 == 0 && ldx % 8 == 0 && ldxq % 8 == 0)
-        return launch_stream<8>(x, inv_m, s_tok, xq, M, L, K, ldx, ldxq, stream);
+        return launch_stream<8>(x, inv_m, s_tok, z_tok, xq, M, L, K, ldx, ldxq, stream);
     if (K % 4 == 0 && ldx % 4 == 0 && ldxq % 4 == 0)
-        return launch_stream<4>(x, inv_m, s_tok, xq, M, L, K, ldx, ldxq, stream);
+        return launch_stream<4>(x, inv_m, s_tok, z_tok, xq, M, L, K, ldx, ldxq, stream);
 
     int64_t blocks = ptq4vm::ceil_div(M * K, kMaxThreads);
     if (blocks > 65536) blocks = 65536;
-    if (inv_m)
-        quantize_pts_generic<true><<<dim3((unsigned)blocks), dim3(kMaxThreads), 0, stream>>>(x, inv_m, s_tok, xq, M,
-                                                                                           L, K, ldx, ldxq);
+    const dim3 grid((unsigned)blocks), block(kMaxThreads);
+    if (inv_m && z_tok)
+        quantize_pts_generic<true, true><<<grid, block, 0, stream>>>(x, inv_m, s_tok, z_tok, xq, M, L, K, ldx, ldxq);
+    else if (inv_m)
+        quantize_pts_generic<true, false><<<grid, block, 0, stream>>>(x, inv_m, s_tok, z_tok, xq, M, L, K, ldx, ldxq);
+    else if (z_tok)
+        quantize_pts_generic<false, true><<<grid, block, 0, stream>>>(x, inv_m, s_tok, z_tok, xq, M, L, K, ldx, ldxq);
     else
-        quantize_pts_generic<false><<<dim3((unsigned)blocks), dim3(kMaxThreads), 0, stream>>>(x, inv_m, s_tok, xq,
-                                                                                            M, L, K, ldx, ldxq);
+        quantize_pts_generic<false, false><<<grid, block, 0, stream>>>(x, inv_m, s_tok, z_tok, xq, M, L, K, ldx, ldxq);
     return ptq4vm::check_launch("quantize_pts_generic");
+}
+
+}  // namespace
+
+extern "C" int ptq4vm_quantize_pts(const void *x_f16, const float *inv_m, const float *s_tok, int8_t *xq,
+                                   int64_t B, int64_t L, int64_t K, int64_t ldx, int64_t ldxq, void *stream_) {
+    if (!x_f16 || !s_tok || !xq) return PTQ4VM_ERR_NULL;
+    return quantize_entry(x_f16, inv_m, s_tok, nullptr, xq, B, L, K, ldx, ldxq, stream_);
+}
+
+extern "C" int ptq4vm_quantize_pts_offset(const void *x_f16, const float *inv_m, const float *s_tok,
+                                          const int32_t *z_tok, int8_t *xq, int64_t B, int64_t L, int64_t K,
+                                          int64_t ldx, int64_t ldxq, void *stream_) {
+    if (!x_f16 || !s_tok || !z_tok || !xq) return PTQ4VM_ERR_NULL;
+    return quantize_entry(x_f16, inv_m, s_tok, z_tok, xq, B, L, K, ldx, ldxq, stream_);
 }

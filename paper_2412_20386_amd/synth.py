@@ -197,3 +197,24 @@ def random_problem(seed: int, B: int, L: int, K: int, N: int, device="cpu",
     clipped = int(((x3.float() / m.view(1, 1, K)).abs() > (127.5 * s_tok).view(1, L, 1)).sum().item())
     return LinearCase(-1, 0, 0, "adhoc", B, L, K, N, x3.reshape(B * L, K).contiguous(),
                       w.contiguous(), bias.contiguous(), m, s_tok, clipped)
+
+
+# ---------------------------------------------------------------------------------- per-token zero offset
+def token_shift(L: int, seed: int, device="cpu", scale: float = 2.0) -> torch.Tensor:
+    """A fixed per-token-position offset (fp16 [L]) to add to activations: makes each token's
+    distribution asymmetric about zero, the situation a per-token zero offset is for."""
+    g = _gen(device, seed + 77_000_000)
+    return (scale * torch.randn(L, generator=g, device=device, dtype=torch.float32)).to(torch.float16)
+
+
+def calibrate_offset(x_cal: torch.Tensor, m: torch.Tensor, L: int) -> Tuple[torch.Tensor, torch.Tensor]:
+    """Min-max initialiser of the asymmetric quantizer (Sec. 2.3) applied per token position on
+    smoothed calibration activations x_cal [n*L, K]: step (max - min) / 255 and the offset
+    round(-min / step), shifted by 128 so that codes are int8.  Returns (s_tok fp32 [L], z_tok int32 [L])."""
+    K = x_cal.shape[1]
+    v = (x_cal.float() / m.view(1, K)).view(-1, L, K)
+    lo = v.amin(dim=(0, 2)).clamp(max=0.0)
+    hi = v.amax(dim=(0, 2)).clamp(min=0.0)
+    s = ((hi - lo) / 255.0).clamp_(min=1e-30)
+    z = (torch.round(-lo / s) - 128.0).clamp_(-128.0, 127.0).to(torch.int32)
+    return s.contiguous(), z.contiguous()

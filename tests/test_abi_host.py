@@ -101,6 +101,37 @@ def test_w8a8_linear_argument_checks(lib):
     assert call(a7=0) == 0 and call(a10=0, a13=0) == 0       # empty problem
 
 
+def test_zero_offset_entry_points_argument_checks(lib):
+    q = lib.ptq4vm_quantize_pts_offset
+    assert q(NULL, P, P, P, P, 1, 1, 8, 8, 8, None) == -1
+    assert q(P, P, P, NULL, P, 1, 1, 8, 8, 8, None) == -1            # the offsets are required here
+    assert q(P, P, P, P, P, 1, 0, 8, 8, 8, None) == -2
+    assert q(P, P, P, P, P, 1, 1, 8, 7, 8, None) == -3
+    assert q(ODD, P, P, P, P, 1, 1, 8, 8, 8, None) == -4
+    assert q(P, NULL, P, P, P, 0, 197, 8, 8, 8, None) == 0
+    rs = lib.ptq4vm_weight_rowsum
+    assert rs(NULL, P, 1, 8, 8, None) == -1 and rs(P, NULL, 1, 8, 8, None) == -1
+    assert rs(P, P, -1, 8, 8, None) == -2 and rs(P, P, 1, 0, 8, None) == -2
+    assert rs(P, P, 1, 8, 7, None) == -3 and rs(P, ODD, 1, 8, 8, None) == -4
+    assert rs(P, P, 0, 8, 8, None) == 0
+    f = lib.ptq4vm_w8a8_linear_offset
+    #     xq wq s_tok z rowsum s_w bias y acc   B  L  K   N   ldxq ldwq ldy stream
+    ok = [P, P, P, P, P, P, P, P, NULL, 1, 1, 16, 16, 16, 16, 16, None]
+
+    def call(**kw):
+        a = list(ok)
+        for i, v in kw.items():
+            a[int(i[1:])] = v
+        return f(*a)
+
+    assert call(a0=NULL) == -1 and call(a3=NULL) == -1 and call(a4=NULL) == -1 and call(a7=NULL) == -1
+    assert call(a9=-1) == -2 and call(a10=0) == -2 and call(a11=0) == -2
+    assert call(a11=65537, a13=65537, a14=65537) == -2               # acc - z * rowsum could overflow int32
+    assert call(a13=15) == -3 and call(a15=15) == -3
+    assert call(a0=ODD) == -4 and call(a3=ctypes.c_void_p(0x1002)) == -4
+    assert call(a9=0) == 0
+
+
 def test_w8a8_linear_fused_argument_checks(lib):
     f = lib.ptq4vm_w8a8_linear_fused
     #     x  inv_m s_tok wq s_w bias y acc  xq   B  L  K   N   ldx ldwq ldy ldxq stream

@@ -496,3 +496,61 @@ def test_dynamic_path_full_size(cfg, linear):
     prod_abs = np.abs(acc_o.astype(np.float64) * s_o.astype(np.float64)[:, None] * s_w_o.astype(np.float64)[None, :])
     bias_abs = np.broadcast_to(np.abs(_np(c.bias).astype(np.float64))[None, :], prod_abs.shape)
     check_dequantized_output(_np(y[ridx]), y_o, y64, prod_abs, bias_abs, f"dynamic cfg{cfg} {c.name}")
+
+
+# ---------------------------------------------------------------------------------- per-token zero offset
+def _offset_case(seed, B, L, K, N):
+    """Activations shifted per token position (asymmetric about zero); offsets calibrated on the first
+    half of the images, so the second half exercises the clip at both ends."""
+    c = synth.random_problem(seed, B, L, K, N, device=DEV)
+    shift = synth.token_shift(L, seed, device=DEV)
+    x = (c.x.view(B, L, K) + shift.view(1, L, 1)).reshape(B * L, K).contiguous()
+    s_off, z_off = synth.calibrate_offset(x[: max(1, B // 2) * L], c.m, L)
+    return c, x, s_off, z_off
+
+
+OFFSET_SHAPES = [  # B, L, K, N
+    (4, 197, 384, 192), (4, 197, 384, 44), (4, 50, 768, 56), (2, 300, 1536, 80), (4, 65, 24, 768),
+    (2, 257, 100, 130), (4, 33, 13, 5), (2, 129, 1000, 257), (6, 7, 16, 1),
+]
+
+
+@pytest.mark.parametrize("B,L,K,N", OFFSET_SHAPES)
+def test_zero_offset_path_against_oracle(B, L, K, N):
+    print(f"offset B={B} L={L} K={K} N={N}", flush=True)
+    c, x, s_off, z_off = _offset_case(400 + K + N, B, L, K, N)
+    M = B * L
+    wq, s_w, inv_m = ptq.fold_smoothing(c.w, c.m)
+    rowsum = ptq.weight_rowsum(wq)
+    xq = ptq.quantize_pts_offset(x, inv_m, s_off, z_off, B, L)
+    acc = torch.full((M, N), -1, dtype=torch.int32, device=DEV)
+    y = ptq.w8a8_linear_offset(xq, wq, s_off, z_off, rowsum, s_w, c.bias, B, L, acc_out=acc)
+    y2 = ptq.w8a8_linear_offset(xq, wq, s_off, z_off, rowsum, s_w, c.bias, B, L)
+    torch.cuda.synchronize()
+
+    wq_o, s_w_o, inv_m_o = oracle.fold_smoothing(_np(c.w), _np(c.m))
+    rowsum_o = oracle.weight_rowsum(wq_o)
+    xq_o = oracle.quantize_pts_offset(_np(x), inv_m_o, _np(s_off), _np(z_off), B, L)
+    acc_o = oracle.int8_gemm(xq_o, wq_o)
+    y_o, y64 = oracle.dequant_offset(acc_o, _np(s_off), _np(z_off), rowsum_o, s_w_o, _np(c.bias), B, L)
+    assert np.array_equal(_np(rowsum), rowsum_o)
+    assert np.array_equal(_np(xq), xq_o), "int8 codes differ"
+    assert xq_o.min() == -128 or xq_o.max() == 127                    # the clip is exercised
+    assert np.array_equal(_np(acc), acc_o), "int32 accumulators differ"
+    st = np.tile(_np(s_off).astype(np.float64), B)[:, None]
+    zt = np.tile(_np(z_off).astype(np.float64), B)[:, None]
+    corrected = acc_o.astype(np.float64) - zt * rowsum_o.astype(np.float64)[None, :]
+    prod_abs = np.abs(corrected * st * s_w_o.astype(np.float64)[None, :])
+    bias_abs = np.broadcast_to(np.abs(_np(c.bias).astype(np.float64))[None, :], prod_abs.shape)
+    check_dequantized_output(_np(y), y_o, y64, prod_abs, bias_abs, "offset")
+    assert torch.equal(y.view(torch.int16), y2.view(torch.int16))
+
+
+def test_zero_offset_quantizer_long_sequence_and_plain_kernels():
+    """L beyond the LDS table (per-row division), K a multiple of 4 only, K odd."""
+    for B, L, K in [(1, 9000, 64), (3, 41, 20), (2, 19, 7)]:
+        c, x, s_off, z_off = _offset_case(900 + L + K, B, L, K, 8)
+        xq = ptq.quantize_pts_offset(x, 1.0 / c.m, s_off, z_off, B, L)
+        torch.cuda.synchronize()
+        xq_o = oracle.quantize_pts_offset(_np(x), _np(1.0 / c.m), _np(s_off), _np(z_off), B, L)
+        assert np.array_equal(_np(xq), xq_o), (B, L, K)
