@@ -140,6 +140,26 @@ int ptq4vm_w8a8_linear_offset(const int8_t *xq, const int8_t *wq, const float *s
                               int64_t ldwq, int64_t ldy, void *stream);
 
 /*
+ * W4A4: the precision of the paper's latency table (Sec. 6.3).  Codes are clipped to +-7
+ * (Sec. 2.3, +-(2^(b-1) - 1) with b = 4) and packed two per byte, the even reduction index in the
+ * low nibble, two's complement (App. B.1: packed = (data[1] << 4) | (data[0] & 15)).  K must be
+ * even; packed matrices are [rows, K / 2] bytes with pitches ldwq / ldxq in bytes.
+ *   ptq4vm_fold_smoothing_w4  as ptq4vm_fold_smoothing with s_w = max|W'| / 7
+ *   ptq4vm_quantize_pts_a4    as ptq4vm_quantize_pts with the +-7 clip (s_tok calibrated for 4 bits)
+ *   ptq4vm_w4a4_linear        as ptq4vm_w8a8_linear on packed operands; acc_out holds sum_k xq wq
+ * gfx950 has no int4 MFMA: packed operands are expanded in registers to int8 right before the
+ * int8 MFMA, so the gain over W8A8 is in bytes moved, not in MFMA rate.  The linear runs on the
+ * tiled kernels.  Errors as for the 8-bit entry points, plus odd K -> PTQ4VM_ERR_SHAPE.
+ */
+int ptq4vm_fold_smoothing_w4(const void *w_f16, const float *m, uint8_t *wq4, float *s_w, float *inv_m,
+                             int64_t N, int64_t K, int64_t ldw, int64_t ldwq, void *stream);
+int ptq4vm_quantize_pts_a4(const void *x_f16, const float *inv_m, const float *s_tok, uint8_t *xq4, int64_t B,
+                           int64_t L, int64_t K, int64_t ldx, int64_t ldxq, void *stream);
+int ptq4vm_w4a4_linear(const uint8_t *xq4, const uint8_t *wq4, const float *s_tok, const float *s_w,
+                       const void *bias_f16, void *y_f16, int32_t *acc_out, int64_t B, int64_t L, int64_t K,
+                       int64_t N, int64_t ldxq, int64_t ldwq, int64_t ldy, void *stream);
+
+/*
  * Fused activation quantizer + W8A8 linear: the stages "Activation smoothing", "Quantization",
  * "INT GEMM" and "Dequantization" of App. B.1 in one launch (PTS equation of Sec. 5.1).
  * Computes exactly, bit for bit, what ptq4vm_quantize_pts followed by ptq4vm_w8a8_linear

@@ -7,6 +7,9 @@ from . import binding, synth  # noqa: F401
 from .binding import (  # noqa: F401
     f16_linear,
     fold_smoothing,
+    fold_smoothing_w4,
+    quantize_pts_a4,
+    w4a4_linear,
     quantize_dynamic,
     quantize_pts,
     quantize_pts_offset,

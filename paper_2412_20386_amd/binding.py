@@ -23,6 +23,9 @@ EXPORTS = (
     "ptq4vm_quantize_pts_offset",
     "ptq4vm_weight_rowsum",
     "ptq4vm_w8a8_linear_offset",
+    "ptq4vm_fold_smoothing_w4",
+    "ptq4vm_quantize_pts_a4",
+    "ptq4vm_w4a4_linear",
     "ptq4vm_w8a8_linear",
     "ptq4vm_w8a8_linear_fused",
     "ptq4vm_f16_linear",
@@ -63,6 +66,12 @@ def load() -> ctypes.CDLL:
     lib.ptq4vm_weight_rowsum.argtypes = [vp, vp, i64, i64, i64, vp]
     lib.ptq4vm_w8a8_linear_offset.restype = ci
     lib.ptq4vm_w8a8_linear_offset.argtypes = [vp, vp, vp, vp, vp, vp, vp, vp, vp, i64, i64, i64, i64, i64, i64, i64, vp]
+    lib.ptq4vm_fold_smoothing_w4.restype = ci
+    lib.ptq4vm_fold_smoothing_w4.argtypes = [vp, vp, vp, vp, vp, i64, i64, i64, i64, vp]
+    lib.ptq4vm_quantize_pts_a4.restype = ci
+    lib.ptq4vm_quantize_pts_a4.argtypes = [vp, vp, vp, vp, i64, i64, i64, i64, i64, vp]
+    lib.ptq4vm_w4a4_linear.restype = ci
+    lib.ptq4vm_w4a4_linear.argtypes = [vp, vp, vp, vp, vp, vp, vp, i64, i64, i64, i64, i64, i64, i64, vp]
     lib.ptq4vm_w8a8_linear.restype = ci
     lib.ptq4vm_w8a8_linear.argtypes = [vp, vp, vp, vp, vp, vp, vp, i64, i64, i64, i64, i64, i64, i64, vp]
     lib.ptq4vm_w8a8_linear_fused.restype = ci
@@ -227,6 +236,57 @@ def w8a8_linear_offset(xq: torch.Tensor, wq: torch.Tensor, s_tok: torch.Tensor, 
         raise TypeError("acc_out: expected a dense CUDA int32 [M, N] tensor")
     check(load().ptq4vm_w8a8_linear_offset(_ptr(xq), _ptr(wq), _ptr(s_tok), _ptr(z_tok), _ptr(rowsum), _ptr(s_w),
                                            _ptr(bias), _ptr(y), _ptr(acc_out), B, L, K, N, ldxq, ldwq, ldy, _stream()))
+    return y
+
+
+def fold_smoothing_w4(w: torch.Tensor, m: torch.Tensor, wq4: Optional[torch.Tensor] = None):
+    """ptq4vm_fold_smoothing_w4: (wq4 uint8 [N, K/2] packed, s_w f32 [N], inv_m f32 [K])."""
+    N, K, ldw = _matrix(w, torch.float16, "w")
+    _vector(m, torch.float32, K, "m")
+    if wq4 is None:
+        wq4 = torch.empty((N, K // 2), dtype=torch.uint8, device=w.device)
+    _, _, ldwq = _matrix(wq4, torch.uint8, "wq4")
+    s_w = torch.empty(N, dtype=torch.float32, device=w.device)
+    inv_m = torch.empty(K, dtype=torch.float32, device=w.device)
+    check(load().ptq4vm_fold_smoothing_w4(_ptr(w), _ptr(m), _ptr(wq4), _ptr(s_w), _ptr(inv_m), N, K, ldw, ldwq,
+                                          _stream()))
+    return wq4, s_w, inv_m
+
+
+def quantize_pts_a4(x: torch.Tensor, inv_m: Optional[torch.Tensor], s_tok: torch.Tensor, B: int, L: int,
+                    xq4: Optional[torch.Tensor] = None) -> torch.Tensor:
+    """ptq4vm_quantize_pts_a4: xq4 uint8 [B*L, K/2], two 4-bit codes per byte."""
+    M, K, ldx = _matrix(x, torch.float16, "x")
+    if M != B * L:
+        raise ValueError("x must have B*L rows")
+    _vector(inv_m, torch.float32, K, "inv_m", optional=True)
+    _vector(s_tok, torch.float32, L, "s_tok")
+    if xq4 is None:
+        xq4 = torch.empty((M, K // 2), dtype=torch.uint8, device=x.device)
+    _, _, ldxq = _matrix(xq4, torch.uint8, "xq4")
+    check(load().ptq4vm_quantize_pts_a4(_ptr(x), _ptr(inv_m), _ptr(s_tok), _ptr(xq4), B, L, K, ldx, ldxq, _stream()))
+    return xq4
+
+
+def w4a4_linear(xq4: torch.Tensor, wq4: torch.Tensor, s_tok: torch.Tensor, s_w: torch.Tensor,
+                bias: Optional[torch.Tensor], B: int, L: int, y: Optional[torch.Tensor] = None,
+                acc_out: Optional[torch.Tensor] = None) -> torch.Tensor:
+    """ptq4vm_w4a4_linear: y fp16 [B*L, N] from packed 4-bit operands."""
+    M, K2, ldxq = _matrix(xq4, torch.uint8, "xq4")
+    N, K2w, ldwq = _matrix(wq4, torch.uint8, "wq4")
+    if K2 != K2w or M != B * L:
+        raise ValueError("shape mismatch")
+    _vector(s_tok, torch.float32, L, "s_tok")
+    _vector(s_w, torch.float32, N, "s_w")
+    _vector(bias, torch.float16, N, "bias", optional=True)
+    if y is None:
+        y = torch.empty((M, N), dtype=torch.float16, device=xq4.device)
+    _, _, ldy = _matrix(y, torch.float16, "y")
+    if acc_out is not None and (acc_out.dtype != torch.int32 or tuple(acc_out.shape) != (M, N)
+                                or not acc_out.is_contiguous() or not acc_out.is_cuda):
+        raise TypeError("acc_out: expected a dense CUDA int32 [M, N] tensor")
+    check(load().ptq4vm_w4a4_linear(_ptr(xq4), _ptr(wq4), _ptr(s_tok), _ptr(s_w), _ptr(bias), _ptr(y), _ptr(acc_out),
+                                    B, L, 2 * K2, N, ldxq, ldwq, ldy, _stream()))
     return y
 
 

@@ -1154,9 +1154,9 @@ int dispatch(LinearArgs a, hipStream_t stream) {
     return launch_generic<Path, 256, 64, 4, 1>(a, la, stream);
 }
 
-// Zero-offset linear: the tiled kernels with the offset correction in their epilogue.
-int dispatch_offset(LinearArgs a, hipStream_t stream) {
-    using Path = Int8OffsetPath;
+// Zero-offset and packed 4-bit linears: the tiled kernels with the variant's MFMA loop / epilogue.
+template <class Path>
+int dispatch_tiled(LinearArgs a, hipStream_t stream) {
     const int la = pick_load_align(a);
     a.y_vec = (a.ldy % 8 == 0 && ptq4vm::aligned_to(a.y, 16)) ? 8
               : ((a.ldy % 4 == 0 && ptq4vm::aligned_to(a.y, 8)) ? 4 : 1);
@@ -1204,7 +1204,38 @@ extern "C" int ptq4vm_w8a8_linear_offset(const int8_t *xq, const int8_t *wq, con
     a.ldw_bytes = ldwq;
     a.ldy = ldy;
     a.L = L;
-    return dispatch_offset(a, static_cast<hipStream_t>(stream_));
+    return dispatch_tiled<Int8OffsetPath>(a, static_cast<hipStream_t>(stream_));
+}
+
+extern "C" int ptq4vm_w4a4_linear(const uint8_t *xq4, const uint8_t *wq4, const float *s_tok, const float *s_w,
+                                  const void *bias_f16, void *y_f16, int32_t *acc_out, int64_t B, int64_t L,
+                                  int64_t K, int64_t N, int64_t ldxq, int64_t ldwq, int64_t ldy, void *stream_) {
+    if (!xq4 || !wq4 || !s_tok || !s_w || !y_f16) return PTQ4VM_ERR_NULL;
+    if (B < 0 || N < 0 || L <= 0 || K <= 0 || K > PTQ4VM_MAX_K || K % 2 != 0) return PTQ4VM_ERR_SHAPE;
+    if (B > 0 && L > INT64_MAX / B) return PTQ4VM_ERR_SHAPE;
+    if (ldxq < K / 2 || ldwq < K / 2 || ldy < N) return PTQ4VM_ERR_STRIDE;
+    if (!ptq4vm::aligned_to(xq4, 16) || !ptq4vm::aligned_to(wq4, 16) || !ptq4vm::aligned_to(y_f16, 2) ||
+        !ptq4vm::aligned_to(s_tok, 4) || !ptq4vm::aligned_to(s_w, 4) || !ptq4vm::aligned_to(bias_f16, 2) ||
+        !ptq4vm::aligned_to(acc_out, 4))
+        return PTQ4VM_ERR_ALIGN;
+    const int64_t M = B * L;
+    if (M == 0 || N == 0) return PTQ4VM_OK;
+    LinearArgs a{};
+    a.x = reinterpret_cast<const char *>(xq4);
+    a.w = reinterpret_cast<const char *>(wq4);
+    a.s_tok = s_tok;
+    a.s_w = s_w;
+    a.bias = static_cast<const __half *>(bias_f16);
+    a.y = static_cast<__half *>(y_f16);
+    a.acc_out = acc_out;
+    a.M = M;
+    a.N = N;
+    a.k_bytes = K / 2;  // packed bytes
+    a.ldx_bytes = ldxq;
+    a.ldw_bytes = ldwq;
+    a.ldy = ldy;
+    a.L = L;
+    return dispatch_tiled<Int4Path>(a, static_cast<hipStream_t>(stream_));
 }
 
 extern "C" int ptq4vm_w8a8_linear(const int8_t *xq, const int8_t *wq, const float *s_tok, const float *s_w,

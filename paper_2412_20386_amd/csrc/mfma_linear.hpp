@@ -29,6 +29,7 @@ constexpr int kXcds = 8;
 struct Int8Path {
     static constexpr int kElemBytes = 1;
     static constexpr bool kOffset = false;
+    static constexpr bool kPacked4 = false;
     using Acc = v16i;
     static __device__ __forceinline__ Acc mfma(v4i a, v4i b, Acc c) {
         return __builtin_amdgcn_mfma_i32_32x32x32_i8(a, b, c, 0, 0, 0);
@@ -46,9 +47,23 @@ struct Int8OffsetPath : Int8Path {
     static constexpr bool kOffset = true;
 };
 
+// Two 4-bit codes per byte, the even index in the low nibble (App. B.1 "Quantization").  gfx950
+// has no int4 MFMA, so packed operands travel through memory, L2 and LDS at half the bytes and are
+// expanded in registers right before the int8 MFMA: `p & 0xF0F0F0F0` is the odd codes times 16 as
+// int8 bytes and `(p << 4) & 0xF0F0F0F0` the even codes times 16 (the nibble's two's complement sits
+// in the byte's top bits, so no sign extension is needed).  One packed 16-byte operand becomes two
+// MFMA operands (even and odd reduction indices; both matrices split the same way, so the sum is
+// unchanged); the accumulator is 256 times the true one and is shifted back, exactly, in the epilogue.
+struct Int4Path : Int8Path {
+    static constexpr bool kPacked4 = true;
+    static __device__ __forceinline__ v4i even_codes(v4i p) { return (p << 4) & (int)0xF0F0F0F0; }
+    static __device__ __forceinline__ v4i odd_codes(v4i p) { return p & (int)0xF0F0F0F0; }
+};
+
 struct Half16Path {
     static constexpr int kElemBytes = 2;
     static constexpr bool kOffset = false;
+    static constexpr bool kPacked4 = false;
     using Acc = v16f;
     static __device__ __forceinline__ Acc mfma(v4i a, v4i b, Acc c) {
         return __builtin_amdgcn_mfma_f32_32x32x16_f16(__builtin_bit_cast(v8h, a), __builtin_bit_cast(v8h, b), c, 0,
@@ -120,10 +135,25 @@ __device__ __forceinline__ void mfma_slab(typename Path::Acc (&acc)[FO][FR], con
             const int row = j * 32 + l32;
             fx[j] = *reinterpret_cast<const v4i *>(x_rows + row * kSlabBytes + ((kc ^ swizzle(row)) << 4));
         }
+        if constexpr (Path::kPacked4) {
 #pragma unroll
-        for (int i = 0; i < FO; i++)
+            for (int half = 0; half < 2; half++) {
+                v4i ew[FO], ex[FR];
 #pragma unroll
-            for (int j = 0; j < FR; j++) acc[i][j] = Path::mfma(fw[i], fx[j], acc[i][j]);
+                for (int i = 0; i < FO; i++) ew[i] = half ? Path::odd_codes(fw[i]) : Path::even_codes(fw[i]);
+#pragma unroll
+                for (int j = 0; j < FR; j++) ex[j] = half ? Path::odd_codes(fx[j]) : Path::even_codes(fx[j]);
+#pragma unroll
+                for (int i = 0; i < FO; i++)
+#pragma unroll
+                    for (int j = 0; j < FR; j++) acc[i][j] = Path::mfma(ew[i], ex[j], acc[i][j]);
+            }
+        } else {
+#pragma unroll
+            for (int i = 0; i < FO; i++)
+#pragma unroll
+                for (int j = 0; j < FR; j++) acc[i][j] = Path::mfma(fw[i], fx[j], acc[i][j]);
+        }
     }
 }
 
@@ -187,7 +217,8 @@ __device__ __forceinline__ void epilogue(const typename Path::Acc (&acc)[FO][FR]
 #pragma unroll
                     for (int c = 0; c < 4; c++) {
                         if constexpr (Path::kElemBytes == 1) {
-                            const int a = acc[i][j][g * 4 + c];
+                            int a = acc[i][j][g * 4 + c];
+                            if constexpr (Path::kPacked4) a >>= 8;  // operands were codes times 16: exact
                             if (p.acc_out) {
                                 const int64_t r = r_base + j * 32 + l32;
                                 const int64_t o = o_base + i * 32 + g * 8 + lhalf * 4 + c;

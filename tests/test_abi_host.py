@@ -132,6 +132,34 @@ def test_zero_offset_entry_points_argument_checks(lib):
     assert call(a9=0) == 0
 
 
+def test_w4a4_entry_points_argument_checks(lib):
+    fold = lib.ptq4vm_fold_smoothing_w4
+    assert fold(NULL, P, P, P, P, 1, 8, 8, 4, None) == -1
+    assert fold(P, P, P, P, P, 1, 7, 8, 4, None) == -2               # odd K cannot be packed in pairs
+    assert fold(P, P, P, P, P, 1, 8, 8, 3, None) == -3
+    assert fold(ODD, P, P, P, P, 1, 8, 8, 4, None) == -4
+    q = lib.ptq4vm_quantize_pts_a4
+    assert q(NULL, P, P, P, 1, 1, 8, 8, 4, None) == -1
+    assert q(P, P, P, P, 1, 1, 9, 9, 5, None) == -2
+    assert q(P, P, P, P, 1, 1, 8, 8, 3, None) == -3
+    assert q(P, P, P, ODD, 1, 1, 8, 8, 4, None) == -4
+    assert q(P, NULL, P, P, 0, 5, 8, 8, 4, None) == 0
+    f = lib.ptq4vm_w4a4_linear
+    ok = [P, P, P, P, P, P, NULL, 1, 1, 16, 16, 8, 8, 16, None]
+
+    def call(**kw):
+        a = list(ok)
+        for i, v in kw.items():
+            a[int(i[1:])] = v
+        return f(*a)
+
+    assert call(a0=NULL) == -1 and call(a5=NULL) == -1
+    assert call(a9=15) == -2 and call(a9=0) == -2 and call(a8=0) == -2
+    assert call(a11=7) == -3 and call(a12=7) == -3 and call(a13=15) == -3
+    assert call(a0=ODD) == -4 and call(a1=ODD) == -4
+    assert call(a7=0) == 0
+
+
 def test_w8a8_linear_fused_argument_checks(lib):
     f = lib.ptq4vm_w8a8_linear_fused
     #     x  inv_m s_tok wq s_w bias y acc  xq   B  L  K   N   ldx ldwq ldy ldxq stream

@@ -554,3 +554,84 @@ def test_zero_offset_quantizer_long_sequence_and_plain_kernels():
         torch.cuda.synchronize()
         xq_o = oracle.quantize_pts_offset(_np(x), _np(1.0 / c.m), _np(s_off), _np(z_off), B, L)
         assert np.array_equal(_np(xq), xq_o), (B, L, K)
+
+
+# ---------------------------------------------------------------------------------- W4A4 (packed 4-bit codes)
+def _steps_4bit(c):
+    """The calibrated +-127 steps rescaled to the +-7 range (input preparation, fp32)."""
+    return (c.s_tok * (127.0 / 7.0)).contiguous()
+
+
+W4A4_SHAPES = [  # B, L, K, N
+    (3, 197, 384, 192), (2, 197, 192, 768), (2, 197, 384, 44), (3, 197, 12, 384), (2, 65, 24, 768), (2, 50, 768, 56),
+    (1, 300, 1536, 80), (1, 1, 64, 32), (1, 257, 100, 130), (2, 33, 14, 5), (1, 129, 1000, 257), (5, 7, 16, 1),
+    (2, 140, 128, 300),
+]
+
+
+@pytest.mark.parametrize("B,L,K,N", W4A4_SHAPES)
+def test_w4a4_path_against_oracle(B, L, K, N):
+    print(f"w4a4 B={B} L={L} K={K} N={N}", flush=True)
+    c = synth.random_problem(53 * K + N, B, L, K, N, device=DEV)
+    s4 = _steps_4bit(c)
+    M = B * L
+    wq4, s_w, inv_m = ptq.fold_smoothing_w4(c.w, c.m)
+    xq4 = ptq.quantize_pts_a4(c.x, inv_m, s4, B, L)
+    acc = torch.full((M, N), -1, dtype=torch.int32, device=DEV)
+    y = ptq.w4a4_linear(xq4, wq4, s4, s_w, c.bias, B, L, acc_out=acc)
+    y2 = ptq.w4a4_linear(xq4, wq4, s4, s_w, c.bias, B, L)
+    torch.cuda.synchronize()
+
+    wq_o, s_w_o, inv_m_o = oracle.fold_smoothing_bits(_np(c.w), _np(c.m), 4)
+    xq_o = oracle.quantize_pts_bits(_np(c.x), inv_m_o, _np(s4), B, L, 4)
+    assert np.array_equal(_np(s_w).view(np.uint32), s_w_o.view(np.uint32))
+    assert np.array_equal(_np(inv_m).view(np.uint32), inv_m_o.view(np.uint32))
+    assert np.array_equal(_np(wq4), oracle.pack_int4(wq_o)), "packed weight codes differ"
+    assert np.array_equal(_np(xq4), oracle.pack_int4(xq_o)), "packed activation codes differ"
+    y_o, y64, acc_o = oracle.w8a8_linear(xq_o, wq_o, _np(s4), s_w_o, _np(c.bias), B, L)
+    assert np.array_equal(_np(acc), acc_o), "int32 accumulators differ"
+    st = np.tile(_np(s4).astype(np.float64), B)[:, None]
+    prod_abs = np.abs(acc_o.astype(np.float64) * st * s_w_o.astype(np.float64)[None, :])
+    bias_abs = np.broadcast_to(np.abs(_np(c.bias).astype(np.float64))[None, :], prod_abs.shape)
+    check_dequantized_output(_np(y), y_o, y64, prod_abs, bias_abs, "w4a4")
+    assert torch.equal(y.view(torch.int16), y2.view(torch.int16))
+
+
+def test_w4a4_all_nibble_pairs_through_the_linear():
+    """Every (activation code, weight code) pair in [-8, 7]^2, including the -8 the quantizers never emit."""
+    codes = np.arange(-8, 8, dtype=np.int8)
+    xq = np.repeat(codes, 16)[None, :].repeat(3, axis=0)             # [3, 256]
+    wq = np.tile(codes, 16)[None, :].repeat(2, axis=0)
+    wq[1] = wq[1, ::-1]
+    xq4 = torch.from_numpy(oracle.pack_int4(xq)).to(DEV)
+    wq4 = torch.from_numpy(oracle.pack_int4(wq)).to(DEV)
+    s_tok = torch.full((3,), 2.0 ** -6, device=DEV)
+    s_w = torch.full((2,), 2.0 ** -5, device=DEV)
+    acc = torch.empty((3, 2), dtype=torch.int32, device=DEV)
+    y = ptq.w4a4_linear(xq4, wq4, s_tok, s_w, None, 1, 3, acc_out=acc)
+    torch.cuda.synchronize()
+    y_o, y64, acc_o = oracle.w8a8_linear(xq, wq, _np(s_tok), _np(s_w), None, 1, 3)
+    assert np.array_equal(_np(acc), acc_o)
+    assert np.array_equal(_np(y).view(np.uint16), y_o.view(np.uint16))
+
+
+@pytest.mark.parametrize("cfg,linear", [(3, 0), (3, 1), (3, 3), (1, 2)])
+def test_w4a4_full_size_sampled(cfg, linear):
+    c = synth.make_linear_case(cfg, 0, linear, device=DEV)
+    M = c.B * c.L
+    print(f"w4a4 full-size cfg{cfg} {c.name}: M={M} K={c.K} N={c.N}", flush=True)
+    s4 = _steps_4bit(c)
+    wq4, s_w, inv_m = ptq.fold_smoothing_w4(c.w, c.m)
+    xq4 = ptq.quantize_pts_a4(c.x, inv_m, s4, c.B, c.L)
+    y = ptq.w4a4_linear(xq4, wq4, s4, s_w, c.bias, c.B, c.L)
+    torch.cuda.synchronize()
+    rows = _sampled_rows(M, 97, c.L)
+    ridx = torch.from_numpy(rows).to(DEV)
+    wq_o, s_w_o, inv_m_o = oracle.fold_smoothing_bits(_np(c.w), _np(c.m), 4)
+    st_rows = _np(s4)[rows % c.L]
+    xq_o = oracle.quantize_pts_bits(_np(c.x[ridx]), inv_m_o, st_rows, 1, len(rows), 4)
+    assert np.array_equal(_np(xq4[ridx]), oracle.pack_int4(xq_o))
+    y_o, y64, acc_o = oracle.w8a8_linear(xq_o, wq_o, st_rows, s_w_o, _np(c.bias), 1, len(rows))
+    prod_abs = np.abs(acc_o.astype(np.float64) * st_rows.astype(np.float64)[:, None] * s_w_o.astype(np.float64)[None, :])
+    bias_abs = np.broadcast_to(np.abs(_np(c.bias).astype(np.float64))[None, :], prod_abs.shape)
+    check_dequantized_output(_np(y[ridx]), y_o, y64, prod_abs, bias_abs, f"w4a4 cfg{cfg} {c.name}")
