@@ -34,8 +34,8 @@ PEAK_HBM_GBS = 8000.0     # HBM3E
 
 # HBM traffic of the dominant kernel (in_proj GEMM of configs[3]) per launch, bytes, from two
 # rocprofv3 --pmc runs (FETCH_SIZE, WRITE_SIZE), each scaled by the 256 MiB copy this script also
-# issues: 107.4 MB fetched + 311.7 MB written (profiles/bench_vim_b_stack_kernel_trace_and_traffic.txt).
-DOMINANT_TRAFFIC_BYTES = {3: 419.1e6}
+# issues: 106.5 MB fetched + 310.1 MB written (profiles/bench_vim_b_stack_kernel_trace_and_traffic.txt).
+DOMINANT_TRAFFIC_BYTES = {3: 416.6e6}
 
 
 def main() -> int:
@@ -165,6 +165,18 @@ def main() -> int:
         tzg = time_launch(lambda lin: ptq.w8a8_linear_offset(lin[li]["xq"], lin[li]["wq"], lin[li]["s_tok"], z_tok,
                                                              rs_of[id(lin)], lin[li]["s_w"], lin[li]["bias"], B, L,
                                                              y=lin[li]["y"]))
+        # W4A4 (packed 4-bit codes, tiled kernels): timing only
+        t4q = t4g = None
+        if K % 2 == 0:
+            s4 = [(lin[li]["s_tok"] * (127.0 / 7.0)).contiguous() for lin in layers]
+            w4 = [ptq.fold_smoothing_w4(lin[li]["w"], 1.0 / lin[li]["inv_m"]) for lin in layers]
+            xq4 = [lin[li]["xq"].view(torch.uint8).view(-1)[: M * (K // 2)].view(M, K // 2) for lin in layers]
+            idx = {id(lin): i for i, lin in enumerate(layers)}
+            t4q = time_launch(lambda lin: ptq.quantize_pts_a4(lin[li]["x"], lin[li]["inv_m"], s4[idx[id(lin)]], B, L,
+                                                              xq4=xq4[idx[id(lin)]]))
+            t4g = time_launch(lambda lin: ptq.w4a4_linear(xq4[idx[id(lin)]], w4[idx[id(lin)]][0], s4[idx[id(lin)]],
+                                                          w4[idx[id(lin)]][1], lin[li]["bias"], B, L, y=lin[li]["y"]))
+            del w4
         tfu = None
         if layers[0][li]["fused"]:
             tfu = time_launch(lambda lin: ptq.w8a8_linear_fused(lin[li]["x"], lin[li]["inv_m"], lin[li]["s_tok"],
@@ -181,6 +193,9 @@ def main() -> int:
             w8a8_frac_int8_peak=round(ops / tg / 1e6 / PEAK_INT8_TOPS, 4),
             w8a8_GBps=round(g_bytes / tg / 1e3, 1), w8a8_frac_hbm=round(g_bytes / tg / 1e3 / PEAK_HBM_GBS, 4),
             offset_quantize_us=round(tzq, 2), offset_w8a8_us=round(tzg, 2),
+            a4_quantize_us=None if t4q is None else round(t4q, 2),
+            a4_quantize_GBps=None if t4q is None else round((2.5 * M * K) / t4q / 1e3, 1),
+            w4a4_us=None if t4g is None else round(t4g, 2),
             dynamic_quantize_us=round(td, 2), dynamic_quantize_GBps=round((q_bytes + 4.0 * M) / td / 1e3, 1),
             f16_us=round(tf, 2), f16_TFLOPS=round(ops / tf / 1e6, 1),
             speedup_gemm_only=round(tf / tg, 3), speedup_quant_plus_gemm=round(tf / (tq + tg), 3)))
