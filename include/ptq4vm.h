@@ -19,7 +19,8 @@
  *     keeps no state between calls and never synchronises: work is enqueued on `stream`
  *     (a hipStream_t passed as void*, NULL = the default stream) and the call returns at once.
  *     Inputs are only read; outputs must not overlap inputs.  fp16 buffers are passed as
- *     void* (IEEE binary16).
+ *     void* (IEEE binary16).  A matrix buffer must span rows * ld elements (the last row's
+ *     padding up to its pitch included): vector loads may touch the padding of a row.
  *   - Alignment: base pointers of fp16 and int8 matrices must be 16-byte aligned, float
  *     vectors 4-byte aligned (else PTQ4VM_ERR_ALIGN).  Rows need not be 16-byte multiples
  *     (K = 12 with ld = 12, N = 44 with ld = 44 are valid); rows whose byte pitch is a multiple
