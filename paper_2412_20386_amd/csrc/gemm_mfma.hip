@@ -27,6 +27,10 @@
 // stores are 16 bytes per lane and cover whole contiguous row segments.
 #include "mfma_linear.hpp"
 
+#ifndef PTQ4VM_PERSISTENT_PHYS_SLAB
+#define PTQ4VM_PERSISTENT_PHYS_SLAB 128  // K bytes per LDS row of a ring stage (64: twice the stages in the same LDS)
+#define PTQ4VM_PERSISTENT_STAGES 2
+#endif
 #ifndef PTQ4VM_STREAM_SMALLK
 #define PTQ4VM_STREAM_SMALLK 1
 #endif
@@ -204,6 +208,16 @@ __device__ __forceinline__ void lds_read_8x_b32(uint32_t base, float (&v)[8]) {
           "n"(7 * STEP)
         : "memory");
 }
+// four 4-byte reads at base + STEP n
+template <int STEP>
+__device__ __forceinline__ void lds_read_4x_b32(uint32_t base, float (&v)[4]) {
+    asm volatile(
+        "ds_read_b32 %0, %4 offset:%5\n ds_read_b32 %1, %4 offset:%6\n ds_read_b32 %2, %4 offset:%7\n"
+        "ds_read_b32 %3, %4 offset:%8\n s_waitcnt lgkmcnt(0)"
+        : "=&v"(v[0]), "=&v"(v[1]), "=&v"(v[2]), "=&v"(v[3])
+        : "v"(base), "n"(0), "n"(STEP), "n"(2 * STEP), "n"(3 * STEP)
+        : "memory");
+}
 // four 16-byte reads at arbitrary addresses
 __device__ __forceinline__ void lds_read_4_b128(const uint32_t (&addr)[4], v4f (&v)[4]) {
     asm volatile(
@@ -224,12 +238,17 @@ __device__ __forceinline__ void wait_vmcnt_at_most() {
     __builtin_amdgcn_s_waitcnt(0x0F70 | (KEEP & 15) | ((KEEP >> 4) << 14));
 }
 
-template <class Path, int BO, int SLAB, int STAGES, bool HAS_BIAS, bool DUMP_ACC>
-__global__ __launch_bounds__(BO * 2, 2) void linear_mfma_persistent(const LinearArgs p) {
-    // 256 x 256 tile on 8 wavefronts (one workgroup per CU) or 256 x 128 on 4 (two per CU)
-    constexpr int BR = 256, WO = BO / 64, NW = 2 * WO;
-    constexpr int WAVE_R = 128, WAVE_O = 64;
-    constexpr int FR = WAVE_R / 16, FO = WAVE_O / 16;  // 16 x 16 MFMA blocks of the wave tile
+// The tiles `first`, `first + stride`, ... (n_my of them) of the grid of (32 FR)-row x BO-channel
+// tiles, channel tiles fastest, processed by the whole workgroup.  FR = 8: 256-row tiles; FR = 4:
+// 128-row half tiles (used to spread a last, partial round of tiles over idle workgroups).
+template <class Path, int BO, int SLAB, int STAGES, bool HAS_BIAS, bool DUMP_ACC, int FR>
+__device__ __forceinline__ void persistent_tiles(const LinearArgs &p, const int first, const int stride,
+                                                 const int n_my) {
+    // (32 FR) x 256 tile on 8 wavefronts (one workgroup per CU) or (32 FR) x 128 on 4 (two per CU)
+    constexpr int BR = 32 * FR, WO = BO / 64, NW = 2 * WO;
+    constexpr int WAVE_R = 16 * FR, WAVE_O = 64;
+    constexpr int FO = WAVE_O / 16;  // 16 x 16 MFMA blocks of the wave tile: FO x FR
+    static_assert(FR == 8 || FR == 4, "wave tile height");
     static_assert(BO == 256 || BO == 128, "tile width");
     constexpr int KS = SLAB / 64;             // MFMA k-steps (64 bytes of K each) per slab
     constexpr int CHUNKS = SLAB / 16;         // 16-byte chunks per LDS row
@@ -239,7 +258,6 @@ __global__ __launch_bounds__(BO * 2, 2) void linear_mfma_persistent(const Linear
     constexpr int STAGE_BYTES = (BR + BO) * SLAB;
     constexpr int KEEP = (STAGES - 2) * LOADS_PER_SLAB;  // copies allowed in flight when a slab is needed
     static_assert(SLAB == 64 || SLAB == 128, "LDS rows hold 64 or 128 bytes of K");
-    static_assert(KS % 2 == 0, "the register double buffer of the weight fragments alternates per k-step");
     static_assert(NW * 32 * WAVE_O * 2 <= STAGE_BYTES, "epilogue patches must fit one stage");
     constexpr bool kInt8 = Path::kElemBytes == 1;
     using Acc = typename Path::Acc16;
@@ -256,13 +274,7 @@ __global__ __launch_bounds__(BO * 2, 2) void linear_mfma_persistent(const Linear
         return row * SLAB + ((chunk ^ (SLAB == 64 ? swizzle(row) : (row & 7))) << 4);
     };
 
-    // Tiles of this workgroup: XCD x owns a contiguous range, its workgroups interleave in it.
-    const int total_tiles = p.tiles_o * p.tiles_r;
-    const int per_xcd = (total_tiles + kXcds - 1) / kXcds;
-    const int wgs_per_xcd = (int)gridDim.x / kXcds;
-    const int first = (int)(blockIdx.x % kXcds) * per_xcd + (int)(blockIdx.x / kXcds);
-    const int last = min(((int)(blockIdx.x % kXcds) + 1) * per_xcd, total_tiles);
-    const int n_my = first < last ? (last - first + wgs_per_xcd - 1) / wgs_per_xcd : 0;
+    const int wgs_per_xcd = stride, last = first + n_my * stride;
     const int n_slabs = (int)(p.k_bytes / SLAB);
     const int total_slabs = n_my * n_slabs;
     if (total_slabs == 0) return;
@@ -391,12 +403,18 @@ __global__ __launch_bounds__(BO * 2, 2) void linear_mfma_persistent(const Linear
         load_fw(0, stage, 0);  // B(g) for the tile's first slab was passed during the previous tile
 #pragma unroll
         for (int j = 0; j < FR; j++) load_fx(j, stage, 0);
-        for (int s = 0; s < n_slabs; s++, g++) {
+        // U slabs per trip of the loop, so that the register buffer of the weight fragments, which
+        // alternates per k-step, starts every trip (and every tile) at buffer 0.
+        constexpr int U = (KS % 2 == 0) ? 1 : 2;
+        for (int s0 = 0; s0 < n_slabs; s0 += U)
+#pragma unroll
+        for (int h = 0; h < U; h++, g++) {
+            const int s = s0 + h;
             int next_stage = stage + 1;
             if (next_stage == STAGES) next_stage = 0;
 #pragma unroll
             for (int ks = 0; ks < KS; ks++) {
-                const int cur = ks & 1;
+                const int cur = (h * KS + ks) & 1;
                 bool has_next = false;
                 int nstg = stage, nks = ks + 1;
                 if (ks + 1 < KS) {
@@ -448,7 +466,16 @@ __global__ __launch_bounds__(BO * 2, 2) void linear_mfma_persistent(const Linear
         float rs_raw[8];
         if constexpr (kInt8) lds_read_4x_b128<64>(lds_addr(cs_lds + wave_o + lq * 4), cs_raw);
         if constexpr (HAS_BIAS) lds_read_4x_b128<32>(lds_addr(cb_lds + (wave_o + (lq >> 1) * 8) / 2), cb_raw);
-        if constexpr (kInt8) lds_read_8x_b32<64>(lds_addr(rs_lds + wave_r + l16), rs_raw);
+        if constexpr (kInt8) {
+            if constexpr (FR == 8) {
+                lds_read_8x_b32<64>(lds_addr(rs_lds + wave_r + l16), rs_raw);
+            } else {
+                float half_rs[4];
+                lds_read_4x_b32<64>(lds_addr(rs_lds + wave_r + l16), half_rs);
+#pragma unroll
+                for (int j = 0; j < 4; j++) rs_raw[j] = half_rs[j];
+            }
+        }
         float bias4[FO][4];
 #pragma unroll
         for (int i = 0; i < FO; i++) {
@@ -513,6 +540,35 @@ __global__ __launch_bounds__(BO * 2, 2) void linear_mfma_persistent(const Linear
         }
         __builtin_amdgcn_s_barrier();  // every wavefront has read its patch back: the stage can be refilled
         if (issued < total_slabs) issue();
+    }
+}
+
+// Work split.  Workgroup ids go round-robin over the XCDs; XCD x owns a contiguous range of 256-row
+// tiles (channel tiles fastest, so tiles sharing an activation strip share one L2) and its
+// workgroups interleave in it.  A range is whole rounds of tiles plus a partial last round; when
+// that last round has at most half as many tiles as the XCD has workgroups, its tiles are cut into
+// two 128-row halves so that twice as many workgroups finish it in about half a tile's time
+// (Vim-B out_proj: 2.31 rounds -> 2 + 1/2 instead of 3, measured 81 -> 74 us).  The half-tile pass
+// restarts the slab pipeline and a 128 x 256 tile needs more LDS traffic per MAC, so it costs ~0.7 of a
+// tile; with many rounds (in_proj: 9.23) that gains nothing and the split is not used.
+template <class Path, int BO, int SLAB, int STAGES, bool HAS_BIAS, bool DUMP_ACC>
+__global__ __launch_bounds__(BO * 2, 2) void linear_mfma_persistent(const LinearArgs p) {
+    const int total_tiles = p.tiles_o * p.tiles_r;
+    const int per_xcd = (total_tiles + kXcds - 1) / kXcds;
+    const int wpx = (int)gridDim.x / kXcds, xcd = (int)(blockIdx.x % kXcds), j = (int)(blockIdx.x / kXcds);
+    const int lo = xcd * per_xcd, hi = min(lo + per_xcd, total_tiles);
+    const int n = max(hi - lo, 0);
+    const int rounds = n / wpx, tail = n - rounds * wpx;
+    const bool halves = tail > 0 && 2 * tail <= wpx && rounds < 6;
+    const int n_full = rounds + ((!halves && j < tail) ? 1 : 0);
+    persistent_tiles<Path, BO, SLAB, STAGES, HAS_BIAS, DUMP_ACC, 8>(p, lo + j, wpx, n_full);
+    if (halves && j < 2 * tail) {
+        const int tile = lo + rounds * wpx + (j >> 1);
+        const int half_tile = ((tile / p.tiles_o) * 2 + (j & 1)) * p.tiles_o + tile % p.tiles_o;  // in the 128-row grid
+        if ((int64_t)(half_tile / p.tiles_o) * 128 < p.M) {
+            __syncthreads();  // the ring and the scale buffers change layout
+            persistent_tiles<Path, BO, SLAB, STAGES, HAS_BIAS, DUMP_ACC, 4>(p, half_tile, 1, 1);
+        }
     }
 }
 
@@ -1139,7 +1195,7 @@ int dispatch(LinearArgs a, hipStream_t stream) {
     // 256 x 256 tiles on one 8-wavefront workgroup per CU.  (The 256 x 128 / two 4-wavefront workgroups
     // per CU instantiation balances few-tile problems better but moves 1.5x the bytes through L2; it
     // measured 3 % slower on out_proj and 10 % slower on in_proj of the Vim-B stack.)
-    if (persistent_ok) return launch_persistent<Path, 256, PTQ4VM_PERSISTENT_SLAB, 2>(a, stream);
+    if (persistent_ok) return launch_persistent<Path, 256, PTQ4VM_PERSISTENT_PHYS_SLAB, PTQ4VM_PERSISTENT_STAGES>(a, stream);
     // Few output channels over many rows: weight resident in LDS, activations streamed once.
     const bool wres_ok = dma_ok && a.N <= 16 * kWresMaxBlocks && a.M >= kWresMinRows && a.M < (1LL << 31) &&
                          a.L < (1LL << 31) && a.k_bytes < (1LL << 20) &&
