@@ -550,7 +550,8 @@ __device__ __forceinline__ void persistent_tiles(const LinearArgs &p, const int 
 // two 128-row halves so that twice as many workgroups finish it in about half a tile's time
 // (Vim-B out_proj: 2.31 rounds -> 2 + 1/2 instead of 3, measured 81 -> 74 us).  The half-tile pass
 // restarts the slab pipeline and a 128 x 256 tile needs more LDS traffic per MAC, so it costs ~0.7 of a
-// tile; with many rounds (in_proj: 9.23) that gains nothing and the split is not used.
+// tile; with many rounds of short tiles (in_proj: 9.23 rounds, K = 768) that gains nothing and the
+// split is not used (K = 1536 over 9.23 rounds still gains 3 %).
 template <class Path, int BO, int SLAB, int STAGES, bool HAS_BIAS, bool DUMP_ACC>
 __global__ __launch_bounds__(BO * 2, 2) void linear_mfma_persistent(const LinearArgs p) {
     const int total_tiles = p.tiles_o * p.tiles_r;
@@ -559,7 +560,7 @@ __global__ __launch_bounds__(BO * 2, 2) void linear_mfma_persistent(const Linear
     const int lo = xcd * per_xcd, hi = min(lo + per_xcd, total_tiles);
     const int n = max(hi - lo, 0);
     const int rounds = n / wpx, tail = n - rounds * wpx;
-    const bool halves = tail > 0 && 2 * tail <= wpx && rounds < 6;
+    const bool halves = tail > 0 && 2 * tail <= wpx && (rounds < 6 || p.k_bytes >= 1536);
     const int n_full = rounds + ((!halves && j < tail) ? 1 : 0);
     persistent_tiles<Path, BO, SLAB, STAGES, HAS_BIAS, DUMP_ACC, 8>(p, lo + j, wpx, n_full);
     if (halves && j < 2 * tail) {
