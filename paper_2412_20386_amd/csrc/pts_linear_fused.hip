@@ -42,15 +42,31 @@ __device__ __forceinline__ uint32_t pack4(int a, int b, int c, int d) {
     return __builtin_amdgcn_perm(hi, lo, 0x05040100u);
 }
 
+// f32(fp16 half of `pair`) * m in one instruction: v_fma_mix_f32 converts the selected half exactly,
+// multiplies and rounds once to fp32 - the same value as a conversion followed by v_mul_f32.
+template <bool HIGH>
+__device__ __forceinline__ float half_times(int pair, float m) {
+    float d;
+    if constexpr (HIGH)
+        asm("v_fma_mix_f32 %0, %1, %2, 0 op_sel:[1,0,0] op_sel_hi:[1,0,0]" : "=v"(d) : "v"(pair), "v"(m));
+    else
+        asm("v_fma_mix_f32 %0, %1, %2, 0 op_sel_hi:[1,0,0]" : "=v"(d) : "v"(pair), "v"(m));
+    return d;
+}
+
+__device__ __forceinline__ int code_of_smoothed(float v, float inv_s) {
+    const int q = cvt_i32_f32(__builtin_rintf(v * inv_s));
+    return min(max(q, -127), 127);
+}
+
 // Eight fp16 values (one 16-byte load) -> eight int8 codes.
 __device__ __forceinline__ u32x2 quantize_8(v4i raw, const float (&im)[8], float inv_s) {
     int q[8];
 #pragma unroll
     for (int e = 0; e < 4; e++) {
         const int word = raw[e];  // (a bit_cast applied directly to a vector element reads element 0 with this compiler)
-        const __half2 h = __builtin_bit_cast(__half2, word);
-        q[2 * e] = quantize_one(__low2float(h), im[2 * e], inv_s);
-        q[2 * e + 1] = quantize_one(__high2float(h), im[2 * e + 1], inv_s);
+        q[2 * e] = code_of_smoothed(half_times<false>(word, im[2 * e]), inv_s);
+        q[2 * e + 1] = code_of_smoothed(half_times<true>(word, im[2 * e + 1]), inv_s);
     }
     u32x2 out = {pack4(q[0], q[1], q[2], q[3]), pack4(q[4], q[5], q[6], q[7])};
     return out;
@@ -71,7 +87,12 @@ __device__ __forceinline__ u32x2 quantize_8(v4i raw, const float (&im)[8], float
 // Requirements (host-checked): K % 64 == 0, 16-byte aligned fp16 rows and weight rows, N <= 128,
 // M, L < 2^31, all tables fit the LDS.
 // ------------------------------------------------------------------------------------------
-constexpr int kFusedWaves = 8;
+#ifndef PTQ4VM_FUSED_RB
+#define PTQ4VM_FUSED_RB 2
+#endif
+constexpr int kFusedRB = PTQ4VM_FUSED_RB;       // 16-row MFMA blocks per unit (2: 32-row units on 8 wavefronts, 1: 16-row units on 16)
+constexpr int kFusedWaves = 16 / kFusedRB;
+constexpr int kFusedPatchRows = 8 * kFusedRB;   // result rows staged per pass of the epilogue
 constexpr int kFusedMaxBlocks = 8;   // 16-channel blocks: N <= 128
 constexpr int kLdsBytes = 160 * 1024;
 constexpr int64_t kFusedMinRows = 16384;  // below this the one-off table copies per workgroup do not pay
@@ -89,8 +110,9 @@ __host__ __device__ __forceinline__ FusedLayout fused_layout(int N, int K, int L
     l.inv_s_off = l.inv_m_off + K * 4;
     l.scale_off = l.inv_s_off + ((L * 4 + 15) & ~15);
     l.tile_off = l.scale_off + l.nb * 16 * 4 * 2;
-    const int patch = 16 * l.n4 * 2;                 // one 16-row block of fp16 results
-    l.tile_bytes = patch > 2048 ? patch : 2048;      // or the 32 x 64-byte tile of codes
+    const int patch = kFusedPatchRows * l.n4 * 2;    // one pass of fp16 results
+    const int codes = 1024 * kFusedRB;               // or the (16 RB) x 64-byte tile of codes
+    l.tile_bytes = patch > codes ? patch : codes;
     l.total = l.tile_off + kFusedWaves * l.tile_bytes;
     return l;
 }
@@ -115,22 +137,23 @@ __global__ __launch_bounds__(kFusedWaves * 64) void pts_linear_wres(const Linear
 
     // Units are dealt wavefront-major, so that a launch with fewer units than wavefronts still
     // spreads them over all workgroups.
-    const int64_t units = (p.M + 31) >> 5;
+    constexpr int RB = kFusedRB, UNIT = 16 * RB, NL = 2 * RB, PR = kFusedPatchRows;  // NL loads of 8 rows per k-step
+    const int64_t units = (p.M + UNIT - 1) / UNIT;
     const int64_t unit_step = (int64_t)gridDim.x * kFusedWaves;
     int64_t unit = (int64_t)wave * gridDim.x + blockIdx.x;
 
-    v4i raw[D][4];
-    const char *xrow[4];
-    uint32_t tok[4];
+    v4i raw[D][NL];
+    const char *xrow[NL];
+    uint32_t tok[NL];
     auto load_x = [&](int d, int ks) {
 #pragma unroll
-        for (int i = 0; i < 4; i++)
+        for (int i = 0; i < NL; i++)
             raw[d][i] = __builtin_nontemporal_load(reinterpret_cast<const v4i *>(xrow[i] + ks * 128));
     };
     auto start_unit = [&](int64_t u) {  // first D k-steps of the unit's 32 rows
 #pragma unroll
-        for (int i = 0; i < 4; i++) {
-            const int64_t r = min(u * 32 + i * 8 + rr, p.M - 1);  // clamped rows are never stored
+        for (int i = 0; i < NL; i++) {
+            const int64_t r = min(u * UNIT + i * 8 + rr, p.M - 1);  // clamped rows are never stored
             xrow[i] = p.x + r * p.ldx_bytes + pc * 16;
             tok[i] = (uint32_t)r % (uint32_t)L;
         }
@@ -165,26 +188,26 @@ __global__ __launch_bounds__(kFusedWaves * 64) void pts_linear_wres(const Linear
     const int chunks8_per_row = n4 >> 2;  // 8-byte groups of four channels per result row
     const char *const w_lane = w_lds + l16 * pw + lq * 16;
     // Code tile: row pitch 64 bytes, 16-byte chunk c of row r stored at chunk position c ^ ((r >> 2) & 3).
-    uint32_t tile_wr[4];
+    uint32_t tile_wr[NL];
 #pragma unroll
-    for (int i = 0; i < 4; i++) {
+    for (int i = 0; i < NL; i++) {
         const int row = i * 8 + rr;
         tile_wr[i] = row * 64 + (((pc >> 1) ^ ((row >> 2) & 3)) << 4) + (pc & 1) * 8;
     }
     const uint32_t tile_rd = l16 * 64 + ((lq ^ ((l16 >> 2) & 3)) << 4);  // + 1024 for rows 16..31
 
     for (; unit < units; unit += unit_step) {
-        Acc acc[2][NB];
+        Acc acc[RB][NB];
 #pragma unroll
-        for (int j = 0; j < 2; j++)
+        for (int j = 0; j < RB; j++)
 #pragma unroll
             for (int i = 0; i < NB; i++)
 #pragma unroll
                 for (int v = 0; v < 4; v++) acc[j][i][v] = 0;
-        float inv_s[4];
+        float inv_s[NL];
 #pragma unroll
-        for (int i = 0; i < 4; i++) inv_s[i] = inv_s_lds[tok[i]];
-        const int64_t r_unit = unit * 32;
+        for (int i = 0; i < NL; i++) inv_s[i] = inv_s_lds[tok[i]];
+        const int64_t r_unit = unit * UNIT;
 
         auto compute = [&](int d, int ks) {
             float im[8];
@@ -193,7 +216,7 @@ __global__ __launch_bounds__(kFusedWaves * 64) void pts_linear_wres(const Linear
 #pragma unroll
             for (int e = 0; e < 4; e++) im[e] = im_lo[e], im[4 + e] = im_hi[e];
 #pragma unroll
-            for (int i = 0; i < 4; i++) {
+            for (int i = 0; i < NL; i++) {
                 const u32x2 codes = quantize_8(raw[d][i], im, inv_s[i]);
                 *reinterpret_cast<u32x2 *>(tile + tile_wr[i]) = codes;
                 if (p.xq_out) {  // parity aid: the codes exactly as the MFMA will see them
@@ -202,16 +225,16 @@ __global__ __launch_bounds__(kFusedWaves * 64) void pts_linear_wres(const Linear
                 }
                 __builtin_amdgcn_sched_barrier(0);  // one load's eight codes at a time: bounds the live registers
             }
-            v4i fw[NB], fb[2];
-            fb[0] = *reinterpret_cast<const v4i *>(tile + tile_rd);
-            fb[1] = *reinterpret_cast<const v4i *>(tile + tile_rd + 1024);
+            v4i fw[NB], fb[RB];
+#pragma unroll
+            for (int j = 0; j < RB; j++) fb[j] = *reinterpret_cast<const v4i *>(tile + tile_rd + j * 1024);
 #pragma unroll
             for (int i = 0; i < NB; i++) fw[i] = *reinterpret_cast<const v4i *>(w_lane + i * 16 * pw + ks * 64);
             __builtin_amdgcn_sched_barrier(0);  // all LDS traffic of the k-step in flight before its first MFMA
 #pragma unroll
             for (int i = 0; i < NB; i++) {
-                acc[0][i] = __builtin_amdgcn_mfma_i32_16x16x64_i8(fw[i], fb[0], acc[0][i], 0, 0, 0);
-                acc[1][i] = __builtin_amdgcn_mfma_i32_16x16x64_i8(fw[i], fb[1], acc[1][i], 0, 0, 0);
+#pragma unroll
+                for (int j = 0; j < RB; j++) acc[j][i] = __builtin_amdgcn_mfma_i32_16x16x64_i8(fw[i], fb[j], acc[j][i], 0, 0, 0);
             }
         };
         // The scheduling barriers keep each refill right behind the work that frees its registers;
@@ -233,39 +256,42 @@ __global__ __launch_bounds__(kFusedWaves * 64) void pts_linear_wres(const Linear
         }
 
         // Accumulator register v of block (j, i): token row 16 j + (lane mod 16), channel 16 i + 4 (lane / 16) + v.
-        float rs[2];
+        float rs[RB];
 #pragma unroll
-        for (int j = 0; j < 2; j++) rs[j] = p.s_tok[(uint32_t)min(r_unit + j * 16 + l16, p.M - 1) % (uint32_t)L];
+        for (int j = 0; j < RB; j++) rs[j] = p.s_tok[(uint32_t)min(r_unit + j * 16 + l16, p.M - 1) % (uint32_t)L];
         const int64_t next = unit + unit_step;
         if (next < units) start_unit(next);  // in flight while this unit's results are written
 
 #pragma unroll
-        for (int j = 0; j < 2; j++) {
-            const int64_t r0 = r_unit + j * 16;
-            const int rows_valid = (int)min((int64_t)16, p.M - r0);
+        for (int pass = 0; pass < UNIT / PR; pass++) {  // PR result rows at a time through the private region
+            const int j = pass * PR / 16, row_in_block = (pass * PR) % 16;  // rows row_in_block .. + PR - 1 of block j
+            const int64_t r0 = r_unit + pass * PR;
+            const int rows_valid = (int)min((int64_t)PR, p.M - r0);
             if (rows_valid <= 0) break;
+            const int prow = l16 - row_in_block;         // this lane's row inside the pass
+            const bool mine = prow >= 0 && prow < PR;
 #pragma unroll
             for (int i = 0; i < NB; i++) {
                 const int col = i * 16 + lq * 4;
-                if (col < n4) {
+                if (col < n4 && mine) {
                     const v4f cs = *reinterpret_cast<const v4f *>(cs_lds + col);
                     const v4f cb = *reinterpret_cast<const v4f *>(cb_lds + col);
                     float out[4];
 #pragma unroll
                     for (int c = 0; c < 4; c++) {
                         const int a = acc[j][i][c];
-                        if (p.acc_out && l16 < rows_valid && col + c < N) p.acc_out[(r0 + l16) * p.N + col + c] = a;
+                        if (p.acc_out && prow < rows_valid && col + c < N) p.acc_out[(r0 + prow) * p.N + col + c] = a;
                         out[c] = (float)a * (rs[j] * cs[c]) + cb[c];
                     }
                     __half2 lo = __floats2half2_rn(out[0], out[1]);
                     __half2 hi = __floats2half2_rn(out[2], out[3]);
                     u32x2 packed = {__builtin_bit_cast(uint32_t, lo), __builtin_bit_cast(uint32_t, hi)};
-                    *reinterpret_cast<u32x2 *>(tile + l16 * (n4 * 2) + col * 2) = packed;
+                    *reinterpret_cast<u32x2 *>(tile + prow * (n4 * 2) + col * 2) = packed;
                 }
             }
             asm volatile("" ::: "memory");  // wavefront-private region: LDS runs a wavefront's accesses in order
             if (dense_y) {
-                const int valid_bytes = rows_valid * N * 2, block_bytes = 32 * N;
+                const int valid_bytes = rows_valid * N * 2, block_bytes = PR * 2 * N;
                 char *dst = reinterpret_cast<char *>(p.y + r0 * p.N);
                 for (int off = lane * 16; off < block_bytes; off += 64 * 16) {
                     const v4i data = *reinterpret_cast<const v4i *>(tile + off);
@@ -279,7 +305,7 @@ __global__ __launch_bounds__(kFusedWaves * 64) void pts_linear_wres(const Linear
                     }
                 }
             } else {
-                for (int idx = lane; idx < 16 * chunks8_per_row; idx += 64) {
+                for (int idx = lane; idx < PR * chunks8_per_row; idx += 64) {
                     const int row = idx / chunks8_per_row, cc = idx - row * chunks8_per_row;
                     if (row >= rows_valid) continue;
                     const u32x2 data = *reinterpret_cast<const u32x2 *>(tile + row * (n4 * 2) + cc * 8);
@@ -656,7 +682,7 @@ int launch_wres(const LinearArgs &a, hipStream_t stream) {
     if (err == hipSuccess) err = hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, device);
     if (err != hipSuccess) return ptq4vm::record_hip_error(err, "hipDeviceGetAttribute(multiprocessor count)");
     if (cus < 1) cus = 1;
-    const int64_t units = ptq4vm::ceil_div(a.M, 32);
+    const int64_t units = ptq4vm::ceil_div(a.M, 16 * kFusedRB);
     int64_t wgs = ptq4vm::ceil_div(units, kFusedWaves);
     if (wgs > cus) wgs = cus;  // one workgroup per CU: the resident tables take most of its LDS
     using Kernel = void (*)(const LinearArgs);

@@ -635,3 +635,24 @@ def test_w4a4_full_size_sampled(cfg, linear):
     prod_abs = np.abs(acc_o.astype(np.float64) * st_rows.astype(np.float64)[:, None] * s_w_o.astype(np.float64)[None, :])
     bias_abs = np.broadcast_to(np.abs(_np(c.bias).astype(np.float64))[None, :], prod_abs.shape)
     check_dequantized_output(_np(y[ridx]), y_o, y64, prod_abs, bias_abs, f"w4a4 cfg{cfg} {c.name}")
+
+
+def test_fused_linear_every_fp16_value():
+    """All 65 536 fp16 bit patterns (subnormals, infinities, NaNs) through the fused weight-resident kernel's
+    quantizer, with steps from 1e-8 to 10 so that subnormal inputs reach non-zero codes: the codes it feeds
+    to the MFMA must equal the oracle's."""
+    B, L, K, N = 64, 256, 64, 16
+    bits = torch.arange(65536, dtype=torch.int32).to(torch.int16)
+    x = bits.repeat(B * L * K // 65536).view(torch.float16).reshape(B * L, K).to(DEV).contiguous()
+    g = torch.Generator().manual_seed(5)
+    s_tok = (10.0 ** (torch.rand(L, generator=g) * 9.0 - 8.0)).to(DEV)
+    inv_m = (0.5 + torch.rand(K, generator=g)).to(DEV)
+    wq = torch.randint(-127, 128, (N, K), generator=g, dtype=torch.int8).to(DEV)
+    s_w = torch.full((N,), 2.0 ** -10, device=DEV)
+    xq = torch.full((B * L, K), 0x55, dtype=torch.int8, device=DEV)
+    ptq.w8a8_linear_fused(x, inv_m, s_tok, wq, s_w, None, B, L, xq_out=xq)
+    xq_two = ptq.quantize_pts(x, inv_m, s_tok, B, L)
+    torch.cuda.synchronize()
+    xq_o = oracle.quantize_pts(_np(x), _np(inv_m), _np(s_tok), B, L)
+    assert np.array_equal(_np(xq), xq_o)
+    assert np.array_equal(_np(xq_two), xq_o)
