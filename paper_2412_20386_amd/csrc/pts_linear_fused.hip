@@ -330,9 +330,10 @@ __global__ __launch_bounds__(kFusedWaves * 64) void pts_linear_wres(const Linear
 }
 
 // Sixteen codes of row `row_ptr` (fp16) starting at code index k0; codes at or beyond K are 0.
+// im[j] is the smoothing factor of code k0 + j (any value for codes at or beyond K).
 template <int X_ALIGN>
 __device__ __forceinline__ v4i load_quantized_chunk(const char *row_ptr, int64_t k0, int64_t K, bool row_ok,
-                                                    const float *inv_m, float inv_s) {
+                                                    const float (&im)[16], float inv_s) {
     v4i out = {0, 0, 0, 0};
     if (!row_ok || k0 >= K) return out;
     const int valid = (int)min((int64_t)16, K - k0);
@@ -360,9 +361,8 @@ __device__ __forceinline__ v4i load_quantized_chunk(const char *row_ptr, int64_t
     int q[16];
 #pragma unroll
     for (int j = 0; j < 16; j++) {
-        const float m = (inv_m && j < valid) ? inv_m[k0 + j] : 1.0f;
         const __half h = __builtin_bit_cast(__half, (uint16_t)(h2[j >> 1] >> (16 * (j & 1))));
-        q[j] = j < valid ? quantize_one(__half2float(h), m, inv_s) : 0;
+        q[j] = j < valid ? quantize_one(__half2float(h), im[j], inv_s) : 0;
     }
 #pragma unroll
     for (int j = 0; j < 4; j++) out[j] = (int)pack4(q[4 * j], q[4 * j + 1], q[4 * j + 2], q[4 * j + 3]);
@@ -391,7 +391,7 @@ constexpr int kStreamPatch = 2048 * kStreamRB;    // bytes of the per-wavefront 
 constexpr int64_t kStreamMinRows = 4096;
 
 struct StreamLayout {
-    int groups, rows, pitch, w_bytes, scale_off, patch_off, total;
+    int groups, rows, pitch, w_bytes, scale_off, inv_m_off, patch_off, total;
 };
 __host__ __device__ __forceinline__ StreamLayout stream_layout(int N, int ksteps) {
     StreamLayout l;
@@ -400,7 +400,8 @@ __host__ __device__ __forceinline__ StreamLayout stream_layout(int N, int ksteps
     l.pitch = 64 * ksteps;
     l.w_bytes = l.rows * l.pitch;
     l.scale_off = l.w_bytes;
-    l.patch_off = l.scale_off + l.rows * 8;
+    l.inv_m_off = l.scale_off + l.rows * 8;          // 64 ksteps smoothing factors (fused form)
+    l.patch_off = l.inv_m_off + 64 * ksteps * 4;
     l.total = l.patch_off + kStreamWaves * kStreamPatch;
     return l;
 }
@@ -415,6 +416,7 @@ __global__ __launch_bounds__(kStreamWaves * 64) void linear_stream_smallk(const 
     char *const w_lds = lds_dyn;
     float *const cs_lds = reinterpret_cast<float *>(lds_dyn + lay.scale_off);
     float *const cb_lds = cs_lds + lay.rows;
+    float *const inv_m_lds = reinterpret_cast<float *>(lds_dyn + lay.inv_m_off);
     char *const patch = lds_dyn + lay.patch_off + wave * kStreamPatch;
     constexpr int RB = kStreamRB, UNIT = 16 * RB;
     auto swz = [](int row) { return KSTEPS == 1 ? ((row >> 2) & 3) : ((row >> 1) & 3); };
@@ -430,6 +432,9 @@ __global__ __launch_bounds__(kStreamWaves * 64) void linear_stream_smallk(const 
         for (int o = tid; o < lay.rows; o += kStreamWaves * 64) {
             cs_lds[o] = o < N ? p.s_w[o] : 0.0f;
             cb_lds[o] = (o < N && p.bias) ? __half2float(p.bias[o]) : 0.0f;
+        }
+        if constexpr (QUANT) {
+            for (int k = tid; k < 64 * KSTEPS; k += kStreamWaves * 64) inv_m_lds[k] = (p.inv_m && k < K) ? p.inv_m[k] : 1.0f;
         }
     }
     __syncthreads();
@@ -455,7 +460,13 @@ __global__ __launch_bounds__(kStreamWaves * 64) void linear_stream_smallk(const 
                 const int k0 = 64 * ks + 16 * lq;
                 if constexpr (QUANT) {
                     const float inv_s = 1.0f / step;  // IEEE division
-                    const v4i codes = load_quantized_chunk<X_ALIGN>(xrow, k0, K, true, p.inv_m, inv_s);
+                    float im[16];
+#pragma unroll
+                    for (int e = 0; e < 4; e++) {
+                        const v4f f = *reinterpret_cast<const v4f *>(inv_m_lds + k0 + 4 * e);
+                        im[4 * e] = f.x, im[4 * e + 1] = f.y, im[4 * e + 2] = f.z, im[4 * e + 3] = f.w;
+                    }
+                    const v4i codes = load_quantized_chunk<X_ALIGN>(xrow, k0, K, true, im, inv_s);
                     if (p.xq_out && r_unit + jb * 16 + l16 < p.M) {  // parity aid
 #pragma unroll
                         for (int b = 0; b < 16; b++)
@@ -601,8 +612,11 @@ __global__ __launch_bounds__(kThreads, 2) void pts_linear_generic(const LinearAr
         for (int i = 0; i < X_CHUNKS; i++) {
             const int cid = tid + kThreads * i, row = cid >> 2, kc = cid & 3;
             const bool ok = r0 + row < p.M;
+            float im[16];
+#pragma unroll
+            for (int e = 0; e < 16; e++) im[e] = (p.inv_m && kb0 + kc * 16 + e < p.k_bytes) ? p.inv_m[kb0 + kc * 16 + e] : 1.0f;
             stage_x[i] = load_quantized_chunk<X_ALIGN>(p.x + (r0 + row) * p.ldx_bytes, kb0 + kc * 16, p.k_bytes, ok,
-                                                       p.inv_m, inv_s[i]);
+                                                       im, inv_s[i]);
             if (p.xq_out && tile_o == 0 && ok) {  // parity aid: the codes exactly as the MFMA will see them
 #pragma unroll
                 for (int b = 0; b < 16; b++)
