@@ -27,6 +27,9 @@
 // stores are 16 bytes per lane and cover whole contiguous row segments.
 #include "mfma_linear.hpp"
 
+#ifndef PTQ4VM_PERSISTENT_BO
+#define PTQ4VM_PERSISTENT_BO 256
+#endif
 #ifndef PTQ4VM_PERSISTENT_PHYS_SLAB
 #define PTQ4VM_PERSISTENT_PHYS_SLAB 128  // K bytes per LDS row of a ring stage (64: twice the stages in the same LDS)
 #define PTQ4VM_PERSISTENT_STAGES 2
@@ -1196,7 +1199,7 @@ int dispatch(LinearArgs a, hipStream_t stream) {
     // 256 x 256 tiles on one 8-wavefront workgroup per CU.  (The 256 x 128 / two 4-wavefront workgroups
     // per CU instantiation balances few-tile problems better but moves 1.5x the bytes through L2; it
     // measured 3 % slower on out_proj and 10 % slower on in_proj of the Vim-B stack.)
-    if (persistent_ok) return launch_persistent<Path, 256, PTQ4VM_PERSISTENT_PHYS_SLAB, PTQ4VM_PERSISTENT_STAGES>(a, stream);
+    if (persistent_ok) return launch_persistent<Path, PTQ4VM_PERSISTENT_BO, PTQ4VM_PERSISTENT_PHYS_SLAB, PTQ4VM_PERSISTENT_STAGES>(a, stream);
     // Few output channels over many rows: weight resident in LDS, activations streamed once.
     const bool wres_ok = dma_ok && a.N <= 16 * kWresMaxBlocks && a.M >= kWresMinRows && a.M < (1LL << 31) &&
                          a.L < (1LL << 31) && a.k_bytes < (1LL << 20) &&
