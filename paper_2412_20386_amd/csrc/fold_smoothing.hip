@@ -6,16 +6,13 @@
 #include <hip/hip_fp16.h>
 
 #include "common.hpp"
+#include "quant_device.hpp"
 
 namespace {
 
-constexpr int kThreads = 256;
+using ptq4vm::cvt_i32_f32;
 
-__device__ __forceinline__ int cvt_i32_f32(float v) {
-    int i;
-    asm("v_cvt_i32_f32 %0, %1" : "=v"(i) : "v"(v));  // NaN -> 0, saturating
-    return i;
-}
+constexpr int kThreads = 256;
 
 // Blocks [0, N) quantize one output channel each; blocks [N, N + ceil(K/256)) write 1/m.
 __global__ __launch_bounds__(kThreads) void fold_smoothing_rows(const __half *__restrict__ w,

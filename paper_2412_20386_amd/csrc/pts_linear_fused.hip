@@ -14,18 +14,14 @@
 //   pts_linear_generic  every other shape: the register-staged tiled kernel with the quantizer in
 //                       its loader (correct everywhere, re-quantizes per tile column).
 #include "mfma_linear.hpp"
+#include "quant_device.hpp"
 
 namespace {
 
-using namespace ptq4vm::mfma;
+using ptq4vm::cvt_i32_f32;
+using ptq4vm::pack4;
 
-// fp32 -> int32 conversion with the hardware's defined behaviour for specials
-// (NaN -> 0, out-of-range saturates), which a C++ cast leaves undefined.
-__device__ __forceinline__ int cvt_i32_f32(float v) {
-    int i;
-    asm("v_cvt_i32_f32 %0, %1" : "=v"(i) : "v"(v));
-    return i;
-}
+using namespace ptq4vm::mfma;
 
 // One PTS code (Sec. 5.1): smoothing multiply, step multiply, round half to even, clip.  Two
 // separate fp32 multiplies in this order: the codes must equal the stand-alone quantizer's.
@@ -34,12 +30,6 @@ __device__ __forceinline__ int quantize_one(float x, float inv_m, float inv_s) {
     v = v * inv_s;
     const int q = cvt_i32_f32(__builtin_rintf(v));
     return min(max(q, -127), 127);
-}
-
-__device__ __forceinline__ uint32_t pack4(int a, int b, int c, int d) {
-    const uint32_t lo = __builtin_amdgcn_perm((uint32_t)b, (uint32_t)a, 0x0c0c0400u);  // a.b0 | b.b0 << 8
-    const uint32_t hi = __builtin_amdgcn_perm((uint32_t)d, (uint32_t)c, 0x0c0c0400u);
-    return __builtin_amdgcn_perm(hi, lo, 0x05040100u);
 }
 
 // f32(fp16 half of `pair`) * m in one instruction: v_fma_mix_f32 converts the selected half exactly,

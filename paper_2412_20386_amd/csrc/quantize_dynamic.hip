@@ -12,29 +12,21 @@
 #include <hip/hip_fp16.h>
 
 #include "common.hpp"
+#include "quant_device.hpp"
 
 namespace {
+
+using ptq4vm::cvt_i32_f32;
+using ptq4vm::pack4;
 
 typedef unsigned int u32x2 __attribute__((ext_vector_type(2)));
 typedef unsigned int u32x4 __attribute__((ext_vector_type(4)));
 
 constexpr int kThreads = 256;
 
-__device__ __forceinline__ int cvt_i32_f32(float v) {
-    int i;
-    asm("v_cvt_i32_f32 %0, %1" : "=v"(i) : "v"(v));  // NaN -> 0, saturating
-    return i;
-}
-
 __device__ __forceinline__ int code_of(float v, float inv_s) {
     const int q = cvt_i32_f32(__builtin_rintf(v * inv_s));
     return min(max(q, -127), 127);
-}
-
-__device__ __forceinline__ uint32_t pack4(int a, int b, int c, int d) {
-    const uint32_t lo = __builtin_amdgcn_perm((uint32_t)b, (uint32_t)a, 0x0c0c0400u);
-    const uint32_t hi = __builtin_amdgcn_perm((uint32_t)d, (uint32_t)c, 0x0c0c0400u);
-    return __builtin_amdgcn_perm(hi, lo, 0x05040100u);
 }
 
 // lanes_per_row = 2^n <= 64 lanes share a row, lane l of the group holding 16-byte chunks

@@ -13,22 +13,18 @@
 #include <hip/hip_fp16.h>
 
 #include "common.hpp"
+#include "quant_device.hpp"
 
 namespace {
+
+using ptq4vm::cvt_i32_f32;
+using ptq4vm::pack4;
 
 typedef unsigned int u32x2 __attribute__((ext_vector_type(2)));
 typedef unsigned int u32x4 __attribute__((ext_vector_type(4)));
 
 constexpr int kMaxThreads = 256;
 constexpr int kMaxLdsTokens = 16384;  // reciprocal-step table of up to 64 KiB; longer sequences divide per row
-
-// fp32 -> int32 conversion with the hardware's defined behaviour for specials
-// (NaN -> 0, out-of-range saturates), which a C++ cast leaves undefined.
-__device__ __forceinline__ int cvt_i32_f32(float v) {
-    int i;
-    asm("v_cvt_i32_f32 %0, %1" : "=v"(i) : "v"(v));
-    return i;
-}
 
 // HAS_Z: per-token zero offset (Sec. 5.1 names it; quantizer form of Sec. 2.3 with the code range shifted
 // into int8): the offset is added to the rounded value and the clip range is [-128, 127].
@@ -42,12 +38,6 @@ __device__ __forceinline__ int quantize_one(float x, float inv_m, float inv_s, i
         return min(max(q + z, -128), 127);
     }
     return min(max(q, -127), 127);
-}
-
-__device__ __forceinline__ uint32_t pack4(int a, int b, int c, int d) {
-    uint32_t lo = __builtin_amdgcn_perm((uint32_t)b, (uint32_t)a, 0x0c0c0400u);  // a.b0 | b.b0 << 8
-    uint32_t hi = __builtin_amdgcn_perm((uint32_t)d, (uint32_t)c, 0x0c0c0400u);
-    return __builtin_amdgcn_perm(hi, lo, 0x05040100u);
 }
 
 template <int VEC>

@@ -10,20 +10,17 @@
 #include <hip/hip_fp16.h>
 
 #include "common.hpp"
+#include "quant_device.hpp"
 
 namespace {
+
+using ptq4vm::cvt_i32_f32;
 
 typedef unsigned int u32x2 __attribute__((ext_vector_type(2)));
 typedef unsigned int u32x4 __attribute__((ext_vector_type(4)));
 
 constexpr int kThreads = 256;
 constexpr int kMaxLdsTokens = 16384;
-
-__device__ __forceinline__ int cvt_i32_f32(float v) {
-    int i;
-    asm("v_cvt_i32_f32 %0, %1" : "=v"(i) : "v"(v));  // NaN -> 0, saturating
-    return i;
-}
 
 __device__ __forceinline__ int code4(float x, float inv_m, float inv_s) {
     float v = x * inv_m;  // two separate fp32 multiplies in this order, as in the 8-bit quantizer
