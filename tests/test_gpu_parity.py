@@ -656,3 +656,19 @@ def test_fused_linear_every_fp16_value():
     xq_o = oracle.quantize_pts(_np(x), _np(inv_m), _np(s_tok), B, L)
     assert np.array_equal(_np(xq), xq_o)
     assert np.array_equal(_np(xq_two), xq_o)
+
+
+STREAM_SHAPES = [  # B, L, K, N, ldy, bias: short reductions over >= 4096 rows (row-streaming kernel), ragged channel counts
+    (22, 197, 40, 100, 104, True),     # N not a multiple of 64, padded rows (8-byte stores)
+    (22, 197, 48, 70, None, False),    # 140-byte rows: 4-byte aligned only
+    (21, 199, 12, 130, None, True),    # 12-byte int8 rows / 24-byte fp16 rows
+    (35, 120, 128, 64, None, True),    # two k-steps
+    (33, 127, 100, 33, 40, True),      # odd N with padding; M mod 16 = 15
+]
+
+
+@pytest.mark.parametrize("B,L,K,N,ldy,bias", STREAM_SHAPES)
+def test_short_reduction_many_rows_two_launch_and_fused(B, L, K, N, ldy, bias):
+    c = synth.random_problem(3100 + K + N, B, L, K, N, device=DEV)
+    _run_w8a8_case(c, use_bias=bias, ldy=ldy, what="stream")
+    _run_fused_case(c, use_bias=bias, ldy=ldy, what="stream-fused")
