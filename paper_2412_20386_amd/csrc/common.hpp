@@ -23,4 +23,13 @@ inline int check_launch(const char *what) {
 
 inline int64_t ceil_div(int64_t a, int64_t b) { return (a + b - 1) / b; }
 
+// Raises a kernel's dynamic-LDS limit (needed above 64 KiB).  The setting belongs to the current
+// device's copy of the function, so it is applied on every launch rather than cached in a flag:
+// a host-side table update, negligible next to the launch itself, and correct for any number of
+// devices and threads.
+inline int set_lds_limit(const void *kernel, int bytes, const char *what) {
+    hipError_t err = hipFuncSetAttribute(kernel, hipFuncAttributeMaxDynamicSharedMemorySize, bytes);
+    return err == hipSuccess ? PTQ4VM_OK : record_hip_error(err, what);
+}
+
 }  // namespace ptq4vm

@@ -1051,13 +1051,7 @@ int launch_dma(LinearArgs a, hipStream_t stream) {
     if (!set_grid<BR, BO>(a, grid)) return PTQ4VM_ERR_SHAPE;
     constexpr int lds_bytes = STAGES * (BR + BO) * kSlabBytes;
     auto kernel = linear_mfma_dma<Path, BR, BO, WR, WO, STAGES>;
-    static bool configured = false;  // raising the dynamic-LDS limit is a per-function, idempotent setting
-    if (!configured) {
-        hipError_t err = hipFuncSetAttribute(reinterpret_cast<const void *>(kernel),
-                                             hipFuncAttributeMaxDynamicSharedMemorySize, lds_bytes);
-        if (err != hipSuccess) return ptq4vm::record_hip_error(err, "hipFuncSetAttribute(linear_mfma_dma)");
-        configured = true;
-    }
+    if (int rc = ptq4vm::set_lds_limit(reinterpret_cast<const void *>(kernel), lds_bytes, "hipFuncSetAttribute(linear_mfma_dma)")) return rc;
     kernel<<<grid, dim3(kThreads), lds_bytes, stream>>>(a);
     return ptq4vm::check_launch("linear_mfma_dma");
 }
@@ -1081,17 +1075,9 @@ int launch_persistent(LinearArgs a, hipStream_t stream) {
                                           linear_mfma_persistent<Path, BO, SLAB, STAGES, false, true>},
                                          {linear_mfma_persistent<Path, BO, SLAB, STAGES, true, false>,
                                           linear_mfma_persistent<Path, BO, SLAB, STAGES, true, true>}};
-    static bool configured = false;  // raising the dynamic-LDS limit is a per-function, idempotent setting
-    if (!configured) {
-        for (int b = 0; b < 2; b++)
-            for (int d = 0; d < 2; d++) {
-                err = hipFuncSetAttribute(reinterpret_cast<const void *>(kernels[b][d]),
-                                          hipFuncAttributeMaxDynamicSharedMemorySize, lds_bytes);
-                if (err != hipSuccess) return ptq4vm::record_hip_error(err, "hipFuncSetAttribute(linear_mfma_persistent)");
-            }
-        configured = true;
-    }
-    kernels[a.bias ? 1 : 0][a.acc_out ? 1 : 0]<<<dim3(wgs), dim3(BO * 2), lds_bytes, stream>>>(a);
+    const Kernel kernel = kernels[a.bias ? 1 : 0][a.acc_out ? 1 : 0];
+    if (int rc = ptq4vm::set_lds_limit(reinterpret_cast<const void *>(kernel), lds_bytes, "hipFuncSetAttribute(linear_mfma_persistent)")) return rc;
+    kernel<<<dim3(wgs), dim3(BO * 2), lds_bytes, stream>>>(a);
     return ptq4vm::check_launch("linear_mfma_persistent");
 }
 
@@ -1140,15 +1126,7 @@ int launch_wres(const LinearArgs &a, hipStream_t stream) {
     static const Kernel kernels[kWresMaxBlocks] = {  // by the number of 16-channel blocks
         linear_mfma_wres<Path, 1>, linear_mfma_wres<Path, 2>, linear_mfma_wres<Path, 3>, linear_mfma_wres<Path, 4>,
         linear_mfma_wres<Path, 5>, linear_mfma_wres<Path, 6>, linear_mfma_wres<Path, 7>, linear_mfma_wres<Path, 8>};
-    static bool configured = false;  // raising the dynamic-LDS limit is a per-function, idempotent setting
-    if (!configured) {
-        for (int i = 0; i < kWresMaxBlocks; i++) {
-            err = hipFuncSetAttribute(reinterpret_cast<const void *>(kernels[i]),
-                                      hipFuncAttributeMaxDynamicSharedMemorySize, kLdsBytes);
-            if (err != hipSuccess) return ptq4vm::record_hip_error(err, "hipFuncSetAttribute(linear_mfma_wres)");
-        }
-        configured = true;
-    }
+    if (int rc = ptq4vm::set_lds_limit(reinterpret_cast<const void *>(kernels[lay.nb - 1]), kLdsBytes, "hipFuncSetAttribute(linear_mfma_wres)")) return rc;
     kernels[lay.nb - 1]<<<dim3((unsigned)wgs), dim3(kWresWaves * 64), lay.total, stream>>>(a);
     return ptq4vm::check_launch("linear_mfma_wres");
 }

@@ -664,18 +664,10 @@ int launch_stream_aligned(const LinearArgs &a, int xa, int wa, const StreamLayou
          linear_stream_smallk<KSTEPS, QUANT, 4, 0>},
         {linear_stream_smallk<KSTEPS, QUANT, 0, 16>, linear_stream_smallk<KSTEPS, QUANT, 0, 4>,
          linear_stream_smallk<KSTEPS, QUANT, 0, 0>}};
-    static bool configured = false;  // raising the dynamic-LDS limit is a per-function, idempotent setting
-    if (!configured) {
-        for (int i = 0; i < 3; i++)
-            for (int j = 0; j < 3; j++) {
-                hipError_t err = hipFuncSetAttribute(reinterpret_cast<const void *>(kernels[i][j]),
-                                                     hipFuncAttributeMaxDynamicSharedMemorySize, kLdsBytes);
-                if (err != hipSuccess) return ptq4vm::record_hip_error(err, "hipFuncSetAttribute(linear_stream_smallk)");
-            }
-        configured = true;
-    }
     auto idx = [](int al) { return al == 16 ? 0 : (al == 4 ? 1 : 2); };
-    kernels[idx(xa)][idx(wa)]<<<dim3(wgs), dim3(kStreamWaves * 64), lay.total, stream>>>(a);
+    const Kernel kernel = kernels[idx(xa)][idx(wa)];
+    if (int rc = ptq4vm::set_lds_limit(reinterpret_cast<const void *>(kernel), kLdsBytes, "hipFuncSetAttribute(linear_stream_smallk)")) return rc;
+    kernel<<<dim3(wgs), dim3(kStreamWaves * 64), lay.total, stream>>>(a);
     return ptq4vm::check_launch("linear_stream_smallk");
 }
 
@@ -696,20 +688,12 @@ int launch_wres(const LinearArgs &a, hipStream_t stream) {
     // [k-steps in flight: 4, 2, 1][number of 16-channel blocks - 1]
     static const Kernel kernels[3][kFusedMaxBlocks] = {PTQ4VM_WRES_ROW(4), PTQ4VM_WRES_ROW(2), PTQ4VM_WRES_ROW(1)};
 #undef PTQ4VM_WRES_ROW
-    static bool configured = false;  // raising the dynamic-LDS limit is a per-function, idempotent setting
-    if (!configured) {
-        for (int d = 0; d < 3; d++)
-            for (int i = 0; i < kFusedMaxBlocks; i++) {
-                err = hipFuncSetAttribute(reinterpret_cast<const void *>(kernels[d][i]),
-                                          hipFuncAttributeMaxDynamicSharedMemorySize, kLdsBytes);
-                if (err != hipSuccess) return ptq4vm::record_hip_error(err, "hipFuncSetAttribute(pts_linear_wres)");
-            }
-        configured = true;
-    }
     const int n_ksteps = (int)(a.k_bytes / 64);
     // four k-steps in flight need too many registers next to the accumulators of 7 or 8 channel blocks
     const int depth_row = (n_ksteps % 4 == 0 && lay.nb <= 6) ? 0 : (n_ksteps % 2 == 0 ? 1 : 2);
-    kernels[depth_row][lay.nb - 1]<<<dim3((unsigned)wgs), dim3(kFusedWaves * 64), lay.total, stream>>>(a);
+    const Kernel kernel = kernels[depth_row][lay.nb - 1];
+    if (int rc = ptq4vm::set_lds_limit(reinterpret_cast<const void *>(kernel), kLdsBytes, "hipFuncSetAttribute(pts_linear_wres)")) return rc;
+    kernel<<<dim3((unsigned)wgs), dim3(kFusedWaves * 64), lay.total, stream>>>(a);
     return ptq4vm::check_launch("pts_linear_wres");
 }
 
