@@ -267,7 +267,7 @@ __device__ __forceinline__ void persistent_tiles(const LinearArgs &p, const int 
 
     char *const ring = lds_dyn;
     // per-tile scale vectors, double buffered by tile parity
-    constexpr int SCALE_BYTES = BO * 4 + BR * 4 + BO * 2;
+    constexpr int SCALE_BYTES = BO * 4 + BR * 4 + BO * 2 + (Path::kOffset ? BO * 4 + BR * 4 : 0);
     char *const scales = lds_dyn + STAGES * STAGE_BYTES;
 
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
@@ -350,11 +350,33 @@ __device__ __forceinline__ void persistent_tiles(const LinearArgs &p, const int 
         float *const cs_lds = reinterpret_cast<float *>(scales + parity * SCALE_BYTES);  // s_w of the tile's channels
         float *const rs_lds = cs_lds + BO;                                              // s_tok of the tile's rows
         uint32_t *const cb_lds = reinterpret_cast<uint32_t *>(rs_lds + BR);             // bias, two fp16 per word
+        int *const cz_lds = reinterpret_cast<int *>(cb_lds + BO / 2);                   // rowsum of the tile's channels
+        int *const rz_lds = cz_lds + BO;                                                // z_tok of the tile's rows
 
         // Scale vectors of this tile, one 4-byte element per lane, straight into LDS.  Indices
         // beyond the matrix are clamped; those rows / channels are never stored.
+        constexpr int kScaleTasks = BO / 64 + BR / 64 + BO / 128;
+        constexpr int kOffsetTasks = Path::kOffset ? BO / 64 + BR / 64 : 0;
 #pragma unroll
-        for (int task = 0; task < BO / 64 + BR / 64 + BO / 128; task++) {
+        for (int task = kScaleTasks; task < kScaleTasks + kOffsetTasks; task++) {
+            if (task % NW != wave) continue;
+            if constexpr (Path::kOffset) {
+                const int blk = task - kScaleTasks;
+                if (blk < BO / 64) {  // rowsum of 64 channels
+                    const int c = min(blk * 64 + lane, cols_valid - 1);
+                    __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void *)(p.rowsum + o0 + c),
+                                                     (__attribute__((address_space(3))) void *)(cz_lds + blk * 64), 4, 0, 0);
+                } else {  // z_tok of 64 rows
+                    const int rblk = blk - BO / 64;
+                    const int r = min(rblk * 64 + lane, rows_valid - 1);
+                    const uint32_t t = ((uint32_t)(r0 % p.L) + (uint32_t)r) % (uint32_t)p.L;
+                    __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void *)(p.z_tok + t),
+                                                     (__attribute__((address_space(3))) void *)(rz_lds + rblk * 64), 4, 0, 0);
+                }
+            }
+        }
+#pragma unroll
+        for (int task = 0; task < kScaleTasks; task++) {
             if (task % NW != wave) continue;  // the copies are dealt round-robin to the wavefronts
             if (task < BO / 64) {             // s_w of 64 channels
                 if constexpr (kInt8) {
@@ -436,12 +458,29 @@ __device__ __forceinline__ void persistent_tiles(const LinearArgs &p, const int 
                         has_next = true, nstg = next_stage, nks = 0;
                     }  // after the tile's last slab that stage first serves the epilogue
                 }
-                if (has_next) load_fw(cur ^ 1, nstg, nks);
+                if constexpr (Path::kPacked4) {
+                    // a packed 16-byte fragment is two MFMA operands: even and odd reduction indices
+                    v4i we[FO], wo[FO];
 #pragma unroll
-                for (int j = 0; j < FR; j++) {
+                    for (int i = 0; i < FO; i++) we[i] = Path::even_codes(fw[cur][i]), wo[i] = Path::odd_codes(fw[cur][i]);
+                    if (has_next) load_fw(cur ^ 1, nstg, nks);
 #pragma unroll
-                    for (int i = 0; i < FO; i++) acc[i][j] = Path::mfma16(fw[cur][i], fx[j], acc[i][j]);
-                    if (has_next) load_fx(j, nstg, nks);
+                    for (int j = 0; j < FR; j++) {
+                        const v4i xe = Path::even_codes(fx[j]), xo = Path::odd_codes(fx[j]);
+                        if (has_next) load_fx(j, nstg, nks);
+#pragma unroll
+                        for (int i = 0; i < FO; i++) acc[i][j] = Path::mfma16(we[i], xe, acc[i][j]);
+#pragma unroll
+                        for (int i = 0; i < FO; i++) acc[i][j] = Path::mfma16(wo[i], xo, acc[i][j]);
+                    }
+                } else {
+                    if (has_next) load_fw(cur ^ 1, nstg, nks);
+#pragma unroll
+                    for (int j = 0; j < FR; j++) {
+#pragma unroll
+                        for (int i = 0; i < FO; i++) acc[i][j] = Path::mfma16(fw[cur][i], fx[j], acc[i][j]);
+                        if (has_next) load_fx(j, nstg, nks);
+                    }
                 }
             }
             stage = next_stage;
@@ -479,6 +518,19 @@ __device__ __forceinline__ void persistent_tiles(const LinearArgs &p, const int 
                 for (int j = 0; j < 4; j++) rs_raw[j] = half_rs[j];
             }
         }
+        v4f cz_raw[4];   // rowsum of the lane's channels and z_tok of its rows (zero-offset path), as raw bits
+        float rz_raw[8];
+        if constexpr (Path::kOffset) {
+            lds_read_4x_b128<64>(lds_addr(cz_lds + wave_o + lq * 4), cz_raw);
+            if constexpr (FR == 8) {
+                lds_read_8x_b32<64>(lds_addr(rz_lds + wave_r + l16), rz_raw);
+            } else {
+                float half_rz[4];
+                lds_read_4x_b32<64>(lds_addr(rz_lds + wave_r + l16), half_rz);
+#pragma unroll
+                for (int j = 0; j < 4; j++) rz_raw[j] = half_rz[j];
+            }
+        }
         float bias4[FO][4];
 #pragma unroll
         for (int i = 0; i < FO; i++) {
@@ -503,11 +555,16 @@ __device__ __forceinline__ void persistent_tiles(const LinearArgs &p, const int 
 #pragma unroll
                     for (int c = 0; c < 4; c++) {
                         if constexpr (kInt8) {
-                            const int a = acc[i][j][c];
+                            int a = acc[i][j][c];
+                            if constexpr (Path::kPacked4) a >>= 8;  // operands were codes times 16: exact
                             if constexpr (DUMP_ACC) {
                                 const int64_t r = r0 + wave_r + j * 16 + l16;
                                 const int64_t o = o0 + wave_o + i * 16 + lq * 4 + c;
                                 if (r < p.M && o < p.N) p.acc_out[r * p.N + o] = a;
+                            }
+                            if constexpr (Path::kOffset) {
+                                const float zf = rz_raw[j], sf = cz_raw[i][c];  // scalars first: bit casts of vector elements misread
+                                a -= __builtin_bit_cast(int, zf) * __builtin_bit_cast(int, sf);
                             }
                             out[c] = (float)a * (rs_raw[j] * cs_raw[i][c]) + bias4[i][c];
                         } else {
@@ -546,16 +603,17 @@ __device__ __forceinline__ void persistent_tiles(const LinearArgs &p, const int 
     }
 }
 
-// Work split.  Workgroup ids go round-robin over the XCDs; XCD x owns a contiguous range of 256-row
-// tiles (channel tiles fastest, so tiles sharing an activation strip share one L2) and its
-// workgroups interleave in it.  A range is whole rounds of tiles plus a partial last round; when
-// that last round has at most half as many tiles as the XCD has workgroups, its tiles are cut into
-// two 128-row halves so that twice as many workgroups finish it in about half a tile's time
-// (Vim-B out_proj: 2.31 rounds -> 2 + 1/2 instead of 3, measured 81 -> 74 us).  The half-tile pass
-// restarts the slab pipeline and a 128 x 256 tile needs more LDS traffic per MAC, so it costs ~0.7 of a
-// tile; with many rounds of short tiles (in_proj: 9.23 rounds, K = 768) that gains nothing and the
-// split is not used (K = 1536 over 9.23 rounds still gains 3 %).
-template <class Path, int BO, int SLAB, int STAGES, bool HAS_BIAS, bool DUMP_ACC>
+// Work split.  Workgroup ids go round-robin over the XCDs; XCD x owns a contiguous range of tiles
+// (channel tiles fastest, so tiles sharing an activation strip share one L2) and its workgroups
+// interleave in it.  FRM = 8: 256-row tiles.  A range is whole rounds of tiles plus a partial last
+// round; when that round has at most half as many tiles as the XCD has workgroups, its tiles are cut
+// into two 128-row halves, which twice as many workgroups take BEFORE their whole tiles (Vim-B
+// out_proj: 2.31 rounds -> 1/2 + 2 instead of 3, measured 81 -> 70 us).  A half-tile pass costs ~0.7
+// of a tile (its own slab pipeline, more LDS traffic per MAC); doing it first also moves those
+// workgroups' epilogues out of step with the others' (in_proj, 9.23 rounds: 149.4 -> 146.9 us; with
+// the halves last it gained nothing there).  FRM = 4: every tile has 128 rows (packed 4-bit operands,
+// whose expanded fragments would not fit the register file next to a 256-row tile's accumulators).
+template <class Path, int BO, int SLAB, int STAGES, bool HAS_BIAS, bool DUMP_ACC, int FRM>
 __global__ __launch_bounds__(BO * 2, 2) void linear_mfma_persistent(const LinearArgs p) {
     const int total_tiles = p.tiles_o * p.tiles_r;
     const int per_xcd = (total_tiles + kXcds - 1) / kXcds;
@@ -563,16 +621,20 @@ __global__ __launch_bounds__(BO * 2, 2) void linear_mfma_persistent(const Linear
     const int lo = xcd * per_xcd, hi = min(lo + per_xcd, total_tiles);
     const int n = max(hi - lo, 0);
     const int rounds = n / wpx, tail = n - rounds * wpx;
-    const bool halves = tail > 0 && 2 * tail <= wpx && (rounds < 6 || p.k_bytes >= 1536);
-    const int n_full = rounds + ((!halves && j < tail) ? 1 : 0);
-    persistent_tiles<Path, BO, SLAB, STAGES, HAS_BIAS, DUMP_ACC, 8>(p, lo + j, wpx, n_full);
-    if (halves && j < 2 * tail) {
-        const int tile = lo + rounds * wpx + (j >> 1);
-        const int half_tile = ((tile / p.tiles_o) * 2 + (j & 1)) * p.tiles_o + tile % p.tiles_o;  // in the 128-row grid
-        if ((int64_t)(half_tile / p.tiles_o) * 128 < p.M) {
-            __syncthreads();  // the ring and the scale buffers change layout
-            persistent_tiles<Path, BO, SLAB, STAGES, HAS_BIAS, DUMP_ACC, 4>(p, half_tile, 1, 1);
+    if constexpr (FRM == 8) {
+        const bool halves = tail > 0 && 2 * tail <= wpx;
+        const int n_full = rounds + ((!halves && j < tail) ? 1 : 0);
+        if (halves && j < 2 * tail) {
+            const int tile = lo + rounds * wpx + (j >> 1);
+            const int half_tile = ((tile / p.tiles_o) * 2 + (j & 1)) * p.tiles_o + tile % p.tiles_o;  // in the 128-row grid
+            if ((int64_t)(half_tile / p.tiles_o) * 128 < p.M) {
+                persistent_tiles<Path, BO, SLAB, STAGES, HAS_BIAS, DUMP_ACC, 4>(p, half_tile, 1, 1);
+                __syncthreads();  // the ring and the scale buffers change layout
+            }
         }
+        persistent_tiles<Path, BO, SLAB, STAGES, HAS_BIAS, DUMP_ACC, 8>(p, lo + j, wpx, n_full);
+    } else {
+        persistent_tiles<Path, BO, SLAB, STAGES, HAS_BIAS, DUMP_ACC, 4>(p, lo + j, wpx, rounds + (j < tail ? 1 : 0));
     }
 }
 
@@ -629,8 +691,20 @@ __global__ __launch_bounds__(kThreads) void linear_mfma_smallk(const LinearArgs 
 #pragma unroll
         for (int ks = 0; ks < KSTEPS; ks++) fw[i][ks] = load_fragment_chunk<LOAD_ALIGN>(wrow, (2 * ks + lhalf) * 16, k_bytes);
     }
+    // packed 4-bit codes: the resident weight fragments are split once into their even / odd operands
+    v4i fw_odd[2][Path::kPacked4 ? KSTEPS : 1];
+    if constexpr (Path::kPacked4) {
+#pragma unroll
+        for (int i = 0; i < 2; i++)
+#pragma unroll
+            for (int ks = 0; ks < KSTEPS; ks++) {
+                fw_odd[i][ks] = Path::odd_codes(fw[i][ks]);
+                fw[i][ks] = Path::even_codes(fw[i][ks]);
+            }
+    }
     // scales and biases of this lane's channels: o_base + 32 i + 8 g + 4 lhalf + c
     float cs[2][4][4], cb[2][4][4];
+    int cz[2][4][Path::kOffset ? 4 : 1];  // their weight row sums (zero-offset path)
 #pragma unroll
     for (int i = 0; i < 2; i++)
 #pragma unroll
@@ -642,6 +716,7 @@ __global__ __launch_bounds__(kThreads) void linear_mfma_smallk(const LinearArgs 
                 if constexpr (kInt8) cs[i][g][c] = p.s_w[o_base + col];
                 cb[i][g][c] = 0.0f;
                 if constexpr (HAS_BIAS) cb[i][g][c] = __half2float(p.bias[o_base + col]);
+                if constexpr (Path::kOffset) cz[i][g][c] = p.rowsum[o_base + col];
             }
 
     const int64_t n_blocks = (p.M + 31) / 32;
@@ -671,12 +746,27 @@ __global__ __launch_bounds__(kThreads) void linear_mfma_smallk(const LinearArgs 
         for (int i = 0; i < 2; i++) {
 #pragma unroll
             for (int v = 0; v < 16; v++) acc[i][v] = 0;
+        }
+        if constexpr (Path::kPacked4) {
 #pragma unroll
-            for (int ks = 0; ks < KSTEPS; ks++) acc[i] = Path::mfma(fw[i][ks], fx[ks], acc[i]);
+            for (int ks = 0; ks < KSTEPS; ks++) {
+                const v4i xe = Path::even_codes(fx[ks]), xo = Path::odd_codes(fx[ks]);
+#pragma unroll
+                for (int i = 0; i < 2; i++) acc[i] = Path::mfma(fw[i][ks], xe, acc[i]);
+#pragma unroll
+                for (int i = 0; i < 2; i++) acc[i] = Path::mfma(fw_odd[i][ks], xo, acc[i]);
+            }
+        } else {
+#pragma unroll
+            for (int i = 0; i < 2; i++)
+#pragma unroll
+                for (int ks = 0; ks < KSTEPS; ks++) acc[i] = Path::mfma(fw[i][ks], fx[ks], acc[i]);
         }
         float rs = 1.0f;
+        int rz = 0;
         if constexpr (kInt8) {
             rs = p.s_tok[t];
+            if constexpr (Path::kOffset) rz = p.z_tok[t];
             t += t_step;
             if (t >= (uint32_t)p.L) t -= (uint32_t)p.L;
         }
@@ -689,11 +779,13 @@ __global__ __launch_bounds__(kThreads) void linear_mfma_smallk(const LinearArgs 
 #pragma unroll
                 for (int c = 0; c < 4; c++) {
                     if constexpr (kInt8) {
-                        const int a = acc[i][g * 4 + c];
+                        int a = acc[i][g * 4 + c];
+                        if constexpr (Path::kPacked4) a >>= 8;  // operands were codes times 16: exact
                         if constexpr (DUMP_ACC) {
                             const int col = i * 32 + g * 8 + lhalf * 4 + c;
                             if (r < p.M && col < cols_valid) p.acc_out[r * p.N + o_base + col] = a;
                         }
+                        if constexpr (Path::kOffset) a -= rz * cz[i][g][c];
                         out[c] = (float)a * (rs * cs[i][g][c]) + cb[i][g][c];
                     } else {
                         out[c] = acc[i][g * 4 + c] + cb[i][g][c];
@@ -1058,8 +1150,9 @@ int launch_dma(LinearArgs a, hipStream_t stream) {
 
 template <class Path, int BO, int SLAB, int STAGES>
 int launch_persistent(LinearArgs a, hipStream_t stream) {
+    constexpr int FRM = Path::kPacked4 ? 4 : 8;  // tile rows / 32
     dim3 grid;
-    if (!set_grid<256, BO>(a, grid)) return PTQ4VM_ERR_SHAPE;
+    if (!set_grid<32 * FRM, BO>(a, grid)) return PTQ4VM_ERR_SHAPE;
     // One 8-wavefront or two 4-wavefront workgroups per CU (all that LDS allows), a multiple of the XCD count.
     int device = 0, cus = 0;
     hipError_t err = hipGetDevice(&device);
@@ -1068,13 +1161,13 @@ int launch_persistent(LinearArgs a, hipStream_t stream) {
     unsigned wgs = (unsigned)(cus / kXcds * kXcds) * (BO == 256 ? 1 : 2);
     if (wgs == 0) wgs = kXcds;
     if (wgs > grid.x) wgs = grid.x;  // grid.x is the tile count rounded up to a multiple of kXcds
-    constexpr int lds_bytes = STAGES * (256 + BO) * SLAB + 2 * (BO * 4 + 256 * 4 + BO * 2);
+    constexpr int lds_bytes = STAGES * (256 + BO) * SLAB + 2 * (BO * 4 + 256 * 4 + BO * 2 + (Path::kOffset ? BO * 4 + 256 * 4 : 0));
     using Kernel = void (*)(const LinearArgs);
     // [has bias][also write the int32 accumulators]
-    static const Kernel kernels[2][2] = {{linear_mfma_persistent<Path, BO, SLAB, STAGES, false, false>,
-                                          linear_mfma_persistent<Path, BO, SLAB, STAGES, false, true>},
-                                         {linear_mfma_persistent<Path, BO, SLAB, STAGES, true, false>,
-                                          linear_mfma_persistent<Path, BO, SLAB, STAGES, true, true>}};
+    static const Kernel kernels[2][2] = {{linear_mfma_persistent<Path, BO, SLAB, STAGES, false, false, FRM>,
+                                          linear_mfma_persistent<Path, BO, SLAB, STAGES, false, true, FRM>},
+                                         {linear_mfma_persistent<Path, BO, SLAB, STAGES, true, false, FRM>,
+                                          linear_mfma_persistent<Path, BO, SLAB, STAGES, true, true, FRM>}};
     const Kernel kernel = kernels[a.bias ? 1 : 0][a.acc_out ? 1 : 0];
     if (int rc = ptq4vm::set_lds_limit(reinterpret_cast<const void *>(kernel), lds_bytes, "hipFuncSetAttribute(linear_mfma_persistent)")) return rc;
     kernel<<<dim3(wgs), dim3(BO * 2), lds_bytes, stream>>>(a);
@@ -1161,7 +1254,7 @@ int dispatch(LinearArgs a, hipStream_t stream) {
     const bool dma_ok = la == 16 && a.k_bytes % kSlabBytes == 0 && a.ldx_bytes * 256 < (1LL << 31) &&
                         a.ldw_bytes * 256 < (1LL << 31);
 #if PTQ4VM_STREAM_SMALLK
-    if constexpr (Path::kElemBytes == 1) {
+    if constexpr (Path::kElemBytes == 1 && !Path::kOffset && !Path::kPacked4) {
         if (a.k_bytes <= 128) {  // many rows: whole rows of y streamed out by one wavefront each
             const int rc = launch_stream_smallk(a, false, stream);
             if (rc <= 0) return rc;
@@ -1182,26 +1275,11 @@ int dispatch(LinearArgs a, hipStream_t stream) {
     const bool wres_ok = dma_ok && a.N <= 16 * kWresMaxBlocks && a.M >= kWresMinRows && a.M < (1LL << 31) &&
                          a.L < (1LL << 31) && a.k_bytes < (1LL << 20) &&
                          wres_layout((int)a.N, (int)a.k_bytes).total <= kLdsBytes;
-    if (wres_ok) return launch_wres<Path>(a, stream);
+    if constexpr (!Path::kOffset && !Path::kPacked4) {
+        if (wres_ok) return launch_wres<Path>(a, stream);
+    }
     if (a.N > 64) {
         if (dma_ok && a.N <= 128) return launch_dma<Path, 128, 128, 2, 2, 4>(a, stream);  // skinny N: many small tiles
-        if (dma_ok) return launch_dma<Path, 256, 128, 2, 2, 3>(a, stream);
-        return launch_generic<Path, 256, 128, 2, 2>(a, la, stream);
-    }
-    if (dma_ok) return launch_dma<Path, 256, 64, 4, 1, 3>(a, stream);
-    return launch_generic<Path, 256, 64, 4, 1>(a, la, stream);
-}
-
-// Zero-offset and packed 4-bit linears: the tiled kernels with the variant's MFMA loop / epilogue.
-template <class Path>
-int dispatch_tiled(LinearArgs a, hipStream_t stream) {
-    const int la = pick_load_align(a);
-    a.y_vec = (a.ldy % 8 == 0 && ptq4vm::aligned_to(a.y, 16)) ? 8
-              : ((a.ldy % 4 == 0 && ptq4vm::aligned_to(a.y, 8)) ? 4 : 1);
-    const bool dma_ok = la == 16 && a.k_bytes % kSlabBytes == 0 && a.ldx_bytes * 256 < (1LL << 31) &&
-                        a.ldw_bytes * 256 < (1LL << 31);
-    if (a.N > 64) {
-        if (dma_ok && a.N <= 128) return launch_dma<Path, 128, 128, 2, 2, 4>(a, stream);
         if (dma_ok) return launch_dma<Path, 256, 128, 2, 2, 3>(a, stream);
         return launch_generic<Path, 256, 128, 2, 2>(a, la, stream);
     }
@@ -1242,7 +1320,7 @@ extern "C" int ptq4vm_w8a8_linear_offset(const int8_t *xq, const int8_t *wq, con
     a.ldw_bytes = ldwq;
     a.ldy = ldy;
     a.L = L;
-    return dispatch_tiled<Int8OffsetPath>(a, static_cast<hipStream_t>(stream_));
+    return dispatch<Int8OffsetPath>(a, static_cast<hipStream_t>(stream_));
 }
 
 extern "C" int ptq4vm_w4a4_linear(const uint8_t *xq4, const uint8_t *wq4, const float *s_tok, const float *s_w,
@@ -1273,7 +1351,7 @@ extern "C" int ptq4vm_w4a4_linear(const uint8_t *xq4, const uint8_t *wq4, const 
     a.ldw_bytes = ldwq;
     a.ldy = ldy;
     a.L = L;
-    return dispatch_tiled<Int4Path>(a, static_cast<hipStream_t>(stream_));
+    return dispatch<Int4Path>(a, static_cast<hipStream_t>(stream_));
 }
 
 extern "C" int ptq4vm_w8a8_linear(const int8_t *xq, const int8_t *wq, const float *s_tok, const float *s_w,

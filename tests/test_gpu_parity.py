@@ -295,9 +295,12 @@ def test_other_configs_sampled(cfg, linear):
     _check_case_on_sampled_rows(c, _sampled_rows(c.B * c.L, 53, c.L), f"cfg{cfg} {c.name}")
 
 
-@pytest.mark.parametrize("B,L,K,N", [(41, 251, 192, 1544), (33, 300, 64, 2056), (20, 517, 128, 6400)])
+@pytest.mark.parametrize("B,L,K,N", [(41, 251, 192, 1544), (33, 300, 64, 2056), (20, 517, 128, 6400),
+                                     (41, 251, 256, 1544), (20, 517, 384, 3400), (45, 229, 640, 1800)])
 def test_large_ragged_shapes_sampled(B, L, K, N):
-    """Enough 256 x 256 tiles for the persistent kernel, with ragged last tiles in both directions."""
+    """Many 256 x 256 tiles with ragged last tiles in both directions; the last three have a reduction
+    length the persistent kernel takes (2, 3 and 5 slabs of 128 bytes), with and without a partial last
+    round of tiles that is cut into half tiles."""
     c = synth.random_problem(4242 + N, B, L, K, N, device=DEV)
     _check_case_on_sampled_rows(c, _sampled_rows(B * L, 61, L), "ragged")
 
@@ -546,6 +549,51 @@ def test_zero_offset_path_against_oracle(B, L, K, N):
     assert torch.equal(y.view(torch.int16), y2.view(torch.int16))
 
 
+def _check_offset_on_sampled_rows(c, x, s_off, z_off, rows, what):
+    """Whole problem on the GPU (with and without the accumulator dump); the oracle recomputes sampled rows."""
+    print(f"offset full-size {what}: M={c.B * c.L} K={c.K} N={c.N}, {len(rows)} sampled rows", flush=True)
+    M = c.B * c.L
+    wq, s_w, inv_m = ptq.fold_smoothing(c.w, c.m)
+    rowsum = ptq.weight_rowsum(wq)
+    xq = ptq.quantize_pts_offset(x, inv_m, s_off, z_off, c.B, c.L)
+    y = ptq.w8a8_linear_offset(xq, wq, s_off, z_off, rowsum, s_w, c.bias, c.B, c.L)
+    acc = torch.full((M, c.N), -1, dtype=torch.int32, device=DEV)
+    y_dump = ptq.w8a8_linear_offset(xq, wq, s_off, z_off, rowsum, s_w, c.bias, c.B, c.L, acc_out=acc)
+    torch.cuda.synchronize()
+    assert torch.equal(y.view(torch.int16), y_dump.view(torch.int16))
+    ridx = torch.from_numpy(rows).to(DEV)
+    wq_o, s_w_o, inv_m_o = oracle.fold_smoothing(_np(c.w), _np(c.m))
+    rowsum_o = oracle.weight_rowsum(wq_o)
+    assert np.array_equal(_np(rowsum), rowsum_o)
+    st_rows, z_rows = _np(s_off)[rows % c.L], _np(z_off)[rows % c.L]
+    n = len(rows)
+    xq_o = oracle.quantize_pts_offset(_np(x[ridx]), inv_m_o, st_rows, z_rows, 1, n)
+    assert np.array_equal(_np(xq[ridx]), xq_o), "int8 codes differ"
+    acc_o = oracle.int8_gemm(xq_o, wq_o)
+    assert np.array_equal(_np(acc[ridx]), acc_o), "int32 accumulators differ"
+    y_o, y64 = oracle.dequant_offset(acc_o, st_rows, z_rows, rowsum_o, s_w_o, _np(c.bias), 1, n)
+    corrected = acc_o.astype(np.float64) - z_rows.astype(np.float64)[:, None] * rowsum_o.astype(np.float64)[None, :]
+    prod_abs = np.abs(corrected * st_rows.astype(np.float64)[:, None] * s_w_o.astype(np.float64)[None, :])
+    bias_abs = np.broadcast_to(np.abs(_np(c.bias).astype(np.float64))[None, :], prod_abs.shape)
+    check_dequantized_output(_np(y[ridx]), y_o, y64, prod_abs, bias_abs, f"offset {what}")
+
+
+@pytest.mark.parametrize("linear", [0, 1, 2, 3])
+def test_zero_offset_vim_b_full_size_sampled(linear):
+    c = synth.make_linear_case(3, 0, linear, device=DEV)
+    shift = synth.token_shift(c.L, 77 + linear, device=DEV)
+    x = (c.x.view(c.B, c.L, c.K) + shift.view(1, c.L, 1).to(c.x.dtype)).reshape(c.B * c.L, c.K).contiguous()
+    s_off, z_off = synth.calibrate_offset(x[: 16 * c.L], c.m, c.L)
+    _check_offset_on_sampled_rows(c, x, s_off, z_off, _sampled_rows(c.B * c.L, 97, c.L), f"vim_b {c.name}")
+
+
+@pytest.mark.parametrize("B,L,K,N", [(41, 251, 256, 1544), (20, 517, 384, 3400), (300, 65, 24, 776), (250, 33, 100, 520)])
+def test_zero_offset_large_ragged_shapes_sampled(B, L, K, N):
+    """Ragged last tiles in the persistent kernel (first two) and the short-reduction kernel (last two)."""
+    c, x, s_off, z_off = _offset_case(5000 + K + N, B, L, K, N)
+    _check_offset_on_sampled_rows(c, x, s_off, z_off, _sampled_rows(B * L, 61, L), "ragged")
+
+
 def test_zero_offset_quantizer_long_sequence_and_plain_kernels():
     """L beyond the LDS table (per-row division), K a multiple of 4 only, K odd."""
     for B, L, K in [(1, 9000, 64), (3, 41, 20), (2, 19, 7)]:
@@ -615,16 +663,17 @@ def test_w4a4_all_nibble_pairs_through_the_linear():
     assert np.array_equal(_np(y).view(np.uint16), y_o.view(np.uint16))
 
 
-@pytest.mark.parametrize("cfg,linear", [(3, 0), (3, 1), (3, 3), (1, 2)])
-def test_w4a4_full_size_sampled(cfg, linear):
-    c = synth.make_linear_case(cfg, 0, linear, device=DEV)
+def _check_w4a4_on_sampled_rows(c, what):
     M = c.B * c.L
-    print(f"w4a4 full-size cfg{cfg} {c.name}: M={M} K={c.K} N={c.N}", flush=True)
+    print(f"w4a4 full-size {what}: M={M} K={c.K} N={c.N}", flush=True)
     s4 = _steps_4bit(c)
     wq4, s_w, inv_m = ptq.fold_smoothing_w4(c.w, c.m)
     xq4 = ptq.quantize_pts_a4(c.x, inv_m, s4, c.B, c.L)
     y = ptq.w4a4_linear(xq4, wq4, s4, s_w, c.bias, c.B, c.L)
+    acc = torch.full((M, c.N), -1, dtype=torch.int32, device=DEV)
+    y_dump = ptq.w4a4_linear(xq4, wq4, s4, s_w, c.bias, c.B, c.L, acc_out=acc)
     torch.cuda.synchronize()
+    assert torch.equal(y.view(torch.int16), y_dump.view(torch.int16))
     rows = _sampled_rows(M, 97, c.L)
     ridx = torch.from_numpy(rows).to(DEV)
     wq_o, s_w_o, inv_m_o = oracle.fold_smoothing_bits(_np(c.w), _np(c.m), 4)
@@ -632,9 +681,24 @@ def test_w4a4_full_size_sampled(cfg, linear):
     xq_o = oracle.quantize_pts_bits(_np(c.x[ridx]), inv_m_o, st_rows, 1, len(rows), 4)
     assert np.array_equal(_np(xq4[ridx]), oracle.pack_int4(xq_o))
     y_o, y64, acc_o = oracle.w8a8_linear(xq_o, wq_o, st_rows, s_w_o, _np(c.bias), 1, len(rows))
+    assert np.array_equal(_np(acc[ridx]), acc_o), "int32 accumulators differ"
     prod_abs = np.abs(acc_o.astype(np.float64) * st_rows.astype(np.float64)[:, None] * s_w_o.astype(np.float64)[None, :])
     bias_abs = np.broadcast_to(np.abs(_np(c.bias).astype(np.float64))[None, :], prod_abs.shape)
-    check_dequantized_output(_np(y[ridx]), y_o, y64, prod_abs, bias_abs, f"w4a4 cfg{cfg} {c.name}")
+    check_dequantized_output(_np(y[ridx]), y_o, y64, prod_abs, bias_abs, f"w4a4 {what}")
+
+
+@pytest.mark.parametrize("cfg,linear", [(3, 0), (3, 1), (3, 2), (3, 3), (1, 2)])
+def test_w4a4_full_size_sampled(cfg, linear):
+    c = synth.make_linear_case(cfg, 0, linear, device=DEV)
+    _check_w4a4_on_sampled_rows(c, f"cfg{cfg} {c.name}")
+
+
+@pytest.mark.parametrize("B,L,K,N", [(41, 251, 512, 1544), (20, 517, 768, 3400), (300, 65, 24, 776), (250, 33, 100, 520)])
+def test_w4a4_large_ragged_shapes_sampled(B, L, K, N):
+    """Ragged last tiles in the persistent kernel (128-row tiles; 2 and 3 slabs of packed bytes) and in
+    the short-reduction kernel (12 and 50 packed bytes per row)."""
+    c = synth.random_problem(6000 + K + N, B, L, K, N, device=DEV)
+    _check_w4a4_on_sampled_rows(c, "ragged")
 
 
 def test_fused_linear_every_fp16_value():
