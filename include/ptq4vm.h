@@ -128,8 +128,10 @@ int ptq4vm_w8a8_linear(const int8_t *xq, const int8_t *wq, const float *s_tok, c
  * ptq4vm_weight_rowsum prepares rowsum once per weight (offline, like the fold).
  * Arguments as in ptq4vm_quantize_pts / ptq4vm_w8a8_linear, plus z_tok [L] int32 in (values in
  * [-128, 127]) and rowsum [N] int32.  acc_out receives the raw accumulators (before the correction).
- * K <= PTQ4VM_MAX_K_OFFSET keeps acc - z * rowsum inside int32.  The linear runs on the tiled
- * kernels (no persistent / weight-resident variant yet).
+ * K <= PTQ4VM_MAX_K_OFFSET keeps acc - z * rowsum inside int32 and |rowsum| <= 128 K inside 24 signed
+ * bits: the kernels form z * rowsum with a 24-bit multiply, so z_tok outside [-128, 127] or a rowsum
+ * that is not the weight's row sum gives undefined results (not checked).  Runs on the same tiled,
+ * persistent and short-reduction kernels as ptq4vm_w8a8_linear.
  */
 #define PTQ4VM_MAX_K_OFFSET 65536
 int ptq4vm_quantize_pts_offset(const void *x_f16, const float *inv_m, const float *s_tok, const int32_t *z_tok,
@@ -150,7 +152,8 @@ int ptq4vm_w8a8_linear_offset(const int8_t *xq, const int8_t *wq, const float *s
  *   ptq4vm_w4a4_linear        as ptq4vm_w8a8_linear on packed operands; acc_out holds sum_k xq wq
  * gfx950 has no int4 MFMA: packed operands are expanded in registers to int8 right before the
  * int8 MFMA, so the gain over W8A8 is in bytes moved, not in MFMA rate.  The linear runs on the
- * tiled kernels.  Errors as for the 8-bit entry points, plus odd K -> PTQ4VM_ERR_SHAPE.
+ * tiled, persistent (128-row tiles) and short-reduction kernels of ptq4vm_w8a8_linear.  Errors as
+ * for the 8-bit entry points, plus odd K -> PTQ4VM_ERR_SHAPE.
  */
 int ptq4vm_fold_smoothing_w4(const void *w_f16, const float *m, uint8_t *wq4, float *s_w, float *inv_m,
                              int64_t N, int64_t K, int64_t ldw, int64_t ldwq, void *stream);

@@ -564,7 +564,7 @@ __device__ __forceinline__ void persistent_tiles(const LinearArgs &p, const int 
                             }
                             if constexpr (Path::kOffset) {
                                 const float zf = rz_raw[j], sf = cz_raw[i][c];  // scalars first: bit casts of vector elements misread
-                                a -= __builtin_bit_cast(int, zf) * __builtin_bit_cast(int, sf);
+                                a -= __mul24(__builtin_bit_cast(int, zf), __builtin_bit_cast(int, sf));  // |z| < 2^8, |rowsum| < 2^23
                             }
                             out[c] = (float)a * (rs_raw[j] * cs_raw[i][c]) + bias4[i][c];
                         } else {
@@ -785,7 +785,7 @@ __global__ __launch_bounds__(kThreads) void linear_mfma_smallk(const LinearArgs 
                             const int col = i * 32 + g * 8 + lhalf * 4 + c;
                             if (r < p.M && col < cols_valid) p.acc_out[r * p.N + o_base + col] = a;
                         }
-                        if constexpr (Path::kOffset) a -= rz * cz[i][g][c];
+                        if constexpr (Path::kOffset) a -= __mul24(rz, cz[i][g][c]);  // |z| < 2^8, |rowsum| < 2^23
                         out[c] = (float)a * (rs * cs[i][g][c]) + cb[i][g][c];
                     } else {
                         out[c] = acc[i][g * 4 + c] + cb[i][g][c];

@@ -225,7 +225,8 @@ __device__ __forceinline__ void epilogue(const typename Path::Acc (&acc)[FO][FR]
                                 if (r < p.M && o < p.N) p.acc_out[r * p.N + o] = a;
                             }
                             int corrected = a;
-                            if constexpr (Path::kOffset) corrected = a - row_z[jj] * col_sum[c];
+                            // 24-bit multiply (full rate): |z| < 2^8 and |rowsum| <= 127 K < 2^23 for every accepted K
+                            if constexpr (Path::kOffset) corrected = a - __mul24(row_z[jj], col_sum[c]);
                             out[c] = (float)corrected * (row_scale[jj] * col_scale[c]) + col_bias[c];
                         } else {
                             out[c] = acc[i][j][g * 4 + c] + col_bias[c];
