@@ -48,6 +48,7 @@ def main() -> int:
     ap.add_argument("--fused", choices=("auto", "off"), default="auto",
                     help="auto: one fused quantize+linear launch for linears with K <= 128 or N <= 128")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-graph", action="store_true", help="skip the extra timing of the step replayed as one HIP graph")
     ap.add_argument("--cpu-sample-batch", type=int, default=256)
     args = ap.parse_args()
     if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
@@ -128,7 +129,30 @@ def main() -> int:
     torch.cuda.synchronize()
     elapsed = time.perf_counter() - t0
     ms_per_step = elapsed / args.steps * 1e3
-    dom_us = sum(a.elapsed_time(b) for a, b in events["pairs"]) / len(events["pairs"]) * 1e3
+    dom_all = sorted(a.elapsed_time(b) * 1e3 for a, b in events["pairs"])
+    dom_us = sum(dom_all) / len(dom_all)
+
+    # ------------------------------------------------------------------ the same step as one HIP graph (extra)
+    graph_ms_per_step = None
+    if not args.no_graph:
+        side = torch.cuda.Stream()  # default priority
+        side.wait_stream(torch.cuda.current_stream())
+        with torch.cuda.stream(side):
+            step_w8a8()
+        torch.cuda.current_stream().wait_stream(side)
+        torch.cuda.synchronize()
+        graph = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(graph, stream=side):
+            step_w8a8()
+        for _ in range(2):
+            graph.replay()
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for _ in range(args.steps):
+            graph.replay()
+        torch.cuda.synchronize()
+        graph_ms_per_step = (time.perf_counter() - t0) / args.steps * 1e3
+        del graph
 
     # ------------------------------------------------------------------ per-kernel detail (untimed extras)
     def time_launch(fn, reps=3):
@@ -156,7 +180,7 @@ def main() -> int:
                                                     lin[li]["bias"], B, L, y=lin[li]["y"]))
         tf = time_launch(lambda lin: ptq.f16_linear(lin[li]["x"], lin[li]["w"], lin[li]["bias"], y=lin[li]["y"]))
         td = time_launch(lambda lin: ptq.quantize_dynamic(lin[li]["x"], lin[li]["inv_m"], xq=lin[li]["xq"], s_row=s_row))
-        # per-token zero offset variant (tiled kernels): timing only, offsets drawn at random
+        # per-token zero offset variant: timing only, offsets drawn at random
         z_tok = torch.randint(-20, 21, (L,), dtype=torch.int32, device=dev)
         rowsums = [ptq.weight_rowsum(lin[li]["wq"]) for lin in layers]
         tzq = time_launch(lambda lin: ptq.quantize_pts_offset(lin[li]["x"], lin[li]["inv_m"], lin[li]["s_tok"], z_tok, B, L,
@@ -165,7 +189,7 @@ def main() -> int:
         tzg = time_launch(lambda lin: ptq.w8a8_linear_offset(lin[li]["xq"], lin[li]["wq"], lin[li]["s_tok"], z_tok,
                                                              rs_of[id(lin)], lin[li]["s_w"], lin[li]["bias"], B, L,
                                                              y=lin[li]["y"]))
-        # W4A4 (packed 4-bit codes, tiled kernels): timing only
+        # W4A4 (packed 4-bit codes): timing only
         t4q = t4g = None
         if K % 2 == 0:
             s4 = [(lin[li]["s_tok"] * (127.0 / 7.0)).contiguous() for lin in layers]
@@ -241,6 +265,8 @@ def main() -> int:
     roofline = dict(bound="mfma", kernel=f"linear_mfma<int8> {dominant[0]} {dK}->{dN}, M={M}",
                     achieved=round(achieved, 1), peak=PEAK_INT8_TOPS, unit="TFLOP/s",
                     frac=round(achieved / PEAK_INT8_TOPS, 4), avg_launch_us=round(dom_us, 2),
+                    median_launch_us=round(dom_all[len(dom_all) // 2], 2), min_launch_us=round(dom_all[0], 2),
+                    p90_launch_us=round(dom_all[min(len(dom_all) - 1, int(0.9 * len(dom_all)))], 2),
                     launches_timed=len(events["pairs"]), traffic=DOMINANT_TRAFFIC_BYTES.get(args.config),
                     algorithmic_bytes=1.0 * M * dK + dN * dK + 2.0 * M * dN)
 
@@ -291,6 +317,7 @@ def main() -> int:
         "tops": round(total_ops / (ms_per_step * 1e-3) / 1e12, 1),
         "speedup_vs_f16_stack": round(f16_ms_per_step / ms_per_step, 3),
         "f16_ms_per_step": round(f16_ms_per_step, 4),
+        "graph_ms_per_step": None if graph_ms_per_step is None else round(graph_ms_per_step, 4),
         "dynamic_ms_per_step": round(dynamic_ms_per_step, 4),
         "speedup_pts_vs_per_token_dynamic": round(dynamic_ms_per_step / ms_per_step, 3),
         "paper_context": "paper: up to 1.83x end-to-end at W4A4 on VMamba-B, batch 32, RTX 3090 (not this metric)",
