@@ -167,10 +167,11 @@ int ptq4vm_w4a4_linear(const uint8_t *xq4, const uint8_t *wq4, const float *s_to
  * Fused activation quantizer + W8A8 linear: the stages "Activation smoothing", "Quantization",
  * "INT GEMM" and "Dequantization" of App. B.1 in one launch (PTS equation of Sec. 5.1).
  * Computes exactly, bit for bit, what ptq4vm_quantize_pts followed by ptq4vm_w8a8_linear
- * compute; the int8 codes stay on chip.  Worth using when the output is narrow (N <= 128 over
- * >= 16384 rows, e.g. x_proj: every activation element is read and quantized once); for wide
- * outputs a tiled GEMM would re-quantize each element once per tile column and the two separate
- * calls are faster, but every shape is accepted.
+ * compute; the int8 codes stay on chip.  Worth using over many rows when the output is narrow
+ * (N <= 128 over >= 4096 rows, e.g. x_proj: every activation element is read and quantized once)
+ * or the reduction short (K <= 128 over >= 16384 rows, e.g. dt_proj); for wide outputs a tiled GEMM
+ * would re-quantize each element once per tile column and below ~2000 rows only that tiled kernel
+ * applies: the two separate calls are faster there, but every shape is accepted.
  *   x_f16    [B*L, ldx]  fp16 in
  *   inv_m    [K]         f32  in   may be NULL (no smoothing)
  *   s_tok    [L]         f32  in

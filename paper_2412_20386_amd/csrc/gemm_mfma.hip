@@ -843,7 +843,7 @@ constexpr int kWresWaves = 8;
 constexpr int kWresDepth = 8;      // k-steps of activation fragments in flight per row block
 constexpr int kWresMaxBlocks = 8;  // 16-channel blocks: N <= 128
 constexpr int kLdsBytes = 160 * 1024;
-constexpr int64_t kWresMinRows = 16384;  // below this the one-off weight copy per workgroup does not pay
+constexpr int64_t kWresMinRows = 2048;   // and at least a quarter as many rows as the weight has bytes: below that the one-off weight copy per workgroup does not pay
 
 struct WresLayout {
     int nb, n4, pw, w_bytes, scale_bytes, patch_bytes, total;
@@ -1272,7 +1272,8 @@ int dispatch(LinearArgs a, hipStream_t stream) {
     // measured 3 % slower on out_proj and 10 % slower on in_proj of the Vim-B stack.)
     if (persistent_ok) return launch_persistent<Path, PTQ4VM_PERSISTENT_BO, PTQ4VM_PERSISTENT_PHYS_SLAB, PTQ4VM_PERSISTENT_STAGES>(a, stream);
     // Few output channels over many rows: weight resident in LDS, activations streamed once.
-    const bool wres_ok = dma_ok && a.N <= 16 * kWresMaxBlocks && a.M >= kWresMinRows && a.M < (1LL << 31) &&
+    const bool wres_ok = dma_ok && a.N <= 16 * kWresMaxBlocks && a.M >= kWresMinRows &&
+                         4 * a.M >= ptq4vm::ceil_div(a.N, 16) * 16 * a.k_bytes && a.M < (1LL << 31) &&
                          a.L < (1LL << 31) && a.k_bytes < (1LL << 20) &&
                          wres_layout((int)a.N, (int)a.k_bytes).total <= kLdsBytes;
     if constexpr (!Path::kOffset && !Path::kPacked4) {

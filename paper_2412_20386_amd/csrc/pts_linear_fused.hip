@@ -85,7 +85,7 @@ constexpr int kFusedWaves = 16 / kFusedRB;
 constexpr int kFusedPatchRows = 8 * kFusedRB;   // result rows staged per pass of the epilogue
 constexpr int kFusedMaxBlocks = 8;   // 16-channel blocks: N <= 128
 constexpr int kLdsBytes = 160 * 1024;
-constexpr int64_t kFusedMinRows = 16384;  // below this the one-off table copies per workgroup do not pay
+constexpr int64_t kFusedMinRows = 2048;   // below this the one-off table copies per workgroup do not pay (4 k rows: 11 us against 48 us for the tiled fused kernel at 384 -> 44)
 
 struct FusedLayout {
     int nb, n4, pw, w_bytes, inv_m_off, inv_s_off, scale_off, tile_off, tile_bytes, total;
@@ -378,7 +378,10 @@ __device__ __forceinline__ v4i load_quantized_chunk(const char *row_ptr, int64_t
 constexpr int kStreamRB = PTQ4VM_STREAM_RB;       // 16-row MFMA blocks per unit
 constexpr int kStreamWaves = 16 / kStreamRB;      // wavefronts per workgroup
 constexpr int kStreamPatch = 2048 * kStreamRB;    // bytes of the per-wavefront transposition patch
-constexpr int64_t kStreamMinRows = 4096;
+// A unit (16 rows x all channels) is one serial chain per wavefront and costs ~1 us per 64 channels however
+// few rows there are; the channel-strip kernel is faster below ~20 k rows (N = 384 ... 1536).  The fused form
+// has only the tiled fused kernel as an alternative and takes over much earlier.
+constexpr int64_t kStreamMinRows = 20480, kStreamMinRowsFused = 1024;
 
 struct StreamLayout {
     int groups, rows, pitch, w_bytes, scale_off, inv_m_off, patch_off, total;
@@ -748,7 +751,7 @@ int ptq4vm::mfma::launch_stream_smallk(const LinearArgs &a, bool quantize, hipSt
         return 0;
     };
     const int xa = align_of(a.x, a.ldx_bytes), wa = align_of(a.w, a.ldw_bytes);
-    if (a.k_bytes > 128 || a.M < kStreamMinRows || a.M >= (1LL << 31) || a.L >= (1LL << 31) || a.N > 8192) return 1;
+    if (a.k_bytes > 128 || a.M < (quantize ? kStreamMinRowsFused : kStreamMinRows) || a.M >= (1LL << 31) || a.L >= (1LL << 31) || a.N > 8192) return 1;
     const int ksteps = a.k_bytes <= 64 ? 1 : 2;
     const StreamLayout lay = stream_layout((int)a.N, ksteps);
     if (lay.total > kLdsBytes) return 1;

@@ -305,7 +305,7 @@ def test_large_ragged_shapes_sampled(B, L, K, N):
     _check_case_on_sampled_rows(c, _sampled_rows(B * L, 61, L), "ragged")
 
 
-SKINNY_SHAPES = [  # B, L, K, N, ldy, bias: few output channels over >= 16384 rows (weight-resident kernel)
+SKINNY_SHAPES = [  # B, L, K, N, ldy, bias: few output channels over many rows (weight-resident kernel)
     (83, 199, 192, 44, None, True),     # 3 k-steps; 88-byte dense rows; M mod 32 = 5
     (64, 257, 320, 80, None, False),    # 5 k-steps, fewer than the fragments kept in flight
     (70, 241, 1024, 128, None, True),   # exactly two register groups of k-steps; 8 channel blocks; M mod 32 = 6
@@ -397,7 +397,7 @@ def test_fused_linear_config0_and_options():
     _run_fused_case(c, ldy=c.N + 8, what="fused-ldy")
 
 
-FUSED_SKINNY = [  # B, L, K, N, ldy, bias, m: weight-resident fused kernel (N <= 128, >= 16384 rows)
+FUSED_SKINNY = [  # B, L, K, N, ldy, bias, m: weight-resident fused kernel (N <= 128, >= 2048 rows)
     (83, 199, 128, 44, None, True, True),     # 2 k-steps (depth 2); 88-byte dense rows; M mod 32 = 5
     (64, 257, 320, 80, None, False, True),    # 5 k-steps (depth 1)
     (70, 241, 1024, 128, None, True, True),   # 16 k-steps, 8 channel blocks (depth 2); M mod 32 = 6
@@ -722,7 +722,11 @@ def test_fused_linear_every_fp16_value():
     assert np.array_equal(_np(xq_two), xq_o)
 
 
-STREAM_SHAPES = [  # B, L, K, N, ldy, bias: short reductions over >= 4096 rows (row-streaming kernel), ragged channel counts
+STREAM_SHAPES = [  # B, L, K, N, ldy, bias: short reductions, ragged channel counts.  The row-streaming kernel takes the
+    # fused form from 1024 rows and the two-launch form from 20480 rows (the channel-strip kernel below that).
+    (105, 197, 40, 100, 104, True),    # 20685 rows: both forms on the row-streaming kernel; padded rows (8-byte stores)
+    (104, 199, 12, 130, None, True),   # 20696 rows; 12-byte int8 rows / 24-byte fp16 rows
+    (172, 120, 128, 64, None, False),  # 20640 rows; two k-steps
     (22, 197, 40, 100, 104, True),     # N not a multiple of 64, padded rows (8-byte stores)
     (22, 197, 48, 70, None, False),    # 140-byte rows: 4-byte aligned only
     (21, 199, 12, 130, None, True),    # 12-byte int8 rows / 24-byte fp16 rows
