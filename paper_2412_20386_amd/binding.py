@@ -102,11 +102,11 @@ def check(status: int) -> None:
 
 
 def _ptr(t: Optional[torch.Tensor]):
-    return None if t is None else ctypes.c_void_p(t.data_ptr())
+    return None if t is None else t.data_ptr()  # plain ints: the declared argtypes convert them
 
 
 def _stream():
-    return ctypes.c_void_p(torch.cuda.current_stream().cuda_stream)
+    return torch.cuda.current_stream().cuda_stream
 
 
 def _matrix(t: torch.Tensor, dtype, name: str) -> Tuple[int, int, int]:
