@@ -35,7 +35,7 @@ PEAK_HBM_GBS = 8000.0     # HBM3E
 # HBM traffic of the dominant kernel (in_proj GEMM of configs[3]) per launch, bytes, from two
 # rocprofv3 --pmc runs (FETCH_SIZE, WRITE_SIZE), each scaled by the 256 MiB copy this script also
 # issues: 109.1 MB fetched + 309.9 MB written (profiles/bench_vim_b_stack_kernel_trace_and_traffic.txt).
-DOMINANT_TRAFFIC_BYTES = {3: 420.9e6}
+DOMINANT_TRAFFIC_BYTES = {3: 421.1e6}
 
 
 def main() -> int:
