@@ -208,6 +208,55 @@ def test_w8a8_linear_extreme_codes():
     assert np.array_equal(_np(y).view(np.uint16), y_o.view(np.uint16))  # exact: power-of-two steps
 
 
+@pytest.mark.parametrize("K", [133143, 133120])
+def test_w8a8_linear_longest_reduction_fills_int32(K):
+    """The largest accepted K (odd: element-wise loads; and the largest multiple of 128: slab kernels) with
+    every code at +-127: the accumulators come within 0.02 % of the int32 range and must not wrap."""
+    B, L, N = 1, 37, 24
+    xq = torch.full((B * L, K), 127, dtype=torch.int8, device=DEV)
+    xq[1::2] = -127
+    wq = torch.full((N, K), 127, dtype=torch.int8, device=DEV)
+    wq[::3] = -127
+    wq[5, ::2] = -127                                   # a row that cancels to (almost) zero
+    s_tok = torch.full((L,), 2.0 ** -20, device=DEV)
+    s_w = torch.full((N,), 2.0 ** -12, device=DEV)
+    acc = torch.empty((B * L, N), dtype=torch.int32, device=DEV)
+    y = ptq.w8a8_linear(xq, wq, s_tok, s_w, None, B, L, acc_out=acc)
+    torch.cuda.synchronize()
+    y_o, y64, acc_o = oracle.w8a8_linear(_np(xq), _np(wq), _np(s_tok), _np(s_w), None, B, L)
+    assert np.abs(acc_o.astype(np.int64)).max() == K * 16129 > 2 ** 31 - 2 ** 19
+    assert np.array_equal(_np(acc), acc_o)
+    prod_abs = np.abs(acc_o.astype(np.float64)) * 2.0 ** -32
+    check_dequantized_output(_np(y), y_o, y64, prod_abs, np.zeros_like(prod_abs), "longest reduction")
+
+
+def test_zero_offset_longest_reduction_24_bit_product():
+    """K = 65536 with every weight code at -128: rowsum = -2^23, the most negative 24-bit value, times the
+    largest offsets; acc - z * rowsum reaches 2^30 + 127 * 2^23 and must be exact."""
+    B, L, K, N = 1, 35, 65536, 24
+    xq = torch.full((B * L, K), -128, dtype=torch.int8, device=DEV)
+    xq[1::2] = 127
+    wq = torch.full((N, K), -128, dtype=torch.int8, device=DEV)
+    wq[::4] = 127
+    s_tok = torch.full((L,), 2.0 ** -20, device=DEV)
+    z_tok = torch.full((L,), -128, dtype=torch.int32, device=DEV)
+    z_tok[::2] = 127                                    # opposite to the row's codes: x - z = -+255
+    s_w = torch.full((N,), 2.0 ** -12, device=DEV)
+    rowsum = ptq.weight_rowsum(wq)
+    acc = torch.empty((B * L, N), dtype=torch.int32, device=DEV)
+    y = ptq.w8a8_linear_offset(xq, wq, s_tok, z_tok, rowsum, s_w, None, B, L, acc_out=acc)
+    torch.cuda.synchronize()
+    rowsum_o = oracle.weight_rowsum(_np(wq))
+    assert rowsum_o.min() == -(2 ** 23) and np.array_equal(_np(rowsum), rowsum_o)
+    acc_o = oracle.int8_gemm(_np(xq), _np(wq))
+    assert np.array_equal(_np(acc), acc_o)
+    y_o, y64 = oracle.dequant_offset(acc_o, _np(s_tok), _np(z_tok), rowsum_o, _np(s_w), None, B, L)
+    corrected = acc_o.astype(np.int64) - np.tile(_np(z_tok).astype(np.int64), B)[:, None] * rowsum_o.astype(np.int64)[None, :]
+    assert np.abs(corrected).max() == 2 ** 30 + 127 * 2 ** 23
+    prod_abs = np.abs(corrected.astype(np.float64)) * 2.0 ** -32
+    check_dequantized_output(_np(y), y_o, y64, prod_abs, np.zeros_like(prod_abs), "offset longest reduction")
+
+
 def test_w8a8_linear_is_deterministic():
     c = synth.random_problem(9, 4, 197, 768, 384, device=DEV)
     wq, s_w, inv_m = ptq.fold_smoothing(c.w, c.m)
