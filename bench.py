@@ -109,7 +109,7 @@ def main() -> int:
                     ptq.w8a8_linear(d["xq"], d["wq"], d["s_tok"], d["s_w"], d["bias"], B, L, y=d["y"])
 
     def step_dynamic():
-        """The per-token dynamic comparison scheme (Sec. 4, latency table of Sec. 6.3): steps computed online."""
+        """The per-token dynamic comparison scheme (Sec. 4, latency table of Sec. 6.4): steps computed online."""
         for lin in layers:
             for d in lin:
                 ptq.quantize_dynamic(d["x"], d["inv_m"], xq=d["xq"], s_row=s_row)

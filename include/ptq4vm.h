@@ -28,7 +28,8 @@
  *   - Return value: PTQ4VM_OK (0) or a negative ptq4vm_status.  All argument checks run on the
  *     host before any launch.  A problem with zero rows or zero output columns is PTQ4VM_OK and
  *     launches nothing.  Device-side values (steps <= 0, NaN scales) are the caller's
- *     responsibility and are not inspected.
+ *     responsibility and are not inspected on the hot path; ptq4vm_validate_scales checks them on
+ *     request.
  */
 #ifndef PTQ4VM_H
 #define PTQ4VM_H
@@ -45,7 +46,8 @@ typedef enum {
     PTQ4VM_ERR_SHAPE = -2,  /* a size is negative, zero where it must not be, or too large */
     PTQ4VM_ERR_STRIDE = -3, /* a leading dimension is smaller than the row width */
     PTQ4VM_ERR_ALIGN = -4,  /* a base pointer is not aligned as stated above */
-    PTQ4VM_ERR_HIP = -5     /* the HIP runtime refused a launch; see ptq4vm_last_hip_error() */
+    PTQ4VM_ERR_HIP = -5,    /* the HIP runtime refused a launch; see ptq4vm_last_hip_error() */
+    PTQ4VM_ERR_VALUE = -6   /* ptq4vm_validate_scales found a scale that is not a finite number > 0 */
 } ptq4vm_status;
 
 /* Largest K for which sum_k (+-127)(+-127) is guaranteed to fit int32: floor((2^31-1)/127^2). */
@@ -84,7 +86,7 @@ int ptq4vm_quantize_pts(const void *x_f16, const float *inv_m, const float *s_to
 
 /*
  * Per-token dynamic activation quantizer: the comparison scheme of Sec. 4 and of the "Per-token
- * dynamic" rows of the latency table (Sec. 6.3).  The step of every token row is computed online
+ * dynamic" rows of the latency table (Sec. 6.4, Computation Acceleration).  The step of every token row is computed online
  * from the row itself, after smoothing (fp32, in this order):
  *   v[k] = f32(x[r,k]) * inv_m[k];  s_row[r] = max_k |v[k]| / 127  (1 for an all-zero row; NaNs
  *   do not take part in the maximum);  xq[r,k] = clip(rne(v[k] * (1 / s_row[r])), -127, 127).
@@ -117,8 +119,8 @@ int ptq4vm_w8a8_linear(const int8_t *xq, const int8_t *wq, const float *s_tok, c
                        int64_t K, int64_t N, int64_t ldxq, int64_t ldwq, int64_t ldy, void *stream);
 
 /*
- * PTS with a per-token zero offset.  Sec. 5.1 allocates "the step size and zero offset for each
- * token" and then omits the offset from its equation; the offset form is the activation quantizer
+ * PTS with a per-token zero offset.  Sec. 5.1 gives every token position a zero offset next to its
+ * step size and then leaves the offset out of its equation; the offset form is the activation quantizer
  * of Sec. 2.3, clip(round(X / Delta) + eps, 0, 2^b - 1), here with the code range shifted by 128
  * so that codes are int8 (z_tok = eps - 128):
  *   xq[r,k] = clip(rne((f32(x[r,k]) * inv_m[k]) * (1 / s_tok[t])) + z_tok[t], -128, 127),  t = r mod L
@@ -143,9 +145,9 @@ int ptq4vm_w8a8_linear_offset(const int8_t *xq, const int8_t *wq, const float *s
                               int64_t ldwq, int64_t ldy, void *stream);
 
 /*
- * W4A4: the precision of the paper's latency table (Sec. 6.3).  Codes are clipped to +-7
+ * W4A4: the precision of the paper's latency table (Sec. 6.4, Computation Acceleration).  Codes are clipped to +-7
  * (Sec. 2.3, +-(2^(b-1) - 1) with b = 4) and packed two per byte, the even reduction index in the
- * low nibble, two's complement (App. B.1: packed = (data[1] << 4) | (data[0] & 15)).  K must be
+ * low nibble, the odd one in the high nibble, two's complement (the packing of App. B.1).  K must be
  * even; packed matrices are [rows, K / 2] bytes with pitches ldwq / ldxq in bytes.
  *   ptq4vm_fold_smoothing_w4  as ptq4vm_fold_smoothing with s_w = max|W'| / 7
  *   ptq4vm_quantize_pts_a4    as ptq4vm_quantize_pts with the +-7 clip (s_tok calibrated for 4 bits)
@@ -153,8 +155,12 @@ int ptq4vm_w8a8_linear_offset(const int8_t *xq, const int8_t *wq, const float *s
  * gfx950 has no int4 MFMA: packed operands are expanded in registers to int8 right before the
  * int8 MFMA, so the gain over W8A8 is in bytes moved, not in MFMA rate.  The linear runs on the
  * tiled, persistent (128-row tiles) and short-reduction kernels of ptq4vm_w8a8_linear.  Errors as
- * for the 8-bit entry points, plus odd K -> PTQ4VM_ERR_SHAPE.
+ * for the 8-bit entry points, plus odd K -> PTQ4VM_ERR_SHAPE and K > PTQ4VM_MAX_K_W4 ->
+ * PTQ4VM_ERR_SHAPE: the kernels multiply codes scaled by 16, so the int32 accumulator holds 256 times
+ * the sum, and with the nibble -8 accepted on input (the quantizers never emit it) |256 acc| can reach
+ * 2^14 K, which must stay below 2^31.
  */
+#define PTQ4VM_MAX_K_W4 131071
 int ptq4vm_fold_smoothing_w4(const void *w_f16, const float *m, uint8_t *wq4, float *s_w, float *inv_m,
                              int64_t N, int64_t K, int64_t ldw, int64_t ldwq, void *stream);
 int ptq4vm_quantize_pts_a4(const void *x_f16, const float *inv_m, const float *s_tok, uint8_t *xq4, int64_t B,
@@ -190,7 +196,31 @@ int ptq4vm_w8a8_linear_fused(const void *x_f16, const float *inv_m, const float 
                              int64_t ldwq, int64_t ldy, int64_t ldxq, void *stream);
 
 /*
- * Unquantized comparison linear (the "FP16" column of the paper's latency table, Sec. 6.3):
+ * Debug validator of the device-resident scale vectors (Sec. 5.1: per-token steps Delta_X and
+ * per-output-channel steps Delta_W; Sec. 2.4: smoothing vector s).  An entry is bad unless it is a
+ * finite number > 0 (zero, negative, +-Inf and NaN are bad).  The hot path never looks at these
+ * values; call this once after calibration / loading a checkpoint.
+ *   s_tok [L], m [K] (the smoothing vector or its reciprocal inv_m), s_w [N]   f32 in; a vector of
+ *                    length 0 is skipped and its pointer may then be NULL
+ *   bad_counts [3]   int32 out (device): bad entries found in s_tok, m, s_w
+ *   workspace        device scratch, 16-byte aligned, at least
+ *                    PTQ4VM_VALIDATE_WORKSPACE_BYTES(L, K, N) bytes; contents need no initialisation
+ *                    and are undefined afterwards (per-workgroup partial counts)
+ * UNLIKE EVERY OTHER ENTRY POINT THIS ONE SYNCHRONISES: it enqueues two small kernels and a 12-byte
+ * device-to-host copy on `stream`, waits for the stream and returns PTQ4VM_OK when all counts are zero,
+ * PTQ4VM_ERR_VALUE otherwise (bad_counts tells which vector).  Not usable under stream capture.
+ * Errors: NULL bad_counts / workspace / a non-empty vector, negative length, more than
+ * PTQ4VM_VALIDATE_MAX_ELEMS entries in total, workspace too small, misalignment.
+ */
+#define PTQ4VM_VALIDATE_BLOCK 4096 /* entries per workgroup = per 16-byte workspace slot */
+#define PTQ4VM_VALIDATE_MAX_ELEMS ((int64_t)1 << 31)
+#define PTQ4VM_VALIDATE_WORKSPACE_BYTES(L, K, N) \
+    (16 * ((((int64_t)(L) + (int64_t)(K) + (int64_t)(N)) + PTQ4VM_VALIDATE_BLOCK - 1) / PTQ4VM_VALIDATE_BLOCK + 1))
+int ptq4vm_validate_scales(const float *s_tok, int64_t L, const float *m, int64_t K, const float *s_w, int64_t N,
+                           int32_t *bad_counts, void *workspace, int64_t workspace_bytes, void *stream);
+
+/*
+ * Unquantized comparison linear (the "FP16" column of the paper's latency table, Sec. 6.4):
  *   y[r,o] = fp16( sum_k x[r,k] * w[o,k]  (fp32 accumulation)  + bias[o] )
  *   x_f16 [M, ldx], w_f16 [N, ldw], bias_f16 [N] or NULL, y_f16 [M, ldy]
  * Errors as for ptq4vm_w8a8_linear.

@@ -21,7 +21,7 @@
  *   oracle_f16_linear       the unquantized FP16 linear the paper's latency table compares to.
  *
  *   oracle_quantize_dynamic per-token dynamic quantization, the comparison scheme of Sec. 4 and of the
- *                           latency table of Sec. 6.3: the step of a token row is computed online
+ *                           latency table of Sec. 6.4: the step of a token row is computed online
  *                           from that row (after smoothing), s_r = max_k|v| / 127.
  *   oracle_fold_smoothing_bits / oracle_quantize_pts_bits
  *                           the same quantizers at b bits (Sec. 2.3: clip to +-(2^(b-1) - 1)); b = 4
@@ -243,7 +243,7 @@ void oracle_f16_linear(const uint16_t *x_f16, const uint16_t *w_f16, const uint1
 
 
 /* ---- per-token dynamic activation quantizer (Sec. 4; the "Per-token dynamic" rows of the latency
- * table, Sec. 6.3).  Every row gets its own step from its own smoothed values:
+ * table, Sec. 6.4).  Every row gets its own step from its own smoothed values:
  *   v[k] = f32(x[r,k]) * inv_m[k];  s_r = max_k |v[k]| / 127 (1 if the row is all zero; NaNs do not
  *   take part in the maximum);  q = clip(rint(v * (1 / s_r)), -127, 127), all in fp32. ---- */
 void oracle_quantize_dynamic(const uint16_t *x_f16, const float *inv_m /* NULL => all ones */,

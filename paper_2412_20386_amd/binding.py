@@ -29,6 +29,7 @@ EXPORTS = (
     "ptq4vm_w8a8_linear",
     "ptq4vm_w8a8_linear_fused",
     "ptq4vm_f16_linear",
+    "ptq4vm_validate_scales",
     "ptq4vm_status_string",
     "ptq4vm_last_hip_error",
     "ptq4vm_version",
@@ -79,6 +80,8 @@ def load() -> ctypes.CDLL:
                                              i64, vp]
     lib.ptq4vm_f16_linear.restype = ci
     lib.ptq4vm_f16_linear.argtypes = [vp, vp, vp, vp, i64, i64, i64, i64, i64, i64, vp]
+    lib.ptq4vm_validate_scales.restype = ci
+    lib.ptq4vm_validate_scales.argtypes = [vp, i64, vp, i64, vp, i64, vp, vp, i64, vp]
     lib.ptq4vm_status_string.restype = ctypes.c_char_p
     lib.ptq4vm_status_string.argtypes = [ci]
     lib.ptq4vm_last_hip_error.restype = ctypes.c_char_p
@@ -332,3 +335,30 @@ def f16_linear(x: torch.Tensor, w: torch.Tensor, bias: Optional[torch.Tensor],
     _, _, ldy = _matrix(y, torch.float16, "y")
     check(load().ptq4vm_f16_linear(_ptr(x), _ptr(w), _ptr(bias), _ptr(y), M, K, N, ldx, ldw, ldy, _stream()))
     return y
+
+
+VALIDATE_BLOCK = 4096  # PTQ4VM_VALIDATE_BLOCK
+
+
+def validate_scales(s_tok: Optional[torch.Tensor], m: Optional[torch.Tensor], s_w: Optional[torch.Tensor],
+                    workspace: Optional[torch.Tensor] = None) -> Tuple[int, torch.Tensor]:
+    """ptq4vm_validate_scales: (status, bad_counts int32 [3] on the device).  status is 0 or
+    PTQ4VM_ERR_VALUE (-6, some entry is not a finite number > 0); other errors raise.  Synchronises."""
+    vecs = [v for v in (s_tok, m, s_w) if v is not None]
+    if not vecs:
+        raise TypeError("at least one vector is required")
+    dev = vecs[0].device
+    sizes = []
+    for v, name in ((s_tok, "s_tok"), (m, "m"), (s_w, "s_w")):
+        if v is not None:
+            _vector(v, torch.float32, v.shape[0], name)
+        sizes.append(0 if v is None else v.shape[0])
+    need = 16 * ((sum(sizes) + VALIDATE_BLOCK - 1) // VALIDATE_BLOCK + 1)
+    if workspace is None:
+        workspace = torch.empty(need, dtype=torch.uint8, device=dev)
+    counts = torch.empty(3, dtype=torch.int32, device=dev)
+    rc = load().ptq4vm_validate_scales(_ptr(s_tok), sizes[0], _ptr(m), sizes[1], _ptr(s_w), sizes[2], _ptr(counts),
+                                       _ptr(workspace), workspace.numel() * workspace.element_size(), _stream())
+    if rc not in (0, -6):
+        check(rc)
+    return rc, counts

@@ -26,22 +26,8 @@ HIPCC_FLAGS = [
 ]
 
 
-PROBE_SRC = os.path.join(CSRC, "probe", "machine_limits.hip")
-PROBE_BIN = os.path.join(CSRC, "probe", "machine_limits")
-
-
 def sources():
     return sorted(glob.glob(os.path.join(CSRC, "*.hip")) + glob.glob(os.path.join(CSRC, "*.cpp")))
-
-
-def build_probe() -> str:
-    """Compile the standalone machine-limits probe (not part of the library)."""
-    cmd = [hipcc(), "--offload-arch=gfx950", "-O3", "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
-           PROBE_SRC, "-o", PROBE_BIN]
-    res = subprocess.run(cmd, capture_output=True, text=True)
-    if res.returncode != 0:
-        raise RuntimeError("hipcc failed on the probe:\n" + res.stdout + res.stderr)
-    return PROBE_BIN
 
 
 def hipcc() -> str:

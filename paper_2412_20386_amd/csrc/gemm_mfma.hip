@@ -1328,7 +1328,8 @@ extern "C" int ptq4vm_w4a4_linear(const uint8_t *xq4, const uint8_t *wq4, const 
                                   const void *bias_f16, void *y_f16, int32_t *acc_out, int64_t B, int64_t L,
                                   int64_t K, int64_t N, int64_t ldxq, int64_t ldwq, int64_t ldy, void *stream_) {
     if (!xq4 || !wq4 || !s_tok || !s_w || !y_f16) return PTQ4VM_ERR_NULL;
-    if (B < 0 || N < 0 || L <= 0 || K <= 0 || K > PTQ4VM_MAX_K || K % 2 != 0) return PTQ4VM_ERR_SHAPE;
+    // operands are codes times 16: the accumulator holds 256 acc, at most 2^14 K with the nibble -8
+    if (B < 0 || N < 0 || L <= 0 || K <= 0 || K > PTQ4VM_MAX_K_W4 || K % 2 != 0) return PTQ4VM_ERR_SHAPE;
     if (B > 0 && L > INT64_MAX / B) return PTQ4VM_ERR_SHAPE;
     if (ldxq < K / 2 || ldwq < K / 2 || ldy < N) return PTQ4VM_ERR_STRIDE;
     if (!ptq4vm::aligned_to(xq4, 16) || !ptq4vm::aligned_to(wq4, 16) || !ptq4vm::aligned_to(y_f16, 2) ||

@@ -1,5 +1,5 @@
 // Per-token dynamic activation quantizer for gfx950: the comparison scheme of Sec. 4 and of the
-// "Per-token dynamic" rows of the latency table (Sec. 6.3).  The step of a token row is computed
+// "Per-token dynamic" rows of the latency table (Sec. 6.4).  The step of a token row is computed
 // online from the row itself, after smoothing:
 //   v[k] = f32(x[r,k]) * inv_m[k];  s_r = max_k |v[k]| / 127 (1 for an all-zero row);
 //   xq[r,k] = clip(rne(v[k] * (1 / s_r)), -127, 127);  s_row[r] = s_r.

@@ -24,6 +24,7 @@ const char *ptq4vm_status_string(int status) {
         case PTQ4VM_ERR_STRIDE: return "leading dimension smaller than the row width";
         case PTQ4VM_ERR_ALIGN: return "misaligned base pointer";
         case PTQ4VM_ERR_HIP: return "HIP runtime error";
+        case PTQ4VM_ERR_VALUE: return "a scale is not a finite number greater than zero";
         default: return "unknown status";
     }
 }

@@ -1,7 +1,7 @@
 // 4-bit forms of the offline weight fold and of the PTS activation quantizer for gfx950: the W4A4
-// setting of the paper's latency table (Sec. 6.3).  Codes are clipped to +-7 (Sec. 2.3:
+// setting of the paper's latency table (Sec. 6.4).  Codes are clipped to +-7 (Sec. 2.3:
 // +-(2^(b-1) - 1)) and stored two per byte, the even index in the low nibble, two's complement
-// (App. B.1 "Quantization": packed = (data[1] << 4) | (data[0] & 15)).
+// (the packing of App. B.1 "Quantization": the odd index fills the high nibble).
 //   ptq4vm_fold_smoothing_w4   W' = W diag(m), s_w = max|W'| / 7, codes packed [N, K / 2]
 //   ptq4vm_quantize_pts_a4     clip(rne((f32(x) inv_m[k]) (1 / s_tok[r mod L])), -7, 7), packed [B L, K / 2]
 // The quantizer is the same column-stationary stream as the 8-bit one (a thread keeps one group of

@@ -42,7 +42,7 @@ def test_library_exports_every_declared_symbol(lib):
 def test_version_and_status_strings(lib):
     assert lib.ptq4vm_version() >= 100
     assert ptq.binding.status_string(0) == "ok"
-    for code in (-1, -2, -3, -4, -5):
+    for code in (-1, -2, -3, -4, -5, -6):
         assert ptq.binding.status_string(code) not in ("ok", "unknown status")
     assert ptq.binding.status_string(-99) == "unknown status"
 
@@ -155,6 +155,8 @@ def test_w4a4_entry_points_argument_checks(lib):
 
     assert call(a0=NULL) == -1 and call(a5=NULL) == -1
     assert call(a9=15) == -2 and call(a9=0) == -2 and call(a8=0) == -2
+    # codes travel times 16: 256 acc must fit int32 even with the nibble -8, so K stops at 131071 (here: 131072)
+    assert call(a9=131072, a11=65536, a12=65536) == -2
     assert call(a11=7) == -3 and call(a12=7) == -3 and call(a13=15) == -3
     assert call(a0=ODD) == -4 and call(a1=ODD) == -4
     assert call(a7=0) == 0
@@ -180,6 +182,21 @@ def test_w8a8_linear_fused_argument_checks(lib):
     assert call(a0=ODD) == -4 and call(a3=ODD) == -4 and call(a1=ctypes.c_void_p(0x1002)) == -4
     assert call(a6=ctypes.c_void_p(0x1001)) == -4
     assert call(a9=0) == 0 and call(a12=0, a15=0) == 0       # empty problem
+
+
+def test_validate_scales_argument_checks(lib):
+    f = lib.ptq4vm_validate_scales
+    f.restype = ctypes.c_int
+    #  s_tok L m K s_w N counts workspace bytes stream
+    assert f(P, 4, P, 4, P, 4, NULL, P, 64, None) == -1
+    assert f(P, 4, P, 4, P, 4, P, NULL, 64, None) == -1
+    assert f(NULL, 4, P, 4, P, 4, P, P, 64, None) == -1               # a non-empty vector needs a pointer
+    assert f(P, -1, P, 4, P, 4, P, P, 64, None) == -2
+    assert f(P, 4, P, 4, P, 4, P, P, 16, None) == -2                  # workspace: 16 * (blocks + 1) bytes
+    assert f(P, 4096, P, 4096, P, 1, P, P, 48, None) == -2            # 8193 entries: 3 blocks -> 64 bytes
+    assert f(P, 1 << 31, P, 4, P, 4, P, P, 1 << 40, None) == -2       # more entries than the validator takes
+    assert f(ODD, 4, P, 4, P, 4, P, P, 64, None) == -4
+    assert f(P, 4, P, 4, P, 4, P, ctypes.c_void_p(0x1008), 64, None) == -4
 
 
 def test_fold_and_f16_argument_checks(lib):

@@ -257,17 +257,32 @@ def test_zero_offset_longest_reduction_24_bit_product():
     check_dequantized_output(_np(y), y_o, y64, prod_abs, np.zeros_like(prod_abs), "offset longest reduction")
 
 
-def test_w8a8_linear_is_deterministic():
-    c = synth.random_problem(9, 4, 197, 768, 384, device=DEV)
+DETERMINISM_SHAPES = [  # B, L, K, N, which kernels the library picks at this shape
+    (4, 197, 768, 384, "tiled 4-wavefront kernel"),
+    (64, 197, 768, 3072, "persistent 256 x 256 kernel, whole rounds plus a round of half tiles"),
+    (64, 197, 1536, 80, "weight-resident kernels (two-launch and fused)"),
+    (110, 197, 48, 1536, "row-streaming short-reduction kernel (two-launch and fused)"),
+]
+
+
+@pytest.mark.parametrize("B,L,K,N,kernels", DETERMINISM_SHAPES)
+def test_w8a8_linear_is_deterministic(B, L, K, N, kernels):
+    """20 runs of quantizer + linear and of the fused launch on the same inputs: identical bytes every
+    time (integer sums do not depend on order, so any difference is a race or an uninitialised read)."""
+    print(f"determinism B={B} L={L} K={K} N={N}: {kernels}", flush=True)
+    c = synth.random_problem(9, B, L, K, N, device=DEV)
     wq, s_w, inv_m = ptq.fold_smoothing(c.w, c.m)
     first_q = first_y = None
-    for _ in range(10):
+    for rep in range(20):
         xq = ptq.quantize_pts(c.x, inv_m, c.s_tok, c.B, c.L)
         y = ptq.w8a8_linear(xq, wq, c.s_tok, s_w, c.bias, c.B, c.L)
+        y_fused = ptq.w8a8_linear_fused(c.x, inv_m, c.s_tok, wq, s_w, c.bias, c.B, c.L)
         torch.cuda.synchronize()
         if first_q is None:
             first_q, first_y = xq.clone(), y.clone()
-        assert torch.equal(xq, first_q) and torch.equal(y.view(torch.int16), first_y.view(torch.int16))
+        assert torch.equal(xq, first_q), f"codes changed in repeat {rep}"
+        assert torch.equal(y.view(torch.int16), first_y.view(torch.int16)), f"output changed in repeat {rep}"
+        assert torch.equal(y_fused.view(torch.int16), first_y.view(torch.int16)), f"fused output changed in repeat {rep}"
 
 
 # ---------------------------------------------------------------------------------- FP16 linear
@@ -291,10 +306,37 @@ def _sampled_rows(M, step, L):
     return rows[(rows >= 0) & (rows < M)]
 
 
+ROW_CHUNK = 8192  # rows handed to the oracle at a time (bounds the host memory of a whole-tensor comparison)
+
+
+def _compare_rows_with_oracle(c, rows, x, xq, acc, y, what, use_bias=True):
+    """The oracle recomputes the given rows (all of them when rows = arange(M)) from the fp16 inputs, in
+    chunks: int8 codes and int32 accumulators must be equal, fp16 outputs within the bar of parity_util."""
+    wq_o, s_w_o, inv_m_o = oracle.fold_smoothing(_np(c.w), _np(c.m))
+    b_o = _np(c.bias) if use_bias else None
+    s_tok = _np(c.s_tok)
+    worst = {"mismatch_fraction": 0.0, "max_ulp": 0}
+    for lo in range(0, len(rows), ROW_CHUNK):
+        part = rows[lo:lo + ROW_CHUNK]
+        n = len(part)
+        contiguous = n > 1 and int(part[-1]) - int(part[0]) == n - 1
+        sel = slice(int(part[0]), int(part[-1]) + 1) if contiguous else torch.from_numpy(part).to(DEV)
+        st_rows = s_tok[part % c.L]                               # token position of each row
+        xq_o = oracle.quantize_pts(_np(x[sel]), inv_m_o, st_rows, 1, n)  # B=1, L=n: one step per row
+        assert np.array_equal(_np(xq[sel]), xq_o), f"{what}: int8 codes differ in rows {part[0]}..{part[-1]}"
+        y_o, y64, acc_o = oracle.w8a8_linear(xq_o, wq_o, st_rows, s_w_o, b_o, 1, n)
+        assert np.array_equal(_np(acc[sel]), acc_o), f"{what}: int32 accumulators differ in rows {part[0]}..{part[-1]}"
+        prod_abs = np.abs(acc_o.astype(np.float64) * st_rows.astype(np.float64)[:, None] * s_w_o.astype(np.float64)[None, :])
+        bias_abs = np.broadcast_to(np.abs(b_o.astype(np.float64))[None, :] if use_bias else 0.0, prod_abs.shape)
+        stats = check_dequantized_output(_np(y[sel]), y_o, y64, prod_abs, bias_abs, what)
+        worst = {k: max(worst[k], stats[k]) for k in worst}
+    return worst
+
+
 def _check_case_on_sampled_rows(c, rows, what, ldy=None, use_bias=True):
     """Whole problem on the GPU in the benchmark's launch configuration (no accumulator dump),
-    plus one launch with the dump; the oracle recomputes the sampled rows from the fp16 inputs."""
-    print(f"full-size {what}: M={c.B * c.L} K={c.K} N={c.N} ldy={ldy} bias={use_bias}, {len(rows)} sampled rows",
+    plus one launch with the dump; the oracle recomputes the given rows from the fp16 inputs."""
+    print(f"full-size {what}: M={c.B * c.L} K={c.K} N={c.N} ldy={ldy} bias={use_bias}, {len(rows)} rows compared",
           flush=True)
     M = c.B * c.L
     bias = c.bias if use_bias else None
@@ -312,36 +354,53 @@ def _check_case_on_sampled_rows(c, rows, what, ldy=None, use_bias=True):
     assert torch.equal(y.contiguous().view(torch.int16), y_dump.view(torch.int16))
     if ybuf is not None:
         assert bool((ybuf[:, c.N:] == 12345.0).all())
-    ridx = torch.from_numpy(rows).to(DEV)
-    x_s, xq_s, y_s, acc_s = _np(c.x[ridx]), _np(xq[ridx]), _np(y[ridx]), _np(acc[ridx])
-
-    wq_o, s_w_o, inv_m_o = oracle.fold_smoothing(_np(c.w), _np(c.m))
+    wq_o, s_w_o, _ = oracle.fold_smoothing(_np(c.w), _np(c.m))
     assert np.array_equal(_np(wq), wq_o) and np.array_equal(_np(s_w), s_w_o)
-    st_rows = _np(c.s_tok)[rows % c.L]                      # token position of each sampled row
-    n = len(rows)
-    xq_o = oracle.quantize_pts(x_s, inv_m_o, st_rows, 1, n)  # B=1, L=n: one step per sampled row
-    assert np.array_equal(xq_s, xq_o), "int8 codes differ"
-    b_o = _np(c.bias) if use_bias else None
-    y_o, y64, acc_o = oracle.w8a8_linear(xq_o, wq_o, st_rows, s_w_o, b_o, 1, n)
-    assert np.array_equal(acc_s, acc_o), "int32 accumulators differ"
-    prod_abs = np.abs(acc_o.astype(np.float64) * st_rows.astype(np.float64)[:, None] * s_w_o.astype(np.float64)[None, :])
-    bias_abs = np.broadcast_to(np.abs(b_o.astype(np.float64))[None, :] if use_bias else 0.0, prod_abs.shape)
-    return check_dequantized_output(y_s, y_o, y64, prod_abs, bias_abs, what)
+    return _compare_rows_with_oracle(c, rows, c.x, xq, acc, y, what, use_bias)
 
 
-@pytest.mark.parametrize("linear", [0, 1, 2, 3])
-def test_vim_b_full_size_sampled(linear):
-    """BASELINE configs[3]: M = 256 * 197 rows, the launch configuration bench.py times."""
-    c = synth.make_linear_case(3, 0, linear, device=DEV)
-    assert c.clipped > 0
-    _check_case_on_sampled_rows(c, _sampled_rows(c.B * c.L, 97, c.L), f"vim_b {c.name}")
+ALL_LINEARS_OF_THE_STACKS = [(cfg, linear) for cfg in (1, 2, 3, 4) for linear in (0, 1, 2, 3)]
 
 
-@pytest.mark.parametrize("cfg,linear", [(1, 0), (1, 1), (1, 2), (1, 3), (2, 0), (2, 3), (4, 0), (4, 1), (4, 2), (4, 3)])
-def test_other_configs_sampled(cfg, linear):
+@pytest.mark.parametrize("cfg,linear", ALL_LINEARS_OF_THE_STACKS)
+def test_stack_configs_layer0_whole_tensors_both_launch_forms(cfg, linear):
+    """BASELINE configs[1..4], layer 0, every linear at the config's size: EVERY int8 code, int32
+    accumulator and fp16 output against the oracle, in the two-launch form (quantizer, then linear) and in
+    the one-launch fused form, each in the launch configuration bench.py times (no dumps) and with the
+    parity dumps.  The four GPU results must agree bit for bit; the oracle then checks all M rows."""
     c = synth.make_linear_case(cfg, 0, linear, device=DEV)
     assert c.clipped > 0
-    _check_case_on_sampled_rows(c, _sampled_rows(c.B * c.L, 53, c.L), f"cfg{cfg} {c.name}")
+    M = c.B * c.L
+    print(f"whole tensors cfg{cfg} {c.name}: M={M} K={c.K} N={c.N}", flush=True)
+    wq, s_w, inv_m = ptq.fold_smoothing(c.w, c.m)
+    xq = ptq.quantize_pts(c.x, inv_m, c.s_tok, c.B, c.L)
+    y = ptq.w8a8_linear(xq, wq, c.s_tok, s_w, c.bias, c.B, c.L)
+    acc = torch.full((M, c.N), -1, dtype=torch.int32, device=DEV)
+    y_dump = ptq.w8a8_linear(xq, wq, c.s_tok, s_w, c.bias, c.B, c.L, acc_out=acc)
+    y_fused = ptq.w8a8_linear_fused(c.x, inv_m, c.s_tok, wq, s_w, c.bias, c.B, c.L)
+    acc_f = torch.full((M, c.N), -1, dtype=torch.int32, device=DEV)
+    xq_f = torch.full((M, c.K), 0x55, dtype=torch.int8, device=DEV)
+    y_fused_dump = ptq.w8a8_linear_fused(c.x, inv_m, c.s_tok, wq, s_w, c.bias, c.B, c.L, acc_out=acc_f, xq_out=xq_f)
+    torch.cuda.synchronize()
+    for other, name in ((y_dump, "two-launch with dump"), (y_fused, "fused"), (y_fused_dump, "fused with dumps")):
+        assert torch.equal(y.view(torch.int16), other.view(torch.int16)), f"{name} differs from the two-launch output"
+    assert torch.equal(acc, acc_f), "fused accumulators differ from the two-launch ones"
+    assert torch.equal(xq, xq_f), "fused codes differ from the quantizer's"
+    del y_dump, y_fused, y_fused_dump, acc_f, xq_f
+    wq_o, s_w_o, _ = oracle.fold_smoothing(_np(c.w), _np(c.m))
+    assert np.array_equal(_np(wq), wq_o) and np.array_equal(_np(s_w), s_w_o)
+    stats = _compare_rows_with_oracle(c, np.arange(M), c.x, xq, acc, y, f"cfg{cfg} {c.name}")
+    print(f"  {stats}", flush=True)
+
+
+@pytest.mark.parametrize("layer", [11, 23])
+@pytest.mark.parametrize("linear", [0, 1, 2, 3])
+def test_vim_b_other_layers_sampled(layer, linear):
+    """Two further layers of BASELINE configs[3] (their own seeded weights and activations): every 97th
+    row plus the edges, all columns."""
+    c = synth.make_linear_case(3, layer, linear, device=DEV)
+    assert c.clipped > 0
+    _check_case_on_sampled_rows(c, _sampled_rows(c.B * c.L, 97, c.L), f"vim_b layer {layer} {c.name}")
 
 
 @pytest.mark.parametrize("B,L,K,N", [(41, 251, 192, 1544), (33, 300, 64, 2056), (20, 517, 128, 6400),
@@ -461,29 +520,6 @@ def test_fused_linear_skinny_whole_result(B, L, K, N, ldy, bias, use_m):
     """Every code, accumulator and output of a weight-resident fused launch against the oracle."""
     c = synth.random_problem(1234 + K + N, B, L, K, N, device=DEV)
     _run_fused_case(c, use_bias=bias, use_m=use_m, ldy=ldy, what="fused-skinny")
-
-
-@pytest.mark.parametrize("cfg,linear", [(3, 1), (3, 2), (1, 1), (2, 1), (4, 1)])
-def test_fused_linear_full_size_matches_two_call_path(cfg, linear):
-    """Full-size x_proj / dt_proj: the fused launch must reproduce, bit for bit, the two-call path
-    (itself checked against the oracle above on sampled rows), and the oracle on sampled rows."""
-    c = synth.make_linear_case(cfg, 0, linear, device=DEV)
-    print(f"fused full-size cfg{cfg} {c.name}: M={c.B * c.L} K={c.K} N={c.N}", flush=True)
-    wq, s_w, inv_m = ptq.fold_smoothing(c.w, c.m)
-    xq = ptq.quantize_pts(c.x, inv_m, c.s_tok, c.B, c.L)
-    y_two = ptq.w8a8_linear(xq, wq, c.s_tok, s_w, c.bias, c.B, c.L)
-    y = ptq.w8a8_linear_fused(c.x, inv_m, c.s_tok, wq, s_w, c.bias, c.B, c.L)
-    torch.cuda.synchronize()
-    assert torch.equal(y.view(torch.int16), y_two.view(torch.int16))
-    rows = _sampled_rows(c.B * c.L, 97, c.L)
-    ridx = torch.from_numpy(rows).to(DEV)
-    wq_o, s_w_o, inv_m_o = oracle.fold_smoothing(_np(c.w), _np(c.m))
-    st_rows = _np(c.s_tok)[rows % c.L]
-    xq_o = oracle.quantize_pts(_np(c.x[ridx]), inv_m_o, st_rows, 1, len(rows))
-    y_o, y64, acc_o = oracle.w8a8_linear(xq_o, wq_o, st_rows, s_w_o, _np(c.bias), 1, len(rows))
-    prod_abs = np.abs(acc_o.astype(np.float64) * st_rows.astype(np.float64)[:, None] * s_w_o.astype(np.float64)[None, :])
-    bias_abs = np.broadcast_to(np.abs(_np(c.bias).astype(np.float64))[None, :], prod_abs.shape)
-    check_dequantized_output(_np(y[ridx]), y_o, y64, prod_abs, bias_abs, f"fused cfg{cfg} {c.name}")
 
 
 # ---------------------------------------------------------------------------------- per-token dynamic quantizer
@@ -789,3 +825,24 @@ def test_short_reduction_many_rows_two_launch_and_fused(B, L, K, N, ldy, bias):
     c = synth.random_problem(3100 + K + N, B, L, K, N, device=DEV)
     _run_w8a8_case(c, use_bias=bias, ldy=ldy, what="stream")
     _run_fused_case(c, use_bias=bias, ldy=ldy, what="stream-fused")
+
+
+# ---------------------------------------------------------------------------------- scale validator
+def test_validate_scales_counts_bad_entries():
+    """Not part of the method's arithmetic: the expected counts are plain numpy predicates on the inputs."""
+    g = torch.Generator().manual_seed(11)
+    for L, K, N in [(197, 768, 3072), (785, 24, 56), (1, 1, 1), (5000, 4096, 9000)]:
+        vecs = [torch.rand(n, generator=g) + 0.01 for n in (L, K, N)]
+        rc, counts = ptq.validate_scales(*[v.to(DEV) for v in vecs])
+        assert rc == 0 and _np(counts).tolist() == [0, 0, 0], (L, K, N)
+        bad_values = [0.0, -1.0, float("nan"), float("inf"), float("-inf"), -0.0]
+        for vi, v in enumerate(vecs):
+            for j, b in enumerate(bad_values):
+                if j < v.numel():
+                    v[(j * 977 + vi) % v.numel()] = b
+        want = [int(np.count_nonzero(~((_v > 0) & np.isfinite(_v)))) for _v in (v.numpy() for v in vecs)]
+        rc, counts = ptq.validate_scales(*[v.to(DEV) for v in vecs])
+        assert rc == -6 and _np(counts).tolist() == want, (L, K, N, want)
+    # a vector may be absent; denormal steps are valid
+    rc, counts = ptq.validate_scales(torch.full((3,), 1e-40, device=DEV), None, None)
+    assert rc == 0 and _np(counts).tolist() == [0, 0, 0]

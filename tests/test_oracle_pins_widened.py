@@ -15,7 +15,7 @@ def _f16(a):
 
 
 # --------------------------------------------------------------------------------------
-# per-token dynamic quantizer (Sec. 4; latency table of Sec. 6.3)
+# per-token dynamic quantizer (Sec. 4; latency table of Sec. 6.4)
 # --------------------------------------------------------------------------------------
 def test_dynamic_closed_form_grid_rows():
     # A row holding j * c for j = -127..127 has max |v| = 127 c, so its step is exactly c and the
@@ -85,7 +85,8 @@ def test_dynamic_scale_invariance_zero_rows_and_specials():
 # 4-bit codes and their packing (Sec. 2.3 clip range; App. B.1 packing expression)
 # --------------------------------------------------------------------------------------
 def test_int4_packing_matches_the_papers_expression_by_hand():
-    # packed = (data[1] << 4) | (data[0] & 15), two's complement nibbles; values worked by hand.
+    # App. B.1 packing: element 2i in the low nibble of byte i, element 2i+1 in its high nibble, two's
+    # complement nibbles; values worked by hand.
     codes = np.array([[1, 2, -1, 3, 7, -7, -8, 0, 0, -1]], np.int8)
     want = np.array([[0x21, 0x3F, 0x97, 0x08, 0xF0]], np.uint8)
     assert np.array_equal(oracle.pack_int4(codes), want)
