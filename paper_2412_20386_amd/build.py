@@ -1,7 +1,9 @@
 """Builds libptq4vm.so (HIP kernels + C ABI) for gfx950, in-tree next to this file."""
 from __future__ import annotations
 
+import concurrent.futures
 import glob
+import hashlib
 import os
 import shutil
 import subprocess
@@ -37,15 +39,52 @@ def hipcc() -> str:
     raise RuntimeError("hipcc not found")
 
 
-def build(verbose: bool = False) -> str:
-    """Compile every source under csrc/ into libptq4vm.so. Always recompiles."""
-    tmp = LIB_PATH + f".tmp{os.getpid()}"
-    cmd = [hipcc(), *HIPCC_FLAGS, "-x", "hip", *sources(), "-o", tmp]
-    res = subprocess.run(cmd, capture_output=True, text=True)
-    noise = "is not a recognized feature for this target"
-    log = "\n".join(l for l in (res.stdout + res.stderr).splitlines() if noise not in l)
+OBJ_DIR = os.path.join(_HERE, "_build")
+
+
+def _headers():
+    return sorted(glob.glob(os.path.join(CSRC, "*.hpp")) + glob.glob(os.path.join(_HERE, "..", "include", "*.h")))
+
+
+def _compile_one(src: str, force: bool):
+    """Compile one source to an object file; returns (object path, compiler log)."""
+    h = hashlib.sha1()
+    for path in [src, *_headers()]:
+        with open(path, "rb") as f:
+            h.update(f.read())
+    h.update(" ".join(HIPCC_FLAGS).encode())
+    obj = os.path.join(OBJ_DIR, os.path.basename(src) + "." + h.hexdigest()[:16] + ".o")
+    if not force and os.path.exists(obj):
+        return obj, ""
+    flags = [f for f in HIPCC_FLAGS if f != "-shared"]
+    tmp = obj + f".tmp{os.getpid()}"
+    res = subprocess.run([hipcc(), *flags, "-x", "hip", "-c", src, "-o", tmp], capture_output=True, text=True)
     if res.returncode != 0:
-        raise RuntimeError("hipcc failed:\n" + log)
+        raise RuntimeError(f"hipcc failed on {src}:\n" + res.stdout + res.stderr)
+    os.replace(tmp, obj)
+    return obj, res.stdout + res.stderr
+
+
+def build(verbose: bool = False, force: bool = True) -> str:
+    """Compile every source under csrc/ (one hipcc process per file, in parallel) and link
+    libptq4vm.so.  force=True recompiles everything; force=False reuses an object file whose source,
+    headers and flags are unchanged (a convenience while iterating on one kernel)."""
+    os.makedirs(OBJ_DIR, exist_ok=True)
+    srcs = sources()
+    with concurrent.futures.ThreadPoolExecutor(max_workers=min(8, len(srcs))) as pool:
+        results = list(pool.map(lambda s: _compile_one(s, force), srcs))
+    keep = {obj for obj, _ in results}
+    for stale in glob.glob(os.path.join(OBJ_DIR, "*.o")):
+        if stale not in keep:
+            os.remove(stale)
+    tmp = LIB_PATH + f".tmp{os.getpid()}"
+    link = subprocess.run([hipcc(), "--offload-arch=gfx950", "-shared", "-fPIC", *sorted(keep), "-o", tmp],
+                          capture_output=True, text=True)
+    noise = "is not a recognized feature for this target"
+    log = "\n".join(l for _, out in results for l in out.splitlines() if noise not in l)
+    log += "\n".join(l for l in (link.stdout + link.stderr).splitlines() if noise not in l)
+    if link.returncode != 0:
+        raise RuntimeError("link failed:\n" + log)
     if verbose and log.strip():
         print(log)
     os.replace(tmp, LIB_PATH)
@@ -53,4 +92,6 @@ def build(verbose: bool = False) -> str:
 
 
 if __name__ == "__main__":
-    print(build(verbose=True))
+    import sys
+
+    print(build(verbose=True, force="--incremental" not in sys.argv))

@@ -170,77 +170,6 @@ __global__ __launch_bounds__(kThreads, 2) void linear_mfma_dma(const LinearArgs 
 // Requirements (host-checked): as linear_mfma_dma, plus k_bytes % SLAB == 0, k_bytes >= 2 SLAB,
 // N % 8 == 0, 16-byte aligned y pitch, 4-byte aligned bias, 256 * ldy * 2 < 2^31, L < 2^31.
 // ------------------------------------------------------------------------------------------
-// LDS accesses of the epilogue are written as inline asm: the compiler does not see them, so it
-// cannot tie them to the outstanding global -> LDS copies (for which it would insert a full
-// vmcnt(0) drain).  Every read block ends with its own s_waitcnt inside the same asm statement,
-// so the outputs are valid as soon as the compiler may touch them.  Outputs are float vectors:
-// this compiler reads every element of an integer-vector asm output from its first register.
-__device__ __forceinline__ uint32_t lds_addr(const void *p) { return (uint32_t)(uintptr_t)p; }
-
-// eight 16-byte reads at base + STEP n (n = 0..3) and base + JUMP + STEP n
-template <int STEP, int JUMP>
-__device__ __forceinline__ void lds_read_8x_b128(uint32_t base, v4f (&v)[8]) {
-    asm volatile(
-        "ds_read_b128 %0, %8 offset:%9\n ds_read_b128 %1, %8 offset:%10\n ds_read_b128 %2, %8 offset:%11\n"
-        "ds_read_b128 %3, %8 offset:%12\n ds_read_b128 %4, %8 offset:%13\n ds_read_b128 %5, %8 offset:%14\n"
-        "ds_read_b128 %6, %8 offset:%15\n ds_read_b128 %7, %8 offset:%16\n s_waitcnt lgkmcnt(0)"
-        : "=&v"(v[0]), "=&v"(v[1]), "=&v"(v[2]), "=&v"(v[3]), "=&v"(v[4]), "=&v"(v[5]), "=&v"(v[6]), "=&v"(v[7])
-        : "v"(base), "n"(0), "n"(STEP), "n"(2 * STEP), "n"(3 * STEP), "n"(JUMP), "n"(JUMP + STEP), "n"(JUMP + 2 * STEP),
-          "n"(JUMP + 3 * STEP)
-        : "memory");
-}
-// four 16-byte reads at base + STEP n
-template <int STEP>
-__device__ __forceinline__ void lds_read_4x_b128(uint32_t base, v4f (&v)[4]) {
-    asm volatile(
-        "ds_read_b128 %0, %4 offset:%5\n ds_read_b128 %1, %4 offset:%6\n ds_read_b128 %2, %4 offset:%7\n"
-        "ds_read_b128 %3, %4 offset:%8\n s_waitcnt lgkmcnt(0)"
-        : "=&v"(v[0]), "=&v"(v[1]), "=&v"(v[2]), "=&v"(v[3])
-        : "v"(base), "n"(0), "n"(STEP), "n"(2 * STEP), "n"(3 * STEP)
-        : "memory");
-}
-// eight 4-byte reads at base + STEP n
-template <int STEP>
-__device__ __forceinline__ void lds_read_8x_b32(uint32_t base, float (&v)[8]) {
-    asm volatile(
-        "ds_read_b32 %0, %8 offset:%9\n ds_read_b32 %1, %8 offset:%10\n ds_read_b32 %2, %8 offset:%11\n"
-        "ds_read_b32 %3, %8 offset:%12\n ds_read_b32 %4, %8 offset:%13\n ds_read_b32 %5, %8 offset:%14\n"
-        "ds_read_b32 %6, %8 offset:%15\n ds_read_b32 %7, %8 offset:%16\n s_waitcnt lgkmcnt(0)"
-        : "=&v"(v[0]), "=&v"(v[1]), "=&v"(v[2]), "=&v"(v[3]), "=&v"(v[4]), "=&v"(v[5]), "=&v"(v[6]), "=&v"(v[7])
-        : "v"(base), "n"(0), "n"(STEP), "n"(2 * STEP), "n"(3 * STEP), "n"(4 * STEP), "n"(5 * STEP), "n"(6 * STEP),
-          "n"(7 * STEP)
-        : "memory");
-}
-// four 4-byte reads at base + STEP n
-template <int STEP>
-__device__ __forceinline__ void lds_read_4x_b32(uint32_t base, float (&v)[4]) {
-    asm volatile(
-        "ds_read_b32 %0, %4 offset:%5\n ds_read_b32 %1, %4 offset:%6\n ds_read_b32 %2, %4 offset:%7\n"
-        "ds_read_b32 %3, %4 offset:%8\n s_waitcnt lgkmcnt(0)"
-        : "=&v"(v[0]), "=&v"(v[1]), "=&v"(v[2]), "=&v"(v[3])
-        : "v"(base), "n"(0), "n"(STEP), "n"(2 * STEP), "n"(3 * STEP)
-        : "memory");
-}
-// four 16-byte reads at arbitrary addresses
-__device__ __forceinline__ void lds_read_4_b128(const uint32_t (&addr)[4], v4f (&v)[4]) {
-    asm volatile(
-        "ds_read_b128 %0, %4\n ds_read_b128 %1, %5\n ds_read_b128 %2, %6\n ds_read_b128 %3, %7\n"
-        "s_waitcnt lgkmcnt(0)"
-        : "=&v"(v[0]), "=&v"(v[1]), "=&v"(v[2]), "=&v"(v[3])
-        : "v"(addr[0]), "v"(addr[1]), "v"(addr[2]), "v"(addr[3])
-        : "memory");
-}
-__device__ __forceinline__ void lds_write_b64(uint32_t addr, u32x2 v) {
-    asm volatile("ds_write_b64 %0, %1" ::"v"(addr), "v"(v) : "memory");
-}
-
-template <int KEEP>
-__device__ __forceinline__ void wait_vmcnt_at_most() {
-    // s_waitcnt immediate on gfx9: vmcnt[3:0] | expcnt[6:4] | lgkmcnt[11:8] | vmcnt[5:4] << 14
-    static_assert(KEEP >= 0 && KEEP <= 63, "vmcnt is a 6-bit counter");
-    __builtin_amdgcn_s_waitcnt(0x0F70 | (KEEP & 15) | ((KEEP >> 4) << 14));
-}
-
 // The tiles `first`, `first + stride`, ... (n_my of them) of the grid of (32 FR)-row x BO-channel
 // tiles, channel tiles fastest, processed by the whole workgroup.  FR = 8: 256-row tiles; FR = 4:
 // 128-row half tiles (used to spread a last, partial round of tiles over idle workgroups).
@@ -1263,6 +1192,11 @@ int dispatch(LinearArgs a, hipStream_t stream) {
 #endif
     if (a.k_bytes <= 128 && la >= 4 && a.L < (1LL << 31))
         return la == 16 ? launch_smallk_ksteps<Path, 16>(a, stream) : launch_smallk_ksteps<Path, 4>(a, stream);
+    if constexpr (Path::kElemBytes == 1 && !Path::kOffset && !Path::kPacked4) {
+        // wide output, short reduction (in_proj of the Vim-S / Vim-B stacks): weight rows held in registers
+        const int rc = launch_wreg(a, stream);
+        if (rc <= 0) return rc;
+    }
     const bool persistent_ok = dma_ok && a.N % 8 == 0 && a.y_vec == 8 && ptq4vm::aligned_to(a.bias, 4) &&
                                a.ldy * 512 < (1LL << 31) && a.L < (1LL << 31) && a.N >= 256 &&
                                a.k_bytes % PTQ4VM_PERSISTENT_SLAB == 0 && a.k_bytes >= 2 * PTQ4VM_PERSISTENT_SLAB &&

@@ -266,6 +266,22 @@ __device__ __forceinline__ void epilogue(const typename Path::Acc (&acc)[FO][FR]
     }
 }
 
+// The dequantization of two neighbouring outputs, y = fp16(a * scale + bias) each, as ONE instruction per
+// output: v_fma_mix computes the multiply-add in fp32 from fp32 a and scale and the fp16 bias and rounds
+// the result to fp16.  Left to itself the compiler picks this form or fma + conversion (two roundings)
+// from one inlined copy of the same source line to the next, and the two differ in the last bit of a few
+// outputs per million; writing the instruction out keeps every kernel that uses this helper on the same
+// bits.  `bias_pair` holds the two fp16 biases (low half: first output) as a raw word; the result is the
+// two fp16 outputs as a raw word.
+__device__ __forceinline__ float dequantize_pair_f16(float a0, float scale0, float a1, float scale1, float bias_pair) {
+    float packed;
+    asm("v_fma_mixlo_f16 %0, %1, %2, %3 op_sel_hi:[0,0,1]" : "=v"(packed) : "v"(a0), "v"(scale0), "v"(bias_pair));
+    asm("v_fma_mixhi_f16 %0, %1, %2, %3 op_sel:[0,0,1] op_sel_hi:[0,0,1]"
+        : "+v"(packed)
+        : "v"(a1), "v"(scale1), "v"(bias_pair));
+    return packed;
+}
+
 __device__ __forceinline__ uint32_t keep_low_bytes(uint32_t v, int nbytes) {
     return nbytes >= 4 ? v : (nbytes <= 0 ? 0u : (v & ((1u << (8 * nbytes)) - 1u)));
 }
@@ -322,11 +338,129 @@ inline bool set_grid(LinearArgs &a, dim3 &grid) {
 }
 
 
+// LDS accesses of the epilogue are written as inline asm: the compiler does not see them, so it
+// cannot tie them to the outstanding global -> LDS copies (for which it would insert a full
+// vmcnt(0) drain).  Every read block ends with its own s_waitcnt inside the same asm statement,
+// so the outputs are valid as soon as the compiler may touch them.  Outputs are float vectors:
+// this compiler reads every element of an integer-vector asm output from its first register.
+__device__ __forceinline__ uint32_t lds_addr(const void *p) { return (uint32_t)(uintptr_t)p; }
+
+// eight 16-byte reads at base + STEP n (n = 0..3) and base + JUMP + STEP n
+template <int STEP, int JUMP>
+__device__ __forceinline__ void lds_read_8x_b128(uint32_t base, v4f (&v)[8]) {
+    asm volatile(
+        "ds_read_b128 %0, %8 offset:%9\n ds_read_b128 %1, %8 offset:%10\n ds_read_b128 %2, %8 offset:%11\n"
+        "ds_read_b128 %3, %8 offset:%12\n ds_read_b128 %4, %8 offset:%13\n ds_read_b128 %5, %8 offset:%14\n"
+        "ds_read_b128 %6, %8 offset:%15\n ds_read_b128 %7, %8 offset:%16\n s_waitcnt lgkmcnt(0)"
+        : "=&v"(v[0]), "=&v"(v[1]), "=&v"(v[2]), "=&v"(v[3]), "=&v"(v[4]), "=&v"(v[5]), "=&v"(v[6]), "=&v"(v[7])
+        : "v"(base), "n"(0), "n"(STEP), "n"(2 * STEP), "n"(3 * STEP), "n"(JUMP), "n"(JUMP + STEP), "n"(JUMP + 2 * STEP),
+          "n"(JUMP + 3 * STEP)
+        : "memory");
+}
+// four 16-byte reads at base + STEP n
+template <int STEP>
+__device__ __forceinline__ void lds_read_4x_b128(uint32_t base, v4f (&v)[4]) {
+    asm volatile(
+        "ds_read_b128 %0, %4 offset:%5\n ds_read_b128 %1, %4 offset:%6\n ds_read_b128 %2, %4 offset:%7\n"
+        "ds_read_b128 %3, %4 offset:%8\n s_waitcnt lgkmcnt(0)"
+        : "=&v"(v[0]), "=&v"(v[1]), "=&v"(v[2]), "=&v"(v[3])
+        : "v"(base), "n"(0), "n"(STEP), "n"(2 * STEP), "n"(3 * STEP)
+        : "memory");
+}
+// eight 4-byte reads at base + STEP n
+template <int STEP>
+__device__ __forceinline__ void lds_read_8x_b32(uint32_t base, float (&v)[8]) {
+    asm volatile(
+        "ds_read_b32 %0, %8 offset:%9\n ds_read_b32 %1, %8 offset:%10\n ds_read_b32 %2, %8 offset:%11\n"
+        "ds_read_b32 %3, %8 offset:%12\n ds_read_b32 %4, %8 offset:%13\n ds_read_b32 %5, %8 offset:%14\n"
+        "ds_read_b32 %6, %8 offset:%15\n ds_read_b32 %7, %8 offset:%16\n s_waitcnt lgkmcnt(0)"
+        : "=&v"(v[0]), "=&v"(v[1]), "=&v"(v[2]), "=&v"(v[3]), "=&v"(v[4]), "=&v"(v[5]), "=&v"(v[6]), "=&v"(v[7])
+        : "v"(base), "n"(0), "n"(STEP), "n"(2 * STEP), "n"(3 * STEP), "n"(4 * STEP), "n"(5 * STEP), "n"(6 * STEP),
+          "n"(7 * STEP)
+        : "memory");
+}
+// four 4-byte reads at base + STEP n
+template <int STEP>
+__device__ __forceinline__ void lds_read_4x_b32(uint32_t base, float (&v)[4]) {
+    asm volatile(
+        "ds_read_b32 %0, %4 offset:%5\n ds_read_b32 %1, %4 offset:%6\n ds_read_b32 %2, %4 offset:%7\n"
+        "ds_read_b32 %3, %4 offset:%8\n s_waitcnt lgkmcnt(0)"
+        : "=&v"(v[0]), "=&v"(v[1]), "=&v"(v[2]), "=&v"(v[3])
+        : "v"(base), "n"(0), "n"(STEP), "n"(2 * STEP), "n"(3 * STEP)
+        : "memory");
+}
+// four 16-byte reads at arbitrary addresses
+__device__ __forceinline__ void lds_read_4_b128(const uint32_t (&addr)[4], v4f (&v)[4]) {
+    asm volatile(
+        "ds_read_b128 %0, %4\n ds_read_b128 %1, %5\n ds_read_b128 %2, %6\n ds_read_b128 %3, %7\n"
+        "s_waitcnt lgkmcnt(0)"
+        : "=&v"(v[0]), "=&v"(v[1]), "=&v"(v[2]), "=&v"(v[3])
+        : "v"(addr[0]), "v"(addr[1]), "v"(addr[2]), "v"(addr[3])
+        : "memory");
+}
+__device__ __forceinline__ void lds_write_b64(uint32_t addr, u32x2 v) {
+    asm volatile("ds_write_b64 %0, %1" ::"v"(addr), "v"(v) : "memory");
+}
+
+template <int KEEP>
+__device__ __forceinline__ void wait_vmcnt_at_most() {
+    // s_waitcnt immediate on gfx9: vmcnt[3:0] | expcnt[6:4] | lgkmcnt[11:8] | vmcnt[5:4] << 14
+    static_assert(KEEP >= 0 && KEEP <= 63, "vmcnt is a 6-bit counter");
+    __builtin_amdgcn_s_waitcnt(0x0F70 | (KEEP & 15) | ((KEEP >> 4) << 14));
+}
+
+__device__ __forceinline__ void lds_read_1x_b128(uint32_t addr, v4f &v) {
+    asm volatile("ds_read_b128 %0, %1\n s_waitcnt lgkmcnt(0)" : "=&v"(v) : "v"(addr) : "memory");
+}
+// two 16-byte reads at base and base + STEP
+template <int STEP>
+__device__ __forceinline__ void lds_read_2x_b128(uint32_t base, v4f (&v)[2]) {
+    asm volatile("ds_read_b128 %0, %2 offset:%3\n ds_read_b128 %1, %2 offset:%4\n s_waitcnt lgkmcnt(0)"
+                 : "=&v"(v[0]), "=&v"(v[1])
+                 : "v"(base), "n"(0), "n"(STEP)
+                 : "memory");
+}
+// Reads that are only ISSUED here (eight 4-byte reads at base + STEP n; three 16-byte reads at base +
+// STEP n): the caller must pass every destination through lds_wait_all before using it.
+template <int STEP>
+__device__ __forceinline__ void lds_issue_8x_b32(uint32_t base, float (&v)[8]) {
+    asm volatile(
+        "ds_read_b32 %0, %8 offset:%9\n ds_read_b32 %1, %8 offset:%10\n ds_read_b32 %2, %8 offset:%11\n"
+        "ds_read_b32 %3, %8 offset:%12\n ds_read_b32 %4, %8 offset:%13\n ds_read_b32 %5, %8 offset:%14\n"
+        "ds_read_b32 %6, %8 offset:%15\n ds_read_b32 %7, %8 offset:%16"
+        : "=&v"(v[0]), "=&v"(v[1]), "=&v"(v[2]), "=&v"(v[3]), "=&v"(v[4]), "=&v"(v[5]), "=&v"(v[6]), "=&v"(v[7])
+        : "v"(base), "n"(0), "n"(STEP), "n"(2 * STEP), "n"(3 * STEP), "n"(4 * STEP), "n"(5 * STEP), "n"(6 * STEP),
+          "n"(7 * STEP)
+        : "memory");
+}
+template <int STEP>
+__device__ __forceinline__ void lds_issue_3x_b128(uint32_t base, v4f (&v)[3]) {
+    asm volatile("ds_read_b128 %0, %3 offset:%4\n ds_read_b128 %1, %3 offset:%5\n ds_read_b128 %2, %3 offset:%6"
+                 : "=&v"(v[0]), "=&v"(v[1]), "=&v"(v[2])
+                 : "v"(base), "n"(0), "n"(STEP), "n"(2 * STEP)
+                 : "memory");
+}
+// s_waitcnt lgkmcnt(0) that the given registers depend on: no use of them can be scheduled ahead of it.
+__device__ __forceinline__ void lds_wait_all(float (&a)[8], v4f (&b)[3]) {
+    asm volatile("s_waitcnt lgkmcnt(0)"
+                 : "+v"(a[0]), "+v"(a[1]), "+v"(a[2]), "+v"(a[3]), "+v"(a[4]), "+v"(a[5]), "+v"(a[6]), "+v"(a[7]),
+                   "+v"(b[0]), "+v"(b[1]), "+v"(b[2])
+                 :
+                 : "memory");
+}
+__device__ __forceinline__ void lds_write_b128(uint32_t addr, v4f v) {
+    asm volatile("ds_write_b128 %0, %1" ::"v"(addr), "v"(v) : "memory");
+}
+
 // Row-streaming kernel for short reductions (K <= 128), defined next to the fused kernels.
 // quantize: x holds fp16 activations and inv_m / xq_out are honoured; otherwise x holds int8 codes.
 // Returns PTQ4VM_OK after a launch, a negative status on error, or 1 if the shape does not fit
 // this kernel (nothing was launched; the caller picks another one).
 int launch_stream_smallk(const LinearArgs &a, bool quantize, hipStream_t stream);
+
+// Weights-in-registers kernel for wide int8 linears with a short reduction (K = 384 or 768, e.g. the
+// in_proj of the Vim-S / Vim-B stacks), defined in gemm_wreg.hip.  Same return convention.
+int launch_wreg(const LinearArgs &a, hipStream_t stream);
 
 }  // namespace mfma
 }  // namespace ptq4vm

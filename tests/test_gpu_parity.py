@@ -404,11 +404,14 @@ def test_vim_b_other_layers_sampled(layer, linear):
 
 
 @pytest.mark.parametrize("B,L,K,N", [(41, 251, 192, 1544), (33, 300, 64, 2056), (20, 517, 128, 6400),
-                                     (41, 251, 256, 1544), (20, 517, 384, 3400), (45, 229, 640, 1800)])
+                                     (41, 251, 256, 1544), (20, 517, 384, 3400), (45, 229, 640, 1800),
+                                     (41, 251, 768, 1280), (67, 193, 768, 256), (53, 211, 384, 768), (20, 517, 384, 3328)])
 def test_large_ragged_shapes_sampled(B, L, K, N):
-    """Many 256 x 256 tiles with ragged last tiles in both directions; the last three have a reduction
-    length the persistent kernel takes (2, 3 and 5 slabs of 128 bytes), with and without a partial last
-    round of tiles that is cut into half tiles."""
+    """Many 256 x 256 tiles with ragged last tiles in both directions; shapes 4 and 6 have a reduction
+    length the persistent kernel takes (2 and 5 slabs of 128 bytes), with and without a partial last
+    round of tiles that is cut into half tiles.  K = 384 and K = 768 with at least 8192 rows and N a
+    multiple of 256 run on the weights-in-registers kernel: ragged last row tile, a single strip, more
+    workgroups than units in an XCD's last band."""
     c = synth.random_problem(4242 + N, B, L, K, N, device=DEV)
     _check_case_on_sampled_rows(c, _sampled_rows(B * L, 61, L), "ragged")
 
@@ -428,6 +431,14 @@ SKINNY_SHAPES = [  # B, L, K, N, ldy, bias: few output channels over many rows (
 def test_skinny_output_shapes_sampled(B, L, K, N, ldy, bias):
     c = synth.random_problem(777 + K + N, B, L, K, N, device=DEV)
     _check_case_on_sampled_rows(c, _sampled_rows(B * L, 37, L), "skinny", ldy=ldy, use_bias=bias)
+
+
+@pytest.mark.parametrize("B,L,K,N,bias", [(43, 197, 768, 512, True), (65, 131, 384, 256, False)])
+def test_weights_in_registers_kernel_whole_result(B, L, K, N, bias):
+    """Every code, accumulator and output of a launch of the weights-in-registers kernel (K = 768 / 384,
+    at least 8192 rows), ragged in rows and channels."""
+    c = synth.random_problem(4100 + K + N, B, L, K, N, device=DEV)
+    _run_w8a8_case(c, use_bias=bias, what="wreg-whole")
 
 
 def test_skinny_output_whole_result():
