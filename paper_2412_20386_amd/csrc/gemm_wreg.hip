@@ -5,30 +5,28 @@
 //
 // One workgroup of 8 wavefronts per CU owns a strip of 256 output channels for (almost) its whole
 // life.  A wavefront keeps the weight rows of 32 channels, all K of them, as MFMA "A" operands in
-// registers (96 VGPRs at K = 768) and never reads the weight again.  Token rows arrive in tiles of
+// registers (96 VGPRs at K = 768) and never reads the weight again.  Token rows arrive in units of
 // 128 rows: their int8 codes are copied global -> LDS (direct copies, no VGPR staging) into a ring
-// of 7 slots, each slot one sixth of K for the 128 rows, and every wavefront reads all of them as
+// of 5 slots, each slot one sixth of K for the 128 rows, and every wavefront reads all of them as
 // "B" operands.  Per 128 x 256 unit that is 96 KiB through L2 -> LDS, half of what a 256 x 256
-// tile with both operands in LDS needs per output, and the ring runs 3 to 4 slots ahead.
+// tile with both operands in LDS needs per output, and the ring runs 3 slots ahead.
 //
-// The wavefronts work in two groups of four, one wavefront of each group per SIMD.  Group B runs
-// three ring slots (half a unit) behind group A.  A unit's results are converted to fp16 in
-// registers, staged through LDS (one 128 x 128 half unit at a time, group A's and group B's
-// alternately) and written to memory in whole 256-byte row segments during the following steps, so
-// that conversion (VALU), output stores and the other group's MFMAs overlap, and the store stream
-// is spread over the whole unit instead of bursting at its end.
-// Roles: group A issues every global -> LDS copy and never stores; group B issues every output store
-// and never waits for a copy.  Loads and stores share one counter (vmcnt) and complete out of order
-// with each other, so a wavefront that did both could only wait for a copy by draining its stores.
-//
-// Step structure (slot g of the ring = step g of group A = step g - 3 of group B): MFMAs of all but
-// the last k-step of the slot; wait; s_barrier; MFMAs of the last k-step while the operands of the
-// next slot's first k-step are fetched.  At the barrier of group A's step g every copy of slot g + 1
-// has landed and slot g - 4 has been read into registers by everyone (group B is still reading slot
-// g - 3 after this barrier when that is a unit's last slot, see below), so it is refilled with slot
-// g + 3.
-// The unit's last step is different: there the MFMAs run row block by row block and each block's
-// results are converted and staged right behind them (see `last_step_run`).
+// Step g of a workgroup consumes ring slot g: MFMAs of all but the last k-step of the slot; wait;
+// s_barrier; MFMAs of the last k-step while the operands of the next slot's first k-step are fetched.
+// At the barrier of step g every copy of slot g + 1 has landed and slot g - 1 has been read into
+// registers by everyone, so its place is refilled with slot g + 4.
+// A unit's last step is different: after its barrier the MFMAs run row block by row block (all
+// k-steps of the slot for 16 rows), and each block's results are converted to fp16 and written to an
+// LDS staging tile right behind its MFMAs.  The conversion is three VALU instructions per output and
+// a lone wavefront issues at most one VALU instruction in ~8 cycles: done as a phase of its own it
+// would leave the matrix pipes idle for a third of the time; woven between the MFMAs of both
+// wavefronts of a SIMD it runs at the SIMD's full VALU rate with the MFMAs underneath.
+// The staged 128 x 256 fp16 tile leaves for memory during the first four steps of the next unit, in
+// whole 512-byte row segments, so the store stream is spread over the unit instead of bursting.
+// Roles: wavefronts 0-3 issue every global -> LDS copy and never store; wavefronts 4-7 issue every
+// output store and never wait for a copy.  Loads and stores share one counter (vmcnt) and complete
+// out of order with each other, so a wavefront that did both could only wait for a copy by draining
+// its stores.
 //
 // Output channel order inside a wavefront: MFMA block i (0, 1), A-operand row a (0..15) carries
 // strip channel 32 w + 8 (a / 4) + 4 i + (a mod 4).  A lane's eight results of a token row are then
@@ -36,6 +34,8 @@
 //
 // Requirements (host-checked): int8 path without zero offset, K = 384 or 768, pitches and bases
 // 16-byte aligned, N a multiple of 256, y 16-byte aligned with 16-byte pitch, M, L < 2^31.
+#include <type_traits>
+
 #include "mfma_linear.hpp"
 
 // Timing experiments only (results are wrong when any bit is set): 1 no output stores, 2 no conversion,
@@ -72,9 +72,9 @@ namespace {
 constexpr int kUnitRows = 128;    // token rows per unit
 constexpr int kStripCols = 256;   // output channels per workgroup
 constexpr int kSteps = 6;         // ring slots per unit
-constexpr int kSlots = 7;         // ring depth
-constexpr int kDelay = 3;         // steps group B runs behind group A
-constexpr int kStagePitch = 272;  // bytes per staged half row: 128 channels of fp16 + 16 (bank spread)
+constexpr int kSlots = 5;         // ring depth
+constexpr int kAhead = kSlots - 1;  // slots copied ahead of the one being consumed
+constexpr int kStagePitch = 528;  // bytes per staged row: 256 channels of fp16 + 16 (bank spread)
 constexpr int kStageBytes = kUnitRows * kStagePitch;
 constexpr int kRowScaleBufs = 4;  // per-row step vectors of the units in flight
 
@@ -128,7 +128,7 @@ __global__ __launch_bounds__(512, 1) void linear_mfma_wreg(const LinearArgs p) {
     constexpr int SLOT_BYTES = kUnitRows * SLAB;
     constexpr int CHUNKS = SLAB / 16;            // 16-byte chunks per slot row
     constexpr int ROWS_PER_COPY = 64 / CHUNKS;   // rows in one wavefront-wide 1 KiB copy
-    constexpr int COPIES = kUnitRows / ROWS_PER_COPY / 4;  // copies per group-A wavefront and slot
+    constexpr int COPIES = kUnitRows / ROWS_PER_COPY / 4;  // copies per copying wavefront and slot
     using Acc = Int8Path::Acc16;
 
     char *const ring = lds_dyn;
@@ -139,8 +139,7 @@ __global__ __launch_bounds__(512, 1) void linear_mfma_wreg(const LinearArgs p) {
 
     const int tid = threadIdx.x, lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
-    const bool group_a = wave < 4;
-    const int gw = wave & 3;  // wavefront inside its group
+    const int gw = wave & 3;  // wavefront inside its group of four
     const int l16 = lane & 15, lq = lane >> 4;
 
 #if PTQ4VM_WREG_TRACE
@@ -162,17 +161,16 @@ __global__ __launch_bounds__(512, 1) void linear_mfma_wreg(const LinearArgs p) {
     v4i fw[2][KSTEPS];
     auto load_strip = [&](int strip) {
         const int64_t o0 = (int64_t)strip * kStripCols;
-        const int cols_valid = (int)min((int64_t)kStripCols, p.N - o0);  // a multiple of 8, at least 8
         const char *w_strip = p.w + o0 * p.ldw_bytes;
 #pragma unroll
         for (int i = 0; i < 2; i++) {
-            const int ch = min(wave * 32 + 8 * (l16 >> 2) + 4 * i + (l16 & 3), cols_valid - 1);  // clamped: never stored
+            const int ch = wave * 32 + 8 * (l16 >> 2) + 4 * i + (l16 & 3);
             const uint32_t off = (uint32_t)ch * (uint32_t)p.ldw_bytes + lq * 16;
 #pragma unroll
             for (int ks = 0; ks < KSTEPS; ks++) fw[i][ks] = *reinterpret_cast<const v4i *>(w_strip + off + ks * 64);
         }
         if (lane < 32) {  // channel wave * 32 + lane: lanes 0..31 write the wavefront's own 4 x 48 bytes
-            const int ch = min(wave * 32 + lane, cols_valid - 1);
+            const int ch = wave * 32 + lane;
             char *slot8 = cs_lds + (wave * 4 + (lane >> 3)) * 48;
             reinterpret_cast<float *>(slot8)[lane & 7] = p.s_w[o0 + ch];
             __half bias = __float2half(0.0f);
@@ -186,14 +184,13 @@ __global__ __launch_bounds__(512, 1) void linear_mfma_wreg(const LinearArgs p) {
     uint32_t frag_off[KPS];
 #pragma unroll
     for (int k2 = 0; k2 < KPS; k2++) frag_off[k2] = (uint32_t)slot_chunk(l16, 4 * k2 + lq);  // row 16 j + l16: same swizzle
-    auto load_fx = [&](int j, int slot, int k2) {
-        fx[j] = *reinterpret_cast<const v4i *>(ring + slot * SLOT_BYTES + frag_off[k2] + j * 16 * SLAB);
+    auto operand = [&](int j, int slot, int k2) {
+        return *reinterpret_cast<const v4i *>(ring + slot * SLOT_BYTES + frag_off[k2] + j * 16 * SLAB);
     };
 
     Acc acc[2][8];
-    // One MFMA k-step: 16 MFMAs; operand j is dead after its two MFMAs and is refetched at once.
-    // REFETCH: operand j is dead after its two MFMAs and is fetched again at once for the k-step named
-    // by (slot, k2).
+    // One MFMA k-step over the 8 row blocks.  REFETCH: operand j is dead after its two MFMAs and is
+    // fetched again at once for the k-step named by (slot, k2).
     auto k_step = [&](const v4i &w0, const v4i &w1, bool fresh, bool refetch, int slot, int k2) {
 #pragma unroll
         for (int j = 0; j < 8; j++) {
@@ -204,7 +201,7 @@ __global__ __launch_bounds__(512, 1) void linear_mfma_wreg(const LinearArgs p) {
             } else if (fresh) {
                 acc[0][j] = fx[j], acc[1][j] = fx[j] + w0 + w1;
             }
-            if (refetch && !(PTQ4VM_WREG_SKIP & 8)) load_fx(j, slot, k2);
+            if (refetch && !(PTQ4VM_WREG_SKIP & 8)) fx[j] = operand(j, slot, k2);
             __builtin_amdgcn_sched_barrier(0);  // keep the refetch behind its MFMAs: hoisted, it would need a second register set
         }
     };
@@ -217,12 +214,9 @@ __global__ __launch_bounds__(512, 1) void linear_mfma_wreg(const LinearArgs p) {
         return z;
     };
 
-    // ---- the unit's last step: its MFMAs run row block by row block (all k-steps of the slot for block
-    // j), and block j - 1 is converted to fp16 and staged right behind them, so that the conversion's VALU
-    // work sits between this wavefront's MFMAs and under those of the other group instead of forming a
-    // phase of its own.  Operands come through a four-deep rotation (fx[0..3]); the per-row steps and
-    // the channels' steps / biases are fetched before the step's barrier (`prefetch`) and are waited for
-    // together with everything else there.
+    // ---- the unit's last step.  Operands come through a four-deep rotation (fx[0..3]); the per-row
+    // steps and the channels' steps / biases are fetched before the step's barrier (`prefetch`) and are
+    // waited for together with everything else there.
     struct LastStep {
         float rs[8];   // s_tok of rows 16 j + l16
         v4f csb[3];    // 8 channel steps, 8 fp16 biases
@@ -234,12 +228,11 @@ __global__ __launch_bounds__(512, 1) void linear_mfma_wreg(const LinearArgs p) {
         const uint32_t l16_now = ln & 15, lq_now = (ln >> 4) & 3;
         lds_issue_8x_b32<64>(lds_addr(rs_lds + rs_buf * kUnitRows) + l16_now * 4, ls.rs);
         lds_issue_3x_b128<16>(lds_addr(cs_lds) + (wave * 4 + lq_now) * 48, ls.csb);
-        ls.dst = lds_addr(stage) + l16_now * kStagePitch + gw * 64 + lq_now * 16;
+        ls.dst = lds_addr(stage) + l16_now * kStagePitch + wave * 64 + lq_now * 16;
 #pragma unroll
         for (int j = 0; j < LOOKAHEAD; j++)
 #pragma unroll
-            for (int k2 = 0; k2 < KPS; k2++)  // fx[j * KPS + k2] <- row block j, k-step k2
-                fx[j * KPS + k2] = *reinterpret_cast<const v4i *>(ring + slot * SLOT_BYTES + frag_off[k2] + j * 16 * SLAB);
+            for (int k2 = 0; k2 < KPS; k2++) fx[j * KPS + k2] = operand(j, slot, k2);
     };
     auto convert_block = [&](const LastStep &ls, int j, int64_t r0, int64_t o0) {
         if constexpr (PTQ4VM_WREG_SKIP & 2) {
@@ -255,8 +248,7 @@ __global__ __launch_bounds__(512, 1) void linear_mfma_wreg(const LinearArgs p) {
                 const int a0 = acc[i][j][2 * h], a1 = acc[i][j][2 * h + 1];
                 if constexpr (DUMP_ACC) {
                     const int64_t r = r0 + j * 16 + l16, o = o0 + wave * 32 + lq * 8 + e;
-                    if (r < p.M && o < p.N) p.acc_out[r * p.N + o] = a0;
-                    if (r < p.M && o + 1 < p.N) p.acc_out[r * p.N + o + 1] = a1;
+                    if (r < p.M) p.acc_out[r * p.N + o] = a0, p.acc_out[r * p.N + o + 1] = a1;
                 }
                 const float bias_word = HAS_BIAS ? ls.csb[2][e >> 1] : 0.0f;  // two fp16 biases
                 packed[2 * i + h] = dequantize_pair_f16((float)a0, ls.rs[j] * ls.csb[i][2 * h], (float)a1,
@@ -266,23 +258,19 @@ __global__ __launch_bounds__(512, 1) void linear_mfma_wreg(const LinearArgs p) {
         }
         lds_write_b128(ls.dst + j * 16 * kStagePitch, packed);
     };
-    // fx[(j % LOOKAHEAD) * KPS + k2] holds the operand of row block j, k-step k2 of the slot.
+    // fx[(j % LOOKAHEAD) * KPS + k2] holds the operand of row block j, k-step k2 of the slot.  Block j - 1
+    // is converted behind the MFMAs of block j: its own MFMAs have left the pipe by then.
     auto last_step_run = [&](const LastStep &ls, int slot, int64_t r0, int64_t o0) {
 #pragma unroll
         for (int j = 0; j < 8; j++) {
 #pragma unroll
             for (int k2 = 0; k2 < KPS; k2++) {
                 const int f = (j % LOOKAHEAD) * KPS + k2, ks = (kSteps - 1) * KPS + k2;
-                const Acc zero = {0, 0, 0, 0};
-                const bool fresh = KSTEPS == 1;  // never: a unit has at least 6 k-steps
                 if constexpr (!(PTQ4VM_WREG_SKIP & 32)) {
-                    acc[0][j] = Int8Path::mfma16(fw[0][ks], fx[f], fresh ? zero : acc[0][j]);
-                    acc[1][j] = Int8Path::mfma16(fw[1][ks], fx[f], fresh ? zero : acc[1][j]);
+                    acc[0][j] = Int8Path::mfma16(fw[0][ks], fx[f], acc[0][j]);
+                    acc[1][j] = Int8Path::mfma16(fw[1][ks], fx[f], acc[1][j]);
                 }
-                if (j + LOOKAHEAD < 8 && !(PTQ4VM_WREG_SKIP & 8)) {
-                    const int jn = j + LOOKAHEAD;
-                    fx[f] = *reinterpret_cast<const v4i *>(ring + slot * SLOT_BYTES + frag_off[k2] + jn * 16 * SLAB);
-                }
+                if (j + LOOKAHEAD < 8 && !(PTQ4VM_WREG_SKIP & 8)) fx[f] = operand(j + LOOKAHEAD, slot, k2);
             }
             if (j > 0) convert_block(ls, j - 1, r0, o0);
             __builtin_amdgcn_sched_barrier(0);
@@ -292,54 +280,81 @@ __global__ __launch_bounds__(512, 1) void linear_mfma_wreg(const LinearArgs p) {
 
     const uint32_t ldy_bytes = (uint32_t)p.ldy * 2;
 
-    if (group_a) {
-        // =========================================================== group A: copies + MFMA
-        UnitCursor pc = wr.start;  // producer: the unit whose slots are being copied
-        int pf_step = 0, pf_in_unit = 0, pf_slot = 0, pf_unit = 0;
-        const char *pf_x = nullptr;
-        int64_t pf_r0 = 0;
-        int pf_rows_valid = 0;
-        auto pf_setup = [&]() {
-            pf_r0 = unit_row0(pc);
-            pf_x = p.x + pf_r0 * p.ldx_bytes;
-            pf_rows_valid = (int)min((int64_t)kUnitRows, p.M - pf_r0);
-        };
-        auto issue = [&]() {  // copy slot `pf_step` of the unit list, then advance
-            const uint32_t ln = (threadIdx.x + opaque_zero()) & 63;
-            if (pf_in_unit == 0 && gw < 2) {  // the unit's per-row steps s_tok[r mod L], 64 rows per wavefront
-                const int r = min((int)(gw * 64 + ln), pf_rows_valid - 1);
-                const uint32_t t = ((uint32_t)(pf_r0 % p.L) + (uint32_t)r) % (uint32_t)p.L;
-                __builtin_amdgcn_global_load_lds(
-                    (const __attribute__((address_space(1))) void *)(p.s_tok + t),
-                    (__attribute__((address_space(3))) void *)(rs_lds + (pf_unit & (kRowScaleBufs - 1)) * kUnitRows + gw * 64), 4, 0, 0);
-            }
-            const char *gx = pf_x + (int64_t)pf_in_unit * SLAB;
-            char *dst = ring + pf_slot * SLOT_BYTES;
+    // ---- copies (wavefronts 0-3): slot `pf_step` of the unit list goes to ring place pf_step mod 5
+    UnitCursor pc = wr.start;
+    int pf_step = 0, pf_in_unit = 0, pf_slot = 0, pf_unit = 0;
+    const char *pf_x = nullptr;
+    int64_t pf_r0 = 0;
+    int pf_rows_valid = 0;
+    auto pf_setup = [&]() {
+        pf_r0 = unit_row0(pc);
+        pf_x = p.x + pf_r0 * p.ldx_bytes;
+        pf_rows_valid = (int)min((int64_t)kUnitRows, p.M - pf_r0);
+    };
+    auto issue = [&]() {
+        const uint32_t ln = (threadIdx.x + opaque_zero()) & 63;
+        if (pf_in_unit == 0 && gw < 2) {  // the unit's per-row steps s_tok[r mod L], 64 rows per wavefront
+            const int r = min((int)(gw * 64 + ln), pf_rows_valid - 1);
+            const uint32_t t = ((uint32_t)(pf_r0 % p.L) + (uint32_t)r) % (uint32_t)p.L;
+            __builtin_amdgcn_global_load_lds(
+                (const __attribute__((address_space(1))) void *)(p.s_tok + t),
+                (__attribute__((address_space(3))) void *)(rs_lds + (pf_unit & (kRowScaleBufs - 1)) * kUnitRows + gw * 64), 4, 0, 0);
+        }
+        const char *gx = pf_x + (int64_t)pf_in_unit * SLAB;
+        char *dst = ring + pf_slot * SLOT_BYTES;
 #pragma unroll
-            for (int c = 0; c < ((PTQ4VM_WREG_SKIP & 4) ? 0 : COPIES); c++) {
-                const int row = (gw + 4 * c) * ROWS_PER_COPY + (int)(ln / CHUNKS);
-                const int chunk = (int)(ln % CHUNKS) ^ (SLAB == 64 ? swizzle(row) : (row & 7));
-                const uint32_t off = (uint32_t)min(row, pf_rows_valid - 1) * (uint32_t)p.ldx_bytes + chunk * 16;  // clamped rows are never stored
-                __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void *)(gx + off),
-                                                 (__attribute__((address_space(3))) void *)(dst + (gw + 4 * c) * 1024), 16, 0, 0);
-            }
-            pf_step++;
-            if (++pf_slot == kSlots) pf_slot = 0;
-            if (++pf_in_unit == kSteps) {
-                pf_in_unit = 0;
-                pf_unit++;
-                advance(pc, wr);
-                if (pf_step < total_steps) pf_setup();
-            }
-        };
+        for (int c = 0; c < ((PTQ4VM_WREG_SKIP & 4) ? 0 : COPIES); c++) {
+            const int row = (gw + 4 * c) * ROWS_PER_COPY + (int)(ln / CHUNKS);
+            const int chunk = (int)(ln % CHUNKS) ^ (SLAB == 64 ? swizzle(row) : (row & 7));
+            // rows beyond M are clamped to row M - 1: their results are copies of that row's (see `drain`)
+            const uint32_t off = (uint32_t)min(row, pf_rows_valid - 1) * (uint32_t)p.ldx_bytes + chunk * 16;
+            __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void *)(gx + off),
+                                             (__attribute__((address_space(3))) void *)(dst + (gw + 4 * c) * 1024), 16, 0, 0);
+        }
+        pf_step++;
+        if (++pf_slot == kSlots) pf_slot = 0;
+        if (++pf_in_unit == kSteps) {
+            pf_in_unit = 0;
+            pf_unit++;
+            advance(pc, wr);
+            if (pf_step < total_steps) pf_setup();
+        }
+    };
 
+    // ---- output stores (wavefronts 4-7): a quarter of this wavefront's 32 staged rows, two stores of
+    // 2 rows x 512 bytes.  No masks and no branches: any control flow inside the unrolled steps, even
+    // uniform, costs this kernel registers it does not have.  N is a multiple of 256, so a unit has all
+    // of its channels.  Rows beyond M hold copies of row M - 1's results (their codes and steps were
+    // clamped to that row when they were copied), so they are written onto row M - 1 again: same bytes,
+    // same address.
+    auto drain = [&](int part, int64_t r0, int64_t o0) {
+        const uint32_t ln = (threadIdx.x + opaque_zero()) & 63;
+        const int row0 = gw * 32 + part * 8 + (int)(ln >> 5), chunk = (int)(ln & 31);
+        const int rows_valid = (int)min((int64_t)kUnitRows, p.M - r0);
+        char *dst = reinterpret_cast<char *>(p.y + r0 * p.ldy + o0) + chunk * 16;
+        const uint32_t src = lds_addr(stage) + row0 * kStagePitch + chunk * 16;
+#pragma unroll
+        for (int q = 0; q < 4; q++) {
+            v4f data;
+            lds_read_1x_b128(src + q * 2 * kStagePitch, data);
+            const int row = min(row0 + q * 2, rows_valid - 1);
+            if (!(PTQ4VM_WREG_SKIP & 1))
+                __builtin_nontemporal_store(data, reinterpret_cast<v4f *>(dst + (uint32_t)row * ldy_bytes));
+        }
+    };
+
+    // One source for both roles; COPIER is a compile-time flag so that neither role's code has branches
+    // on the other's duties.
+    auto run = [&](auto copier_tag) {
+        constexpr bool COPIER = decltype(copier_tag)::value;
         UnitCursor cc = wr.start;
-        pf_setup();
+        if constexpr (COPIER) {
+            pf_setup();
 #pragma unroll
-        for (int t = 0; t < kSlots - kDelay - 1; t++)  // slots 0..2 (every unit list has at least 6)
-            issue();
-
+            for (int t = 0; t < kAhead; t++) issue();  // slots 0..3 (every unit list has at least 6)
+        }
         int g = 0, slot = 0, u = 0;
+        int64_t prev_r0 = 0, prev_o0 = 0;
         bool first_run = true;
 #pragma unroll 1
         while (u < wr.count) {
@@ -347,7 +362,7 @@ __global__ __launch_bounds__(512, 1) void linear_mfma_wreg(const LinearArgs p) {
             const int strip = cc.strip;
             load_strip(strip);
             wait_vmcnt_at_most<0>();  // also lands every copy in flight; happens once or twice per launch
-            if (first_run) __builtin_amdgcn_s_barrier();  // P: slot 0 is visible to everyone
+            if (first_run) __builtin_amdgcn_s_barrier();  // slot 0 is visible to everyone
             first_run = false;
             WREG_TRACE();
             const int64_t o0 = (int64_t)strip * kStripCols;
@@ -355,7 +370,7 @@ __global__ __launch_bounds__(512, 1) void linear_mfma_wreg(const LinearArgs p) {
             do {
                 const int64_t r0 = unit_row0(cc);
 #pragma unroll
-                for (int j = 0; j < 8; j++) load_fx(j, slot, 0);  // the unit's first operands (its slot has landed)
+                for (int j = 0; j < 8; j++) fx[j] = operand(j, slot, 0);  // the unit's first operands (its slot has landed)
 #pragma unroll
                 for (int s = 0; s < kSteps; s++, g++) {
                     int next_slot = slot + 1;
@@ -368,99 +383,26 @@ __global__ __launch_bounds__(512, 1) void linear_mfma_wreg(const LinearArgs p) {
                         last_step_prefetch(ls, slot, u & (kRowScaleBufs - 1));
                         lds_wait_all(ls.rs, ls.csb);
                     }
-                    if (g + 1 < total_steps) {  // slot g + 1 has landed for this wavefront
-                        if (g + 2 < total_steps && !DUMP_ACC)
-                            wait_vmcnt_at_most<COPIES>();  // only slot g + 2 may still be in flight
-                        else
-                            wait_vmcnt_at_most<0>();
+                    if constexpr (COPIER) {
+                        if (g + 1 < total_steps) {  // slot g + 1 has landed for this wavefront
+                            if (g + kAhead - 1 < total_steps && !DUMP_ACC)
+                                wait_vmcnt_at_most<(kAhead - 2) * COPIES>();  // slots g + 2, g + 3 may still be in flight
+                            else
+                                wait_vmcnt_at_most<0>();
+                        }
                     }
                     if constexpr (!(PTQ4VM_WREG_SKIP & 16)) __builtin_amdgcn_s_barrier();
                     WREG_TRACE();
-                    if (pf_step < total_steps) issue();  // slot g + 3 into the ring slot of g - 4
+                    if constexpr (COPIER) {
+                        if (pf_step < total_steps) issue();  // slot g + 4 into the ring place of slot g - 1
+                    }
                     if (s < kSteps - 1)
                         k_step(fw[0][KPS * s + KPS - 1], fw[1][KPS * s + KPS - 1], KPS == 1 && s == 0, s + 2 < kSteps, next_slot, 0);
                     else
                         last_step_run(ls, slot, r0, o0);
-                    slot = next_slot;
-                }
-                WREG_TRACE();
-                advance(cc, wr);
-                u++;
-            } while (u < wr.count && cc.strip == strip);
-        }
-        asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");  // the staged results are in LDS before the next barrier
-#pragma unroll 1
-        for (int t = 0; t < kDelay + 1; t++) __builtin_amdgcn_s_barrier();
-    } else {
-        // =========================================================== group B: MFMA + output stores
-        UnitCursor cc = wr.start;
-
-        // Half a unit (128 rows x 128 channels) leaves the staging buffer in two parts of 64 rows; a
-        // wavefront writes 16 rows of a part: four stores of 4 rows x 256 bytes, two at a time.
-        auto drain = [&](int part, int64_t r0, int64_t o_first) {
-            const uint32_t ln = (threadIdx.x + opaque_zero()) & 63;
-            const int row0 = part * 64 + gw * 16 + (int)(ln >> 4), chunk = (int)(ln & 15);
-            const int rows_valid = (int)min((int64_t)kUnitRows, p.M - r0);
-            char *dst = reinterpret_cast<char *>(p.y + r0 * p.ldy + o_first) + chunk * 16;
-            const uint32_t src = lds_addr(stage) + row0 * kStagePitch + chunk * 16;
-            // No masks and no branches: any control flow inside the unrolled steps, even uniform, costs
-            // this kernel registers it does not have.  N is a multiple of 256, so every half unit has all
-            // of its channels.  Rows beyond M hold copies of row M - 1's results (their codes and steps
-            // were clamped to that row when they were copied), so they are written onto row M - 1 again:
-            // same bytes, same address.
-#pragma unroll
-            for (int q = 0; q < 4; q++) {
-                v4f data;
-                lds_read_1x_b128(src + q * 4 * kStagePitch, data);
-                const int row = min(row0 + q * 4, rows_valid - 1);
-                if (!(PTQ4VM_WREG_SKIP & 1))
-                    __builtin_nontemporal_store(data, reinterpret_cast<v4f *>(dst + (uint32_t)row * ldy_bytes));
-            }
-        };
-
-        int slot = 0, u = 0;
-        int64_t prev_r0 = 0, prev_o0 = 0;
-        bool first_run = true;
-#pragma unroll 1
-        while (u < wr.count) {
-            const int strip = cc.strip;
-            load_strip(strip);
-            wait_vmcnt_at_most<0>();
-            if (first_run) {
-                __builtin_amdgcn_s_barrier();  // P
-                WREG_TRACE();
-#pragma unroll 1
-                for (int t = 0; t < kDelay; t++) __builtin_amdgcn_s_barrier();  // group A's first three steps
-            }
-            first_run = false;
-            const int64_t o0 = (int64_t)strip * kStripCols;
-#pragma unroll 1
-            do {
-                const int64_t r0 = unit_row0(cc);
-#pragma unroll
-                for (int j = 0; j < 8; j++) load_fx(j, slot, 0);
-#pragma unroll
-                for (int s = 0; s < kSteps; s++) {
-                    int next_slot = slot + 1;
-                    if (next_slot == kSlots) next_slot = 0;
-                    LastStep ls;
-                    if (s < kSteps - 1) {
-                        if constexpr (KPS == 2) k_step(fw[0][2 * s], fw[1][2 * s], s == 0, true, slot, 1);
-                        asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
-                    } else {
-                        last_step_prefetch(ls, slot, u & (kRowScaleBufs - 1));
-                        lds_wait_all(ls.rs, ls.csb);
+                    if constexpr (!COPIER) {  // the previous unit's staged tile, a quarter per step
+                        if (s < 4 && u > 0) drain(s, prev_r0, prev_o0);
                     }
-                    if constexpr (!(PTQ4VM_WREG_SKIP & 16)) __builtin_amdgcn_s_barrier();
-                    WREG_TRACE();
-                    if (s < kSteps - 1)
-                        k_step(fw[0][KPS * s + KPS - 1], fw[1][KPS * s + KPS - 1], KPS == 1 && s == 0, s + 2 < kSteps, next_slot, 0);
-                    else
-                        last_step_run(ls, slot, r0, o0);
-                    // group B's half of the previous unit was staged in that unit's last step; group A's half
-                    // of this unit was staged while this group ran step 2
-                    if ((s == 0 || s == 1) && u > 0) drain(s, prev_r0, prev_o0 + 128);
-                    if (s == 3 || s == 4) drain(s - 3, r0, o0);
                     slot = next_slot;
                 }
                 WREG_TRACE();
@@ -469,11 +411,17 @@ __global__ __launch_bounds__(512, 1) void linear_mfma_wreg(const LinearArgs p) {
                 u++;
             } while (u < wr.count && cc.strip == strip);
         }
-        asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
+        asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");  // the last unit's staged results are in LDS before the barrier
         __builtin_amdgcn_s_barrier();
-        drain(0, prev_r0, prev_o0 + 128);
-        drain(1, prev_r0, prev_o0 + 128);
-    }
+        if constexpr (!COPIER) {
+#pragma unroll 1
+            for (int part = 0; part < 4; part++) drain(part, prev_r0, prev_o0);
+        }
+    };
+    if (wave < 4)
+        run(std::true_type{});
+    else
+        run(std::false_type{});
 }
 
 }  // namespace
