@@ -37,6 +37,7 @@
 #include <type_traits>
 
 #include "mfma_linear.hpp"
+#include "unit_order.hpp"
 
 // Timing experiments only (results are wrong when any bit is set): 1 no output stores, 2 no conversion,
 // 4 no global -> LDS copies, 8 no operand refetch from LDS, 16 no step barriers, 32 no MFMAs.
@@ -77,48 +78,6 @@ constexpr int kAhead = kSlots - 1;  // slots copied ahead of the one being consu
 constexpr int kStagePitch = 528;  // bytes per staged row: 256 channels of fp16 + 16 (bank spread)
 constexpr int kStageBytes = kUnitRows * kStagePitch;
 constexpr int kRowScaleBufs = 4;  // per-row step vectors of the units in flight
-
-// Position in the workgroup's list of units.  An XCD owns a contiguous range of row tiles and all
-// strips; its units are ordered band by band (a band = `band_h` consecutive row tiles), inside a
-// band strip by strip, inside a strip by row tile.  Consecutive workgroups of an XCD take
-// consecutive runs of `band_h` units: in a full band that is one strip of the band each, so the
-// workgroups of a band read the same row tiles at about the same time and share them through L2.
-struct UnitCursor {
-    int band, strip, row, band_rows;
-};
-
-struct WorkRange {
-    int t_lo, tiles_x, band_h, strips, count;
-    UnitCursor start;
-};
-
-__device__ __forceinline__ WorkRange work_range(const LinearArgs &p) {
-    WorkRange w;
-    const int xcd = (int)(blockIdx.x % kXcds), ci = (int)(blockIdx.x / kXcds), per_xcd = (int)(gridDim.x / kXcds);
-    w.strips = p.tiles_o;
-    w.t_lo = (int)((int64_t)xcd * p.tiles_r / kXcds);
-    w.tiles_x = (int)((int64_t)(xcd + 1) * p.tiles_r / kXcds) - w.t_lo;
-    const int units = w.strips * w.tiles_x;
-    w.band_h = max(1, (units + per_xcd - 1) / per_xcd);
-    const int first = ci * w.band_h;
-    w.count = max(0, min(w.band_h, units - first));
-    const int per_band = w.strips * w.band_h;
-    w.start.band = first / per_band;
-    const int rem = first - w.start.band * per_band;
-    w.start.band_rows = max(1, min(w.band_h, w.tiles_x - w.start.band * w.band_h));
-    w.start.strip = rem / w.start.band_rows;
-    w.start.row = rem - w.start.strip * w.start.band_rows;
-    return w;
-}
-
-__device__ __forceinline__ void advance(UnitCursor &c, const WorkRange &w) {
-    if (++c.row < c.band_rows) return;
-    c.row = 0;
-    if (++c.strip < w.strips) return;
-    c.strip = 0;
-    c.band++;
-    c.band_rows = max(1, min(w.band_h, w.tiles_x - c.band * w.band_h));
-}
 
 template <int KSTEPS, bool HAS_BIAS, bool DUMP_ACC>
 __global__ __launch_bounds__(512, 1) void linear_mfma_wreg(const LinearArgs p) {
