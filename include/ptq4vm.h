@@ -220,6 +220,26 @@ int ptq4vm_validate_scales(const float *s_tok, int64_t L, const float *m, int64_
                            int32_t *bad_counts, void *workspace, int64_t workspace_bytes, void *stream);
 
 /*
+ * ptq4vm_validate_scales for callers that can neither allocate device memory nor synchronise: code
+ * under HIP graph capture, tight serving loops, harnesses that forbid hipMalloc.  Same vectors and
+ * the same bad_counts [3] (device) as above, but
+ *   - the per-workgroup partial counts live in a device array of the library itself
+ *     (16 * (PTQ4VM_VALIDATE_STATIC_MAX_ELEMS / PTQ4VM_VALIDATE_BLOCK + 1) = 65552 bytes, which
+ *     every GPU the library runs on holds until the process ends), so L + K + N may not exceed
+ *     PTQ4VM_VALIDATE_STATIC_MAX_ELEMS (else PTQ4VM_ERR_SHAPE, nothing is launched);
+ *   - the call only enqueues its two kernels on `stream` and returns PTQ4VM_OK: the counts are in
+ *     bad_counts once the stream has reached that point, and PTQ4VM_ERR_VALUE is never returned.
+ * No hipMalloc / hipFree, no copy, no synchronisation; nothing in the array has to be zero (every
+ * slot that is read was written by the same call).  All calls on one GPU share that GPU's array:
+ * calls that may overlap (different streams, several threads) race; order them on one stream.
+ * The first call on a device looks the array's address up (hipGetSymbolAddress).
+ * Errors: as ptq4vm_validate_scales without the workspace ones; PTQ4VM_ERR_HIP if the lookup fails.
+ */
+#define PTQ4VM_VALIDATE_STATIC_MAX_ELEMS ((int64_t)1 << 24)
+int ptq4vm_validate_scales_static(const float *s_tok, int64_t L, const float *m, int64_t K, const float *s_w,
+                                  int64_t N, int32_t *bad_counts, void *stream);
+
+/*
  * Unquantized comparison linear (the "FP16" column of the paper's latency table, Sec. 6.4):
  *   y[r,o] = fp16( sum_k x[r,k] * w[o,k]  (fp32 accumulation)  + bias[o] )
  *   x_f16 [M, ldx], w_f16 [N, ldw], bias_f16 [N] or NULL, y_f16 [M, ldy]

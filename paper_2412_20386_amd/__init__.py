@@ -18,4 +18,5 @@ from .binding import (  # noqa: F401
     w8a8_linear,
     w8a8_linear_fused,
     validate_scales,
+    validate_scales_static,
 )

@@ -30,6 +30,7 @@ EXPORTS = (
     "ptq4vm_w8a8_linear_fused",
     "ptq4vm_f16_linear",
     "ptq4vm_validate_scales",
+    "ptq4vm_validate_scales_static",
     "ptq4vm_status_string",
     "ptq4vm_last_hip_error",
     "ptq4vm_version",
@@ -82,6 +83,8 @@ def load() -> ctypes.CDLL:
     lib.ptq4vm_f16_linear.argtypes = [vp, vp, vp, vp, i64, i64, i64, i64, i64, i64, vp]
     lib.ptq4vm_validate_scales.restype = ci
     lib.ptq4vm_validate_scales.argtypes = [vp, i64, vp, i64, vp, i64, vp, vp, i64, vp]
+    lib.ptq4vm_validate_scales_static.restype = ci
+    lib.ptq4vm_validate_scales_static.argtypes = [vp, i64, vp, i64, vp, i64, vp, vp]
     lib.ptq4vm_status_string.restype = ctypes.c_char_p
     lib.ptq4vm_status_string.argtypes = [ci]
     lib.ptq4vm_last_hip_error.restype = ctypes.c_char_p
@@ -362,3 +365,17 @@ def validate_scales(s_tok: Optional[torch.Tensor], m: Optional[torch.Tensor], s_
     if rc not in (0, -6):
         check(rc)
     return rc, counts
+
+
+def validate_scales_static(s_tok: Optional[torch.Tensor], m: Optional[torch.Tensor], s_w: Optional[torch.Tensor],
+                           counts: torch.Tensor) -> None:
+    """ptq4vm_validate_scales_static: enqueue only; `counts` (int32 [3], device, the caller's) holds the bad-entry
+    counts once the current stream has run the two kernels.  Allocates nothing and does not synchronise."""
+    sizes = []
+    for v, name in ((s_tok, "s_tok"), (m, "m"), (s_w, "s_w")):
+        if v is not None:
+            _vector(v, torch.float32, v.shape[0], name)
+        sizes.append(0 if v is None else v.shape[0])
+    _vector(counts, torch.int32, 3, "counts")
+    check(load().ptq4vm_validate_scales_static(_ptr(s_tok), sizes[0], _ptr(m), sizes[1], _ptr(s_w), sizes[2],
+                                               _ptr(counts), _stream()))

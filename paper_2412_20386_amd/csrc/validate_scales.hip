@@ -8,6 +8,8 @@
 // entries of the concatenated index space [s_tok | m | s_w] and writes that block's three counts to
 // partial[block]; `sum_bad_scales` (one workgroup) adds the partial counts up.  No atomics, and
 // nothing has to be zeroed beforehand: every partial slot that is read was written by this call.
+#include <mutex>
+
 #include "common.hpp"
 
 namespace {
@@ -79,7 +81,7 @@ __global__ __launch_bounds__(kThreads) void sum_bad_scales(const Counts *__restr
 
 namespace ptq4vm {
 
-// Host half shared with the variant that keeps `partial` in the library's own static device array.
+// Host half shared by both entry points.
 int validate_scales_args(const float *s_tok, int64_t L, const float *m, int64_t K, const float *s_w, int64_t N,
                          const int32_t *bad_counts, int64_t *blocks) {
     if (!bad_counts) return PTQ4VM_ERR_NULL;
@@ -94,17 +96,24 @@ int validate_scales_args(const float *s_tok, int64_t L, const float *m, int64_t 
     return PTQ4VM_OK;
 }
 
-// Launches both kernels with `partial` (device, blocks slots of 16 bytes), copies the three counts
-// to the host, waits for the stream and turns a non-zero count into PTQ4VM_ERR_VALUE.
-int validate_scales_run(const float *s_tok, int64_t L, const float *m, int64_t K, const float *s_w, int64_t N,
-                        int32_t *bad_counts, void *partial, int64_t blocks, hipStream_t stream) {
+// Enqueues both kernels with `partial` (device, blocks slots of 16 bytes): afterwards, in stream order,
+// bad_counts holds the three counts.
+int validate_scales_enqueue(const float *s_tok, int64_t L, const float *m, int64_t K, const float *s_w, int64_t N,
+                            int32_t *bad_counts, void *partial, int64_t blocks, hipStream_t stream) {
     if (blocks == 0) blocks = 1;  // all three vectors empty: one workgroup writes three zeros
     count_bad_scales<<<dim3((unsigned)blocks), dim3(kThreads), 0, stream>>>(s_tok, L, m, K, s_w, N,
                                                                           static_cast<Counts *>(partial));
-    int rc = check_launch("count_bad_scales");
+    const int rc = check_launch("count_bad_scales");
     if (rc != PTQ4VM_OK) return rc;
     sum_bad_scales<<<dim3(1), dim3(kThreads), 0, stream>>>(static_cast<const Counts *>(partial), blocks, bad_counts);
-    rc = check_launch("sum_bad_scales");
+    return check_launch("sum_bad_scales");
+}
+
+// Enqueues the kernels, copies the three counts to the host, waits for the stream and turns a non-zero
+// count into PTQ4VM_ERR_VALUE.
+int validate_scales_run(const float *s_tok, int64_t L, const float *m, int64_t K, const float *s_w, int64_t N,
+                        int32_t *bad_counts, void *partial, int64_t blocks, hipStream_t stream) {
+    const int rc = validate_scales_enqueue(s_tok, L, m, K, s_w, N, bad_counts, partial, blocks, stream);
     if (rc != PTQ4VM_OK) return rc;
     int32_t host_counts[3] = {0, 0, 0};
     hipError_t err = hipMemcpyAsync(host_counts, bad_counts, sizeof(host_counts), hipMemcpyDeviceToHost, stream);
@@ -127,4 +136,50 @@ extern "C" int ptq4vm_validate_scales(const float *s_tok, int64_t L, const float
     if (!ptq4vm::aligned_to(workspace, 16)) return PTQ4VM_ERR_ALIGN;
     return ptq4vm::validate_scales_run(s_tok, L, m, K, s_w, N, bad_counts, workspace, blocks,
                                        static_cast<hipStream_t>(stream_));
+}
+
+// ---- the variant that allocates nothing: the partial counts live in a device array of the library itself
+
+namespace {
+
+constexpr int64_t kStaticSlots = PTQ4VM_VALIDATE_STATIC_MAX_ELEMS / PTQ4VM_VALIDATE_BLOCK + 1;
+static __device__ __align__(256) unsigned char scratch[16 * kStaticSlots];
+
+// In host code `scratch` is only a handle for the symbol: each GPU holds its own copy of the array at its own
+// address, asked for once per device (with that device current) and kept.
+constexpr int kMaxDevices = 64;
+std::mutex g_scratch_mutex;
+void *g_scratch_of_device[kMaxDevices] = {};
+
+int scratch_of_current_device(void **out) {
+    int device = -1;
+    hipError_t err = hipGetDevice(&device);
+    if (err != hipSuccess) return ptq4vm::record_hip_error(err, "hipGetDevice");
+    if (device < 0 || device >= kMaxDevices)
+        return ptq4vm::record_hip_error(hipErrorInvalidDevice, "validate_scales_static: device ordinal beyond the table");
+    std::lock_guard<std::mutex> lock(g_scratch_mutex);
+    if (!g_scratch_of_device[device]) {
+        void *ptr = nullptr;
+        err = hipGetSymbolAddress(&ptr, HIP_SYMBOL(scratch));
+        if (err != hipSuccess || !ptr)
+            return ptq4vm::record_hip_error(err == hipSuccess ? hipErrorInvalidSymbol : err, "hipGetSymbolAddress(scratch)");
+        g_scratch_of_device[device] = ptr;
+    }
+    *out = g_scratch_of_device[device];
+    return PTQ4VM_OK;
+}
+
+}  // namespace
+
+extern "C" int ptq4vm_validate_scales_static(const float *s_tok, int64_t L, const float *m, int64_t K, const float *s_w,
+                                             int64_t N, int32_t *bad_counts, void *stream_) {
+    int64_t blocks = 0;
+    int rc = ptq4vm::validate_scales_args(s_tok, L, m, K, s_w, N, bad_counts, &blocks);
+    if (rc != PTQ4VM_OK) return rc;
+    if (L + K + N > PTQ4VM_VALIDATE_STATIC_MAX_ELEMS) return PTQ4VM_ERR_SHAPE;  // more partial counts than the array holds
+    void *partial = nullptr;
+    rc = scratch_of_current_device(&partial);
+    if (rc != PTQ4VM_OK) return rc;
+    return ptq4vm::validate_scales_enqueue(s_tok, L, m, K, s_w, N, bad_counts, partial, blocks,
+                                           static_cast<hipStream_t>(stream_));
 }

@@ -199,6 +199,20 @@ def test_validate_scales_argument_checks(lib):
     assert f(P, 4, P, 4, P, 4, P, ctypes.c_void_p(0x1008), 64, None) == -4
 
 
+def test_validate_scales_static_argument_checks(lib):
+    """The variant without a workspace: every rejection happens before the device is touched."""
+    f = lib.ptq4vm_validate_scales_static
+    f.restype = ctypes.c_int
+    f.argtypes = [ctypes.c_void_p, ctypes.c_int64] * 3 + [ctypes.c_void_p, ctypes.c_void_p]
+    #  s_tok L m K s_w N counts stream
+    assert f(P, 4, P, 4, P, 4, NULL, None) == -1
+    assert f(NULL, 4, P, 4, P, 4, P, None) == -1
+    assert f(P, -1, P, 4, P, 4, P, None) == -2
+    assert f(ODD, 4, P, 4, P, 4, P, None) == -4
+    assert f(P, (1 << 24) - 7, P, 4, P, 4, P, None) == -2             # one entry more than the static array covers
+    assert f(P, 1 << 31, P, 4, P, 4, P, None) == -2
+
+
 def test_fold_and_f16_argument_checks(lib):
     f = lib.ptq4vm_fold_smoothing
     assert f(NULL, P, P, P, P, 1, 8, 8, 8, None) == -1
