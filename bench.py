@@ -14,6 +14,10 @@ INT8 weights) and is not timed.  All inputs are resident in HBM before the
 timed region; every layer has its own buffers (~1.1 GB per layer), so the working set of a step
 (~27 GB) cannot sit in the 256 MB last-level cache.
 
+After the timed configuration the other four configurations of the benchmark spec are timed the same
+way (they take 0.04-4 ms per step) and reported under "configs"; for the two launch-bound ones
+(configs 0 and 1) the headline of their record is the step replayed as one HIP graph.
+
 Prints ONE JSON line (see README for the fields).
 """
 from __future__ import annotations
@@ -21,6 +25,7 @@ from __future__ import annotations
 import argparse
 import json
 import os
+import statistics
 import sys
 import time
 
@@ -32,43 +37,33 @@ PEAK_INT8_TOPS = 5000.0   # MI355X dense int8 MFMA, TOP/s
 PEAK_F16_TFLOPS = 2500.0  # dense fp16 MFMA
 PEAK_HBM_GBS = 8000.0     # HBM3E
 
-# HBM traffic of the dominant kernel (in_proj GEMM of configs[3]) per launch, bytes, from two
-# rocprofv3 --pmc runs (FETCH_SIZE, WRITE_SIZE), each scaled by the 256 MiB copy this script also
-# issues: 109.1 MB fetched + 309.9 MB written (profiles/bench_vim_b_stack_kernel_trace_and_traffic.txt).
-DOMINANT_TRAFFIC_BYTES = {3: 421.1e6}
+# HBM traffic of the dominant kernel per launch: written by `python -m paper_2412_20386_amd.profile_summary`
+# from two rocprofv3 --pmc runs of this script (FETCH_SIZE, WRITE_SIZE, each scaled by the 256 MiB copy that
+# this script also issues).  Absent or for another workload: "traffic" is null.
+TRAFFIC_FILE = os.path.join(ROOT, "profiles", "dominant_kernel_traffic.json")
+GRAPH_HEADLINE_CONFIGS = (0, 1)  # launch-bound: a step is tens of microseconds of kernels
 
 
-def main() -> int:
-    ap = argparse.ArgumentParser()
-    ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=20)
-    ap.add_argument("--warmup", type=int, default=5)
-    ap.add_argument("--config", type=int, default=3, help="workload config (BASELINE.json configs index)")
-    ap.add_argument("--layers", type=int, default=None, help="override the number of layers (debug only)")
-    ap.add_argument("--fused", choices=("auto", "off"), default="auto",
-                    help="auto: one fused quantize+linear launch for linears with K <= 128 or N <= 128 when there are enough rows")
-    ap.add_argument("--no-cpu-baseline", action="store_true")
-    ap.add_argument("--no-graph", action="store_true", help="skip the extra timing of the step replayed as one HIP graph")
-    ap.add_argument("--cpu-sample-batch", type=int, default=256)
-    args = ap.parse_args()
-    if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
-        print("bench.py: this build runs on one GPU only (the path shards data-parallel over the batch "
-              "with no collectives, see DESIGN.md); run with --gpus 1", file=sys.stderr)
-        return 2
+def dominant_traffic(config: int):
+    try:
+        with open(TRAFFIC_FILE) as f:
+            rec = json.load(f)
+        return float(rec["traffic_bytes"]) if int(rec["config"]) == config else None
+    except (OSError, ValueError, KeyError):
+        return None
 
+
+def measure_config(args, config: int, full: bool):
+    """Builds the buffers of one configuration, times its step and its kernels, frees the buffers.
+    full: also the comparison schemes (fp16, per-token dynamic, zero offset, W4A4) and the CPU oracle."""
     import torch
 
     import paper_2412_20386_amd as ptq
     from paper_2412_20386_amd import synth
 
-    if not torch.cuda.is_available():
-        print("bench.py: no GPU visible", file=sys.stderr)
-        return 2
-    ptq.binding.load()  # fail loudly if the HIP library is missing
     dev = "cuda:0"
-    torch.cuda.set_device(0)
-    cfg = synth.CONFIGS[args.config]
-    n_layers = args.layers or cfg.layers
+    cfg = synth.CONFIGS[config]
+    n_layers = (args.layers if full and args.layers else None) or cfg.layers
     B, L, M = cfg.B, cfg.L, cfg.M
 
     # ------------------------------------------------------------------ setup (untimed)
@@ -77,7 +72,7 @@ def main() -> int:
     for layer in range(n_layers):
         lin = []
         for li, (name, K, N) in enumerate(cfg.linears):
-            c = synth.make_linear_case(args.config, layer, li, device=dev)
+            c = synth.make_linear_case(config, layer, li, device=dev)
             wq, s_w, inv_m = ptq.fold_smoothing(c.w, c.m)  # offline weight preparation
             # One fused launch where it beats quantize + linear (measured crossovers: narrow outputs from ~16 k
             # rows, short reductions from ~24 k rows; below that the two small kernels are faster).
@@ -126,14 +121,18 @@ def main() -> int:
         step_w8a8()
     torch.cuda.synchronize()
     events = dict(name=dominant[0], pairs=[])
+    marks = [torch.cuda.Event(enable_timing=True) for _ in range(args.steps + 1)]  # step boundaries, for the median
     t0 = time.perf_counter()
-    for _ in range(args.steps):
+    marks[0].record()
+    for s in range(args.steps):
         step_w8a8(events)
+        marks[s + 1].record()
     torch.cuda.synchronize()
     elapsed = time.perf_counter() - t0
     ms_per_step = elapsed / args.steps * 1e3
+    step_ms = sorted(marks[s].elapsed_time(marks[s + 1]) for s in range(args.steps))
     dom_all = sorted(a.elapsed_time(b) * 1e3 for a, b in events["pairs"])
-    dom_us = sum(dom_all) / len(dom_all)
+    dom_us = sum(dom_all) / len(dom_all) if dom_all else None
 
     # ------------------------------------------------------------------ the same step as one HIP graph (extra)
     graph_ms_per_step = None
@@ -162,80 +161,89 @@ def main() -> int:
         """Average device time of fn: one HIP-event pair (on the launch stream) around a back-to-back
         sweep over all layers' distinct buffers, so that launch latency is hidden as in the stack."""
         fn(layers[0])
+        sweeps = max(1, 24 // len(layers))  # short stacks (config 0 has one layer): repeat the sweep
         tot = 0.0
         for _ in range(reps):
             a = torch.cuda.Event(enable_timing=True)
             b = torch.cuda.Event(enable_timing=True)
             a.record()
-            for lin in layers:
-                fn(lin)
+            for _ in range(sweeps):
+                for lin in layers:
+                    fn(lin)
             b.record()
             b.synchronize()
             tot += a.elapsed_time(b)
-        return tot / (reps * len(layers)) * 1e3  # us
+        return tot / (reps * sweeps * len(layers)) * 1e3  # us
 
     kernels = []
-    f16_total_us = w8_total_us = q_total_us = 0.0
     for li, (name, K, N) in enumerate(cfg.linears):
         tq = time_launch(lambda lin: ptq.quantize_pts(lin[li]["x"], lin[li]["inv_m"], lin[li]["s_tok"], B, L,
                                                      xq=lin[li]["xq"]))
         tg = time_launch(lambda lin: ptq.w8a8_linear(lin[li]["xq"], lin[li]["wq"], lin[li]["s_tok"], lin[li]["s_w"],
                                                     lin[li]["bias"], B, L, y=lin[li]["y"]))
         tf = time_launch(lambda lin: ptq.f16_linear(lin[li]["x"], lin[li]["w"], lin[li]["bias"], y=lin[li]["y"]))
-        td = time_launch(lambda lin: ptq.quantize_dynamic(lin[li]["x"], lin[li]["inv_m"], xq=lin[li]["xq"], s_row=s_row))
-        # per-token zero offset variant: timing only, offsets drawn at random
-        z_tok = torch.randint(-20, 21, (L,), dtype=torch.int32, device=dev)
-        rowsums = [ptq.weight_rowsum(lin[li]["wq"]) for lin in layers]
-        tzq = time_launch(lambda lin: ptq.quantize_pts_offset(lin[li]["x"], lin[li]["inv_m"], lin[li]["s_tok"], z_tok, B, L,
-                                                              xq=lin[li]["xq"]))
-        rs_of = {id(lin): r for lin, r in zip(layers, rowsums)}
-        tzg = time_launch(lambda lin: ptq.w8a8_linear_offset(lin[li]["xq"], lin[li]["wq"], lin[li]["s_tok"], z_tok,
-                                                             rs_of[id(lin)], lin[li]["s_w"], lin[li]["bias"], B, L,
-                                                             y=lin[li]["y"]))
-        # W4A4 (packed 4-bit codes): timing only
-        t4q = t4g = None
-        if K % 2 == 0:
-            s4 = [(lin[li]["s_tok"] * (127.0 / 7.0)).contiguous() for lin in layers]
-            w4 = [ptq.fold_smoothing_w4(lin[li]["w"], 1.0 / lin[li]["inv_m"]) for lin in layers]
-            xq4 = [lin[li]["xq"].view(torch.uint8).view(-1)[: M * (K // 2)].view(M, K // 2) for lin in layers]
-            idx = {id(lin): i for i, lin in enumerate(layers)}
-            t4q = time_launch(lambda lin: ptq.quantize_pts_a4(lin[li]["x"], lin[li]["inv_m"], s4[idx[id(lin)]], B, L,
-                                                              xq4=xq4[idx[id(lin)]]))
-            t4g = time_launch(lambda lin: ptq.w4a4_linear(xq4[idx[id(lin)]], w4[idx[id(lin)]][0], s4[idx[id(lin)]],
-                                                          w4[idx[id(lin)]][1], lin[li]["bias"], B, L, y=lin[li]["y"]))
-            del w4
-        tfu = None
-        if layers[0][li]["fused"]:
-            tfu = time_launch(lambda lin: ptq.w8a8_linear_fused(lin[li]["x"], lin[li]["inv_m"], lin[li]["s_tok"],
-                                                                lin[li]["wq"], lin[li]["s_w"], lin[li]["bias"], B, L,
-                                                                y=lin[li]["y"]))
         ops = 2.0 * M * K * N
         q_bytes = 3.0 * M * K + 4 * K + 4 * L
         g_bytes = 1.0 * M * K + N * K + 2.0 * M * N + 4 * L + 6 * N
-        kernels.append(dict(
+        rec = dict(
             linear=name, K=K, N=N,
             quantize_us=round(tq, 2), quantize_GBps=round(q_bytes / tq / 1e3, 1),
             quantize_frac_hbm=round(q_bytes / tq / 1e3 / PEAK_HBM_GBS, 4),
             w8a8_us=round(tg, 2), w8a8_TOPS=round(ops / tg / 1e6, 1),
             w8a8_frac_int8_peak=round(ops / tg / 1e6 / PEAK_INT8_TOPS, 4),
             w8a8_GBps=round(g_bytes / tg / 1e3, 1), w8a8_frac_hbm=round(g_bytes / tg / 1e3 / PEAK_HBM_GBS, 4),
-            offset_quantize_us=round(tzq, 2), offset_w8a8_us=round(tzg, 2),
-            a4_quantize_us=None if t4q is None else round(t4q, 2),
-            a4_quantize_GBps=None if t4q is None else round((2.5 * M * K) / t4q / 1e3, 1),
-            w4a4_us=None if t4g is None else round(t4g, 2),
-            dynamic_quantize_us=round(td, 2), dynamic_quantize_GBps=round((q_bytes + 4.0 * M) / td / 1e3, 1),
             f16_us=round(tf, 2), f16_TFLOPS=round(ops / tf / 1e6, 1),
-            speedup_gemm_only=round(tf / tg, 3), speedup_quant_plus_gemm=round(tf / (tq + tg), 3)))
-        if tfu is not None:  # the form the timed step uses for this linear
+            speedup_gemm_only=round(tf / tg, 3), speedup_quant_plus_gemm=round(tf / (tq + tg), 3))
+        if full:
+            td = time_launch(lambda lin: ptq.quantize_dynamic(lin[li]["x"], lin[li]["inv_m"], xq=lin[li]["xq"], s_row=s_row))
+            # per-token zero offset variant: timing only, offsets drawn at random
+            z_tok = torch.randint(-20, 21, (L,), dtype=torch.int32, device=dev)
+            rowsums = [ptq.weight_rowsum(lin[li]["wq"]) for lin in layers]
+            tzq = time_launch(lambda lin: ptq.quantize_pts_offset(lin[li]["x"], lin[li]["inv_m"], lin[li]["s_tok"], z_tok,
+                                                                  B, L, xq=lin[li]["xq"]))
+            rs_of = {id(lin): r for lin, r in zip(layers, rowsums)}
+            tzg = time_launch(lambda lin: ptq.w8a8_linear_offset(lin[li]["xq"], lin[li]["wq"], lin[li]["s_tok"], z_tok,
+                                                                 rs_of[id(lin)], lin[li]["s_w"], lin[li]["bias"], B, L,
+                                                                 y=lin[li]["y"]))
+            # W4A4 (packed 4-bit codes): timing only
+            t4q = t4g = None
+            if K % 2 == 0:
+                s4 = [(lin[li]["s_tok"] * (127.0 / 7.0)).contiguous() for lin in layers]
+                w4 = [ptq.fold_smoothing_w4(lin[li]["w"], 1.0 / lin[li]["inv_m"]) for lin in layers]
+                xq4 = [lin[li]["xq"].view(torch.uint8).view(-1)[: M * (K // 2)].view(M, K // 2) for lin in layers]
+                idx = {id(lin): i for i, lin in enumerate(layers)}
+                t4q = time_launch(lambda lin: ptq.quantize_pts_a4(lin[li]["x"], lin[li]["inv_m"], s4[idx[id(lin)]], B, L,
+                                                                  xq4=xq4[idx[id(lin)]]))
+                t4g = time_launch(lambda lin: ptq.w4a4_linear(xq4[idx[id(lin)]], w4[idx[id(lin)]][0], s4[idx[id(lin)]],
+                                                              w4[idx[id(lin)]][1], lin[li]["bias"], B, L, y=lin[li]["y"]))
+                del w4
+            rec.update(
+                offset_quantize_us=round(tzq, 2), offset_w8a8_us=round(tzg, 2),
+                a4_quantize_us=None if t4q is None else round(t4q, 2),
+                a4_quantize_GBps=None if t4q is None else round((2.5 * M * K) / t4q / 1e3, 1),
+                w4a4_us=None if t4g is None else round(t4g, 2),
+                dynamic_quantize_us=round(td, 2), dynamic_quantize_GBps=round((q_bytes + 4.0 * M) / td / 1e3, 1))
+        if layers[0][li]["fused"]:  # the form the timed step uses for this linear
+            tfu = time_launch(lambda lin: ptq.w8a8_linear_fused(lin[li]["x"], lin[li]["inv_m"], lin[li]["s_tok"],
+                                                                lin[li]["wq"], lin[li]["s_w"], lin[li]["bias"], B, L,
+                                                                y=lin[li]["y"]))
             f_bytes = 2.0 * M * K + N * K + 2.0 * M * N + 4 * K + 4 * L + 6 * N
-            kernels[-1].update(in_timed_step="fused", fused_us=round(tfu, 2), fused_GBps=round(f_bytes / tfu / 1e3, 1),
-                               fused_frac_hbm=round(f_bytes / tfu / 1e3 / PEAK_HBM_GBS, 4),
-                               speedup_fused=round(tf / tfu, 3))
+            rec.update(in_timed_step="fused", fused_us=round(tfu, 2), fused_GBps=round(f_bytes / tfu / 1e3, 1),
+                       fused_frac_hbm=round(f_bytes / tfu / 1e3 / PEAK_HBM_GBS, 4), speedup_fused=round(tf / tfu, 3))
         else:
-            kernels[-1].update(in_timed_step="quantize + w8a8")
-        f16_total_us += tf
-        w8_total_us += tg
-        q_total_us += tq
+            rec.update(in_timed_step="quantize + w8a8")
+        kernels.append(rec)
+
+    total_ops = sum(2.0 * M * K * N for _, K, N in cfg.linears) * n_layers
+    result = dict(config=config, cfg=cfg, n_layers=n_layers, ms_per_step=ms_per_step, step_ms=step_ms,
+                  graph_ms_per_step=graph_ms_per_step, kernels=kernels, setup_s=setup_s, total_ops=total_ops,
+                  dominant=dominant, dom_all=dom_all, dom_us=dom_us, launches_timed=len(events["pairs"]),
+                  fused_linears=[d["name"] for d in layers[0] if d["fused"]])
+    if not full:
+        del layers, s_row
+        torch.cuda.empty_cache()
+        return result
+
     for _ in range(2):
         step_f16()
     torch.cuda.synchronize()
@@ -243,7 +251,7 @@ def main() -> int:
     for _ in range(max(1, args.steps // 2)):
         step_f16()
     torch.cuda.synchronize()
-    f16_ms_per_step = (time.perf_counter() - t0) / max(1, args.steps // 2) * 1e3
+    result["f16_ms_per_step"] = (time.perf_counter() - t0) / max(1, args.steps // 2) * 1e3
     for _ in range(2):
         step_dynamic()
     torch.cuda.synchronize()
@@ -251,7 +259,7 @@ def main() -> int:
     for _ in range(max(1, args.steps // 2)):
         step_dynamic()
     torch.cuda.synchronize()
-    dynamic_ms_per_step = (time.perf_counter() - t0) / max(1, args.steps // 2) * 1e3
+    result["dynamic_ms_per_step"] = (time.perf_counter() - t0) / max(1, args.steps // 2) * 1e3
 
     # One plain device-to-device copy of known size (untimed): the reference against which the
     # rocprofv3 FETCH_SIZE / WRITE_SIZE counters of the GEMM are scaled in profiles/.
@@ -261,20 +269,8 @@ def main() -> int:
     torch.cuda.synchronize()
     del calib_src, calib_dst
 
-    # ------------------------------------------------------------------ roofline of the dominant kernel
-    _, dK, dN = dominant
-    dom_ops = 2.0 * M * dK * dN                     # algorithmic int8 ops per launch
-    achieved = dom_ops / dom_us / 1e6               # TOP/s
-    roofline = dict(bound="mfma", kernel=f"linear_mfma<int8> {dominant[0]} {dK}->{dN}, M={M}",
-                    achieved=round(achieved, 1), peak=PEAK_INT8_TOPS, unit="TFLOP/s",
-                    frac=round(achieved / PEAK_INT8_TOPS, 4), avg_launch_us=round(dom_us, 2),
-                    median_launch_us=round(dom_all[len(dom_all) // 2], 2), min_launch_us=round(dom_all[0], 2),
-                    p90_launch_us=round(dom_all[min(len(dom_all) - 1, int(0.9 * len(dom_all)))], 2),
-                    launches_timed=len(events["pairs"]), traffic=DOMINANT_TRAFFIC_BYTES.get(args.config),
-                    algorithmic_bytes=1.0 * M * dK + dN * dK + 2.0 * M * dN)
-
     # ------------------------------------------------------------------ CPU oracle baseline (bounded sample)
-    cpu = None
+    result["cpu"] = None
     if not args.no_cpu_baseline:
         import numpy as np
 
@@ -291,12 +287,97 @@ def main() -> int:
             xq_o = oracle.quantize_pts(h["x"], h["inv_m"], h["s_tok"], sb, L)
             oracle.w8a8_linear(xq_o, wq_o, h["s_tok"], s_w_o, h["bias"], sb, L)
         cpu_s = time.perf_counter() - t0
-        cpu = dict(value=round(rows / (cpu_s * n_layers), 2), unit="tokens/s", cores=oracle.threads(), kind="oracle",
-                   sample=f"layer 0, all four linears (quantize + int GEMM + dequantize), first {sb} of {B} images "
-                          f"({rows} rows) in {cpu_s:.2f} s; extrapolated to {n_layers} layers")
+        result["cpu"] = dict(value=round(rows / (cpu_s * n_layers), 2), unit="tokens/s", cores=oracle.threads(),
+                             kind="oracle",
+                             sample=f"layer 0, all four linears (quantize + int GEMM + dequantize), first {sb} of {B} "
+                                    f"images ({rows} rows) in {cpu_s:.2f} s; extrapolated to {n_layers} layers")
+    del layers, s_row
+    torch.cuda.empty_cache()
+    return result
+
+
+def workload_text(r, fused_mode: str) -> str:
+    cfg = r["cfg"]
+    return (f"configs[{r['config']}] {cfg.name}: {r['n_layers']} layers x "
+            f"{[f'{n} {k}->{o}' for n, k, o in cfg.linears]}, B={cfg.B}, L={cfg.L}, M={cfg.M}; "
+            + (f"step = per layer PTS-quantize + W8A8-linear, one fused quantize+linear launch for {r['fused_linears']} "
+               "(same codes and outputs, bit for bit); " if fused_mode == "auto" and r["fused_linears"]
+               else "step = one PTS-quantize + one W8A8-linear launch per linear; ")
+            + "fold offline")
+
+
+def config_record(r, fused_mode: str):
+    """The compact record of one configuration for the "configs" list."""
+    cfg = r["cfg"]
+    use_graph = r["config"] in GRAPH_HEADLINE_CONFIGS and r["graph_ms_per_step"] is not None
+    head_ms = r["graph_ms_per_step"] if use_graph else r["ms_per_step"]
+    keep = ("linear", "K", "N", "in_timed_step", "quantize_us", "quantize_GBps", "quantize_frac_hbm", "w8a8_us",
+            "w8a8_TOPS", "w8a8_frac_int8_peak", "w8a8_GBps", "w8a8_frac_hbm", "fused_us", "fused_GBps", "fused_frac_hbm",
+            "f16_us", "speedup_gemm_only", "speedup_quant_plus_gemm", "speedup_fused")
+    return dict(config=r["config"], workload=workload_text(r, fused_mode),
+                ms_per_step=round(head_ms, 4), timing="one HIP graph replay per step" if use_graph else "eager launches",
+                eager_ms_per_step=round(r["ms_per_step"], 4),
+                eager_ms_per_step_median=round(statistics.median(r["step_ms"]), 4),
+                graph_ms_per_step=None if r["graph_ms_per_step"] is None else round(r["graph_ms_per_step"], 4),
+                tokens_per_s=round(cfg.M / (head_ms * 1e-3), 1), tops=round(r["total_ops"] / (head_ms * 1e-3) / 1e12, 2),
+                linears=[{k: rec[k] for k in keep if k in rec} for rec in r["kernels"]])
+
+
+def main() -> int:
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=20)
+    ap.add_argument("--warmup", type=int, default=5)
+    ap.add_argument("--config", type=int, default=3, help="timed workload (BASELINE.json configs index)")
+    ap.add_argument("--layers", type=int, default=None, help="override the number of layers of the timed workload (debug only)")
+    ap.add_argument("--fused", choices=("auto", "off"), default="auto",
+                    help="auto: one fused quantize+linear launch for linears with K <= 128 or N <= 128 when there are enough rows")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-graph", action="store_true", help="skip the extra timing of the step replayed as one HIP graph")
+    ap.add_argument("--no-other-configs", action="store_true", help="time only the workload named by --config")
+    ap.add_argument("--cpu-sample-batch", type=int, default=256)
+    args = ap.parse_args()
+    if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
+        print("bench.py: this build runs on one GPU only (the path shards data-parallel over the batch "
+              "with no collectives, see DESIGN.md); run with --gpus 1", file=sys.stderr)
+        return 2
+
+    import torch
+
+    import paper_2412_20386_amd as ptq
+    from paper_2412_20386_amd import synth
+
+    if not torch.cuda.is_available():
+        print("bench.py: no GPU visible", file=sys.stderr)
+        return 2
+    ptq.binding.load()  # fail loudly if the HIP library is missing
+    torch.cuda.set_device(0)
+
+    r = measure_config(args, args.config, full=True)
+    M = r["cfg"].M
+    ms_per_step = r["ms_per_step"]
+
+    # ------------------------------------------------------------------ roofline of the dominant kernel
+    _, dK, dN = r["dominant"]
+    dom_ops = 2.0 * M * dK * dN                     # algorithmic int8 ops per launch
+    dom_all, dom_us = r["dom_all"], r["dom_us"]
+    achieved = dom_ops / dom_us / 1e6               # TOP/s
+    roofline = dict(bound="mfma", kernel=f"W8A8 GEMM of {r['dominant'][0]} {dK}->{dN}, M={M}",
+                    achieved=round(achieved, 1), peak=PEAK_INT8_TOPS, unit="TOP/s",
+                    frac=round(achieved / PEAK_INT8_TOPS, 4), avg_launch_us=round(dom_us, 2),
+                    median_launch_us=round(dom_all[len(dom_all) // 2], 2), min_launch_us=round(dom_all[0], 2),
+                    p90_launch_us=round(dom_all[min(len(dom_all) - 1, int(0.9 * len(dom_all)))], 2),
+                    launches_timed=r["launches_timed"], traffic=dominant_traffic(args.config),
+                    algorithmic_bytes=1.0 * M * dK + dN * dK + 2.0 * M * dN)
+
+    configs = [config_record(r, args.fused)]
+    if not args.no_other_configs:
+        for other in sorted(synth.CONFIGS):
+            if other != args.config:
+                configs.append(config_record(measure_config(args, other, full=False), args.fused))
+        configs.sort(key=lambda c: c["config"])
 
     tokens_per_s = M / (ms_per_step * 1e-3)
-    total_ops = sum(2.0 * M * K * N for _, K, N in cfg.linears) * n_layers
     out = {
         "metric": "W8A8 linear TOPS + tokens/sec, Vim-B shapes batch 256; speedup vs fp16 GEMM",
         "value": round(tokens_per_s, 1),
@@ -305,29 +386,25 @@ def main() -> int:
         "steps": args.steps,
         "warmup": args.warmup,
         "ms_per_step": round(ms_per_step, 4),
+        "ms_per_step_median": round(statistics.median(r["step_ms"]), 4),
         "higher_is_better": True,
         "scaling": "weak",
         "vs_baseline": None,
         "dtype": "int8",
         "data": "synthetic",
-        "config": {"workload": f"configs[{args.config}] {cfg.name}: {n_layers} layers x "
-                               f"{[f'{n} {k}->{o}' for n, k, o in cfg.linears]}, B={B}, L={L}, M={M}; "
-                               + ("step = per layer PTS-quantize + W8A8-linear for in_proj and out_proj, one fused "
-                                  "quantize+linear launch for x_proj and dt_proj (same codes and outputs, bit for bit); "
-                                  if args.fused == "auto" else "step = 96 PTS-quantize + 96 W8A8-linear launches; ")
-                               + "fold offline",
-                   "fused_linears": [d["name"] for d in layers[0] if d["fused"]]},
-        "tops": round(total_ops / (ms_per_step * 1e-3) / 1e12, 1),
-        "speedup_vs_f16_stack": round(f16_ms_per_step / ms_per_step, 3),
-        "f16_ms_per_step": round(f16_ms_per_step, 4),
-        "graph_ms_per_step": None if graph_ms_per_step is None else round(graph_ms_per_step, 4),
-        "dynamic_ms_per_step": round(dynamic_ms_per_step, 4),
-        "speedup_pts_vs_per_token_dynamic": round(dynamic_ms_per_step / ms_per_step, 3),
+        "config": {"workload": workload_text(r, args.fused), "fused_linears": r["fused_linears"]},
+        "tops": round(r["total_ops"] / (ms_per_step * 1e-3) / 1e12, 1),
+        "speedup_vs_f16_stack": round(r["f16_ms_per_step"] / ms_per_step, 3),
+        "f16_ms_per_step": round(r["f16_ms_per_step"], 4),
+        "graph_ms_per_step": None if r["graph_ms_per_step"] is None else round(r["graph_ms_per_step"], 4),
+        "dynamic_ms_per_step": round(r["dynamic_ms_per_step"], 4),
+        "speedup_pts_vs_per_token_dynamic": round(r["dynamic_ms_per_step"] / ms_per_step, 3),
         "paper_context": "paper: up to 1.83x end-to-end at W4A4 on VMamba-B, batch 32, RTX 3090 (not this metric)",
         "roofline": roofline,
-        "cpu_baseline": cpu,
-        "kernels": kernels,
-        "setup_s": round(setup_s, 1),
+        "cpu_baseline": r["cpu"],
+        "kernels": r["kernels"],
+        "configs": configs,
+        "setup_s": round(r["setup_s"], 1),
     }
     print(json.dumps(out))
     return 0

@@ -13,6 +13,8 @@
 //                       activation read once from HBM in whole 128-byte lines, quantized once.
 //   pts_linear_generic  every other shape: the register-staged tiled kernel with the quantizer in
 //                       its loader (correct everywhere, re-quantizes per tile column).
+#include <type_traits>
+
 #include "mfma_linear.hpp"
 #include "quant_device.hpp"
 
@@ -78,7 +80,7 @@ __device__ __forceinline__ u32x2 quantize_8(v4i raw, const float (&im)[8], float
 // M, L < 2^31, all tables fit the LDS.
 // ------------------------------------------------------------------------------------------
 #ifndef PTQ4VM_FUSED_RB
-#define PTQ4VM_FUSED_RB 2
+#define PTQ4VM_FUSED_RB 1
 #endif
 constexpr int kFusedRB = PTQ4VM_FUSED_RB;       // 16-row MFMA blocks per unit (2: 32-row units on 8 wavefronts, 1: 16-row units on 16)
 constexpr int kFusedWaves = 16 / kFusedRB;
@@ -107,7 +109,9 @@ __host__ __device__ __forceinline__ FusedLayout fused_layout(int N, int K, int L
     return l;
 }
 
-template <int NB, int D>
+// DUMP: also write the int8 codes (xq_out) and the int32 accumulators (acc_out), the parity aids; without it
+// their address arithmetic (a third of the VALU instructions of the k loop) is not even compiled in.
+template <int NB, int D, bool DUMP>
 __global__ __launch_bounds__(kFusedWaves * 64) void pts_linear_wres(const LinearArgs p) {
     using Acc = v4i;
 
@@ -125,32 +129,79 @@ __global__ __launch_bounds__(kFusedWaves * 64) void pts_linear_wres(const Linear
     float *const cb_lds = cs_lds + NB * 16;
     char *const tile = lds_dyn + lay.tile_off + wave * lay.tile_bytes;  // codes in the K loop, results after it
 
-    // Units are dealt wavefront-major, so that a launch with fewer units than wavefronts still
-    // spreads them over all workgroups.
+    // Work items.  A wavefront handles units of up to UNIT rows, one per pass over the matrix; in a pass the
+    // units are dealt wavefront-major, so that a launch with fewer units than wavefronts still spreads them
+    // over all workgroups.  The kernel is bound by the VALU work of the quantizer, which is proportional to the
+    // rows a SIMD's wavefronts load, and with about one unit per wavefront (M = 50 432: 3152 units of 16 rows on
+    // 4096 wavefronts) whole units cannot be dealt evenly: some SIMDs would get four and most three.  So the
+    // last, partial pass is dealt in groups of 8 rows (the rows of one load instruction): every workgroup gets
+    // a contiguous share of the groups and hands them to its wavefronts two at a time (16 rows) until the rest
+    // is one group per wavefront; wavefront w sits on SIMD w mod 4, so the SIMDs' row counts differ by at most 8.
     constexpr int RB = kFusedRB, UNIT = 16 * RB, NL = 2 * RB, PR = kFusedPatchRows;  // NL loads of 8 rows per k-step
-    const int64_t units = (p.M + UNIT - 1) / UNIT;
-    const int64_t unit_step = (int64_t)gridDim.x * kFusedWaves;
-    int64_t unit = (int64_t)wave * gridDim.x + blockIdx.x;
+    const int64_t wavefronts = (int64_t)gridDim.x * kFusedWaves;
+    const int64_t full_passes = p.M / (wavefronts * UNIT);
+    const int64_t tail_row0 = full_passes * wavefronts * UNIT;
+    const int64_t tail_groups = (p.M - tail_row0 + 7) / 8;  // fewer than NL groups per wavefront on average
+    auto item = [&](int64_t k, int64_t &r0, int &nrows) -> bool {  // k-th item of this wavefront: rows r0 .. r0 + nrows - 1
+#ifdef PTQ4VM_FUSED_NO_BALANCE  // timing experiment: whole units only, dealt wavefront-major
+        const int64_t first_row = ((k * wavefronts) + (int64_t)wave * gridDim.x + blockIdx.x) * UNIT;
+        if (first_row >= p.M) return false;
+        r0 = first_row;
+        nrows = UNIT;
+        return true;
+#endif
+        if (k < full_passes) {
+            r0 = ((k * wavefronts) + (int64_t)wave * gridDim.x + blockIdx.x) * UNIT;
+            nrows = UNIT;
+            return true;
+        }
+        if (k > full_passes || tail_groups == 0) return false;
+        const int64_t per_wg = tail_groups / gridDim.x, extra = tail_groups % gridDim.x;
+        const int64_t g0 = blockIdx.x * per_wg + min((int64_t)blockIdx.x, extra);
+        const int n = (int)(per_wg + (blockIdx.x < extra ? 1 : 0));  // this workgroup's groups: at most NL per wavefront
+        // the first `big` wavefronts take NL groups, the others NL / 2 (or what is left), so that every group is taken once
+        constexpr int small_size = NL / 2, big_size = NL;
+        const int big = max(0, min(kFusedWaves, (n - small_size * kFusedWaves + (big_size - small_size) - 1) / (big_size - small_size)));
+        int first, count;
+        if (wave < big) {
+            first = wave * big_size, count = big_size;
+        } else {
+            first = big * big_size + (wave - big) * small_size, count = small_size;
+        }
+        count = min(count, n - first);
+        if (count <= 0) return false;
+        r0 = tail_row0 + (g0 + first) * 8;
+        nrows = count * 8;
+        return true;
+    };
+    int64_t item_k = 0, unit_r0 = 0, next_r0 = 0;
+    int unit_rows = 0, next_rows = 0;
+    bool have = item(0, unit_r0, unit_rows);
 
     v4i raw[D][NL];
     const char *xrow[NL];
     uint32_t tok[NL];
-    auto load_x = [&](int d, int ks) {
+    // 8-row groups (load instructions per k-step) of the unit being loaded: all NL, or half of them for a short
+    // unit, whose further groups are neither loaded nor quantized.  The k loop is compiled once for either count
+    // (branches inside it would cost the counted waits on the loads).
+    int groups = 0;
+    auto load_x = [&](int d, int ks) {  // outside the k loop only
 #pragma unroll
         for (int i = 0; i < NL; i++)
-            raw[d][i] = __builtin_nontemporal_load(reinterpret_cast<const v4i *>(xrow[i] + ks * 128));
+            if (i < groups) raw[d][i] = __builtin_nontemporal_load(reinterpret_cast<const v4i *>(xrow[i] + ks * 128));
     };
-    auto start_unit = [&](int64_t u) {  // first D k-steps of the unit's 32 rows
+    auto start_unit = [&](int64_t r0, int nrows) {  // first D k-steps of the unit's rows
+        groups = nrows > 8 * (NL / 2) ? NL : NL / 2;
 #pragma unroll
         for (int i = 0; i < NL; i++) {
-            const int64_t r = min(u * UNIT + i * 8 + rr, p.M - 1);  // clamped rows are never stored
+            const int64_t r = min(r0 + i * 8 + rr, p.M - 1);  // clamped rows are never stored
             xrow[i] = p.x + r * p.ldx_bytes + pc * 16;
             tok[i] = (uint32_t)r % (uint32_t)L;
         }
 #pragma unroll
         for (int d = 0; d < D; d++) load_x(d, d);
     };
-    if (unit < units) start_unit(unit);
+    if (have) start_unit(unit_r0, unit_rows);
 
     // Tables, once per workgroup.  The weight goes global -> LDS in 1 KiB copies, linear on the LDS
     // side; the lane picks the global chunk that belongs at its LDS position (pad chunks and pad
@@ -186,7 +237,8 @@ __global__ __launch_bounds__(kFusedWaves * 64) void pts_linear_wres(const Linear
     }
     const uint32_t tile_rd = l16 * 64 + ((lq ^ ((l16 >> 2) & 3)) << 4);  // + 1024 for rows 16..31
 
-    for (; unit < units; unit += unit_step) {
+    bool next_have = false;
+    for (; have; have = next_have, unit_r0 = next_r0, unit_rows = next_rows) {
         Acc acc[RB][NB];
 #pragma unroll
         for (int j = 0; j < RB; j++)
@@ -197,66 +249,81 @@ __global__ __launch_bounds__(kFusedWaves * 64) void pts_linear_wres(const Linear
         float inv_s[NL];
 #pragma unroll
         for (int i = 0; i < NL; i++) inv_s[i] = inv_s_lds[tok[i]];
-        const int64_t r_unit = unit * UNIT;
+        const int64_t r_unit = unit_r0;
+        const int64_t r_end = min(p.M, unit_r0 + unit_rows);  // rows at or beyond it are not this unit's
+        const int unit_groups = groups;                        // (`groups` moves on to the next unit before the epilogue)
 
-        auto compute = [&](int d, int ks) {
-            float im[8];
-            const v4f im_lo = *reinterpret_cast<const v4f *>(inv_m_lds + ks * 64 + pc * 8);
-            const v4f im_hi = *reinterpret_cast<const v4f *>(inv_m_lds + ks * 64 + pc * 8 + 4);
+        auto k_loop = [&](auto g_tag) {
+            constexpr int G = decltype(g_tag)::value;
+            auto load_g = [&](int d, int ks) {
 #pragma unroll
-            for (int e = 0; e < 4; e++) im[e] = im_lo[e], im[4 + e] = im_hi[e];
+                for (int i = 0; i < G; i++)
+                    raw[d][i] = __builtin_nontemporal_load(reinterpret_cast<const v4i *>(xrow[i] + ks * 128));
+            };
+            auto compute = [&](int d, int ks) {
+                float im[8];
+                const v4f im_lo = *reinterpret_cast<const v4f *>(inv_m_lds + ks * 64 + pc * 8);
+                const v4f im_hi = *reinterpret_cast<const v4f *>(inv_m_lds + ks * 64 + pc * 8 + 4);
 #pragma unroll
-            for (int i = 0; i < NL; i++) {
-                const u32x2 codes = quantize_8(raw[d][i], im, inv_s[i]);
-                *reinterpret_cast<u32x2 *>(tile + tile_wr[i]) = codes;
-                if (p.xq_out) {  // parity aid: the codes exactly as the MFMA will see them
-                    const int64_t r = r_unit + i * 8 + rr;
-                    if (r < p.M) *reinterpret_cast<u32x2 *>(p.xq_out + r * p.ldxq_out + ks * 64 + pc * 8) = codes;
+                for (int e = 0; e < 4; e++) im[e] = im_lo[e], im[4 + e] = im_hi[e];
+#pragma unroll
+                for (int i = 0; i < G; i++) {  // tile rows of further groups keep stale codes: results of rows nobody stores
+                    const u32x2 codes = quantize_8(raw[d][i], im, inv_s[i]);
+                    *reinterpret_cast<u32x2 *>(tile + tile_wr[i]) = codes;
+                    if (DUMP && p.xq_out) {  // parity aid: the codes exactly as the MFMA will see them
+                        const int64_t r = r_unit + i * 8 + rr;
+                        if (r < p.M) *reinterpret_cast<u32x2 *>(p.xq_out + r * p.ldxq_out + ks * 64 + pc * 8) = codes;
+                    }
+                    __builtin_amdgcn_sched_barrier(0);  // one load's eight codes at a time: bounds the live registers
                 }
-                __builtin_amdgcn_sched_barrier(0);  // one load's eight codes at a time: bounds the live registers
+                v4i fw[NB], fb[RB];
+#pragma unroll
+                for (int j = 0; j < RB; j++) fb[j] = *reinterpret_cast<const v4i *>(tile + tile_rd + j * 1024);
+#pragma unroll
+                for (int i = 0; i < NB; i++) fw[i] = *reinterpret_cast<const v4i *>(w_lane + i * 16 * pw + ks * 64);
+                __builtin_amdgcn_sched_barrier(0);  // all LDS traffic of the k-step in flight before its first MFMA
+#pragma unroll
+                for (int i = 0; i < NB; i++) {
+#pragma unroll
+                    for (int j = 0; j < RB; j++) acc[j][i] = __builtin_amdgcn_mfma_i32_16x16x64_i8(fw[i], fb[j], acc[j][i], 0, 0, 0);
+                }
+            };
+            // The scheduling barriers keep each refill right behind the work that frees its registers;
+            // left alone the scheduler sinks all loads of a group to its end and the wavefront then
+            // waits for the whole group before every pass.
+            int ks0 = 0;
+            for (; ks0 + D < n_ksteps; ks0 += D) {  // every register slot is refilled (K is a multiple of 64 D)
+#pragma unroll
+                for (int d = 0; d < D; d++) {
+                    compute(d, ks0 + d);
+                    load_g(d, ks0 + d + D);
+                    __builtin_amdgcn_sched_barrier(0);
+                }
             }
-            v4i fw[NB], fb[RB];
 #pragma unroll
-            for (int j = 0; j < RB; j++) fb[j] = *reinterpret_cast<const v4i *>(tile + tile_rd + j * 1024);
-#pragma unroll
-            for (int i = 0; i < NB; i++) fw[i] = *reinterpret_cast<const v4i *>(w_lane + i * 16 * pw + ks * 64);
-            __builtin_amdgcn_sched_barrier(0);  // all LDS traffic of the k-step in flight before its first MFMA
-#pragma unroll
-            for (int i = 0; i < NB; i++) {
-#pragma unroll
-                for (int j = 0; j < RB; j++) acc[j][i] = __builtin_amdgcn_mfma_i32_16x16x64_i8(fw[i], fb[j], acc[j][i], 0, 0, 0);
-            }
-        };
-        // The scheduling barriers keep each refill right behind the work that frees its registers;
-        // left alone the scheduler sinks all loads of a group to its end and the wavefront then
-        // waits for the whole group before every pass.
-        int ks0 = 0;
-        for (; ks0 + D < n_ksteps; ks0 += D) {  // every register slot is refilled (K is a multiple of 64 D)
-#pragma unroll
-            for (int d = 0; d < D; d++) {
+            for (int d = 0; d < D; d++) {  // last group: drain
                 compute(d, ks0 + d);
-                load_x(d, ks0 + d + D);
                 __builtin_amdgcn_sched_barrier(0);
             }
-        }
-#pragma unroll
-        for (int d = 0; d < D; d++) {  // last group: drain
-            compute(d, ks0 + d);
-            __builtin_amdgcn_sched_barrier(0);
-        }
+        };
+        if (unit_groups == NL)
+            k_loop(std::integral_constant<int, NL>{});
+        else
+            k_loop(std::integral_constant<int, NL / 2>{});
 
         // Accumulator register v of block (j, i): token row 16 j + (lane mod 16), channel 16 i + 4 (lane / 16) + v.
         float rs[RB];
 #pragma unroll
         for (int j = 0; j < RB; j++) rs[j] = p.s_tok[(uint32_t)min(r_unit + j * 16 + l16, p.M - 1) % (uint32_t)L];
-        const int64_t next = unit + unit_step;
-        if (next < units) start_unit(next);  // in flight while this unit's results are written
+        item_k++;
+        next_have = item(item_k, next_r0, next_rows);
+        if (next_have) start_unit(next_r0, next_rows);  // in flight while this unit's results are written
 
 #pragma unroll
         for (int pass = 0; pass < UNIT / PR; pass++) {  // PR result rows at a time through the private region
             const int j = pass * PR / 16, row_in_block = (pass * PR) % 16;  // rows row_in_block .. + PR - 1 of block j
             const int64_t r0 = r_unit + pass * PR;
-            const int rows_valid = (int)min((int64_t)PR, p.M - r0);
+            const int rows_valid = (int)min((int64_t)PR, r_end - r0);
             if (rows_valid <= 0) break;
             const int prow = l16 - row_in_block;         // this lane's row inside the pass
             const bool mine = prow >= 0 && prow < PR;
@@ -270,7 +337,7 @@ __global__ __launch_bounds__(kFusedWaves * 64) void pts_linear_wres(const Linear
 #pragma unroll
                     for (int c = 0; c < 4; c++) {
                         const int a = acc[j][i][c];
-                        if (p.acc_out && prow < rows_valid && col + c < N) p.acc_out[(r0 + prow) * p.N + col + c] = a;
+                        if (DUMP && p.acc_out && prow < rows_valid && col + c < N) p.acc_out[(r0 + prow) * p.N + col + c] = a;
                         out[c] = (float)a * (rs[j] * cs[c]) + cb[c];
                     }
                     __half2 lo = __floats2half2_rn(out[0], out[1]);
@@ -685,16 +752,21 @@ int launch_wres(const LinearArgs &a, hipStream_t stream) {
     int64_t wgs = ptq4vm::ceil_div(units, kFusedWaves);
     if (wgs > cus) wgs = cus;  // one workgroup per CU: the resident tables take most of its LDS
     using Kernel = void (*)(const LinearArgs);
-#define PTQ4VM_WRES_ROW(D) \
-    {pts_linear_wres<1, D>, pts_linear_wres<2, D>, pts_linear_wres<3, D>, pts_linear_wres<4, D>, \
-     pts_linear_wres<5, D>, pts_linear_wres<6, D>, pts_linear_wres<7, D>, pts_linear_wres<8, D>}
-    // [k-steps in flight: 4, 2, 1][number of 16-channel blocks - 1]
-    static const Kernel kernels[3][kFusedMaxBlocks] = {PTQ4VM_WRES_ROW(4), PTQ4VM_WRES_ROW(2), PTQ4VM_WRES_ROW(1)};
+#define PTQ4VM_WRES_ROW(D, DUMP) \
+    {pts_linear_wres<1, D, DUMP>, pts_linear_wres<2, D, DUMP>, pts_linear_wres<3, D, DUMP>, pts_linear_wres<4, D, DUMP>, \
+     pts_linear_wres<5, D, DUMP>, pts_linear_wres<6, D, DUMP>, pts_linear_wres<7, D, DUMP>, pts_linear_wres<8, D, DUMP>}
+    // [parity aids][k-steps in flight: 4, 2, 1][number of 16-channel blocks - 1]
+    static const Kernel kernels[2][3][kFusedMaxBlocks] = {
+        {PTQ4VM_WRES_ROW(4, false), PTQ4VM_WRES_ROW(2, false), PTQ4VM_WRES_ROW(1, false)},
+        {PTQ4VM_WRES_ROW(4, true), PTQ4VM_WRES_ROW(2, true), PTQ4VM_WRES_ROW(1, true)}};
 #undef PTQ4VM_WRES_ROW
     const int n_ksteps = (int)(a.k_bytes / 64);
     // four k-steps in flight need too many registers next to the accumulators of 7 or 8 channel blocks
-    const int depth_row = (n_ksteps % 4 == 0 && lay.nb <= 6) ? 0 : (n_ksteps % 2 == 0 ? 1 : 2);
-    const Kernel kernel = kernels[depth_row][lay.nb - 1];
+#ifndef PTQ4VM_FUSED_MAXD
+#define PTQ4VM_FUSED_MAXD (PTQ4VM_FUSED_RB == 1 ? 2 : 4)  // 16 wavefronts of 128 registers: two k-steps in flight (measured best)
+#endif
+    const int depth_row = (PTQ4VM_FUSED_MAXD >= 4 && n_ksteps % 4 == 0 && lay.nb <= 6) ? 0 : (n_ksteps % 2 == 0 ? 1 : 2);
+    const Kernel kernel = kernels[(a.xq_out || a.acc_out) ? 1 : 0][depth_row][lay.nb - 1];
     if (int rc = ptq4vm::set_lds_limit(reinterpret_cast<const void *>(kernel), kLdsBytes, "hipFuncSetAttribute(pts_linear_wres)")) return rc;
     kernel<<<dim3((unsigned)wgs), dim3(kFusedWaves * 64), lay.total, stream>>>(a);
     return ptq4vm::check_launch("pts_linear_wres");
