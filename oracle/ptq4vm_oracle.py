@@ -33,11 +33,22 @@ def build(force: bool = False) -> str:
     return _LIB
 
 
+def build_sanitized() -> str:
+    """The same source with AddressSanitizer and UndefinedBehaviorSanitizer (-O1), next to the normal library.
+    To run the pins under it: PTQ4VM_ORACLE_LIB=<this path>, with gcc's libasan.so preloaded."""
+    out = os.path.join(_HERE, "libptq4vm_oracle_asan.so")
+    flags = [f for f in _CFLAGS if f != "-O2"] + ["-O1", "-g", "-fsanitize=address,undefined", "-fno-omit-frame-pointer"]
+    subprocess.run(["gcc", *flags, _SRC, "-o", out, "-lm"], check=True)
+    return out
+
+
 def _load():
     global _lib
     if _lib is None:
-        build()
-        lib = ctypes.CDLL(_LIB)
+        override = os.environ.get("PTQ4VM_ORACLE_LIB")  # a sanitized build of the same source
+        if not override:
+            build()
+        lib = ctypes.CDLL(override or _LIB)
         i64, vp = ctypes.c_int64, ctypes.c_void_p
         lib.oracle_half_to_float.restype = ctypes.c_float
         lib.oracle_half_to_float.argtypes = [ctypes.c_uint16]

@@ -14,7 +14,8 @@ from typing import Optional, Tuple
 import torch
 
 _HERE = os.path.dirname(os.path.abspath(__file__))
-LIB_PATH = os.path.join(_HERE, "libptq4vm.so")
+# PTQ4VM_LIB: another build of the same sources (the sanitized host build of the test suite)
+LIB_PATH = os.environ.get("PTQ4VM_LIB") or os.path.join(_HERE, "libptq4vm.so")
 
 EXPORTS = (
     "ptq4vm_fold_smoothing",

@@ -46,17 +46,22 @@ def _headers():
     return sorted(glob.glob(os.path.join(CSRC, "*.hpp")) + glob.glob(os.path.join(_HERE, "..", "include", "*.h")))
 
 
-def _compile_one(src: str, force: bool):
+# Host code only: on a hipcc line each -fsanitize= goes directly after -Xarch_host (GPU sanitizers are not available).
+SANITIZE_FLAGS = ["-Xarch_host", "-fsanitize=address", "-Xarch_host", "-fsanitize=undefined", "-fno-omit-frame-pointer", "-g"]
+SANITIZED_LIB_PATH = os.path.join(_HERE, "libptq4vm_asan.so")
+
+
+def _compile_one(src: str, force: bool, extra=()):
     """Compile one source to an object file; returns (object path, compiler log)."""
     h = hashlib.sha1()
     for path in [src, *_headers()]:
         with open(path, "rb") as f:
             h.update(f.read())
-    h.update(" ".join(HIPCC_FLAGS).encode())
+    h.update(" ".join([*HIPCC_FLAGS, *extra]).encode())
     obj = os.path.join(OBJ_DIR, os.path.basename(src) + "." + h.hexdigest()[:16] + ".o")
     if not force and os.path.exists(obj):
         return obj, ""
-    flags = [f for f in HIPCC_FLAGS if f != "-shared"]
+    flags = [f for f in HIPCC_FLAGS if f != "-shared"] + list(extra)
     tmp = obj + f".tmp{os.getpid()}"
     res = subprocess.run([hipcc(), *flags, "-x", "hip", "-c", src, "-o", tmp], capture_output=True, text=True)
     if res.returncode != 0:
@@ -91,7 +96,32 @@ def build(verbose: bool = False, force: bool = True) -> str:
     return LIB_PATH
 
 
+def build_sanitized() -> str:
+    """libptq4vm_asan.so: the same sources with AddressSanitizer and UndefinedBehaviorSanitizer on the HOST half
+    (argument checks, launch set-up, status strings); the device code is compiled as always.  Load it with
+    PTQ4VM_LIB=<path> and clang's ASan runtime preloaded (see tests/test_sanitized_host.py)."""
+    os.makedirs(OBJ_DIR, exist_ok=True)
+    srcs = sources()
+    with concurrent.futures.ThreadPoolExecutor(max_workers=min(8, len(srcs))) as pool:
+        results = list(pool.map(lambda s: _compile_one(s, False, SANITIZE_FLAGS), srcs))
+    objs = sorted(obj for obj, _ in results)
+    link = subprocess.run([hipcc(), "--offload-arch=gfx950", "-shared", "-fPIC", "-shared-libsan", "-fsanitize=address",
+                           "-fsanitize=undefined", *objs, "-o", SANITIZED_LIB_PATH], capture_output=True, text=True)
+    if link.returncode != 0:
+        raise RuntimeError("link failed:\n" + link.stdout + link.stderr)
+    return SANITIZED_LIB_PATH
+
+
+def sanitizer_runtime() -> str:
+    """Path of clang's shared ASan runtime (to preload into the Python process that loads the sanitized library)."""
+    res = subprocess.run([hipcc(), "-print-file-name=libclang_rt.asan-x86_64.so"], capture_output=True, text=True, check=True)
+    return res.stdout.strip()
+
+
 if __name__ == "__main__":
     import sys
 
-    print(build(verbose=True, force="--incremental" not in sys.argv))
+    if "--sanitize" in sys.argv:
+        print(build_sanitized())
+    else:
+        print(build(verbose=True, force="--incremental" not in sys.argv))

@@ -499,12 +499,22 @@ __global__ __launch_bounds__(kStreamWaves * 64) void linear_stream_smallk(const 
     }
     __syncthreads();
 
+    // Work items: a unit (UNIT rows) times a part of the channel groups.  The time of a SIMD is the sum of its
+    // wavefronts' items (dequantization VALU work and store issue), and whole units do not divide evenly: at
+    // M = 50 432 there are 3152 of them for 4096 wavefronts, so some SIMDs would carry four units and most three.
+    // In quarters a SIMD carries 12 or 13 items.  The parts of a unit go to neighbouring workgroups at the same
+    // time (they read the same rows).
     const int64_t units = (p.M + UNIT - 1) / UNIT;
-    const int64_t unit_step = (int64_t)gridDim.x * kStreamWaves;
+    const int parts = min(4, lay.groups), groups_per_part = (lay.groups + parts - 1) / parts;
+    const int64_t items = units * parts;
+    const int64_t item_step = (int64_t)gridDim.x * kStreamWaves;
     const bool y_wide = p.y_vec == 8;
     auto patch_chunk = [&](int row, int chunk) { return row * 128 + ((chunk ^ (row & 7)) << 4); };
 
-    for (int64_t unit = (int64_t)wave * gridDim.x + blockIdx.x; unit < units; unit += unit_step) {
+    for (int64_t it = (int64_t)wave * gridDim.x + blockIdx.x; it < items; it += item_step) {
+        const int64_t unit = it / parts;
+        const int part = (int)(it - unit * parts);
+        const int g_begin = part * groups_per_part, g_end = min(lay.groups, g_begin + groups_per_part);
         const int64_t r_unit = unit * UNIT;
         // ---- the unit's two activation operands (lane: row 16 jb + lane mod 16, codes 64 ks + 16 (lane / 16) ..)
         v4i fx[RB][KSTEPS];
@@ -527,7 +537,7 @@ __global__ __launch_bounds__(kStreamWaves * 64) void linear_stream_smallk(const 
                         im[4 * e] = f.x, im[4 * e + 1] = f.y, im[4 * e + 2] = f.z, im[4 * e + 3] = f.w;
                     }
                     const v4i codes = load_quantized_chunk<X_ALIGN>(xrow, k0, K, true, im, inv_s);
-                    if (p.xq_out && r_unit + jb * 16 + l16 < p.M) {  // parity aid
+                    if (p.xq_out && part == 0 && r_unit + jb * 16 + l16 < p.M) {  // parity aid
 #pragma unroll
                         for (int b = 0; b < 16; b++)
                             if (k0 + b < K) p.xq_out[r * p.ldxq_out + k0 + b] = (int8_t)((uint32_t)codes[b >> 2] >> (8 * (b & 3)));
@@ -539,8 +549,8 @@ __global__ __launch_bounds__(kStreamWaves * 64) void linear_stream_smallk(const 
             }
         }
 
-        // ---- all output channels, 64 at a time
-        for (int g = 0; g < lay.groups; g++) {
+        // ---- the part's output channels, 64 at a time
+        for (int g = g_begin; g < g_end; g++) {
             v4i acc[RB][4];
             v4f cs[4], cb[4];
 #pragma unroll
@@ -832,7 +842,8 @@ int ptq4vm::mfma::launch_stream_smallk(const LinearArgs &a, bool quantize, hipSt
     if (err == hipSuccess) err = hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, device);
     if (err != hipSuccess) return ptq4vm::record_hip_error(err, "hipDeviceGetAttribute(multiprocessor count)");
     if (cus < 1) cus = 1;
-    int64_t wgs = ptq4vm::ceil_div(ptq4vm::ceil_div(a.M, 16 * kStreamRB), kStreamWaves);
+    const int64_t items = ptq4vm::ceil_div(a.M, 16 * kStreamRB) * (lay.groups < 4 ? lay.groups : 4);  // as the kernel counts them
+    int64_t wgs = ptq4vm::ceil_div(items, kStreamWaves);
     if (wgs > cus) wgs = cus;  // one workgroup per CU: the resident weight takes most of its LDS
     if (quantize)
         return ksteps == 1 ? launch_stream_aligned<1, true>(a, xa, wa, lay, (unsigned)wgs, stream)
