@@ -128,6 +128,35 @@ def dominant_median(agg, substr: str):
     return statistics.median(parts[-1][1])
 
 
+def counter_table(directories, kernels, out: list) -> None:
+    """Per kernel (short-name substring) the median over dispatches of every counter found in the given
+    rocprofv3 --pmc output directories (values of one dispatch are summed over its rows: one per XCD / SE)."""
+    for directory in directories:
+        f = first(os.path.join(directory, "**", "*counter_collection.csv")) or first(os.path.join(directory, "*counter_collection.csv"))
+        if not f:
+            continue
+        per_dispatch = collections.defaultdict(lambda: collections.defaultdict(float))
+        names = {}
+        for r in csv.DictReader(open(f)):
+            if any(k in r["Kernel_Name"] for k in OURS):
+                per_dispatch[r["Dispatch_Id"]][r["Counter_Name"]] += float(r["Counter_Value"])
+                names[r["Dispatch_Id"]] = short(r["Kernel_Name"])
+        out.append(f"counters of {directory} (median per dispatch, summed over the device):")
+        for want in kernels:
+            rows = [c for d, c in per_dispatch.items() if want in names[d]]
+            if not rows:
+                continue
+            # a kernel used for two problem shapes: keep the cluster with the larger first counter
+            key = sorted(rows[0])[0]
+            vals = [r[key] for r in rows]
+            if len(vals) > 8 and max(vals) > 1.5 * min(vals):
+                cut = (max(vals) * min(vals)) ** 0.5
+                rows = [r for r in rows if r[key] >= cut]
+            out.append(f"  {want}: {len(rows)} dispatches")
+            for k in sorted(rows[0]):
+                out.append(f"     {k:34s} {statistics.median(r[k] for r in rows):18.0f}")
+
+
 def main() -> int:
     ap = argparse.ArgumentParser(description=__doc__, formatter_class=argparse.RawDescriptionHelpFormatter)
     ap.add_argument("--kernel-trace", help="output directory of the rocprofv3 --kernel-trace --stats run")
@@ -136,6 +165,9 @@ def main() -> int:
     ap.add_argument("--bench-json", help="stdout of bench.py under the kernel-trace run")
     ap.add_argument("--config", type=int, default=3)
     ap.add_argument("--dominant", default="linear_mfma_wreg<K=768>", help="short name (substring) of the dominant kernel")
+    ap.add_argument("--counters", nargs="*", default=[], help="output directories of further rocprofv3 --pmc runs (SQ_* ...)")
+    ap.add_argument("--kernels", default="linear_mfma_wreg<K=768>,linear_mfma_persistent<int8>,pts_linear_wres,linear_stream_smallk<fused>,quantize_pts_stream",
+                    help="comma-separated short-name substrings for the --counters table")
     ap.add_argument("--header", help="text file whose content is put in front of the summary (workload, commands)")
     ap.add_argument("--out", help="summary text file to write (default: stdout only)")
     ap.add_argument("--traffic-json", default=os.path.join("profiles", "dominant_kernel_traffic.json"))
@@ -150,6 +182,8 @@ def main() -> int:
         out.append(f"bench.py under the profiler: ms_per_step {bj['ms_per_step']}, roofline {bj['roofline']}")
     if args.kernel_trace:
         kernel_trace_lines(args.kernel_trace, out)
+    if args.counters:
+        counter_table(args.counters, [k for k in args.kernels.split(",") if k], out)
     traffic = {}
     for name, directory in (("FETCH_SIZE", args.fetch), ("WRITE_SIZE", args.write)):
         if not directory:
