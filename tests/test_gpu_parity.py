@@ -523,6 +523,9 @@ FUSED_SKINNY = [  # B, L, K, N, ldy, bias, m: weight-resident fused kernel (N <=
     (83, 199, 768, 50, None, True, False),    # 12 k-steps (depth 4); N not a multiple of 4; no smoothing
     (83, 199, 1536, 72, 80, True, True),      # padded output rows
     (66, 250, 1600, 16, None, True, True),    # 25 k-steps (depth 1); one channel block; M mod 32 = 20
+    (330, 199, 128, 44, None, True, True),    # 65670 rows: one full pass of 16-row units, then a tail of 17 groups of 8 rows
+    (11, 191, 256, 80, None, True, True),     # 2101 rows: a grid of 9 workgroups, 29 or 30 groups each (wavefronts with 2 and 1)
+    (13, 163, 192, 33, None, False, True),    # 2119 rows, M mod 8 = 7: the last group is ragged
 ]
 
 
@@ -828,6 +831,8 @@ STREAM_SHAPES = [  # B, L, K, N, ldy, bias: short reductions, ragged channel cou
     (21, 199, 12, 130, None, True),    # 12-byte int8 rows / 24-byte fp16 rows
     (35, 120, 128, 64, None, True),    # two k-steps
     (33, 127, 100, 33, 40, True),      # odd N with padding; M mod 16 = 15
+    (106, 197, 48, 320, None, True),   # 5 channel groups in 4 parts of 2: the last part is half empty
+    (30, 197, 24, 576, None, False),   # 9 channel groups in 4 parts of 3: the last part is empty
 ]
 
 
