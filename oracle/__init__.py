@@ -19,6 +19,9 @@ from .ptq4vm_oracle import (  # noqa: F401
     quantize_pts_bits,
     pack_int4,
     unpack_int4,
+    e2m3_row_bytes,
+    pack_e2m3,
+    unpack_e2m3,
     quantize_pts_offset,
     weight_rowsum,
     dequant_offset,

@@ -29,6 +29,12 @@
  *   oracle_pack_int4 / oracle_unpack_int4
  *                           two adjacent 4-bit codes per byte, the even index in the low nibble
  *                           (App. B.1 "Quantization").
+ *   oracle_pack_e2m3 / oracle_unpack_e2m3
+ *                           the same 4-bit codes (-7..7) written as 6-bit floating-point numbers
+ *                           (1 sign, 2 exponent, 3 mantissa bits, exponent bias 1: the "E2M3" element
+ *                           of the OCP microscaling formats), which hold every integer of that range
+ *                           exactly; a storage container of the boundary, not a step of the paper's
+ *                           method (the paper packs two's-complement nibbles, App. B.1).
  *   oracle_quantize_pts_offset / oracle_weight_rowsum / oracle_dequant_offset
  *                           PTS with the per-token zero offset that Sec. 5.1 mentions and then
  *                           omits; the offset form is the activation quantizer of Sec. 2.3
@@ -337,6 +343,67 @@ void oracle_unpack_int4(const uint8_t *packed, int8_t *codes, int64_t rows, int6
             codes[r * K + 2 * j] = (int8_t)(lo >= 8 ? lo - 16 : lo);
             codes[r * K + 2 * j + 1] = (int8_t)(hi >= 8 ? hi - 16 : hi);
         }
+}
+
+/* ---- E2M3 container of 4-bit codes.  A 6-bit pattern s e1 e0 m2 m1 m0 stands for
+ *   (-1)^s * 2^(e - 1) * (1 + m / 8)   for e = 1, 2, 3,        (-1)^s * (m / 8)   for e = 0,
+ * so the integers 0..7 are the patterns with values 0, 1, 2, 3, 4, 5, 6, 7 and a clear sign bit, and
+ * their negatives have the sign bit set (zero is always written with a clear sign bit).
+ * A row of K codes is padded with zeros to a multiple of 128 and written in blocks of 96 bytes, one per
+ * 128 codes.  Inside a block, group g = 0..3 holds codes 32 g .. 32 g + 31 as a 192-bit little-endian
+ * string, code j of the group at bits [6 j, 6 j + 6); the first 16 bytes of group g sit at block offset
+ * 16 g, its last 8 bytes at block offset 64 + 8 g. ---- */
+static double e2m3_value(int pattern) {
+    int s = (pattern >> 5) & 1, e = (pattern >> 3) & 3, m = pattern & 7;
+    double mag = e == 0 ? m / 8.0 : ldexp(1.0 + m / 8.0, e - 1);
+    return s ? -mag : mag;
+}
+
+static int e2m3_pattern_of(int code) { /* the pattern whose value is `code`; -1 if there is none */
+    for (int pattern = 0; pattern < 64; pattern++)
+        if (e2m3_value(pattern) == (double)code && !(code == 0 && pattern != 0)) return pattern;
+    return -1;
+}
+
+int64_t oracle_e2m3_row_bytes(int64_t K) { return (K + 127) / 128 * 96; }
+
+/* returns 0, or -1 if a code has no E2M3 pattern (|code| > 7) */
+int oracle_pack_e2m3(const int8_t *codes, uint8_t *packed, int64_t rows, int64_t K) {
+    const int64_t pitch = oracle_e2m3_row_bytes(K);
+    memset(packed, 0, (size_t)(rows * pitch));
+    for (int64_t r = 0; r < rows; r++)
+        for (int64_t k = 0; k < K; k++) {
+            const int pattern = e2m3_pattern_of(codes[r * K + k]);
+            if (pattern < 0) return -1;
+            const int64_t block = k / 128, g = (k % 128) / 32, j = k % 32;
+            for (int b = 0; b < 6; b++) {
+                if (!((pattern >> b) & 1)) continue;
+                const int64_t bit = 6 * j + b;           /* position in the group's 192-bit string */
+                const int64_t byte = bit / 8;            /* 0..23 */
+                const int64_t off = byte < 16 ? 16 * g + byte : 64 + 8 * g + (byte - 16);
+                packed[r * pitch + block * 96 + off] |= (uint8_t)(1u << (bit % 8));
+            }
+        }
+    return 0;
+}
+
+/* returns 0, or -1 if a pattern's value is not an integer (codes of padding positions are skipped) */
+int oracle_unpack_e2m3(const uint8_t *packed, int8_t *codes, int64_t rows, int64_t K) {
+    const int64_t pitch = oracle_e2m3_row_bytes(K);
+    for (int64_t r = 0; r < rows; r++)
+        for (int64_t k = 0; k < K; k++) {
+            const int64_t block = k / 128, g = (k % 128) / 32, j = k % 32;
+            int pattern = 0;
+            for (int b = 0; b < 6; b++) {
+                const int64_t bit = 6 * j + b, byte = bit / 8;
+                const int64_t off = byte < 16 ? 16 * g + byte : 64 + 8 * g + (byte - 16);
+                if ((packed[r * pitch + block * 96 + off] >> (bit % 8)) & 1) pattern |= 1 << b;
+            }
+            const double v = e2m3_value(pattern);
+            if (v != floor(v)) return -1;
+            codes[r * K + k] = (int8_t)v;
+        }
+    return 0;
 }
 
 /* ---- PTS with a per-token zero offset (Sec. 5.1 names it, the PTS equation omits it; Sec. 2.3

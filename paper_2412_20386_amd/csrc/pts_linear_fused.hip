@@ -442,6 +442,9 @@ __device__ __forceinline__ v4i load_quantized_chunk(const char *row_ptr, int64_t
 #ifndef PTQ4VM_STREAM_RB
 #define PTQ4VM_STREAM_RB 1
 #endif
+#ifndef PTQ4VM_STREAM_SKIP
+#define PTQ4VM_STREAM_SKIP 0
+#endif
 constexpr int kStreamRB = PTQ4VM_STREAM_RB;       // 16-row MFMA blocks per unit
 constexpr int kStreamWaves = 16 / kStreamRB;      // wavefronts per workgroup
 constexpr int kStreamPatch = 2048 * kStreamRB;    // bytes of the per-wavefront transposition patch
@@ -567,6 +570,9 @@ __global__ __launch_bounds__(kStreamWaves * 64) void linear_stream_smallk(const 
                     v4i a = {0, 0, 0, 0};
 #pragma unroll
                     for (int ks = 0; ks < KSTEPS; ks++) a = __builtin_amdgcn_mfma_i32_16x16x64_i8(fw[ks], fx[jb][ks], a, 0, 0, 0);
+#if PTQ4VM_STREAM_SKIP & 4
+                    a = fx[jb][0] + i;
+#endif
                     acc[jb][i] = a;
                 }
             }
@@ -594,9 +600,15 @@ __global__ __launch_bounds__(kStreamWaves * 64) void linear_stream_smallk(const 
                     __half2 lo = __floats2half2_rn(out[0], out[1]);
                     __half2 hi = __floats2half2_rn(out[2], out[3]);
                     u32x2 packed = {__builtin_bit_cast(uint32_t, lo), __builtin_bit_cast(uint32_t, hi)};
+#if PTQ4VM_STREAM_SKIP & 2
+                    packed = u32x2{(uint32_t)acc[jb][i][0] ^ (uint32_t)acc[jb][i][1], (uint32_t)acc[jb][i][2] ^ (uint32_t)acc[jb][i][3]};
+#endif
                     *reinterpret_cast<u32x2 *>(patch + patch_chunk(jb * 16 + l16, 2 * i + (lq >> 1)) + (lq & 1) * 8) = packed;
                 }
             asm volatile("" ::: "memory");  // wavefront-private patch: LDS runs a wavefront's accesses in order
+#if PTQ4VM_STREAM_SKIP & 1
+            if (p.M < 0)
+#endif
             if (y_wide && cols_valid == 64 && r_unit + UNIT <= p.M) {  // uniform: whole lines, no per-lane tests
                 __half *dst = p.y + (r_unit + (lane >> 3)) * p.ldy + g * 64 + (lane & 7) * 8;
 #pragma unroll

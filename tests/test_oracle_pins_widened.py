@@ -102,6 +102,72 @@ def test_int4_pack_unpack_is_a_bijection_on_all_bytes():
     assert np.array_equal(oracle.pack_int4(codes), allb)
 
 
+# The E2M3 container of the 4-bit codes (a storage format of the boundary: 6-bit floating-point patterns with
+# 1 sign, 2 exponent and 3 mantissa bits, exponent bias 1, which hold the integers -7..7 exactly).
+def _e2m3_value(pattern):
+    s, e, m = (pattern >> 5) & 1, (pattern >> 3) & 3, pattern & 7
+    mag = Fraction(m, 8) if e == 0 else Fraction(2) ** (e - 1) * (1 + Fraction(m, 8))
+    return -mag if s else mag
+
+
+def test_e2m3_patterns_of_the_integers_by_hand_and_by_value():
+    # By hand: 1 = 2^0 * 1.000 -> e = 1, m = 0 -> 0b0_01_000 = 8;  3 = 2^1 * 1.100b -> e = 2, m = 4 -> 0b0_10_100 = 20;
+    # -7 = -(2^2 * 1.110b) -> s = 1, e = 3, m = 6 -> 0b1_11_110 = 62.  Three codes fill bits 0..17 of the row:
+    # 8 | 62 << 6 | 20 << 12 = 0x014F88 -> bytes 88 4F 01.
+    packed = oracle.pack_e2m3(np.array([[1, -7, 3]], np.int8))
+    assert packed.shape == (1, 96) and oracle.e2m3_row_bytes(3) == 96
+    assert packed[0, :3].tolist() == [0x88, 0x4F, 0x01] and not packed[0, 3:].any()
+    # Every integer of the range: the stored pattern's value under the format's definition is the integer,
+    # zero has a clear sign bit, and the patterns are the 15 distinct ones with integer values up to 7.
+    for v in range(-7, 8):
+        pattern = int(oracle.pack_e2m3(np.array([[v]], np.int8))[0, 0]) & 63
+        assert _e2m3_value(pattern) == v, (v, pattern)
+        if v == 0:
+            assert pattern == 0
+    for bad in (-8, 8, 100):
+        with pytest.raises(ValueError):
+            oracle.pack_e2m3(np.array([[bad]], np.int8))
+
+
+def test_e2m3_block_layout_by_hand():
+    # 256 codes = two 96-byte blocks.  Code k sits in block k // 128, group g = (k % 128) // 32, at bits
+    # [6 j, 6 j + 6) of the group's 24-byte string (j = k % 32); string bytes 0..15 at block offset 16 g,
+    # bytes 16..23 at block offset 64 + 8 g.
+    codes = np.zeros((1, 256), np.int8)
+    codes[0, 32] = 1      # group 1, j = 0: bits 0..5 of string byte 0 -> block offset 16, value 8
+    codes[0, 21] = 7      # group 0, j = 21: bits 126..131: pattern 30 = 0b011110; its bits 0,1 -> byte 15 bits 6,7 (0x80),
+    #                       its bits 2..5 (0b0111) -> byte 16 = block offset 64, value 0x07
+    codes[0, 255] = -1    # block 1, group 3, j = 31: bits 186..191 = byte 23 bits 2..7: pattern 40 = 0b101000 -> 0xA0
+    #                       at block offset 64 + 24 + 7 = 95 of block 1
+    packed = oracle.pack_e2m3(codes)
+    assert packed.shape == (1, 192)
+    want = np.zeros(192, np.uint8)
+    want[16], want[15], want[64], want[96 + 95] = 0x08, 0x80, 0x07, 0xA0
+    assert np.array_equal(packed[0], want)
+    assert np.array_equal(oracle.unpack_e2m3(packed, 256), codes)
+
+
+@pytest.mark.parametrize("K", [1, 31, 32, 33, 127, 128, 129, 384, 500])
+def test_e2m3_round_trip_and_zero_padding(K):
+    rng = np.random.default_rng(K)
+    codes = rng.integers(-7, 8, size=(5, K)).astype(np.int8)
+    packed = oracle.pack_e2m3(codes)
+    assert packed.shape == (5, (K + 127) // 128 * 96)
+    assert np.array_equal(oracle.unpack_e2m3(packed, K), codes)
+    # Independent decode of the bit string: gather each group's 24 bytes, read 6-bit fields, map by value.
+    by_value = {p: int(_e2m3_value(p)) for p in range(64) if _e2m3_value(p).denominator == 1}
+    Kp = (K + 127) // 128 * 128
+    full = np.zeros((5, Kp), np.int64)
+    for r in range(5):
+        for blk in range(Kp // 128):
+            b = packed[r, blk * 96:(blk + 1) * 96]
+            for g in range(4):
+                string = int.from_bytes(bytes(b[16 * g:16 * g + 16]) + bytes(b[64 + 8 * g:72 + 8 * g]), "little")
+                for j in range(32):
+                    full[r, blk * 128 + 32 * g + j] = by_value[(string >> (6 * j)) & 63]
+    assert np.array_equal(full[:, :K], codes) and not full[:, K:].any()
+
+
 def test_bits_8_reduces_to_the_pinned_8_bit_functions_and_4_bit_range():
     rng = np.random.default_rng(21)
     B, L, K, N = 2, 9, 32, 12
