@@ -10,6 +10,10 @@ from .binding import (  # noqa: F401
     fold_smoothing_w4,
     quantize_pts_a4,
     w4a4_linear,
+    e2m3_row_bytes,
+    fold_smoothing_w4_e2m3,
+    quantize_pts_a4_e2m3,
+    w4a4_linear_e2m3,
     quantize_dynamic,
     quantize_pts,
     quantize_pts_offset,

@@ -27,6 +27,9 @@ EXPORTS = (
     "ptq4vm_fold_smoothing_w4",
     "ptq4vm_quantize_pts_a4",
     "ptq4vm_w4a4_linear",
+    "ptq4vm_fold_smoothing_w4_e2m3",
+    "ptq4vm_quantize_pts_a4_e2m3",
+    "ptq4vm_w4a4_linear_e2m3",
     "ptq4vm_w8a8_linear",
     "ptq4vm_w8a8_linear_fused",
     "ptq4vm_f16_linear",
@@ -75,6 +78,12 @@ def load() -> ctypes.CDLL:
     lib.ptq4vm_quantize_pts_a4.argtypes = [vp, vp, vp, vp, i64, i64, i64, i64, i64, vp]
     lib.ptq4vm_w4a4_linear.restype = ci
     lib.ptq4vm_w4a4_linear.argtypes = [vp, vp, vp, vp, vp, vp, vp, i64, i64, i64, i64, i64, i64, i64, vp]
+    lib.ptq4vm_fold_smoothing_w4_e2m3.restype = ci
+    lib.ptq4vm_fold_smoothing_w4_e2m3.argtypes = [vp, vp, vp, vp, vp, i64, i64, i64, i64, vp]
+    lib.ptq4vm_quantize_pts_a4_e2m3.restype = ci
+    lib.ptq4vm_quantize_pts_a4_e2m3.argtypes = [vp, vp, vp, vp, i64, i64, i64, i64, i64, vp]
+    lib.ptq4vm_w4a4_linear_e2m3.restype = ci
+    lib.ptq4vm_w4a4_linear_e2m3.argtypes = [vp, vp, vp, vp, vp, vp, vp, i64, i64, i64, i64, i64, i64, i64, vp]
     lib.ptq4vm_w8a8_linear.restype = ci
     lib.ptq4vm_w8a8_linear.argtypes = [vp, vp, vp, vp, vp, vp, vp, i64, i64, i64, i64, i64, i64, i64, vp]
     lib.ptq4vm_w8a8_linear_fused.restype = ci
@@ -294,6 +303,63 @@ def w4a4_linear(xq4: torch.Tensor, wq4: torch.Tensor, s_tok: torch.Tensor, s_w: 
         raise TypeError("acc_out: expected a dense CUDA int32 [M, N] tensor")
     check(load().ptq4vm_w4a4_linear(_ptr(xq4), _ptr(wq4), _ptr(s_tok), _ptr(s_w), _ptr(bias), _ptr(y), _ptr(acc_out),
                                     B, L, 2 * K2, N, ldxq, ldwq, ldy, _stream()))
+    return y
+
+
+def e2m3_row_bytes(K: int) -> int:
+    """PTQ4VM_E2M3_ROW_BYTES: bytes of a row of K codes in the E2M3 container (96 per started block of 128)."""
+    return (K + 127) // 128 * 96
+
+
+def fold_smoothing_w4_e2m3(w: torch.Tensor, m: torch.Tensor, wq6: Optional[torch.Tensor] = None):
+    """ptq4vm_fold_smoothing_w4_e2m3: (wq6 uint8 [N, e2m3_row_bytes(K)], s_w f32 [N], inv_m f32 [K])."""
+    N, K, ldw = _matrix(w, torch.float16, "w")
+    _vector(m, torch.float32, K, "m")
+    if wq6 is None:
+        wq6 = torch.empty((N, e2m3_row_bytes(K)), dtype=torch.uint8, device=w.device)
+    _, _, ldwq = _matrix(wq6, torch.uint8, "wq6")
+    s_w = torch.empty(N, dtype=torch.float32, device=w.device)
+    inv_m = torch.empty(K, dtype=torch.float32, device=w.device)
+    check(load().ptq4vm_fold_smoothing_w4_e2m3(_ptr(w), _ptr(m), _ptr(wq6), _ptr(s_w), _ptr(inv_m), N, K, ldw, ldwq,
+                                               _stream()))
+    return wq6, s_w, inv_m
+
+
+def quantize_pts_a4_e2m3(x: torch.Tensor, inv_m: Optional[torch.Tensor], s_tok: torch.Tensor, B: int, L: int,
+                         xq6: Optional[torch.Tensor] = None) -> torch.Tensor:
+    """ptq4vm_quantize_pts_a4_e2m3: xq6 uint8 [B*L, e2m3_row_bytes(K)], 4-bit codes as E2M3 patterns."""
+    M, K, ldx = _matrix(x, torch.float16, "x")
+    if M != B * L:
+        raise ValueError("x must have B*L rows")
+    _vector(inv_m, torch.float32, K, "inv_m", optional=True)
+    _vector(s_tok, torch.float32, L, "s_tok")
+    if xq6 is None:
+        xq6 = torch.empty((M, e2m3_row_bytes(K)), dtype=torch.uint8, device=x.device)
+    _, _, ldxq = _matrix(xq6, torch.uint8, "xq6")
+    check(load().ptq4vm_quantize_pts_a4_e2m3(_ptr(x), _ptr(inv_m), _ptr(s_tok), _ptr(xq6), B, L, K, ldx, ldxq,
+                                             _stream()))
+    return xq6
+
+
+def w4a4_linear_e2m3(xq6: torch.Tensor, wq6: torch.Tensor, s_tok: torch.Tensor, s_w: torch.Tensor,
+                     bias: Optional[torch.Tensor], B: int, L: int, K: int, y: Optional[torch.Tensor] = None,
+                     acc_out: Optional[torch.Tensor] = None) -> torch.Tensor:
+    """ptq4vm_w4a4_linear_e2m3: y fp16 [B*L, N] from operands in the E2M3 container (K codes per row)."""
+    M, _, ldxq = _matrix(xq6, torch.uint8, "xq6")
+    N, _, ldwq = _matrix(wq6, torch.uint8, "wq6")
+    if M != B * L:
+        raise ValueError("shape mismatch")
+    _vector(s_tok, torch.float32, L, "s_tok")
+    _vector(s_w, torch.float32, N, "s_w")
+    _vector(bias, torch.float16, N, "bias", optional=True)
+    if y is None:
+        y = torch.empty((M, N), dtype=torch.float16, device=xq6.device)
+    _, _, ldy = _matrix(y, torch.float16, "y")
+    if acc_out is not None and (acc_out.dtype != torch.int32 or tuple(acc_out.shape) != (M, N)
+                                or not acc_out.is_contiguous() or not acc_out.is_cuda):
+        raise TypeError("acc_out: expected a dense CUDA int32 [M, N] tensor")
+    check(load().ptq4vm_w4a4_linear_e2m3(_ptr(xq6), _ptr(wq6), _ptr(s_tok), _ptr(s_w), _ptr(bias), _ptr(y),
+                                         _ptr(acc_out), B, L, K, N, ldxq, ldwq, ldy, _stream()))
     return y
 
 
