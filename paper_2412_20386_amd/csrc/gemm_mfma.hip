@@ -1183,9 +1183,9 @@ int dispatch(LinearArgs a, hipStream_t stream) {
     const bool dma_ok = la == 16 && a.k_bytes % kSlabBytes == 0 && a.ldx_bytes * 256 < (1LL << 31) &&
                         a.ldw_bytes * 256 < (1LL << 31);
 #if PTQ4VM_STREAM_SMALLK
-    if constexpr (Path::kElemBytes == 1 && !Path::kOffset && !Path::kPacked4) {
-        if (a.k_bytes <= 128) {  // many rows: whole rows of y streamed out by one wavefront each
-            const int rc = launch_stream_smallk(a, false, stream);
+    if constexpr (Path::kElemBytes == 1 && !Path::kOffset) {
+        if (a.k_bytes <= (Path::kPacked4 ? 64 : 128)) {  // many rows: whole rows of y streamed out by one wavefront each
+            const int rc = launch_stream_smallk(a, false, stream, Path::kPacked4);
             if (rc <= 0) return rc;
         }
     }

@@ -456,7 +456,8 @@ __device__ __forceinline__ void lds_write_b128(uint32_t addr, v4f v) {
 // quantize: x holds fp16 activations and inv_m / xq_out are honoured; otherwise x holds int8 codes.
 // Returns PTQ4VM_OK after a launch, a negative status on error, or 1 if the shape does not fit
 // this kernel (nothing was launched; the caller picks another one).
-int launch_stream_smallk(const LinearArgs &a, bool quantize, hipStream_t stream);
+// packed4: x and w hold two 4-bit codes per byte (k_bytes = K / 2), expanded on chip; not with `quantize`.
+int launch_stream_smallk(const LinearArgs &a, bool quantize, hipStream_t stream, bool packed4 = false);
 
 // Weights-in-registers kernel for wide int8 linears with a short reduction (K = 384 or 768, e.g. the
 // in_proj of the Vim-S / Vim-B stacks), defined in gemm_wreg.hip.  Same return convention.

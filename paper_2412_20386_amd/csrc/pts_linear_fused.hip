@@ -469,8 +469,9 @@ __host__ __device__ __forceinline__ StreamLayout stream_layout(int N, int ksteps
     return l;
 }
 
-template <int KSTEPS, bool QUANT, int X_ALIGN, int W_ALIGN>
+template <int KSTEPS, bool QUANT, int X_ALIGN, int W_ALIGN, bool PACKED4 = false>
 __global__ __launch_bounds__(kStreamWaves * 64) void linear_stream_smallk(const LinearArgs p) {
+    static_assert(!(QUANT && PACKED4), "the fused form quantizes to 8 bits");
     const int tid = threadIdx.x, lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);  // scalar: unit numbers and row bounds stay in SGPRs
     const int l16 = lane & 15, lq = lane >> 4;
@@ -486,14 +487,24 @@ __global__ __launch_bounds__(kStreamWaves * 64) void linear_stream_smallk(const 
 
     // Set-up: weight (zero beyond N and K), scales, bias.
     {
-        constexpr int CPR = 4 * KSTEPS;  // 16-byte chunks per weight row
+        constexpr int CPR = 4 * KSTEPS;  // 16-byte chunks per weight row in LDS
+        if constexpr (PACKED4) {
+            // a packed chunk (32 codes) becomes two int8 chunks, codes times 16: even reduction indices, then odd ones
+            for (int idx = tid; idx < lay.rows * (CPR / 2); idx += kStreamWaves * 64) {
+                const int row = idx / (CPR / 2), c = idx - row * (CPR / 2);
+                const v4i v = load_chunk<W_ALIGN, 1>(p.w + (int64_t)min(row, N - 1) * p.ldw_bytes, c * 16, K, row < N);
+                *reinterpret_cast<v4i *>(w_lds + row * lay.pitch + (((2 * c) ^ swz(row)) << 4)) = Int4Path::even_codes(v);
+                *reinterpret_cast<v4i *>(w_lds + row * lay.pitch + (((2 * c + 1) ^ swz(row)) << 4)) = Int4Path::odd_codes(v);
+            }
+        } else
         for (int idx = tid; idx < lay.rows * CPR; idx += kStreamWaves * 64) {
             const int row = idx / CPR, c = idx - row * CPR;
             const v4i v = load_chunk<W_ALIGN, 1>(p.w + (int64_t)min(row, N - 1) * p.ldw_bytes, c * 16, K, row < N);
             *reinterpret_cast<v4i *>(w_lds + row * lay.pitch + ((c ^ swz(row)) << 4)) = v;
         }
         for (int o = tid; o < lay.rows; o += kStreamWaves * 64) {
-            cs_lds[o] = o < N ? p.s_w[o] : 0.0f;
+            // packed operands are codes times 16: the accumulator is 256 times the sum, undone here (a power of two: exact)
+            cs_lds[o] = o < N ? (PACKED4 ? p.s_w[o] * (1.0f / 256.0f) : p.s_w[o]) : 0.0f;
             cb_lds[o] = (o < N && p.bias) ? __half2float(p.bias[o]) : 0.0f;
         }
         if constexpr (QUANT) {
@@ -546,6 +557,10 @@ __global__ __launch_bounds__(kStreamWaves * 64) void linear_stream_smallk(const 
                             if (k0 + b < K) p.xq_out[r * p.ldxq_out + k0 + b] = (int8_t)((uint32_t)codes[b >> 2] >> (8 * (b & 3)));
                     }
                     fx[jb][ks] = codes;
+                } else if constexpr (PACKED4) {
+                    // int8 chunk 4 ks + lq comes from packed chunk (4 ks + lq) / 2: its even codes, or its odd ones
+                    const v4i packed = load_chunk<X_ALIGN, 1>(xrow, ((4 * ks + lq) >> 1) * 16, K, true);
+                    fx[jb][ks] = (lq & 1) ? Int4Path::odd_codes(packed) : Int4Path::even_codes(packed);
                 } else {
                     fx[jb][ks] = load_chunk<X_ALIGN, 1>(xrow, k0, K, true);
                 }
@@ -587,7 +602,7 @@ __global__ __launch_bounds__(kStreamWaves * 64) void linear_stream_smallk(const 
                         for (int c = 0; c < 4; c++) {
                             const int64_t r = r_unit + jb * 16 + l16;
                             const int col = i * 16 + lq * 4 + c;
-                            if (r < p.M && col < cols_valid) p.acc_out[r * p.N + g * 64 + col] = acc[jb][i][c];
+                            if (r < p.M && col < cols_valid) p.acc_out[r * p.N + g * 64 + col] = PACKED4 ? acc[jb][i][c] >> 8 : acc[jb][i][c];
                         }
             }
 #pragma unroll
@@ -745,17 +760,17 @@ __global__ __launch_bounds__(kThreads, 2) void pts_linear_generic(const LinearAr
 // ------------------------------------------------------------------------------------------
 // Host side
 // ------------------------------------------------------------------------------------------
-template <int KSTEPS, bool QUANT>
+template <int KSTEPS, bool QUANT, bool PACKED4 = false>
 int launch_stream_aligned(const LinearArgs &a, int xa, int wa, const StreamLayout &lay, unsigned wgs, hipStream_t stream) {
     using Kernel = void (*)(const LinearArgs);
     // [activation alignment 16 / 4 / 0][weight alignment 16 / 4 / 0]
     static const Kernel kernels[3][3] = {
-        {linear_stream_smallk<KSTEPS, QUANT, 16, 16>, linear_stream_smallk<KSTEPS, QUANT, 16, 4>,
-         linear_stream_smallk<KSTEPS, QUANT, 16, 0>},
-        {linear_stream_smallk<KSTEPS, QUANT, 4, 16>, linear_stream_smallk<KSTEPS, QUANT, 4, 4>,
-         linear_stream_smallk<KSTEPS, QUANT, 4, 0>},
-        {linear_stream_smallk<KSTEPS, QUANT, 0, 16>, linear_stream_smallk<KSTEPS, QUANT, 0, 4>,
-         linear_stream_smallk<KSTEPS, QUANT, 0, 0>}};
+        {linear_stream_smallk<KSTEPS, QUANT, 16, 16, PACKED4>, linear_stream_smallk<KSTEPS, QUANT, 16, 4, PACKED4>,
+         linear_stream_smallk<KSTEPS, QUANT, 16, 0, PACKED4>},
+        {linear_stream_smallk<KSTEPS, QUANT, 4, 16, PACKED4>, linear_stream_smallk<KSTEPS, QUANT, 4, 4, PACKED4>,
+         linear_stream_smallk<KSTEPS, QUANT, 4, 0, PACKED4>},
+        {linear_stream_smallk<KSTEPS, QUANT, 0, 16, PACKED4>, linear_stream_smallk<KSTEPS, QUANT, 0, 4, PACKED4>,
+         linear_stream_smallk<KSTEPS, QUANT, 0, 0, PACKED4>}};
     auto idx = [](int al) { return al == 16 ? 0 : (al == 4 ? 1 : 2); };
     const Kernel kernel = kernels[idx(xa)][idx(wa)];
     if (int rc = ptq4vm::set_lds_limit(reinterpret_cast<const void *>(kernel), kLdsBytes, "hipFuncSetAttribute(linear_stream_smallk)")) return rc;
@@ -838,15 +853,16 @@ int dispatch(LinearArgs a, hipStream_t stream) {
 
 }  // namespace
 
-int ptq4vm::mfma::launch_stream_smallk(const LinearArgs &a, bool quantize, hipStream_t stream) {
+int ptq4vm::mfma::launch_stream_smallk(const LinearArgs &a, bool quantize, hipStream_t stream, bool packed4) {
     auto align_of = [](const void *base, int64_t pitch_bytes) {
         if (ptq4vm::aligned_to(base, 16) && pitch_bytes % 16 == 0) return 16;
         if (ptq4vm::aligned_to(base, 4) && pitch_bytes % 4 == 0) return 4;
         return 0;
     };
     const int xa = align_of(a.x, a.ldx_bytes), wa = align_of(a.w, a.ldw_bytes);
-    if (a.k_bytes > 128 || a.M < (quantize ? kStreamMinRowsFused : kStreamMinRows) || a.M >= (1LL << 31) || a.L >= (1LL << 31) || a.N > 8192) return 1;
-    const int ksteps = a.k_bytes <= 64 ? 1 : 2;
+    const int64_t k_codes = packed4 ? 2 * a.k_bytes : a.k_bytes;  // bytes of K per row once the operands are int8
+    if (k_codes > 128 || (packed4 && quantize) || a.M < (quantize ? kStreamMinRowsFused : kStreamMinRows) || a.M >= (1LL << 31) || a.L >= (1LL << 31) || a.N > 8192) return 1;
+    const int ksteps = k_codes <= 64 ? 1 : 2;
     const StreamLayout lay = stream_layout((int)a.N, ksteps);
     if (lay.total > kLdsBytes) return 1;
     int device = 0, cus = 0;
@@ -857,6 +873,9 @@ int ptq4vm::mfma::launch_stream_smallk(const LinearArgs &a, bool quantize, hipSt
     const int64_t items = ptq4vm::ceil_div(a.M, 16 * kStreamRB) * (lay.groups < 4 ? lay.groups : 4);  // as the kernel counts them
     int64_t wgs = ptq4vm::ceil_div(items, kStreamWaves);
     if (wgs > cus) wgs = cus;  // one workgroup per CU: the resident weight takes most of its LDS
+    if (packed4)
+        return ksteps == 1 ? launch_stream_aligned<1, false, true>(a, xa, wa, lay, (unsigned)wgs, stream)
+                           : launch_stream_aligned<2, false, true>(a, xa, wa, lay, (unsigned)wgs, stream);
     if (quantize)
         return ksteps == 1 ? launch_stream_aligned<1, true>(a, xa, wa, lay, (unsigned)wgs, stream)
                            : launch_stream_aligned<2, true>(a, xa, wa, lay, (unsigned)wgs, stream);

@@ -792,10 +792,12 @@ def test_w4a4_full_size_sampled(cfg, linear):
     _check_w4a4_on_sampled_rows(c, f"cfg{cfg} {c.name}")
 
 
-@pytest.mark.parametrize("B,L,K,N", [(41, 251, 512, 1544), (20, 517, 768, 3400), (300, 65, 24, 776), (250, 33, 100, 520)])
+@pytest.mark.parametrize("B,L,K,N", [(41, 251, 512, 1544), (20, 517, 768, 3400), (300, 65, 24, 776), (250, 33, 100, 520),
+                                     (110, 197, 24, 776), (105, 197, 100, 520), (107, 199, 48, 1536), (104, 197, 128, 130)])
 def test_w4a4_large_ragged_shapes_sampled(B, L, K, N):
-    """Ragged last tiles in the persistent kernel (128-row tiles; 2 and 3 slabs of packed bytes) and in
-    the short-reduction kernel (12 and 50 packed bytes per row)."""
+    """Ragged last tiles in the persistent kernel (128-row tiles; 2 and 3 slabs of packed bytes), in
+    the short-reduction kernel (12 and 50 packed bytes per row) and, from 20 480 rows, in the row-streaming
+    kernel (12, 50, 24 and 64 packed bytes per row: one and two k-steps once expanded, ragged rows and channels)."""
     c = synth.random_problem(6000 + K + N, B, L, K, N, device=DEV)
     _check_w4a4_on_sampled_rows(c, "ragged")
 
