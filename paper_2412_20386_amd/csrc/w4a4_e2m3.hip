@@ -113,6 +113,78 @@ __global__ __launch_bounds__(kThreads) void quantize_pts_a4_e2m3_stream(const __
     }
 }
 
+// Block-column stream (K % 128 == 0, 16-byte aligned rows).  A wavefront owns one block column (128 channels) and
+// walks down the rows 16 at a time.  Loads are whole 256-byte row segments: lane l of load c reads the 8 values
+// of chunk (l mod 16) of row 4 c + l / 16, so a lane keeps the smoothing factors of 8 channels for life.  The 32
+// values of a group are spread over 4 lanes, and the packing instruction wants them in one: the integer-valued
+// floats cross through a wavefront-private LDS patch (group pitch 144 bytes: the 16 lanes of an access phase
+// start 4 banks apart), after which lane G holds group G mod 4 of row G / 4 and writes its 24 bytes.
+constexpr int kPatchPitch = 144;
+constexpr int kPatchBytes = 64 * kPatchPitch;  // per wavefront
+constexpr int kMaxBlockTokens = 4096;        // reciprocal steps of all token positions sit next to the patches (52 KiB in all)
+
+template <bool HAS_M>
+__global__ __launch_bounds__(kThreads) void quantize_pts_a4_e2m3_blocks(const __half *__restrict__ x,
+                                                                        const float *__restrict__ inv_m,
+                                                                        const float *__restrict__ s_tok,
+                                                                        uint8_t *__restrict__ xq6, int64_t M, int L,
+                                                                        int n_blocks, int64_t ldx, int64_t ldxq,
+                                                                        int64_t unit_step) {
+    extern __shared__ __attribute__((aligned(16))) char lds_raw[];
+    float *const inv_s_lds = reinterpret_cast<float *>(lds_raw + (kThreads / 64) * kPatchBytes);
+    for (int i = threadIdx.x; i < L; i += kThreads) inv_s_lds[i] = 1.0f / s_tok[i];  // IEEE division
+    __syncthreads();
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    char *const patch = lds_raw + wave * kPatchBytes;
+    const int64_t gwave = (int64_t)blockIdx.x * (kThreads / 64) + wave;
+    const int block = (int)(gwave % n_blocks);
+    const int chunk = lane & 15, sub = lane >> 4;
+    float im[8];
+#pragma unroll
+    for (int i = 0; i < 8; i++) im[i] = HAS_M ? inv_m[block * 128 + chunk * 8 + i] : 1.0f;
+    // write side: row 4 c + sub, group chunk / 4, floats 8 (chunk mod 4) ..; read side: group `lane`
+    const int wr_off = (sub * 4 + (chunk >> 2)) * kPatchPitch + (chunk & 3) * 32;
+    const int rd_off = lane * kPatchPitch;
+    for (int64_t unit = gwave / n_blocks; unit * 16 < M; unit += unit_step) {
+        const int64_t r0 = unit * 16;
+        u32x4 in[4];
+#pragma unroll
+        for (int c = 0; c < 4; c++) {
+            const int64_t r = r0 + 4 * c + sub;
+            in[c] = u32x4{0, 0, 0, 0};
+            if (r < M) in[c] = __builtin_nontemporal_load(reinterpret_cast<const u32x4 *>(x + r * ldx + block * 128 + chunk * 8));
+        }
+        const int t0 = (int)(r0 % L);
+#pragma unroll
+        for (int c = 0; c < 4; c++) {
+            int t = t0 + 4 * c + sub;
+            t = t >= L ? t % L : t;
+            const float inv_s = inv_s_lds[t];
+            float q[8];
+#pragma unroll
+            for (int e = 0; e < 4; e++) {
+                const uint32_t word = in[c][e];  // a scalar first: a bit cast applied to a vector element misreads it
+                const __half2 h = __builtin_bit_cast(__half2, word);
+                q[2 * e] = code4_as_float(__low2float(h), im[2 * e], inv_s);
+                q[2 * e + 1] = code4_as_float(__high2float(h), im[2 * e + 1], inv_s);
+            }
+            float *dst = reinterpret_cast<float *>(patch + c * 16 * kPatchPitch + wr_off);
+            *reinterpret_cast<float4 *>(dst) = float4{q[0], q[1], q[2], q[3]};
+            *reinterpret_cast<float4 *>(dst + 4) = float4{q[4], q[5], q[6], q[7]};
+        }
+        asm volatile("" ::: "memory");  // wavefront-private patch: LDS runs a wavefront's accesses in order
+        float v[kGroupCodes];
+#pragma unroll
+        for (int i = 0; i < 8; i++) {
+            const float4 f = *reinterpret_cast<const float4 *>(patch + rd_off + 16 * i);
+            v[4 * i] = f.x, v[4 * i + 1] = f.y, v[4 * i + 2] = f.z, v[4 * i + 3] = f.w;
+        }
+        asm volatile("" ::: "memory");
+        const int64_t r = r0 + (lane >> 2);
+        if (r < M) store_group(xq6 + r * ldxq, block * 4 + (lane & 3), pack32_e2m3(v));
+    }
+}
+
 // Any K and any fp16 pitch: one group (32 codes, element-wise guarded loads) per thread-iteration.
 template <bool HAS_M>
 __global__ __launch_bounds__(kThreads) void quantize_pts_a4_e2m3_generic(const __half *__restrict__ x,
@@ -221,6 +293,25 @@ extern "C" int ptq4vm_quantize_pts_a4_e2m3(const void *x_f16, const float *inv_m
     const __half *x = static_cast<const __half *>(x_f16);
     const int64_t groups_padded = ptq4vm::ceil_div(K, 128) * 4;
 
+    if (K % 128 == 0 && ldx % 8 == 0 && ptq4vm::aligned_to(x_f16, 16) && L <= kMaxBlockTokens) {
+        const int64_t n_blocks = K / 128, units = ptq4vm::ceil_div(M, 16);
+        constexpr int kWavesPerWg = kThreads / 64;
+        // about 3 workgroups per CU; the wavefront count is a multiple of the block columns so that every
+        // wavefront keeps its column
+        int64_t waves = 768 * kWavesPerWg;
+        if (waves > units * n_blocks) waves = units * n_blocks;
+        const int64_t lcm = n_blocks * kWavesPerWg / gcd64(n_blocks, kWavesPerWg);
+        waves = ptq4vm::ceil_div(waves, lcm) * lcm;
+        const int64_t blocks = waves / kWavesPerWg;
+        if (blocks > 0x7fffffffLL) return PTQ4VM_ERR_SHAPE;
+        const size_t lds = (size_t)kWavesPerWg * kPatchBytes + (size_t)L * sizeof(float);
+        const dim3 grid((unsigned)blocks), block(kThreads);
+        if (inv_m)
+            quantize_pts_a4_e2m3_blocks<true><<<grid, block, lds, stream>>>(x, inv_m, s_tok, xq6, M, (int)L, (int)n_blocks, ldx, ldxq, waves / n_blocks);
+        else
+            quantize_pts_a4_e2m3_blocks<false><<<grid, block, lds, stream>>>(x, inv_m, s_tok, xq6, M, (int)L, (int)n_blocks, ldx, ldxq, waves / n_blocks);
+        return ptq4vm::check_launch("quantize_pts_a4_e2m3_blocks");
+    }
     if (K % kGroupCodes == 0 && ldx % 8 == 0 && ptq4vm::aligned_to(x_f16, 16)) {
         const int64_t unit = groups_padded / gcd64(groups_padded, kThreads);
         int64_t want = 768;  // about 3 workgroups per CU striding over the rows together

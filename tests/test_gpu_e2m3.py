@@ -136,6 +136,21 @@ def test_e2m3_quantizer_special_values_padding_and_pitch():
         assert (_np(buf[:, ptq.e2m3_row_bytes(K):]) == 0xAB).all()
 
 
+@pytest.mark.parametrize("B,L,K", [(40, 7, 128), (3, 5, 256), (1, 5000, 128), (1, 20000, 128), (7, 33, 96), (2, 9, 1000), (5, 197, 640)])
+@pytest.mark.parametrize("use_m", [True, False])
+def test_e2m3_quantizer_kernels(B, L, K, use_m):
+    """Block-column kernel (K a multiple of 128; token periods shorter than a 16-row unit), the column-stationary
+    kernel (longer token tables, K a multiple of 32 only; per-row division beyond the LDS table) and the element path."""
+    print(f"quantize e2m3 B={B} L={L} K={K} use_m={use_m}", flush=True)
+    c = synth.random_problem(4000 + 3 * L + K, B, L, K, 8, device=DEV)
+    s4 = _steps_4bit(c)
+    inv_m = (1.0 / c.m).contiguous() if use_m else None
+    xq6 = ptq.quantize_pts_a4_e2m3(c.x, inv_m, s4, B, L)
+    torch.cuda.synchronize()
+    want = oracle.quantize_pts_bits(_np(c.x), _np(inv_m) if use_m else None, _np(s4), B, L, 4)
+    assert np.array_equal(_np(xq6), oracle.pack_e2m3(want))
+
+
 def _check_e2m3_on_sampled_rows(c, what):
     M = c.B * c.L
     print(f"w4a4 e2m3 full-size {what}: M={M} K={c.K} N={c.N}", flush=True)
