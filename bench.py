@@ -206,12 +206,22 @@ def measure_config(args, config: int, full: bool):
                                                                  rs_of[id(lin)], lin[li]["s_w"], lin[li]["bias"], B, L,
                                                                  y=lin[li]["y"]))
             # W4A4 (packed 4-bit codes): timing only
-            t4q = t4g = None
+            t4q = t4g = t6q = t6g = None
+            s4 = [(lin[li]["s_tok"] * (127.0 / 7.0)).contiguous() for lin in layers]
+            idx = {id(lin): i for i, lin in enumerate(layers)}
+            row6 = ptq.e2m3_row_bytes(K)
+            if row6 <= K:  # the same codes in the FP6 (E2M3) container, where it fits the int8 code buffer (K % 128 == 0)
+                w6 = [ptq.fold_smoothing_w4_e2m3(lin[li]["w"], 1.0 / lin[li]["inv_m"]) for lin in layers]
+                xq6 = [lin[li]["xq"].view(torch.uint8).view(-1)[: M * row6].view(M, row6) for lin in layers]
+                t6q = time_launch(lambda lin: ptq.quantize_pts_a4_e2m3(lin[li]["x"], lin[li]["inv_m"], s4[idx[id(lin)]], B, L,
+                                                                       xq6=xq6[idx[id(lin)]]))
+                t6g = time_launch(lambda lin: ptq.w4a4_linear_e2m3(xq6[idx[id(lin)]], w6[idx[id(lin)]][0], s4[idx[id(lin)]],
+                                                                   w6[idx[id(lin)]][1], lin[li]["bias"], B, L, K,
+                                                                   y=lin[li]["y"]))
+                del w6
             if K % 2 == 0:
-                s4 = [(lin[li]["s_tok"] * (127.0 / 7.0)).contiguous() for lin in layers]
                 w4 = [ptq.fold_smoothing_w4(lin[li]["w"], 1.0 / lin[li]["inv_m"]) for lin in layers]
                 xq4 = [lin[li]["xq"].view(torch.uint8).view(-1)[: M * (K // 2)].view(M, K // 2) for lin in layers]
-                idx = {id(lin): i for i, lin in enumerate(layers)}
                 t4q = time_launch(lambda lin: ptq.quantize_pts_a4(lin[li]["x"], lin[li]["inv_m"], s4[idx[id(lin)]], B, L,
                                                                   xq4=xq4[idx[id(lin)]]))
                 t4g = time_launch(lambda lin: ptq.w4a4_linear(xq4[idx[id(lin)]], w4[idx[id(lin)]][0], s4[idx[id(lin)]],
@@ -222,6 +232,13 @@ def measure_config(args, config: int, full: bool):
                 a4_quantize_us=None if t4q is None else round(t4q, 2),
                 a4_quantize_GBps=None if t4q is None else round((2.5 * M * K) / t4q / 1e3, 1),
                 w4a4_us=None if t4g is None else round(t4g, 2),
+                a4_e2m3_quantize_us=None if t6q is None else round(t6q, 2),
+                a4_e2m3_quantize_GBps=None if t6q is None else round((2.75 * M * K) / t6q / 1e3, 1),
+                w4a4_e2m3_us=None if t6g is None else round(t6g, 2),
+                w4a4_e2m3_TOPS=None if t6g is None else round(ops / t6g / 1e6, 1),
+                w4a4_best_us=None if (t4g is None and t6g is None) else round(min(t for t in (t4g, t6g) if t is not None), 2),
+                w4a4_best_container=None if (t4g is None and t6g is None)
+                else ("e2m3" if (t6g is not None and (t4g is None or t6g < t4g)) else "nibbles"),
                 dynamic_quantize_us=round(td, 2), dynamic_quantize_GBps=round((q_bytes + 4.0 * M) / td / 1e3, 1))
         if layers[0][li]["fused"]:  # the form the timed step uses for this linear
             tfu = time_launch(lambda lin: ptq.w8a8_linear_fused(lin[li]["x"], lin[li]["inv_m"], lin[li]["s_tok"],
@@ -378,6 +395,14 @@ def main() -> int:
         configs.sort(key=lambda c: c["config"])
 
     tokens_per_s = M / (ms_per_step * 1e-3)
+    # W4A4 (the precision of the paper's latency table, Sec. 6.4): sums of the kernel times measured above, per layer
+    # quantizer + linear in the faster container of each linear (nibbles or E2M3) against quantizer + W8A8 linear.
+    w4a4_sum = w8a8_sum = 0.0
+    for k in r["kernels"]:
+        pairs = [(k.get("a4_quantize_us"), k.get("w4a4_us")), (k.get("a4_e2m3_quantize_us"), k.get("w4a4_e2m3_us"))]
+        pairs = [q + g for q, g in pairs if q is not None and g is not None]
+        w4a4_sum = w4a4_sum + min(pairs) if (pairs and w4a4_sum is not None) else None
+        w8a8_sum += k["quantize_us"] + k["w8a8_us"]
     out = {
         "metric": "W8A8 linear TOPS + tokens/sec, Vim-B shapes batch 256; speedup vs fp16 GEMM",
         "value": round(tokens_per_s, 1),
@@ -399,6 +424,9 @@ def main() -> int:
         "graph_ms_per_step": None if r["graph_ms_per_step"] is None else round(r["graph_ms_per_step"], 4),
         "dynamic_ms_per_step": round(r["dynamic_ms_per_step"], 4),
         "speedup_pts_vs_per_token_dynamic": round(r["dynamic_ms_per_step"] / ms_per_step, 3),
+        "w4a4_two_launch_us_per_layer": None if w4a4_sum is None else round(w4a4_sum, 1),
+        "w8a8_two_launch_us_per_layer": round(w8a8_sum, 1),
+        "speedup_w4a4_vs_w8a8_kernel_sums": None if not w4a4_sum else round(w8a8_sum / w4a4_sum, 3),
         "paper_context": "paper: up to 1.83x end-to-end at W4A4 on VMamba-B, batch 32, RTX 3090 (not this metric)",
         "roofline": roofline,
         "cpu_baseline": r["cpu"],
