@@ -19,11 +19,13 @@ import csv
 import glob
 import json
 import os
+import re
 import statistics
 import sys
 
 OURS = ("linear_", "pts_linear", "quantize_", "fold_smoothing", "weight_rowsum", "count_bad_scales", "sum_bad_scales")
-BASES = ("linear_mfma_wreg", "linear_mfma_persistent", "linear_mfma_smallk", "linear_mfma_dma", "linear_mfma_generic",
+BASES = ("linear_e2m3_persistent", "linear_e2m3_generic", "quantize_pts_a4_e2m3_blocks", "quantize_pts_a4_e2m3_stream",
+         "quantize_pts_a4_e2m3_generic", "fold_smoothing_w4_e2m3_rows", "linear_mfma_wreg", "linear_mfma_persistent", "linear_mfma_smallk", "linear_mfma_dma", "linear_mfma_generic",
          "linear_mfma_wres", "linear_stream_smallk", "pts_linear_wres", "pts_linear_generic", "quantize_pts_a4_stream",
          "quantize_pts_stream", "quantize_pts_generic", "quantize_dynamic_rows", "fold_smoothing_w4_rows",
          "fold_smoothing_rows", "weight_rowsum_rows", "count_bad_scales", "sum_bad_scales")
@@ -40,8 +42,10 @@ def short(name: str) -> str:
         if t in name:
             tag = label
             break
-    if base == "linear_stream_smallk":
-        tag = "<fused>" if ("ELb1E" in name or ", true," in name) else "<int8>"
+    if base == "linear_stream_smallk":  # template arguments: k-steps, fused quantizer, two alignments, packed 4-bit operands
+        m = re.search(r"smallkILi\d+ELb([01])ELi\d+ELi\d+ELb([01])E", name) or re.search(r"smallk<\d+, (true|false), \d+, \d+, (true|false)>", name)
+        fused, packed = (m.group(1) in ("1", "true"), m.group(2) in ("1", "true")) if m else (False, False)
+        tag = "<fused>" if fused else ("<int4>" if packed else "<int8>")
     if base == "linear_mfma_wreg":
         tag = "<K=768>" if ("ILi12E" in name or "<12," in name) else "<K=384>"
     return base + tag
