@@ -118,17 +118,28 @@ __global__ __launch_bounds__(kThreads) void linear_e2m3_generic(const LinearArgs
 // Requirements (host-checked): K a multiple of 128 and at least 256 codes, 16-byte aligned operand rows,
 // N a multiple of 8, y rows 16-byte aligned, 4-byte aligned bias, 256 row pitches below 2^31, L < 2^31.
 // ------------------------------------------------------------------------------------------
-constexpr int kTile = 256;
-constexpr int kStages = 3;
-constexpr int kStageBytes = 2 * kTile * kBlockBytes;  // 48 KiB
-constexpr int kScaleBytes = kTile * 4 + kTile * 4 + kTile * 2;
+// Tile geometry: BR token rows x 256 channels; 4 wavefronts side by side along the channels per 128 rows.
+#ifndef PTQ4VM_E2M3_BR
+#define PTQ4VM_E2M3_BR 256
+#endif
+#ifndef PTQ4VM_E2M3_STAGES
+#define PTQ4VM_E2M3_STAGES 3
+#endif
+constexpr int kTile = 256;                 // channels per tile
+constexpr int kTileRows = PTQ4VM_E2M3_BR;  // token rows per tile: 256 (one workgroup of 8 wavefronts per CU) or 128 (two of 4)
+constexpr int kStages = PTQ4VM_E2M3_STAGES;
+constexpr int kWavesPerWg = 4 * kTileRows / 128;
+constexpr int kStageBytes = (kTileRows + kTile) * kBlockBytes;
+constexpr int kScaleBytes = kTile * 4 + kTileRows * 4 + kTile * 2;
 constexpr int kPersistentLds = kStages * kStageBytes + 2 * kScaleBytes;
+static_assert(kTileRows == 256 || kTileRows == 128, "tile height");
 
 template <bool HAS_BIAS, bool DUMP_ACC>
-__global__ __launch_bounds__(512, 1) void linear_e2m3_persistent(const LinearArgs p) {
-    constexpr int NW = 8, FR = 8, FO = 4, WAVE_R = 128, WAVE_O = 64;
-    constexpr int COPIES = kTile * 6 / 64 / NW;  // 1 KiB copies per wavefront and tile half: 3
-    constexpr int LOADS_PER_BLOCK = 2 * COPIES;
+__global__ __launch_bounds__(kWavesPerWg * 64, 2) void linear_e2m3_persistent(const LinearArgs p) {
+    constexpr int NW = kWavesPerWg, FR = 8, FO = 4, WAVE_R = 128, WAVE_O = 64;
+    constexpr int X_COPIES = kTileRows * 6 / 64 / NW;  // 1 KiB copies per wavefront and stage: 3 of token rows,
+    constexpr int W_COPIES = kTile * 6 / 64 / NW;      // 3 or 6 of weight rows
+    constexpr int LOADS_PER_BLOCK = X_COPIES + W_COPIES;
     constexpr int KEEP = (kStages - 2) * LOADS_PER_BLOCK;  // copies allowed in flight when a block is needed
 
     char *const ring = lds_dyn;
@@ -158,35 +169,40 @@ __global__ __launch_bounds__(512, 1) void linear_e2m3_persistent(const LinearArg
     // ---- producer: the next block to copy, possibly of a later tile than the one being computed
     int pf_tile = first, pf_block = 0, pf_stage = 0, issued = 0;
     const char *pf_x = nullptr, *pf_w = nullptr;
-    uint32_t x_off[COPIES], w_off[COPIES];
+    uint32_t x_off[X_COPIES], w_off[W_COPIES];
     auto pf_setup = [&]() {
         const int to = pf_tile % p.tiles_o, tr = pf_tile / p.tiles_o;
-        const int64_t r0 = (int64_t)tr * kTile, o0 = (int64_t)to * kTile;
+        const int64_t r0 = (int64_t)tr * kTileRows, o0 = (int64_t)to * kTile;
         pf_x = p.x + r0 * p.ldx_bytes;
         pf_w = p.w + o0 * p.ldw_bytes;
-        const int rows_x = (int)min((int64_t)kTile, p.M - r0), rows_w = (int)min((int64_t)kTile, p.N - o0);
+        const int rows_x = (int)min((int64_t)kTileRows, p.M - r0), rows_w = (int)min((int64_t)kTile, p.N - o0);
+        // 16-byte chunk q of a stage half: row q / 6, chunk q mod 6; rows with bit 3 set keep chunk pairs swapped.
+        // Rows beyond the matrix are clamped: their results are never stored.
 #pragma unroll
-        for (int i = 0; i < COPIES; i++) {
-            const int q = (wave + NW * i) * 64 + lane;  // 16-byte chunk of the stage half
+        for (int i = 0; i < X_COPIES; i++) {
+            const int q = (wave + NW * i) * 64 + lane;
             const int row = q / 6, c = q - row * 6;
-            const int src = c ^ ((row >> 3) & 1);       // rows with bit 3 set: chunk pairs swapped
-            // rows beyond the matrix are clamped: their results are never stored
-            x_off[i] = (uint32_t)min(row, rows_x - 1) * (uint32_t)p.ldx_bytes + src * 16;
-            w_off[i] = (uint32_t)min(row, rows_w - 1) * (uint32_t)p.ldw_bytes + src * 16;
+            x_off[i] = (uint32_t)min(row, rows_x - 1) * (uint32_t)p.ldx_bytes + (c ^ ((row >> 3) & 1)) * 16;
+        }
+#pragma unroll
+        for (int i = 0; i < W_COPIES; i++) {
+            const int q = (wave + NW * i) * 64 + lane;
+            const int row = q / 6, c = q - row * 6;
+            w_off[i] = (uint32_t)min(row, rows_w - 1) * (uint32_t)p.ldw_bytes + (c ^ ((row >> 3) & 1)) * 16;
         }
     };
     auto issue = [&]() {  // copy the producer's block into ring stage pf_stage, then advance
         char *sx = ring + pf_stage * kStageBytes;
-        char *sw = sx + kTile * kBlockBytes;
+        char *sw = sx + kTileRows * kBlockBytes;
         const char *gx = pf_x + (int64_t)pf_block * kBlockBytes;
         const char *gw = pf_w + (int64_t)pf_block * kBlockBytes;
 #pragma unroll
-        for (int i = 0; i < ((PTQ4VM_E2M3_SKIP & 4) ? 0 : COPIES); i++)
+        for (int i = 0; i < ((PTQ4VM_E2M3_SKIP & 4) ? 0 : X_COPIES); i++)
             __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void *)(gx + x_off[i]),
                                              (__attribute__((address_space(3))) void *)(sx + (wave + NW * i) * 1024),
                                              16, 0, 0);
 #pragma unroll
-        for (int i = 0; i < ((PTQ4VM_E2M3_SKIP & 4) ? 0 : COPIES); i++)
+        for (int i = 0; i < ((PTQ4VM_E2M3_SKIP & 4) ? 0 : W_COPIES); i++)
             __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void *)(gw + w_off[i]),
                                              (__attribute__((address_space(3))) void *)(sw + (wave + NW * i) * 1024),
                                              16, 0, 0);
@@ -214,29 +230,30 @@ __global__ __launch_bounds__(512, 1) void linear_e2m3_persistent(const LinearArg
     int stage = 0, g = 0, parity = 0;  // consumer: ring stage, running block number, scale buffer
     for (int tile = first; tile < last; tile += wpx, parity ^= 1) {
         const int tile_o = tile % p.tiles_o, tile_r = tile / p.tiles_o;
-        const int64_t r0 = (int64_t)tile_r * kTile, o0 = (int64_t)tile_o * kTile;
-        const int rows_valid = (int)min((int64_t)kTile, p.M - r0), cols_valid = (int)min((int64_t)kTile, p.N - o0);
+        const int64_t r0 = (int64_t)tile_r * kTileRows, o0 = (int64_t)tile_o * kTile;
+        const int rows_valid = (int)min((int64_t)kTileRows, p.M - r0), cols_valid = (int)min((int64_t)kTile, p.N - o0);
         float *const cs_lds = reinterpret_cast<float *>(scales + parity * kScaleBytes);  // s_w of the tile's channels
         float *const rs_lds = cs_lds + kTile;                                           // s_tok of the tile's rows
-        uint32_t *const cb_lds = reinterpret_cast<uint32_t *>(rs_lds + kTile);          // bias, two fp16 per word
+        uint32_t *const cb_lds = reinterpret_cast<uint32_t *>(rs_lds + kTileRows);      // bias, two fp16 per word
 
         // Scale vectors of this tile, one 4-byte element per lane, straight into LDS (indices beyond the
-        // matrix are clamped; those rows / channels are never stored).  Tasks 0-3: s_w, 4-7: s_tok, 8-9: bias.
+        // matrix are clamped; those rows / channels are never stored).  Tasks 0-3: s_w, then s_tok (64 rows each), then 2 of bias.
+        constexpr int kRowTasks = kTileRows / 64;
 #pragma unroll
-        for (int task = 0; task < 10; task++) {
+        for (int task = 0; task < 4 + kRowTasks + 2; task++) {
             if (task % NW != wave) continue;
             if (task < 4) {
                 const int c = min(task * 64 + lane, cols_valid - 1);
                 __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void *)(p.s_w + o0 + c),
                                                  (__attribute__((address_space(3))) void *)(cs_lds + task * 64), 4, 0, 0);
-            } else if (task < 8) {
+            } else if (task < 4 + kRowTasks) {
                 const int blk = task - 4;
                 const int r = min(blk * 64 + lane, rows_valid - 1);
                 const uint32_t t = ((uint32_t)(r0 % p.L) + (uint32_t)r) % (uint32_t)p.L;
                 __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void *)(p.s_tok + t),
                                                  (__attribute__((address_space(3))) void *)(rs_lds + blk * 64), 4, 0, 0);
             } else if constexpr (HAS_BIAS) {
-                const int blk = task - 8;
+                const int blk = task - 4 - kRowTasks;
                 const int c2 = min(blk * 64 + lane, cols_valid / 2 - 1);
                 __builtin_amdgcn_global_load_lds(
                     (const __attribute__((address_space(1))) void *)(reinterpret_cast<const uint32_t *>(p.bias + o0) + c2),
@@ -254,7 +271,7 @@ __global__ __launch_bounds__(512, 1) void linear_e2m3_persistent(const LinearArg
         // An operand is dead after its last MFMA of a block and is fetched again at once for the next block.
         v8i fw[FO], fx[FR];
         auto load_fw = [&](int i, int stg) {
-            const char *sw = ring + stg * kStageBytes + (kTile + wave_o + i * 16) * kBlockBytes;
+            const char *sw = ring + stg * kStageBytes + (kTileRows + wave_o + i * 16) * kBlockBytes;
             fw[i] = make_fragment(*reinterpret_cast<const v4i *>(sw + frag_lo), *reinterpret_cast<const v2i *>(sw + frag_hi));
         };
         auto load_fx = [&](int j, int stg) {
@@ -311,7 +328,7 @@ __global__ __launch_bounds__(512, 1) void linear_e2m3_persistent(const LinearArg
         char *y_tile = reinterpret_cast<char *>(p.y + r0 * p.ldy + o0);
         const uint32_t ldy_bytes = (uint32_t)p.ldy * 2;
         auto patch_chunk = [&](int row, int chunk) { return row * (WAVE_O * 2) + ((chunk ^ (row & 7)) << 4); };
-        const bool full_tile = rows_valid == kTile && cols_valid == kTile;
+        const bool full_tile = rows_valid == kTileRows && cols_valid == kTile;
 
         // Accumulator register v of block (i, j): token row 16 j + (lane mod 16), channel 16 i + 4 (lane / 16) + v.
         // cs_raw[i]: steps of this lane's four channels of block i; cb_raw[i]: the eight fp16 biases around them.
@@ -389,16 +406,17 @@ int launch_persistent(LinearArgs a, hipStream_t stream) {
     hipError_t err = hipGetDevice(&device);
     if (err == hipSuccess) err = hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, device);
     if (err != hipSuccess) return ptq4vm::record_hip_error(err, "hipDeviceGetAttribute(multiprocessor count)");
-    const int64_t tiles_r = ptq4vm::ceil_div(a.M, kTile), tiles_o = ptq4vm::ceil_div(a.N, kTile);
+    const int64_t tiles_r = ptq4vm::ceil_div(a.M, kTileRows), tiles_o = ptq4vm::ceil_div(a.N, kTile);
     a.tiles_r = (int)tiles_r;
     a.tiles_o = (int)tiles_o;
-    const unsigned wgs = (unsigned)max(1, cus / kXcds) * kXcds;  // one workgroup per CU, a multiple of the XCD count
+    // 8 wavefronts per CU (one workgroup, or two of 4), a multiple of the XCD count
+    const unsigned wgs = (unsigned)max(1, cus / kXcds) * kXcds * (8 / kWavesPerWg);
     using Kernel = void (*)(const LinearArgs);
     static const Kernel kernels[2][2] = {{linear_e2m3_persistent<false, false>, linear_e2m3_persistent<false, true>},
                                          {linear_e2m3_persistent<true, false>, linear_e2m3_persistent<true, true>}};
     const Kernel kernel = kernels[a.bias ? 1 : 0][a.acc_out ? 1 : 0];
     if (int rc = ptq4vm::set_lds_limit(reinterpret_cast<const void *>(kernel), kPersistentLds, "hipFuncSetAttribute(linear_e2m3_persistent)")) return rc;
-    kernel<<<dim3(wgs), dim3(512), kPersistentLds, stream>>>(a);
+    kernel<<<dim3(wgs), dim3(kWavesPerWg * 64), kPersistentLds, stream>>>(a);
     return ptq4vm::check_launch("linear_e2m3_persistent");
 }
 
@@ -444,7 +462,7 @@ extern "C" int ptq4vm_w4a4_linear_e2m3(const uint8_t *xq6, const uint8_t *wq6, c
     a.ldy = ldy;
     a.L = L;
     hipStream_t stream = static_cast<hipStream_t>(stream_);
-    const int64_t tiles = ptq4vm::ceil_div(M, kTile) * ptq4vm::ceil_div(N, kTile);
+    const int64_t tiles = ptq4vm::ceil_div(M, 256) * ptq4vm::ceil_div(N, kTile);
     const bool persistent_ok = K % 128 == 0 && K >= 256 && N % 8 == 0 && ptq4vm::aligned_to(y_f16, 16) && ldy % 8 == 0 &&
                                ptq4vm::aligned_to(bias_f16, 4) && ldxq * kTile < (1LL << 31) && ldwq * kTile < (1LL << 31) &&
                                ldy * 2 * kTile < (1LL << 31) && L < (1LL << 31) && tiles >= 128 && tiles <= 0x3fffffffLL;
