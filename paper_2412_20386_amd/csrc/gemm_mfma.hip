@@ -783,7 +783,7 @@ __host__ __device__ __forceinline__ WresLayout wres_layout(int N, int k_bytes) {
     l.n4 = (N + 3) & ~3;
     l.pw = k_bytes + 16;
     l.w_bytes = (l.nb * 16 * l.pw + 1023) & ~1023;  // whole 1 KiB wavefront copies
-    l.scale_bytes = l.nb * 16 * 4 * 2;
+    l.scale_bytes = l.nb * 16 * 4 * 3;  // step, bias and (zero-offset path) weight row sum per channel
     l.patch_bytes = 16 * l.n4 * 2;                   // one 16-row block of fp16 results
     l.total = l.w_bytes + l.scale_bytes + kWresWaves * l.patch_bytes;
     return l;
@@ -803,6 +803,7 @@ __global__ __launch_bounds__(kWresWaves * 64) void linear_mfma_wres(const Linear
     char *const w_lds = lds_dyn;
     float *const cs_lds = reinterpret_cast<float *>(lds_dyn + lay.w_bytes);
     float *const cb_lds = cs_lds + NB * 16;
+    int *const cz_lds = reinterpret_cast<int *>(cb_lds + NB * 16);  // weight row sums (zero-offset path)
     char *const patch = lds_dyn + lay.w_bytes + lay.scale_bytes + wave * lay.patch_bytes;
 
     // Units are dealt wavefront-major, so that a launch with fewer units than wavefronts still
@@ -848,6 +849,7 @@ __global__ __launch_bounds__(kWresWaves * 64) void linear_mfma_wres(const Linear
             }
             cs_lds[o] = s;
             cb_lds[o] = b;
+            if constexpr (Path::kOffset) cz_lds[o] = o < N ? p.rowsum[o] : 0;
         }
     }
     __builtin_amdgcn_s_waitcnt(0);  // vmcnt(0) expcnt(0) lgkmcnt(0): this wavefront's copies have landed
@@ -907,10 +909,14 @@ __global__ __launch_bounds__(kWresWaves * 64) void linear_mfma_wres(const Linear
         // Accumulator register v of block (j, i): token row 16 j + (lane mod 16), channel 16 i + 4 (lane / 16) + v.
         const int64_t r_unit = unit * 32;
         float rs[2] = {1.0f, 1.0f};
+        int rz[2] = {0, 0};  // per-token zero offsets of the lane's two rows (zero-offset path)
         if constexpr (kInt8) {
 #pragma unroll
-            for (int j = 0; j < 2; j++)
-                rs[j] = p.s_tok[(uint32_t)min(r_unit + j * 16 + l16, p.M - 1) % (uint32_t)p.L];
+            for (int j = 0; j < 2; j++) {
+                const uint32_t t = (uint32_t)min(r_unit + j * 16 + l16, p.M - 1) % (uint32_t)p.L;
+                rs[j] = p.s_tok[t];
+                if constexpr (Path::kOffset) rz[j] = p.z_tok[t];
+            }
         }
         const int64_t next = unit + unit_step;
         if (next < units) start_unit(next);  // in flight while this unit's results are written
@@ -926,12 +932,15 @@ __global__ __launch_bounds__(kWresWaves * 64) void linear_mfma_wres(const Linear
                 if (col < n4) {
                     const v4f cs = *reinterpret_cast<const v4f *>(cs_lds + col);
                     const v4f cb = *reinterpret_cast<const v4f *>(cb_lds + col);
+                    v4i cz = {0, 0, 0, 0};
+                    if constexpr (Path::kOffset) cz = *reinterpret_cast<const v4i *>(cz_lds + col);
                     float out[4];
 #pragma unroll
                     for (int c = 0; c < 4; c++) {
                         if constexpr (kInt8) {
-                            const int a = acc[j][i][c];
+                            int a = acc[j][i][c];
                             if (p.acc_out && l16 < rows_valid && col + c < N) p.acc_out[(r0 + l16) * p.N + col + c] = a;
+                            if constexpr (Path::kOffset) a -= __mul24(rz[j], cz[c]);  // |z| < 2^8, |rowsum| < 2^23
                             out[c] = (float)a * (rs[j] * cs[c]) + cb[c];
                         } else {
                             out[c] = acc[j][i][c] + cb[c];
@@ -1183,9 +1192,9 @@ int dispatch(LinearArgs a, hipStream_t stream) {
     const bool dma_ok = la == 16 && a.k_bytes % kSlabBytes == 0 && a.ldx_bytes * 256 < (1LL << 31) &&
                         a.ldw_bytes * 256 < (1LL << 31);
 #if PTQ4VM_STREAM_SMALLK
-    if constexpr (Path::kElemBytes == 1 && !Path::kOffset) {
+    if constexpr (Path::kElemBytes == 1) {
         if (a.k_bytes <= (Path::kPacked4 ? 64 : 128)) {  // many rows: whole rows of y streamed out by one wavefront each
-            const int rc = launch_stream_smallk(a, false, stream, Path::kPacked4);
+            const int rc = launch_stream_smallk(a, false, stream, Path::kPacked4, Path::kOffset);
             if (rc <= 0) return rc;
         }
     }
@@ -1210,7 +1219,7 @@ int dispatch(LinearArgs a, hipStream_t stream) {
                          4 * a.M >= ptq4vm::ceil_div(a.N, 16) * 16 * a.k_bytes && a.M < (1LL << 31) &&
                          a.L < (1LL << 31) && a.k_bytes < (1LL << 20) &&
                          wres_layout((int)a.N, (int)a.k_bytes).total <= kLdsBytes;
-    if constexpr (!Path::kOffset && !Path::kPacked4) {
+    if constexpr (!Path::kPacked4) {
         if (wres_ok) return launch_wres<Path>(a, stream);
     }
     if (a.N > 64) {

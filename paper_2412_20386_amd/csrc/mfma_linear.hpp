@@ -457,7 +457,8 @@ __device__ __forceinline__ void lds_write_b128(uint32_t addr, v4f v) {
 // Returns PTQ4VM_OK after a launch, a negative status on error, or 1 if the shape does not fit
 // this kernel (nothing was launched; the caller picks another one).
 // packed4: x and w hold two 4-bit codes per byte (k_bytes = K / 2), expanded on chip; not with `quantize`.
-int launch_stream_smallk(const LinearArgs &a, bool quantize, hipStream_t stream, bool packed4 = false);
+// offset: z_tok / rowsum are honoured (per-token zero offset); not with `quantize` or `packed4`.
+int launch_stream_smallk(const LinearArgs &a, bool quantize, hipStream_t stream, bool packed4 = false, bool offset = false);
 
 // Weights-in-registers kernel for wide int8 linears with a short reduction (K = 384 or 768, e.g. the
 // in_proj of the Vim-S / Vim-B stacks), defined in gemm_wreg.hip.  Same return convention.

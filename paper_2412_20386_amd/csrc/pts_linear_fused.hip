@@ -220,6 +220,7 @@ __global__ __launch_bounds__(kFusedWaves * 64) void pts_linear_wres(const Linear
         for (int o = tid; o < NB * 16; o += kFusedWaves * 64) {
             cs_lds[o] = o < N ? p.s_w[o] : 0.0f;
             cb_lds[o] = (o < N && p.bias) ? __half2float(p.bias[o]) : 0.0f;
+            if constexpr (OFFSET) cz_lds[o] = o < N ? p.rowsum[o] : 0;
         }
     }
     __builtin_amdgcn_s_waitcnt(0);  // vmcnt(0) expcnt(0) lgkmcnt(0): this wavefront's copies have landed
@@ -463,15 +464,15 @@ __host__ __device__ __forceinline__ StreamLayout stream_layout(int N, int ksteps
     l.pitch = 64 * ksteps;
     l.w_bytes = l.rows * l.pitch;
     l.scale_off = l.w_bytes;
-    l.inv_m_off = l.scale_off + l.rows * 8;          // 64 ksteps smoothing factors (fused form)
+    l.inv_m_off = l.scale_off + l.rows * 12;         // steps, biases, weight row sums; then 64 ksteps smoothing factors (fused form)
     l.patch_off = l.inv_m_off + 64 * ksteps * 4;
     l.total = l.patch_off + kStreamWaves * kStreamPatch;
     return l;
 }
 
-template <int KSTEPS, bool QUANT, int X_ALIGN, int W_ALIGN, bool PACKED4 = false>
+template <int KSTEPS, bool QUANT, int X_ALIGN, int W_ALIGN, bool PACKED4 = false, bool OFFSET = false>
 __global__ __launch_bounds__(kStreamWaves * 64) void linear_stream_smallk(const LinearArgs p) {
-    static_assert(!(QUANT && PACKED4), "the fused form quantizes to 8 bits");
+    static_assert(!(QUANT && PACKED4) && !(OFFSET && (QUANT || PACKED4)), "one variant at a time");
     const int tid = threadIdx.x, lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);  // scalar: unit numbers and row bounds stay in SGPRs
     const int l16 = lane & 15, lq = lane >> 4;
@@ -480,6 +481,7 @@ __global__ __launch_bounds__(kStreamWaves * 64) void linear_stream_smallk(const 
     char *const w_lds = lds_dyn;
     float *const cs_lds = reinterpret_cast<float *>(lds_dyn + lay.scale_off);
     float *const cb_lds = cs_lds + lay.rows;
+    int *const cz_lds = reinterpret_cast<int *>(cb_lds + lay.rows);  // weight row sums (zero-offset form)
     float *const inv_m_lds = reinterpret_cast<float *>(lds_dyn + lay.inv_m_off);
     char *const patch = lds_dyn + lay.patch_off + wave * kStreamPatch;
     constexpr int RB = kStreamRB, UNIT = 16 * RB;
@@ -533,11 +535,14 @@ __global__ __launch_bounds__(kStreamWaves * 64) void linear_stream_smallk(const 
         // ---- the unit's two activation operands (lane: row 16 jb + lane mod 16, codes 64 ks + 16 (lane / 16) ..)
         v4i fx[RB][KSTEPS];
         float rs[RB];
+        int rz[RB];  // per-token zero offset of the lane's row (zero-offset form)
 #pragma unroll
         for (int jb = 0; jb < RB; jb++) {
             const int64_t r = min(r_unit + jb * 16 + l16, p.M - 1);  // clamped rows are never stored
             const float step = p.s_tok[(uint32_t)r % (uint32_t)p.L];
             rs[jb] = step;
+            rz[jb] = 0;
+            if constexpr (OFFSET) rz[jb] = p.z_tok[(uint32_t)r % (uint32_t)p.L];
             const char *xrow = p.x + r * p.ldx_bytes;
 #pragma unroll
             for (int ks = 0; ks < KSTEPS; ks++) {
@@ -571,8 +576,10 @@ __global__ __launch_bounds__(kStreamWaves * 64) void linear_stream_smallk(const 
         for (int g = g_begin; g < g_end; g++) {
             v4i acc[RB][4];
             v4f cs[4], cb[4];
+            v4i cz[4];
 #pragma unroll
             for (int i = 0; i < 4; i++) {
+                if constexpr (OFFSET) cz[i] = *reinterpret_cast<const v4i *>(cz_lds + g * 64 + i * 16 + lq * 4);
                 const int row = g * 64 + i * 16 + l16;
                 v4i fw[KSTEPS];
 #pragma unroll
@@ -611,7 +618,11 @@ __global__ __launch_bounds__(kStreamWaves * 64) void linear_stream_smallk(const 
                 for (int i = 0; i < 4; i++) {
                     float out[4];
 #pragma unroll
-                    for (int c = 0; c < 4; c++) out[c] = (float)acc[jb][i][c] * (rs[jb] * cs[i][c]) + cb[i][c];
+                    for (int c = 0; c < 4; c++) {
+                        int a = acc[jb][i][c];
+                        if constexpr (OFFSET) a -= __mul24(rz[jb], cz[i][c]);  // |z| < 2^8, |rowsum| < 2^23
+                        out[c] = (float)a * (rs[jb] * cs[i][c]) + cb[i][c];
+                    }
                     __half2 lo = __floats2half2_rn(out[0], out[1]);
                     __half2 hi = __floats2half2_rn(out[2], out[3]);
                     u32x2 packed = {__builtin_bit_cast(uint32_t, lo), __builtin_bit_cast(uint32_t, hi)};
@@ -760,17 +771,17 @@ __global__ __launch_bounds__(kThreads, 2) void pts_linear_generic(const LinearAr
 // ------------------------------------------------------------------------------------------
 // Host side
 // ------------------------------------------------------------------------------------------
-template <int KSTEPS, bool QUANT, bool PACKED4 = false>
+template <int KSTEPS, bool QUANT, bool PACKED4 = false, bool OFFSET = false>
 int launch_stream_aligned(const LinearArgs &a, int xa, int wa, const StreamLayout &lay, unsigned wgs, hipStream_t stream) {
     using Kernel = void (*)(const LinearArgs);
     // [activation alignment 16 / 4 / 0][weight alignment 16 / 4 / 0]
     static const Kernel kernels[3][3] = {
-        {linear_stream_smallk<KSTEPS, QUANT, 16, 16, PACKED4>, linear_stream_smallk<KSTEPS, QUANT, 16, 4, PACKED4>,
-         linear_stream_smallk<KSTEPS, QUANT, 16, 0, PACKED4>},
-        {linear_stream_smallk<KSTEPS, QUANT, 4, 16, PACKED4>, linear_stream_smallk<KSTEPS, QUANT, 4, 4, PACKED4>,
-         linear_stream_smallk<KSTEPS, QUANT, 4, 0, PACKED4>},
-        {linear_stream_smallk<KSTEPS, QUANT, 0, 16, PACKED4>, linear_stream_smallk<KSTEPS, QUANT, 0, 4, PACKED4>,
-         linear_stream_smallk<KSTEPS, QUANT, 0, 0, PACKED4>}};
+        {linear_stream_smallk<KSTEPS, QUANT, 16, 16, PACKED4, OFFSET>, linear_stream_smallk<KSTEPS, QUANT, 16, 4, PACKED4, OFFSET>,
+         linear_stream_smallk<KSTEPS, QUANT, 16, 0, PACKED4, OFFSET>},
+        {linear_stream_smallk<KSTEPS, QUANT, 4, 16, PACKED4, OFFSET>, linear_stream_smallk<KSTEPS, QUANT, 4, 4, PACKED4, OFFSET>,
+         linear_stream_smallk<KSTEPS, QUANT, 4, 0, PACKED4, OFFSET>},
+        {linear_stream_smallk<KSTEPS, QUANT, 0, 16, PACKED4, OFFSET>, linear_stream_smallk<KSTEPS, QUANT, 0, 4, PACKED4, OFFSET>,
+         linear_stream_smallk<KSTEPS, QUANT, 0, 0, PACKED4, OFFSET>}};
     auto idx = [](int al) { return al == 16 ? 0 : (al == 4 ? 1 : 2); };
     const Kernel kernel = kernels[idx(xa)][idx(wa)];
     if (int rc = ptq4vm::set_lds_limit(reinterpret_cast<const void *>(kernel), kLdsBytes, "hipFuncSetAttribute(linear_stream_smallk)")) return rc;
@@ -853,7 +864,7 @@ int dispatch(LinearArgs a, hipStream_t stream) {
 
 }  // namespace
 
-int ptq4vm::mfma::launch_stream_smallk(const LinearArgs &a, bool quantize, hipStream_t stream, bool packed4) {
+int ptq4vm::mfma::launch_stream_smallk(const LinearArgs &a, bool quantize, hipStream_t stream, bool packed4, bool offset) {
     auto align_of = [](const void *base, int64_t pitch_bytes) {
         if (ptq4vm::aligned_to(base, 16) && pitch_bytes % 16 == 0) return 16;
         if (ptq4vm::aligned_to(base, 4) && pitch_bytes % 4 == 0) return 4;
@@ -861,7 +872,7 @@ int ptq4vm::mfma::launch_stream_smallk(const LinearArgs &a, bool quantize, hipSt
     };
     const int xa = align_of(a.x, a.ldx_bytes), wa = align_of(a.w, a.ldw_bytes);
     const int64_t k_codes = packed4 ? 2 * a.k_bytes : a.k_bytes;  // bytes of K per row once the operands are int8
-    if (k_codes > 128 || (packed4 && quantize) || a.M < (quantize ? kStreamMinRowsFused : kStreamMinRows) || a.M >= (1LL << 31) || a.L >= (1LL << 31) || a.N > 8192) return 1;
+    if (k_codes > 128 || (packed4 && quantize) || (offset && (quantize || packed4)) || a.M < (quantize ? kStreamMinRowsFused : kStreamMinRows) || a.M >= (1LL << 31) || a.L >= (1LL << 31) || a.N > 8192) return 1;
     const int ksteps = k_codes <= 64 ? 1 : 2;
     const StreamLayout lay = stream_layout((int)a.N, ksteps);
     if (lay.total > kLdsBytes) return 1;
@@ -873,6 +884,9 @@ int ptq4vm::mfma::launch_stream_smallk(const LinearArgs &a, bool quantize, hipSt
     const int64_t items = ptq4vm::ceil_div(a.M, 16 * kStreamRB) * (lay.groups < 4 ? lay.groups : 4);  // as the kernel counts them
     int64_t wgs = ptq4vm::ceil_div(items, kStreamWaves);
     if (wgs > cus) wgs = cus;  // one workgroup per CU: the resident weight takes most of its LDS
+    if (offset)
+        return ksteps == 1 ? launch_stream_aligned<1, false, false, true>(a, xa, wa, lay, (unsigned)wgs, stream)
+                           : launch_stream_aligned<2, false, false, true>(a, xa, wa, lay, (unsigned)wgs, stream);
     if (packed4)
         return ksteps == 1 ? launch_stream_aligned<1, false, true>(a, xa, wa, lay, (unsigned)wgs, stream)
                            : launch_stream_aligned<2, false, true>(a, xa, wa, lay, (unsigned)wgs, stream);

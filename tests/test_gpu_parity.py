@@ -686,9 +686,13 @@ def test_zero_offset_vim_b_full_size_sampled(linear):
     _check_offset_on_sampled_rows(c, x, s_off, z_off, _sampled_rows(c.B * c.L, 97, c.L), f"vim_b {c.name}")
 
 
-@pytest.mark.parametrize("B,L,K,N", [(41, 251, 256, 1544), (20, 517, 384, 3400), (300, 65, 24, 776), (250, 33, 100, 520)])
+@pytest.mark.parametrize("B,L,K,N", [(41, 251, 256, 1544), (20, 517, 384, 3400), (300, 65, 24, 776), (250, 33, 100, 520),
+                                     (110, 197, 24, 776), (105, 197, 100, 520), (107, 199, 48, 1536),
+                                     (83, 199, 256, 80), (64, 257, 1536, 44), (70, 241, 704, 121)])
 def test_zero_offset_large_ragged_shapes_sampled(B, L, K, N):
-    """Ragged last tiles in the persistent kernel (first two) and the short-reduction kernel (last two)."""
+    """Ragged last tiles in the persistent kernel (first two), the short-reduction kernel (next two), the
+    row-streaming kernel (from 20 480 rows: one and two k-steps, ragged rows and channels) and the weight-resident
+    kernel (N <= 128: 5, 3 and 8 channel blocks, ragged rows and channels)."""
     c, x, s_off, z_off = _offset_case(5000 + K + N, B, L, K, N)
     _check_offset_on_sampled_rows(c, x, s_off, z_off, _sampled_rows(B * L, 61, L), "ragged")
 
