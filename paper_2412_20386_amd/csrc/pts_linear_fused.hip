@@ -220,7 +220,6 @@ __global__ __launch_bounds__(kFusedWaves * 64) void pts_linear_wres(const Linear
         for (int o = tid; o < NB * 16; o += kFusedWaves * 64) {
             cs_lds[o] = o < N ? p.s_w[o] : 0.0f;
             cb_lds[o] = (o < N && p.bias) ? __half2float(p.bias[o]) : 0.0f;
-            if constexpr (OFFSET) cz_lds[o] = o < N ? p.rowsum[o] : 0;
         }
     }
     __builtin_amdgcn_s_waitcnt(0);  // vmcnt(0) expcnt(0) lgkmcnt(0): this wavefront's copies have landed
@@ -508,6 +507,7 @@ __global__ __launch_bounds__(kStreamWaves * 64) void linear_stream_smallk(const 
             // packed operands are codes times 16: the accumulator is 256 times the sum, undone here (a power of two: exact)
             cs_lds[o] = o < N ? (PACKED4 ? p.s_w[o] * (1.0f / 256.0f) : p.s_w[o]) : 0.0f;
             cb_lds[o] = (o < N && p.bias) ? __half2float(p.bias[o]) : 0.0f;
+            if constexpr (OFFSET) cz_lds[o] = o < N ? p.rowsum[o] : 0;
         }
         if constexpr (QUANT) {
             for (int k = tid; k < 64 * KSTEPS; k += kStreamWaves * 64) inv_m_lds[k] = (p.inv_m && k < K) ? p.inv_m[k] : 1.0f;
