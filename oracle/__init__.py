@@ -19,7 +19,7 @@ from .ptq4vm_oracle import (  # noqa: F401
     quantize_pts_bits,
     pack_int4,
     unpack_int4,
-    e2m3_row_bytes,
+    e2m3_blocks,
     pack_e2m3,
     unpack_e2m3,
     quantize_pts_offset,

@@ -352,7 +352,9 @@ void oracle_unpack_int4(const uint8_t *packed, int8_t *codes, int64_t rows, int6
  * A row of K codes is padded with zeros to a multiple of 128 and written in blocks of 96 bytes, one per
  * 128 codes.  Inside a block, group g = 0..3 holds codes 32 g .. 32 g + 31 as a 192-bit little-endian
  * string, code j of the group at bits [6 j, 6 j + 6); the first 16 bytes of group g sit at block offset
- * 16 g, its last 8 bytes at block offset 64 + 8 g. ---- */
+ * 16 g, its last 8 bytes at block offset 64 + 8 g.
+ * The matrix is stored block-major: plane b holds block b of every row, row r at byte 96 r of the plane,
+ * planes back to back (plane pitch 96 rows): packed[b][r][96]. ---- */
 static double e2m3_value(int pattern) {
     int s = (pattern >> 5) & 1, e = (pattern >> 3) & 3, m = pattern & 7;
     double mag = e == 0 ? m / 8.0 : ldexp(1.0 + m / 8.0, e - 1);
@@ -365,12 +367,12 @@ static int e2m3_pattern_of(int code) { /* the pattern whose value is `code`; -1 
     return -1;
 }
 
-int64_t oracle_e2m3_row_bytes(int64_t K) { return (K + 127) / 128 * 96; }
+int64_t oracle_e2m3_blocks(int64_t K) { return (K + 127) / 128; }
 
 /* returns 0, or -1 if a code has no E2M3 pattern (|code| > 7) */
 int oracle_pack_e2m3(const int8_t *codes, uint8_t *packed, int64_t rows, int64_t K) {
-    const int64_t pitch = oracle_e2m3_row_bytes(K);
-    memset(packed, 0, (size_t)(rows * pitch));
+    const int64_t plane = rows * 96;
+    memset(packed, 0, (size_t)(oracle_e2m3_blocks(K) * plane));
     for (int64_t r = 0; r < rows; r++)
         for (int64_t k = 0; k < K; k++) {
             const int pattern = e2m3_pattern_of(codes[r * K + k]);
@@ -381,7 +383,7 @@ int oracle_pack_e2m3(const int8_t *codes, uint8_t *packed, int64_t rows, int64_t
                 const int64_t bit = 6 * j + b;           /* position in the group's 192-bit string */
                 const int64_t byte = bit / 8;            /* 0..23 */
                 const int64_t off = byte < 16 ? 16 * g + byte : 64 + 8 * g + (byte - 16);
-                packed[r * pitch + block * 96 + off] |= (uint8_t)(1u << (bit % 8));
+                packed[block * plane + r * 96 + off] |= (uint8_t)(1u << (bit % 8));
             }
         }
     return 0;
@@ -389,7 +391,7 @@ int oracle_pack_e2m3(const int8_t *codes, uint8_t *packed, int64_t rows, int64_t
 
 /* returns 0, or -1 if a pattern's value is not an integer (codes of padding positions are skipped) */
 int oracle_unpack_e2m3(const uint8_t *packed, int8_t *codes, int64_t rows, int64_t K) {
-    const int64_t pitch = oracle_e2m3_row_bytes(K);
+    const int64_t plane = rows * 96;
     for (int64_t r = 0; r < rows; r++)
         for (int64_t k = 0; k < K; k++) {
             const int64_t block = k / 128, g = (k % 128) / 32, j = k % 32;
@@ -397,7 +399,7 @@ int oracle_unpack_e2m3(const uint8_t *packed, int8_t *codes, int64_t rows, int64
             for (int b = 0; b < 6; b++) {
                 const int64_t bit = 6 * j + b, byte = bit / 8;
                 const int64_t off = byte < 16 ? 16 * g + byte : 64 + 8 * g + (byte - 16);
-                if ((packed[r * pitch + block * 96 + off] >> (bit % 8)) & 1) pattern |= 1 << b;
+                if ((packed[block * plane + r * 96 + off] >> (bit % 8)) & 1) pattern |= 1 << b;
             }
             const double v = e2m3_value(pattern);
             if (v != floor(v)) return -1;

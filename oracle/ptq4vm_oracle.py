@@ -75,8 +75,8 @@ def _load():
         lib.oracle_pack_int4.argtypes = [vp, vp, i64, i64]
         lib.oracle_unpack_int4.restype = None
         lib.oracle_unpack_int4.argtypes = [vp, vp, i64, i64]
-        lib.oracle_e2m3_row_bytes.restype = i64
-        lib.oracle_e2m3_row_bytes.argtypes = [i64]
+        lib.oracle_e2m3_blocks.restype = i64
+        lib.oracle_e2m3_blocks.argtypes = [i64]
         lib.oracle_pack_e2m3.restype = ctypes.c_int
         lib.oracle_pack_e2m3.argtypes = [vp, vp, i64, i64]
         lib.oracle_unpack_e2m3.restype = ctypes.c_int
@@ -251,16 +251,17 @@ def unpack_int4(packed: np.ndarray) -> np.ndarray:
     return codes
 
 
-def e2m3_row_bytes(K: int) -> int:
-    """Bytes of one row of K codes in the E2M3 container: 96 per started block of 128 codes."""
-    return int(_load().oracle_e2m3_row_bytes(K))
+def e2m3_blocks(K: int) -> int:
+    """Blocks of 128 codes (96 bytes each) that a row of K codes takes in the E2M3 container."""
+    return int(_load().oracle_e2m3_blocks(K))
 
 
 def pack_e2m3(codes: np.ndarray) -> np.ndarray:
-    """[rows, K] int8 codes in [-7, 7] -> [rows, e2m3_row_bytes(K)] bytes (6-bit E2M3 patterns, zero padded)."""
+    """[rows, K] int8 codes in [-7, 7] -> [e2m3_blocks(K), rows, 96] bytes: 6-bit E2M3 patterns, rows zero padded
+    to whole blocks, block-major (plane b holds block b of every row)."""
     codes = _arr(codes, np.int8)
     rows, K = codes.shape
-    packed = np.empty((rows, e2m3_row_bytes(K)), np.uint8)
+    packed = np.empty((e2m3_blocks(K), rows, 96), np.uint8)
     if _load().oracle_pack_e2m3(_p(codes), _p(packed), rows, K) != 0:
         raise ValueError("codes outside [-7, 7] have no E2M3 pattern")
     return packed
@@ -268,9 +269,9 @@ def pack_e2m3(codes: np.ndarray) -> np.ndarray:
 
 def unpack_e2m3(packed: np.ndarray, K: int) -> np.ndarray:
     packed = _arr(packed, np.uint8)
-    rows, pitch = packed.shape
-    if pitch != e2m3_row_bytes(K):
-        raise ValueError("row pitch does not match K")
+    blocks, rows, width = packed.shape
+    if blocks != e2m3_blocks(K) or width != 96:
+        raise ValueError("container shape does not match K")
     codes = np.empty((rows, K), np.int8)
     if _load().oracle_unpack_e2m3(_p(packed), _p(codes), rows, K) != 0:
         raise ValueError("a pattern does not stand for an integer")

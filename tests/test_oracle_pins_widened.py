@@ -115,12 +115,12 @@ def test_e2m3_patterns_of_the_integers_by_hand_and_by_value():
     # -7 = -(2^2 * 1.110b) -> s = 1, e = 3, m = 6 -> 0b1_11_110 = 62.  Three codes fill bits 0..17 of the row:
     # 8 | 62 << 6 | 20 << 12 = 0x014F88 -> bytes 88 4F 01.
     packed = oracle.pack_e2m3(np.array([[1, -7, 3]], np.int8))
-    assert packed.shape == (1, 96) and oracle.e2m3_row_bytes(3) == 96
-    assert packed[0, :3].tolist() == [0x88, 0x4F, 0x01] and not packed[0, 3:].any()
+    assert packed.shape == (1, 1, 96) and oracle.e2m3_blocks(3) == 1
+    assert packed[0, 0, :3].tolist() == [0x88, 0x4F, 0x01] and not packed[0, 0, 3:].any()
     # Every integer of the range: the stored pattern's value under the format's definition is the integer,
     # zero has a clear sign bit, and the patterns are the 15 distinct ones with integer values up to 7.
     for v in range(-7, 8):
-        pattern = int(oracle.pack_e2m3(np.array([[v]], np.int8))[0, 0]) & 63
+        pattern = int(oracle.pack_e2m3(np.array([[v]], np.int8))[0, 0, 0]) & 63
         assert _e2m3_value(pattern) == v, (v, pattern)
         if v == 0:
             assert pattern == 0
@@ -132,18 +132,22 @@ def test_e2m3_patterns_of_the_integers_by_hand_and_by_value():
 def test_e2m3_block_layout_by_hand():
     # 256 codes = two 96-byte blocks.  Code k sits in block k // 128, group g = (k % 128) // 32, at bits
     # [6 j, 6 j + 6) of the group's 24-byte string (j = k % 32); string bytes 0..15 at block offset 16 g,
-    # bytes 16..23 at block offset 64 + 8 g.
-    codes = np.zeros((1, 256), np.int8)
+    # bytes 16..23 at block offset 64 + 8 g.  Storage is block-major: packed[block][row][96].
+    codes = np.zeros((3, 256), np.int8)
     codes[0, 32] = 1      # group 1, j = 0: bits 0..5 of string byte 0 -> block offset 16, value 8
     codes[0, 21] = 7      # group 0, j = 21: bits 126..131: pattern 30 = 0b011110; its bits 0,1 -> byte 15 bits 6,7 (0x80),
     #                       its bits 2..5 (0b0111) -> byte 16 = block offset 64, value 0x07
     codes[0, 255] = -1    # block 1, group 3, j = 31: bits 186..191 = byte 23 bits 2..7: pattern 40 = 0b101000 -> 0xA0
     #                       at block offset 64 + 24 + 7 = 95 of block 1
+    codes[2, 128] = 2     # row 2, block 1, group 0, j = 0: pattern 16 at offset 0 of row 2 in plane 1
     packed = oracle.pack_e2m3(codes)
-    assert packed.shape == (1, 192)
-    want = np.zeros(192, np.uint8)
-    want[16], want[15], want[64], want[96 + 95] = 0x08, 0x80, 0x07, 0xA0
-    assert np.array_equal(packed[0], want)
+    assert packed.shape == (2, 3, 96)
+    want = np.zeros((2, 3, 96), np.uint8)
+    want[0, 0, 16], want[0, 0, 15], want[0, 0, 64], want[1, 0, 95], want[1, 2, 0] = 0x08, 0x80, 0x07, 0xA0, 0x10
+    assert np.array_equal(packed, want)
+    # as flat bytes: plane b starts at 96 * rows * b
+    flat = packed.reshape(-1)
+    assert flat[96 * 3 * 1 + 96 * 2 + 0] == 0x10 and flat[96 * 3 * 1 + 95] == 0xA0
     assert np.array_equal(oracle.unpack_e2m3(packed, 256), codes)
 
 
@@ -152,7 +156,7 @@ def test_e2m3_round_trip_and_zero_padding(K):
     rng = np.random.default_rng(K)
     codes = rng.integers(-7, 8, size=(5, K)).astype(np.int8)
     packed = oracle.pack_e2m3(codes)
-    assert packed.shape == (5, (K + 127) // 128 * 96)
+    assert packed.shape == ((K + 127) // 128, 5, 96)
     assert np.array_equal(oracle.unpack_e2m3(packed, K), codes)
     # Independent decode of the bit string: gather each group's 24 bytes, read 6-bit fields, map by value.
     by_value = {p: int(_e2m3_value(p)) for p in range(64) if _e2m3_value(p).denominator == 1}
@@ -160,7 +164,7 @@ def test_e2m3_round_trip_and_zero_padding(K):
     full = np.zeros((5, Kp), np.int64)
     for r in range(5):
         for blk in range(Kp // 128):
-            b = packed[r, blk * 96:(blk + 1) * 96]
+            b = packed[blk, r]
             for g in range(4):
                 string = int.from_bytes(bytes(b[16 * g:16 * g + 16]) + bytes(b[64 + 8 * g:72 + 8 * g]), "little")
                 for j in range(32):
