@@ -209,10 +209,10 @@ def measure_config(args, config: int, full: bool):
             t4q = t4g = t6q = t6g = None
             s4 = [(lin[li]["s_tok"] * (127.0 / 7.0)).contiguous() for lin in layers]
             idx = {id(lin): i for i, lin in enumerate(layers)}
-            row6 = ptq.e2m3_row_bytes(K)
-            if row6 <= K:  # the same codes in the FP6 (E2M3) container, where it fits the int8 code buffer (K % 128 == 0)
+            blocks6 = ptq.e2m3_blocks(K)
+            if blocks6 * 96 <= K:  # the same codes in the FP6 (E2M3) container, where it fits the int8 code buffer (K % 128 == 0)
                 w6 = [ptq.fold_smoothing_w4_e2m3(lin[li]["w"], 1.0 / lin[li]["inv_m"]) for lin in layers]
-                xq6 = [lin[li]["xq"].view(torch.uint8).view(-1)[: M * row6].view(M, row6) for lin in layers]
+                xq6 = [lin[li]["xq"].view(torch.uint8).view(-1)[: blocks6 * M * 96].view(blocks6, M, 96) for lin in layers]
                 t6q = time_launch(lambda lin: ptq.quantize_pts_a4_e2m3(lin[li]["x"], lin[li]["inv_m"], s4[idx[id(lin)]], B, L,
                                                                        xq6=xq6[idx[id(lin)]]))
                 t6g = time_launch(lambda lin: ptq.w4a4_linear_e2m3(xq6[idx[id(lin)]], w6[idx[id(lin)]][0], s4[idx[id(lin)]],

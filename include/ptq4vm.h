@@ -176,22 +176,23 @@ int ptq4vm_w4a4_linear(const uint8_t *xq4, const uint8_t *wq4, const float *s_to
  * int8 MFMA rate.  Products and partial sums are integers below 2^24 for K <= PTQ4VM_MAX_K_E2M3, so the fp32
  * accumulators hold sum_k xq wq of App. B.1 "INT GEMM" exactly and the outputs equal those of
  * ptq4vm_w4a4_linear on the same codes.
- * Container (xq6, wq6): a row of K codes is zero padded to a multiple of 128 and written as
- * PTQ4VM_E2M3_ROW_BYTES(K) bytes, 96 per block of 128 codes.  In a block, group g = 0..3 holds codes
- * 32 g .. 32 g + 31 as a 192-bit little-endian string, code j of the group at bits [6 j, 6 j + 6); the
- * string's first 16 bytes sit at block offset 16 g, its last 8 bytes at block offset 64 + 8 g.  The pattern of
- * an integer v is its E2M3 encoding with zero written as 0 (never as "-0"); patterns of padding codes must
- * be 0, and patterns that are not one of these 15 give undefined results in the linear (not checked).
- *   ptq4vm_fold_smoothing_w4_e2m3  as ptq4vm_fold_smoothing_w4, codes to wq6 [N, ldwq bytes]
- *   ptq4vm_quantize_pts_a4_e2m3    as ptq4vm_quantize_pts_a4, codes to xq6 [B*L, ldxq bytes]
+ * Container (xq6, wq6) of a matrix of R rows: a row of K codes is zero padded to PTQ4VM_E2M3_BLOCKS(K) blocks of
+ * 128 codes, each block 96 bytes.  In a block, group g = 0..3 holds codes 32 g .. 32 g + 31 as a 192-bit
+ * little-endian string, code j of the group at bits [6 j, 6 j + 6); the string's first 16 bytes sit at block
+ * offset 16 g, its last 8 bytes at block offset 64 + 8 g.  Storage is block-major: block b of row r starts at
+ * byte b * pitch + 96 r, where the plane pitch (ldxq / ldwq, in bytes) is at least 96 R and a multiple of 16 -
+ * what a tile of the linear reads per block, and what the quantizer writes per 16 rows, is one contiguous span.
+ * The pattern of an integer v is its E2M3 encoding with zero written as 0 (never as "-0"); patterns of padding
+ * codes must be 0, and patterns that are not one of these 15 give undefined results in the linear (not checked).
+ *   ptq4vm_fold_smoothing_w4_e2m3  as ptq4vm_fold_smoothing_w4, codes to wq6 (R = N)
+ *   ptq4vm_quantize_pts_a4_e2m3    as ptq4vm_quantize_pts_a4, codes to xq6 (R = B*L)
  *   ptq4vm_w4a4_linear_e2m3        as ptq4vm_w4a4_linear on these containers; acc_out holds sum_k xq wq (int32)
- * Pitches ldxq / ldwq are in bytes, at least PTQ4VM_E2M3_ROW_BYTES(K) and multiples of 16; xq6 / wq6 are
- * 16-byte aligned; any K >= 1 (odd K too).  Errors as for the 4-bit entry points, with K > PTQ4VM_MAX_K_E2M3
- * -> PTQ4VM_ERR_SHAPE and a pitch that is not a multiple of 16 -> PTQ4VM_ERR_STRIDE.
+ * xq6 / wq6 are 16-byte aligned; any K >= 1 (odd K too).  Errors as for the 4-bit entry points, with
+ * K > PTQ4VM_MAX_K_E2M3 -> PTQ4VM_ERR_SHAPE and a plane pitch below 96 R or not a multiple of 16 -> PTQ4VM_ERR_STRIDE.
  * The linear runs on a persistent 256 x 256-tile kernel (K a multiple of 128 and >= 256, N a multiple of 8,
  * 16-byte aligned y rows, enough tiles to fill the device) or on a small tiled kernel (every other shape).
  */
-#define PTQ4VM_E2M3_ROW_BYTES(K) ((((int64_t)(K)) + 127) / 128 * 96)
+#define PTQ4VM_E2M3_BLOCKS(K) ((((int64_t)(K)) + 127) / 128)
 #define PTQ4VM_MAX_K_E2M3 262144
 int ptq4vm_fold_smoothing_w4_e2m3(const void *w_f16, const float *m, uint8_t *wq6, float *s_w, float *inv_m,
                                   int64_t N, int64_t K, int64_t ldw, int64_t ldwq, void *stream);

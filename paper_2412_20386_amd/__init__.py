@@ -10,7 +10,7 @@ from .binding import (  # noqa: F401
     fold_smoothing_w4,
     quantize_pts_a4,
     w4a4_linear,
-    e2m3_row_bytes,
+    e2m3_blocks,
     fold_smoothing_w4_e2m3,
     quantize_pts_a4_e2m3,
     w4a4_linear_e2m3,

@@ -306,18 +306,27 @@ def w4a4_linear(xq4: torch.Tensor, wq4: torch.Tensor, s_tok: torch.Tensor, s_w: 
     return y
 
 
-def e2m3_row_bytes(K: int) -> int:
-    """PTQ4VM_E2M3_ROW_BYTES: bytes of a row of K codes in the E2M3 container (96 per started block of 128)."""
-    return (K + 127) // 128 * 96
+def e2m3_blocks(K: int) -> int:
+    """PTQ4VM_E2M3_BLOCKS: 96-byte blocks of 128 codes that a row of K codes takes in the E2M3 container."""
+    return (K + 127) // 128
+
+
+def _e2m3_container(t: torch.Tensor, rows: int, K: int, what: str) -> int:
+    """Checks a block-major container [e2m3_blocks(K), rows, 96] uint8 and returns its plane pitch in bytes."""
+    if not isinstance(t, torch.Tensor) or not t.is_cuda or t.dtype != torch.uint8 or t.dim() != 3:
+        raise TypeError(f"{what}: expected a CUDA uint8 tensor [blocks, rows, 96]")
+    if tuple(t.shape) != (e2m3_blocks(K), rows, 96) or t.stride(2) != 1 or (rows > 1 and t.stride(1) != 96):
+        raise ValueError(f"{what}: expected shape {(e2m3_blocks(K), rows, 96)} with dense 96-byte blocks")
+    return t.stride(0) if t.shape[0] > 1 else max(t.stride(0), 96 * rows)
 
 
 def fold_smoothing_w4_e2m3(w: torch.Tensor, m: torch.Tensor, wq6: Optional[torch.Tensor] = None):
-    """ptq4vm_fold_smoothing_w4_e2m3: (wq6 uint8 [N, e2m3_row_bytes(K)], s_w f32 [N], inv_m f32 [K])."""
+    """ptq4vm_fold_smoothing_w4_e2m3: (wq6 uint8 [e2m3_blocks(K), N, 96] block-major, s_w f32 [N], inv_m f32 [K])."""
     N, K, ldw = _matrix(w, torch.float16, "w")
     _vector(m, torch.float32, K, "m")
     if wq6 is None:
-        wq6 = torch.empty((N, e2m3_row_bytes(K)), dtype=torch.uint8, device=w.device)
-    _, _, ldwq = _matrix(wq6, torch.uint8, "wq6")
+        wq6 = torch.empty((e2m3_blocks(K), N, 96), dtype=torch.uint8, device=w.device)
+    ldwq = _e2m3_container(wq6, N, K, "wq6")
     s_w = torch.empty(N, dtype=torch.float32, device=w.device)
     inv_m = torch.empty(K, dtype=torch.float32, device=w.device)
     check(load().ptq4vm_fold_smoothing_w4_e2m3(_ptr(w), _ptr(m), _ptr(wq6), _ptr(s_w), _ptr(inv_m), N, K, ldw, ldwq,
@@ -327,15 +336,15 @@ def fold_smoothing_w4_e2m3(w: torch.Tensor, m: torch.Tensor, wq6: Optional[torch
 
 def quantize_pts_a4_e2m3(x: torch.Tensor, inv_m: Optional[torch.Tensor], s_tok: torch.Tensor, B: int, L: int,
                          xq6: Optional[torch.Tensor] = None) -> torch.Tensor:
-    """ptq4vm_quantize_pts_a4_e2m3: xq6 uint8 [B*L, e2m3_row_bytes(K)], 4-bit codes as E2M3 patterns."""
+    """ptq4vm_quantize_pts_a4_e2m3: xq6 uint8 [e2m3_blocks(K), B*L, 96], 4-bit codes as E2M3 patterns, block-major."""
     M, K, ldx = _matrix(x, torch.float16, "x")
     if M != B * L:
         raise ValueError("x must have B*L rows")
     _vector(inv_m, torch.float32, K, "inv_m", optional=True)
     _vector(s_tok, torch.float32, L, "s_tok")
     if xq6 is None:
-        xq6 = torch.empty((M, e2m3_row_bytes(K)), dtype=torch.uint8, device=x.device)
-    _, _, ldxq = _matrix(xq6, torch.uint8, "xq6")
+        xq6 = torch.empty((e2m3_blocks(K), M, 96), dtype=torch.uint8, device=x.device)
+    ldxq = _e2m3_container(xq6, M, K, "xq6")
     check(load().ptq4vm_quantize_pts_a4_e2m3(_ptr(x), _ptr(inv_m), _ptr(s_tok), _ptr(xq6), B, L, K, ldx, ldxq,
                                              _stream()))
     return xq6
@@ -344,11 +353,13 @@ def quantize_pts_a4_e2m3(x: torch.Tensor, inv_m: Optional[torch.Tensor], s_tok: 
 def w4a4_linear_e2m3(xq6: torch.Tensor, wq6: torch.Tensor, s_tok: torch.Tensor, s_w: torch.Tensor,
                      bias: Optional[torch.Tensor], B: int, L: int, K: int, y: Optional[torch.Tensor] = None,
                      acc_out: Optional[torch.Tensor] = None) -> torch.Tensor:
-    """ptq4vm_w4a4_linear_e2m3: y fp16 [B*L, N] from operands in the E2M3 container (K codes per row)."""
-    M, _, ldxq = _matrix(xq6, torch.uint8, "xq6")
-    N, _, ldwq = _matrix(wq6, torch.uint8, "wq6")
-    if M != B * L:
-        raise ValueError("shape mismatch")
+    """ptq4vm_w4a4_linear_e2m3: y fp16 [B*L, N] from operands in the block-major E2M3 container (K codes per row)."""
+    M = B * L
+    ldxq = _e2m3_container(xq6, M, K, "xq6")
+    if not isinstance(wq6, torch.Tensor) or wq6.dim() != 3:
+        raise TypeError("wq6: expected a CUDA uint8 tensor [blocks, N, 96]")
+    N = wq6.shape[1]
+    ldwq = _e2m3_container(wq6, N, K, "wq6")
     _vector(s_tok, torch.float32, L, "s_tok")
     _vector(s_w, torch.float32, N, "s_w")
     _vector(bias, torch.float16, N, "bias", optional=True)

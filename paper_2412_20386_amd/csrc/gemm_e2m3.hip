@@ -61,8 +61,8 @@ __global__ __launch_bounds__(kThreads) void linear_e2m3_generic(const LinearArgs
         for (int q = tid; q < 64 * 6; q += kThreads) {  // 16-byte chunks of the two 64-row tiles
             const int row = q / 6, c = q - row * 6;
             v4i vx = {0, 0, 0, 0}, vw = {0, 0, 0, 0};
-            if (r0 + row < p.M) vx = *reinterpret_cast<const v4i *>(p.x + (r0 + row) * p.ldx_bytes + kb * kBlockBytes + c * 16);
-            if (o0 + row < p.N) vw = *reinterpret_cast<const v4i *>(p.w + (o0 + row) * p.ldw_bytes + kb * kBlockBytes + c * 16);
+            if (r0 + row < p.M) vx = *reinterpret_cast<const v4i *>(p.x + kb * p.ldx_bytes + (r0 + row) * kBlockBytes + c * 16);
+            if (o0 + row < p.N) vw = *reinterpret_cast<const v4i *>(p.w + kb * p.ldw_bytes + (o0 + row) * kBlockBytes + c * 16);
             *reinterpret_cast<v4i *>(xs + q * 16) = vx;
             *reinterpret_cast<v4i *>(ws + q * 16) = vw;
         }
@@ -108,7 +108,8 @@ __global__ __launch_bounds__(kThreads) void linear_e2m3_generic(const LinearArgs
 
 // ------------------------------------------------------------------------------------------
 // Persistent kernel.  LDS: ring of kStages stages, each (256 token rows + 256 channels) x 96 bytes, then two
-// buffers of per-tile scale vectors.  A stage row is the 96-byte block as in memory, except that for rows with
+// buffers of per-tile scale vectors.  The containers are block-major, so what a stage receives is two contiguous
+// 24 KiB spans of memory.  A stage row is the 96-byte block as in memory, except that for rows with
 // bit 3 set the 16-byte chunks are swapped in pairs (0<->1, 2<->3, 4<->5): with the 96-byte row pitch the 16
 // rows of an MFMA operand then start 4 banks apart, all 64 banks once.
 // Ring discipline: barrier B(g) sits before the MFMAs of block g - 1, after its fragments have arrived in
@@ -173,8 +174,8 @@ __global__ __launch_bounds__(kWavesPerWg * 64, 2) void linear_e2m3_persistent(co
     auto pf_setup = [&]() {
         const int to = pf_tile % p.tiles_o, tr = pf_tile / p.tiles_o;
         const int64_t r0 = (int64_t)tr * kTileRows, o0 = (int64_t)to * kTile;
-        pf_x = p.x + r0 * p.ldx_bytes;
-        pf_w = p.w + o0 * p.ldw_bytes;
+        pf_x = p.x + r0 * kBlockBytes;  // in plane 0; block b is b plane pitches further
+        pf_w = p.w + o0 * kBlockBytes;
         const int rows_x = (int)min((int64_t)kTileRows, p.M - r0), rows_w = (int)min((int64_t)kTile, p.N - o0);
         // 16-byte chunk q of a stage half: row q / 6, chunk q mod 6; rows with bit 3 set keep chunk pairs swapped.
         // Rows beyond the matrix are clamped: their results are never stored.
@@ -182,20 +183,20 @@ __global__ __launch_bounds__(kWavesPerWg * 64, 2) void linear_e2m3_persistent(co
         for (int i = 0; i < X_COPIES; i++) {
             const int q = (wave + NW * i) * 64 + lane;
             const int row = q / 6, c = q - row * 6;
-            x_off[i] = (uint32_t)min(row, rows_x - 1) * (uint32_t)p.ldx_bytes + (c ^ ((row >> 3) & 1)) * 16;
+            x_off[i] = (uint32_t)min(row, rows_x - 1) * kBlockBytes + (c ^ ((row >> 3) & 1)) * 16;
         }
 #pragma unroll
         for (int i = 0; i < W_COPIES; i++) {
             const int q = (wave + NW * i) * 64 + lane;
             const int row = q / 6, c = q - row * 6;
-            w_off[i] = (uint32_t)min(row, rows_w - 1) * (uint32_t)p.ldw_bytes + (c ^ ((row >> 3) & 1)) * 16;
+            w_off[i] = (uint32_t)min(row, rows_w - 1) * kBlockBytes + (c ^ ((row >> 3) & 1)) * 16;
         }
     };
     auto issue = [&]() {  // copy the producer's block into ring stage pf_stage, then advance
         char *sx = ring + pf_stage * kStageBytes;
         char *sw = sx + kTileRows * kBlockBytes;
-        const char *gx = pf_x + (int64_t)pf_block * kBlockBytes;
-        const char *gw = pf_w + (int64_t)pf_block * kBlockBytes;
+        const char *gx = pf_x + (int64_t)pf_block * p.ldx_bytes;
+        const char *gw = pf_w + (int64_t)pf_block * p.ldw_bytes;
 #pragma unroll
         for (int i = 0; i < ((PTQ4VM_E2M3_SKIP & 4) ? 0 : X_COPIES); i++)
             __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void *)(gx + x_off[i]),
@@ -438,8 +439,10 @@ extern "C" int ptq4vm_w4a4_linear_e2m3(const uint8_t *xq6, const uint8_t *wq6, c
     if (!xq6 || !wq6 || !s_tok || !s_w || !y_f16) return PTQ4VM_ERR_NULL;
     if (B < 0 || N < 0 || L <= 0 || K <= 0 || K > PTQ4VM_MAX_K_E2M3) return PTQ4VM_ERR_SHAPE;
     if (B > 0 && L > INT64_MAX / B) return PTQ4VM_ERR_SHAPE;
-    const int64_t row_bytes = PTQ4VM_E2M3_ROW_BYTES(K);
-    if (ldxq < row_bytes || ldwq < row_bytes || ldxq % 16 != 0 || ldwq % 16 != 0 || ldy < N) return PTQ4VM_ERR_STRIDE;
+    const int64_t row_bytes = PTQ4VM_E2M3_BLOCKS(K) * kBlockBytes;
+    // ldxq / ldwq: plane pitches of the block-major containers
+    if ((B > 0 && ldxq / kBlockBytes < B * L) || ldwq / kBlockBytes < N || ldxq % 16 != 0 || ldwq % 16 != 0 || ldy < N)
+        return PTQ4VM_ERR_STRIDE;
     if (!ptq4vm::aligned_to(xq6, 16) || !ptq4vm::aligned_to(wq6, 16) || !ptq4vm::aligned_to(y_f16, 2) ||
         !ptq4vm::aligned_to(s_tok, 4) || !ptq4vm::aligned_to(s_w, 4) || !ptq4vm::aligned_to(bias_f16, 2) ||
         !ptq4vm::aligned_to(acc_out, 4))
@@ -464,7 +467,7 @@ extern "C" int ptq4vm_w4a4_linear_e2m3(const uint8_t *xq6, const uint8_t *wq6, c
     hipStream_t stream = static_cast<hipStream_t>(stream_);
     const int64_t tiles = ptq4vm::ceil_div(M, 256) * ptq4vm::ceil_div(N, kTile);
     const bool persistent_ok = K % 128 == 0 && K >= 256 && N % 8 == 0 && ptq4vm::aligned_to(y_f16, 16) && ldy % 8 == 0 &&
-                               ptq4vm::aligned_to(bias_f16, 4) && ldxq * kTile < (1LL << 31) && ldwq * kTile < (1LL << 31) &&
+                               ptq4vm::aligned_to(bias_f16, 4) &&
                                ldy * 2 * kTile < (1LL << 31) && L < (1LL << 31) && tiles >= 128 && tiles <= 0x3fffffffLL;
     if (persistent_ok) return launch_persistent(a, stream);
     return launch_generic(a, stream);

@@ -8,7 +8,9 @@
 // Container: a row is zero padded to a multiple of 128 codes and written as 96-byte blocks of 128 codes; in a
 // block, group g = 0..3 holds codes 32 g .. 32 g + 31 as a 192-bit little-endian string (code j at bits
 // [6 j, 6 j + 6)), the string's first 16 bytes at block offset 16 g, its last 8 bytes at offset 64 + 8 g: a
-// lane of the MFMA reads its 32 codes with one 16-byte and one 8-byte access.
+// lane of the MFMA reads its 32 codes with one 16-byte and one 8-byte access.  Storage is block-major: block b
+// of row r starts at byte b * pitch + 96 r (plane pitch >= 96 rows), so the blocks that 16 consecutive rows have
+// in one block column are one contiguous 1536-byte span.
 // The integer decision is the one of the nibble quantizer (same fp32 products, rint, hardware float -> int
 // conversion, clamp); the integer is then converted back to fp32 (exact) and 32 of them are packed by one
 // v_cvt_scalef32_2xpk16_fp6_f32 (scale 1: exact for these values; -0 cannot occur because the value comes
@@ -48,8 +50,9 @@ __device__ __forceinline__ u32x6 pack32_e2m3(const float (&v)[32]) {
     return __builtin_amdgcn_cvt_scalef32_2xpk16_fp6_f32(even, odd, 1.0f);
 }
 
-__device__ __forceinline__ void store_group(uint8_t *row, int group, const u32x6 &s) {
-    uint8_t *block = row + (group >> 2) * kBlockBytes;
+// `base`: the container; group: 4 * block + g; pitch: plane pitch in bytes
+__device__ __forceinline__ void store_group(uint8_t *base, int64_t row, int group, int64_t pitch, const u32x6 &s) {
+    uint8_t *block = base + (group >> 2) * pitch + row * kBlockBytes;
     const int g = group & 3;
     const u32x4 lo = {s[0], s[1], s[2], s[3]};
     const u32x2 hi = {s[4], s[5]};
@@ -75,11 +78,9 @@ __global__ __launch_bounds__(kThreads) void quantize_pts_a4_e2m3_stream(const __
     const int64_t gtid = (int64_t)blockIdx.x * kThreads + threadIdx.x;
     const int group = (int)(gtid % groups_padded);
     int64_t row = gtid / groups_padded;
-    uint8_t *qp = xq6 + row * ldxq;
-    const int64_t q_step = row_step * ldxq;
     if (group >= groups) {
         const u32x6 zero = {0, 0, 0, 0, 0, 0};
-        for (; row < M; row += row_step, qp += q_step) store_group(qp, group, zero);
+        for (; row < M; row += row_step) store_group(xq6, row, group, ldxq, zero);
         return;
     }
     int t = (int)(row % L);
@@ -107,9 +108,8 @@ __global__ __launch_bounds__(kThreads) void quantize_pts_a4_e2m3_stream(const __
                 v[k] = code4_as_float(__low2float(h), im[k], inv_s);
                 v[k + 1] = code4_as_float(__high2float(h), im[k + 1], inv_s);
             }
-        store_group(qp, group, pack32_e2m3(v));
+        store_group(xq6, row, group, ldxq, pack32_e2m3(v));
         xp += x_step;
-        qp += q_step;
     }
 }
 
@@ -118,9 +118,11 @@ __global__ __launch_bounds__(kThreads) void quantize_pts_a4_e2m3_stream(const __
 // of chunk (l mod 16) of row 4 c + l / 16, so a lane keeps the smoothing factors of 8 channels for life.  The 32
 // values of a group are spread over 4 lanes, and the packing instruction wants them in one: the integer-valued
 // floats cross through a wavefront-private LDS patch (group pitch 144 bytes: the 16 lanes of an access phase
-// start 4 banks apart), after which lane G holds group G mod 4 of row G / 4 and writes its 24 bytes.
+// start 4 banks apart), after which lane G holds group G mod 4 of row G / 4; its 24 bytes go to a second patch laid
+// out like the unit's 1536 contiguous bytes of the container, which leave as 16-byte stores of consecutive lines.
 constexpr int kPatchPitch = 144;
-constexpr int kPatchBytes = 64 * kPatchPitch;  // per wavefront
+constexpr int kOutBytes = 16 * kBlockBytes;                // the unit's 16 blocks as they lie in memory
+constexpr int kPatchBytes = 64 * kPatchPitch + kOutBytes;  // per wavefront
 constexpr int kMaxBlockTokens = 4096;        // reciprocal steps of all token positions sit next to the patches (52 KiB in all)
 
 template <bool HAS_M>
@@ -180,8 +182,22 @@ __global__ __launch_bounds__(kThreads) void quantize_pts_a4_e2m3_blocks(const __
             v[4 * i] = f.x, v[4 * i + 1] = f.y, v[4 * i + 2] = f.z, v[4 * i + 3] = f.w;
         }
         asm volatile("" ::: "memory");
-        const int64_t r = r0 + (lane >> 2);
-        if (r < M) store_group(xq6 + r * ldxq, block * 4 + (lane & 3), pack32_e2m3(v));
+        const u32x6 packed = pack32_e2m3(v);
+        char *out = patch + 64 * kPatchPitch;
+        *reinterpret_cast<u32x4 *>(out + (lane >> 2) * kBlockBytes + 16 * (lane & 3)) = u32x4{packed[0], packed[1], packed[2], packed[3]};
+        *reinterpret_cast<u32x2 *>(out + (lane >> 2) * kBlockBytes + 64 + 8 * (lane & 3)) = u32x2{packed[4], packed[5]};
+        asm volatile("" ::: "memory");
+        const int valid = (int)min((int64_t)16, M - r0) * kBlockBytes;  // bytes of the unit inside the matrix
+        uint8_t *dst = xq6 + block * ldxq + r0 * kBlockBytes;
+#pragma unroll
+        for (int h = 0; h < 2; h++) {
+            const int off = (h * 64 + lane) * 16;
+            if (off < valid && (h == 0 || lane < 32)) {
+                const u32x4 data = *reinterpret_cast<const u32x4 *>(out + off);
+                __builtin_nontemporal_store(data, reinterpret_cast<u32x4 *>(dst + off));
+            }
+        }
+        asm volatile("" ::: "memory");
     }
 }
 
@@ -204,7 +220,7 @@ __global__ __launch_bounds__(kThreads) void quantize_pts_a4_e2m3_generic(const _
             const int64_t k = (int64_t)group * kGroupCodes + j;
             v[j] = k < K ? code4_as_float(__half2float(x[r * ldx + k]), HAS_M ? inv_m[k] : 1.0f, inv_s) : 0.0f;
         }
-        store_group(xq6 + r * ldxq, group, pack32_e2m3(v));
+        store_group(xq6, r, group, ldxq, pack32_e2m3(v));
     }
 }
 
@@ -234,7 +250,6 @@ __global__ __launch_bounds__(kThreads) void fold_smoothing_w4_e2m3_rows(const __
     for (int i = 1; i < kThreads / 64; i++) amax = fmaxf(amax, red[i]);
     const float step = (amax == 0.0f) ? 1.0f : amax / 7.0f;
     if (threadIdx.x == 0) s_w[o] = step;
-    uint8_t *qrow = wq6 + o * ldwq;
     for (int group = threadIdx.x; group < groups_padded; group += kThreads) {
         float v[kGroupCodes];
 #pragma unroll
@@ -247,7 +262,7 @@ __global__ __launch_bounds__(kThreads) void fold_smoothing_w4_e2m3_rows(const __
             }
             v[j] = q;
         }
-        store_group(qrow, group, pack32_e2m3(v));
+        store_group(wq6, o, group, ldwq, pack32_e2m3(v));
     }
 }
 
@@ -266,7 +281,7 @@ extern "C" int ptq4vm_fold_smoothing_w4_e2m3(const void *w_f16, const float *m, 
                                              int64_t N, int64_t K, int64_t ldw, int64_t ldwq, void *stream_) {
     if (!w_f16 || !m || !wq6 || !s_w || !inv_m) return PTQ4VM_ERR_NULL;
     if (N < 0 || K <= 0 || K > PTQ4VM_MAX_K_E2M3) return PTQ4VM_ERR_SHAPE;
-    if (ldw < K || ldwq < PTQ4VM_E2M3_ROW_BYTES(K) || ldwq % 16 != 0) return PTQ4VM_ERR_STRIDE;
+    if (ldw < K || ldwq / 96 < N || ldwq % 16 != 0) return PTQ4VM_ERR_STRIDE;
     if (!ptq4vm::aligned_to(w_f16, 2) || !ptq4vm::aligned_to(wq6, 16) || !ptq4vm::aligned_to(m, 4) ||
         !ptq4vm::aligned_to(s_w, 4) || !ptq4vm::aligned_to(inv_m, 4))
         return PTQ4VM_ERR_ALIGN;
@@ -283,7 +298,7 @@ extern "C" int ptq4vm_quantize_pts_a4_e2m3(const void *x_f16, const float *inv_m
     if (!x_f16 || !s_tok || !xq6) return PTQ4VM_ERR_NULL;
     if (B < 0 || L <= 0 || K <= 0 || K > PTQ4VM_MAX_K_E2M3) return PTQ4VM_ERR_SHAPE;
     if (L > 0x7fffffffLL || (B > 0 && L > INT64_MAX / B)) return PTQ4VM_ERR_SHAPE;
-    if (ldx < K || ldxq < PTQ4VM_E2M3_ROW_BYTES(K) || ldxq % 16 != 0) return PTQ4VM_ERR_STRIDE;
+    if (ldx < K || (B > 0 && ldxq / 96 < B * L) || ldxq % 16 != 0) return PTQ4VM_ERR_STRIDE;
     if (!ptq4vm::aligned_to(x_f16, 2) || !ptq4vm::aligned_to(xq6, 16) || !ptq4vm::aligned_to(s_tok, 4) ||
         (inv_m && !ptq4vm::aligned_to(inv_m, 4)))
         return PTQ4VM_ERR_ALIGN;

@@ -163,12 +163,12 @@ def test_w4a4_entry_points_argument_checks(lib):
 
 
 def test_w4a4_e2m3_entry_points_argument_checks(lib):
-    # container rows: 96 bytes per started block of 128 codes, pitches multiples of 16
+    # block-major containers: 96 bytes per row and block of 128 codes; plane pitch >= 96 rows, a multiple of 16
     fold = lib.ptq4vm_fold_smoothing_w4_e2m3
     assert fold(NULL, P, P, P, P, 1, 8, 8, 96, None) == -1
     assert fold(P, P, P, P, P, 1, 0, 8, 96, None) == -2
-    assert fold(P, P, P, P, P, 1, 262145, 262145, 196704, None) == -2     # beyond PTQ4VM_MAX_K_E2M3
-    assert fold(P, P, P, P, P, 1, 129, 129, 96, None) == -3                # two blocks need 192 bytes
+    assert fold(P, P, P, P, P, 1, 262145, 262145, 96, None) == -2          # beyond PTQ4VM_MAX_K_E2M3
+    assert fold(P, P, P, P, P, 2, 8, 8, 96, None) == -3                    # two rows need a plane of 192 bytes
     assert fold(P, P, P, P, P, 1, 8, 8, 100, None) == -3                   # pitch not a multiple of 16
     assert fold(P, P, ODD, P, P, 1, 8, 8, 96, None) == -4
     q = lib.ptq4vm_quantize_pts_a4_e2m3
@@ -176,11 +176,12 @@ def test_w4a4_e2m3_entry_points_argument_checks(lib):
     assert q(P, P, P, P, 1, 0, 8, 8, 96, None) == -2
     assert q(P, P, P, P, 1, 1, 9, 8, 96, None) == -3                       # ldx < K
     assert q(P, P, P, P, 1, 1, 8, 8, 80, None) == -3
+    assert q(P, P, P, P, 2, 3, 8, 8, 480, None) == -3                      # six rows need 576 bytes
     assert q(P, P, P, ODD, 1, 1, 8, 8, 96, None) == -4
     assert q(P, NULL, P, P, 0, 5, 7, 7, 96, None) == 0                     # odd K is fine; no rows: nothing to do
     f = lib.ptq4vm_w4a4_linear_e2m3
-    #     xq6 wq6 s_tok s_w bias y acc  B  L  K   N   ldxq ldwq ldy stream
-    ok = [P, P, P, P, P, P, NULL, 1, 1, 16, 16, 96, 96, 16, None]
+    #     xq6 wq6 s_tok s_w bias y acc  B  L  K   N   ldxq ldwq  ldy stream
+    ok = [P, P, P, P, P, P, NULL, 1, 1, 16, 16, 96, 1536, 16, None]
 
     def call(**kw):
         a = list(ok)
@@ -189,8 +190,8 @@ def test_w4a4_e2m3_entry_points_argument_checks(lib):
         return f(*a)
 
     assert call(a0=NULL) == -1 and call(a1=NULL) == -1 and call(a5=NULL) == -1
-    assert call(a9=0) == -2 and call(a8=0) == -2 and call(a9=262145, a11=196704, a12=196704) == -2
-    assert call(a11=80) == -3 and call(a12=104) == -3 and call(a13=15) == -3 and call(a9=129) == -3
+    assert call(a9=0) == -2 and call(a8=0) == -2 and call(a9=262145) == -2
+    assert call(a11=80) == -3 and call(a12=1520) == -3 and call(a12=1544) == -3 and call(a13=15) == -3
     assert call(a0=ODD) == -4 and call(a1=ODD) == -4
     assert call(a7=0) == 0 and call(a10=0) == 0
 

@@ -117,8 +117,8 @@ def test_e2m3_extreme_codes_and_every_code_pair():
 
 
 def test_e2m3_quantizer_special_values_padding_and_pitch():
-    """NaN -> 0, +-Inf -> +-7, ties to even, negative values that round to zero (no "-0" pattern), a pitch wider
-    than the row (bytes beyond the container stay untouched), K that is no multiple of 32 (element path)."""
+    """NaN -> 0, +-Inf -> +-7, ties to even, negative values that round to zero (no "-0" pattern), a plane pitch
+    wider than the rows need (bytes beyond them stay untouched), K that is no multiple of 32 (element path)."""
     for K in (64, 50):
         B, L = 2, 5
         M = B * L
@@ -127,13 +127,12 @@ def test_e2m3_quantizer_special_values_padding_and_pitch():
         x[:, :len(vals)] = torch.tensor(vals, dtype=torch.float16, device=DEV)
         x[:, len(vals):] = torch.linspace(-9, 9, K - len(vals), device=DEV).half()
         s_tok = torch.ones(L, device=DEV)
-        pitch = ptq.e2m3_row_bytes(K) + 32
-        buf = torch.full((M, pitch), 0xAB, dtype=torch.uint8, device=DEV)
-        ptq.quantize_pts_a4_e2m3(x, None, s_tok, B, L, xq6=buf[:, :ptq.e2m3_row_bytes(K)])
+        buf = torch.full((ptq.e2m3_blocks(K), M + 3, 96), 0xAB, dtype=torch.uint8, device=DEV)  # planes 3 rows longer
+        ptq.quantize_pts_a4_e2m3(x, None, s_tok, B, L, xq6=buf[:, :M, :])
         torch.cuda.synchronize()
         want = oracle.pack_e2m3(oracle.quantize_pts_bits(_np(x), None, _np(s_tok), B, L, 4))
-        assert np.array_equal(_np(buf[:, :ptq.e2m3_row_bytes(K)]), want)
-        assert (_np(buf[:, ptq.e2m3_row_bytes(K):]) == 0xAB).all()
+        assert np.array_equal(_np(buf[:, :M, :]), want)
+        assert (_np(buf[:, M:, :]) == 0xAB).all()
 
 
 @pytest.mark.parametrize("B,L,K", [(40, 7, 128), (3, 5, 256), (1, 5000, 128), (1, 20000, 128), (7, 33, 96), (2, 9, 1000), (5, 197, 640)])
@@ -168,7 +167,7 @@ def _check_e2m3_on_sampled_rows(c, what):
     assert np.array_equal(_np(wq6), oracle.pack_e2m3(wq_o))
     st_rows = _np(s4)[rows % c.L]
     xq_o = oracle.quantize_pts_bits(_np(c.x[ridx]), inv_m_o, st_rows, 1, len(rows), 4)
-    assert np.array_equal(_np(xq6[ridx]), oracle.pack_e2m3(xq_o))
+    assert np.array_equal(_np(xq6[:, ridx]), oracle.pack_e2m3(xq_o))
     y_o, y64, acc_o = oracle.w8a8_linear(xq_o, wq_o, st_rows, s_w_o, _np(c.bias), 1, len(rows))
     assert np.array_equal(_np(acc[ridx]), acc_o), "int32 accumulators differ"
     prod_abs = np.abs(acc_o.astype(np.float64) * st_rows.astype(np.float64)[:, None] * s_w_o.astype(np.float64)[None, :])
