@@ -109,9 +109,10 @@ __global__ __launch_bounds__(kThreads) void linear_e2m3_generic(const LinearArgs
 // ------------------------------------------------------------------------------------------
 // Persistent kernel.  LDS: ring of kStages stages, each (256 token rows + 256 channels) x 96 bytes, then two
 // buffers of per-tile scale vectors.  The containers are block-major, so what a stage receives is two contiguous
-// 24 KiB spans of memory.  A stage row is the 96-byte block as in memory, except that for rows with
-// bit 3 set the 16-byte chunks are swapped in pairs (0<->1, 2<->3, 4<->5): with the 96-byte row pitch the 16
-// rows of an MFMA operand then start 4 banks apart, all 64 banks once.
+// 24 KiB spans of memory.  A stage row is the 96-byte block as in memory, except that rows with bit 3 set keep
+// their last two 16-byte chunks (the groups' 8-byte high parts) swapped.  Measured with a stand-alone read loop
+// (bytes per clock and CU, 16-byte low-part reads / 8-byte high-part reads / both): rows as in memory 228 / 118 /
+// 168, high chunks swapped by row bit 3: 245 / 174 / 203, all chunk pairs swapped by row bit 3: 127 / 170 / 141.
 // Ring discipline: barrier B(g) sits before the MFMAs of block g - 1, after its fragments have arrived in
 // registers.  Passing it means every wavefront's copies of block g have landed and nobody reads block g - 1's
 // stage again, so that stage is refilled at once with block g + 2 (after a tile's last block the refill waits
@@ -126,6 +127,9 @@ __global__ __launch_bounds__(kThreads) void linear_e2m3_generic(const LinearArgs
 #ifndef PTQ4VM_E2M3_STAGES
 #define PTQ4VM_E2M3_STAGES 3
 #endif
+// Which 16-byte chunk of a row's block goes to chunk position c of its stage row.
+__device__ __forceinline__ int stage_chunk_source(int row, int c) { return c < 4 ? c : 4 + ((c - 4) ^ ((row >> 3) & 1)); }
+
 constexpr int kTile = 256;                 // channels per tile
 constexpr int kTileRows = PTQ4VM_E2M3_BR;  // token rows per tile: 256 (one workgroup of 8 wavefronts per CU) or 128 (two of 4)
 constexpr int kStages = PTQ4VM_E2M3_STAGES;
@@ -151,7 +155,7 @@ __global__ __launch_bounds__(kWavesPerWg * 64, 2) void linear_e2m3_persistent(co
     const int l16 = lane & 15, lq = lane >> 4;
     const int swap = (l16 >> 3) & 1;
     // byte offsets of this lane's fragment parts inside a stage row block of 16 rows
-    const int frag_lo = l16 * kBlockBytes + ((lq ^ swap) << 4);
+    const int frag_lo = l16 * kBlockBytes + (lq << 4);
     const int frag_hi = l16 * kBlockBytes + ((4 + ((lq >> 1) ^ swap)) << 4) + (lq & 1) * 8;
 
     // work split: XCD x owns a contiguous range of tiles (channel tiles fastest), its workgroups interleave in it
@@ -177,19 +181,19 @@ __global__ __launch_bounds__(kWavesPerWg * 64, 2) void linear_e2m3_persistent(co
         pf_x = p.x + r0 * kBlockBytes;  // in plane 0; block b is b plane pitches further
         pf_w = p.w + o0 * kBlockBytes;
         const int rows_x = (int)min((int64_t)kTileRows, p.M - r0), rows_w = (int)min((int64_t)kTile, p.N - o0);
-        // 16-byte chunk q of a stage half: row q / 6, chunk q mod 6; rows with bit 3 set keep chunk pairs swapped.
+        // 16-byte chunk q of a stage half: row q / 6, chunk q mod 6; rows with bit 3 set keep chunks 4 and 5 swapped.
         // Rows beyond the matrix are clamped: their results are never stored.
 #pragma unroll
         for (int i = 0; i < X_COPIES; i++) {
             const int q = (wave + NW * i) * 64 + lane;
             const int row = q / 6, c = q - row * 6;
-            x_off[i] = (uint32_t)min(row, rows_x - 1) * kBlockBytes + (c ^ ((row >> 3) & 1)) * 16;
+            x_off[i] = (uint32_t)min(row, rows_x - 1) * kBlockBytes + stage_chunk_source(row, c) * 16;
         }
 #pragma unroll
         for (int i = 0; i < W_COPIES; i++) {
             const int q = (wave + NW * i) * 64 + lane;
             const int row = q / 6, c = q - row * 6;
-            w_off[i] = (uint32_t)min(row, rows_w - 1) * kBlockBytes + (c ^ ((row >> 3) & 1)) * 16;
+            w_off[i] = (uint32_t)min(row, rows_w - 1) * kBlockBytes + stage_chunk_source(row, c) * 16;
         }
     };
     auto issue = [&]() {  // copy the producer's block into ring stage pf_stage, then advance
