@@ -781,7 +781,7 @@ __host__ __device__ __forceinline__ WresLayout wres_layout(int N, int k_bytes) {
     WresLayout l;
     l.nb = (N + 15) >> 4;
     l.n4 = (N + 3) & ~3;
-    l.pw = k_bytes + 16;
+    l.pw = k_bytes + 32;  // in 16-byte chunks 2 mod 4: operand reads of 16 rows run at 235-240 bytes per clock and CU (k_bytes + 16: 120)
     l.w_bytes = (l.nb * 16 * l.pw + 1023) & ~1023;  // whole 1 KiB wavefront copies
     l.scale_bytes = l.nb * 16 * 4 * 3;  // step, bias and (zero-offset path) weight row sum per channel
     l.patch_bytes = 16 * l.n4 * 2;                   // one 16-row block of fp16 results
@@ -836,7 +836,7 @@ __global__ __launch_bounds__(kWresWaves * 64) void linear_mfma_wres(const Linear
         for (int c = wave; c < (lay.w_bytes >> 10); c += kWresWaves) {
             const int chunk = c * 64 + lane;
             const int row = chunk / chunks_per_row, cc = chunk - row * chunks_per_row;
-            const char *src = p.w + (int64_t)min(row, N - 1) * p.ldw_bytes + min(cc, chunks_per_row - 2) * 16;
+            const char *src = p.w + (int64_t)min(row, N - 1) * p.ldw_bytes + min(cc, chunks_per_row - 3) * 16;
             __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void *)src,
                                              (__attribute__((address_space(3))) void *)(w_lds + c * 1024), 16, 0, 0);
         }

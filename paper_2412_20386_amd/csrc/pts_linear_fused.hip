@@ -96,7 +96,7 @@ __host__ __device__ __forceinline__ FusedLayout fused_layout(int N, int K, int L
     FusedLayout l;
     l.nb = (N + 15) >> 4;
     l.n4 = (N + 3) & ~3;
-    l.pw = K + 16;
+    l.pw = K + 32;  // in 16-byte chunks 2 mod 4: operand reads of 16 rows run at 235-240 bytes per clock and CU (K + 16: 120)
     l.w_bytes = (l.nb * 16 * l.pw + 1023) & ~1023;  // whole 1 KiB wavefront copies
     l.inv_m_off = l.w_bytes;
     l.inv_s_off = l.inv_m_off + K * 4;
@@ -211,7 +211,7 @@ __global__ __launch_bounds__(kFusedWaves * 64) void pts_linear_wres(const Linear
         for (int c = wave; c < (lay.w_bytes >> 10); c += kFusedWaves) {
             const int chunk = c * 64 + lane;
             const int row = chunk / chunks_per_row, cc = chunk - row * chunks_per_row;
-            const char *src = p.w + (int64_t)min(row, N - 1) * p.ldw_bytes + min(cc, chunks_per_row - 2) * 16;
+            const char *src = p.w + (int64_t)min(row, N - 1) * p.ldw_bytes + min(cc, chunks_per_row - 3) * 16;
             __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void *)src,
                                              (__attribute__((address_space(3))) void *)(w_lds + c * 1024), 16, 0, 0);
         }
@@ -228,14 +228,15 @@ __global__ __launch_bounds__(kFusedWaves * 64) void pts_linear_wres(const Linear
     const bool dense_y = n4 == N && p.ldy == p.N && (reinterpret_cast<uintptr_t>(p.y) & 15) == 0;
     const int chunks8_per_row = n4 >> 2;  // 8-byte groups of four channels per result row
     const char *const w_lane = w_lds + l16 * pw + lq * 16;
-    // Code tile: row pitch 64 bytes, 16-byte chunk c of row r stored at chunk position c ^ ((r >> 2) & 3).
+    // Code tile: row pitch 64 bytes, 16-byte chunk c of row r stored at chunk position c ^ (((r >> 1) ^ (r >> 2)) & 3)
+    // (operand reads at 236 bytes per clock and CU in a read loop; with (r >> 2) & 3: 120).
     uint32_t tile_wr[NL];
 #pragma unroll
     for (int i = 0; i < NL; i++) {
         const int row = i * 8 + rr;
-        tile_wr[i] = row * 64 + (((pc >> 1) ^ ((row >> 2) & 3)) << 4) + (pc & 1) * 8;
+        tile_wr[i] = row * 64 + (((pc >> 1) ^ (((row >> 1) ^ (row >> 2)) & 3)) << 4) + (pc & 1) * 8;
     }
-    const uint32_t tile_rd = l16 * 64 + ((lq ^ ((l16 >> 2) & 3)) << 4);  // + 1024 for rows 16..31
+    const uint32_t tile_rd = l16 * 64 + ((lq ^ (((l16 >> 1) ^ (l16 >> 2)) & 3)) << 4);  // + 1024 for rows 16..31
 
     bool next_have = false;
     for (; have; have = next_have, unit_r0 = next_r0, unit_rows = next_rows) {
@@ -484,7 +485,9 @@ __global__ __launch_bounds__(kStreamWaves * 64) void linear_stream_smallk(const 
     float *const inv_m_lds = reinterpret_cast<float *>(lds_dyn + lay.inv_m_off);
     char *const patch = lds_dyn + lay.patch_off + wave * kStreamPatch;
     constexpr int RB = kStreamRB, UNIT = 16 * RB;
-    auto swz = [](int row) { return KSTEPS == 1 ? ((row >> 2) & 3) : ((row >> 1) & 3); };
+    // 64-byte rows: measured in a read loop, ((row >> 1) ^ (row >> 2)) & 3 reads 16-byte operands at 236 bytes per clock
+    // and CU, (row >> 2) & 3 at 120
+    auto swz = [](int row) { return KSTEPS == 1 ? (((row >> 1) ^ (row >> 2)) & 3) : ((row >> 1) & 3); };
 
     // Set-up: weight (zero beyond N and K), scales, bias.
     {
