@@ -284,6 +284,53 @@ def measure_config(args, config: int, full: bool):
     torch.cuda.synchronize()
     result["dynamic_ms_per_step"] = (time.perf_counter() - t0) / max(1, args.steps // 2) * 1e3
 
+    # W4A4 stack (the precision of the paper's latency table, Sec. 6.4): per layer and linear PTS-quantize to 4 bits +
+    # W4A4 linear, two launches, in the container that the per-kernel sweep above found faster for that linear.
+    result["w4a4_ms_per_step"] = None
+    if all(k.get("w4a4_best_us") is not None for k in kernels):
+        choice = []
+        for k in kernels:
+            nib = (k["a4_quantize_us"] + k["w4a4_us"]) if k.get("w4a4_us") is not None else float("inf")
+            e2m3 = (k["a4_e2m3_quantize_us"] + k["w4a4_e2m3_us"]) if k.get("w4a4_e2m3_us") is not None else float("inf")
+            choice.append("e2m3" if e2m3 < nib else "nibbles")
+        prepared = []
+        for lin in layers:
+            row = []
+            for li, d in enumerate(lin):
+                K = d["K"]
+                s4 = (d["s_tok"] * (127.0 / 7.0)).contiguous()
+                m = 1.0 / d["inv_m"]
+                flat = d["xq"].view(torch.uint8).view(-1)
+                if choice[li] == "e2m3":
+                    wq6, s_w6, _ = ptq.fold_smoothing_w4_e2m3(d["w"], m)
+                    nb = ptq.e2m3_blocks(K)
+                    row.append(("e2m3", wq6, s_w6, s4, flat[: nb * M * 96].view(nb, M, 96)))
+                else:
+                    wq4, s_w4, _ = ptq.fold_smoothing_w4(d["w"], m)
+                    row.append(("nibbles", wq4, s_w4, s4, flat[: M * (K // 2)].view(M, K // 2)))
+            prepared.append(row)
+
+        def step_w4a4():
+            for lin, row in zip(layers, prepared):
+                for d, (kind, wq_, s_w_, s4, xq_) in zip(lin, row):
+                    if kind == "e2m3":
+                        ptq.quantize_pts_a4_e2m3(d["x"], d["inv_m"], s4, B, L, xq6=xq_)
+                        ptq.w4a4_linear_e2m3(xq_, wq_, s4, s_w_, d["bias"], B, L, d["K"], y=d["y"])
+                    else:
+                        ptq.quantize_pts_a4(d["x"], d["inv_m"], s4, B, L, xq4=xq_)
+                        ptq.w4a4_linear(xq_, wq_, s4, s_w_, d["bias"], B, L, y=d["y"])
+
+        for _ in range(2):
+            step_w4a4()
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for _ in range(max(1, args.steps // 2)):
+            step_w4a4()
+        torch.cuda.synchronize()
+        result["w4a4_ms_per_step"] = (time.perf_counter() - t0) / max(1, args.steps // 2) * 1e3
+        result["w4a4_containers"] = {k["linear"]: c for k, c in zip(kernels, choice)}
+        del prepared
+
     # One plain device-to-device copy of known size (untimed): the reference against which the
     # rocprofv3 FETCH_SIZE / WRITE_SIZE counters of the GEMM are scaled in profiles/.
     calib_src = torch.empty(256 << 20, dtype=torch.uint8, device=dev).fill_(1)
@@ -431,6 +478,9 @@ def main() -> int:
         "graph_ms_per_step": None if r["graph_ms_per_step"] is None else round(r["graph_ms_per_step"], 4),
         "dynamic_ms_per_step": round(r["dynamic_ms_per_step"], 4),
         "speedup_pts_vs_per_token_dynamic": round(r["dynamic_ms_per_step"] / ms_per_step, 3),
+        "w4a4_ms_per_step": None if r.get("w4a4_ms_per_step") is None else round(r["w4a4_ms_per_step"], 4),
+        "w4a4_containers": r.get("w4a4_containers"),
+        "speedup_w4a4_vs_f16_stack": None if r.get("w4a4_ms_per_step") is None else round(r["f16_ms_per_step"] / r["w4a4_ms_per_step"], 3),
         "w4a4_two_launch_us_per_layer": None if w4a4_sum is None else round(w4a4_sum, 1),
         "w8a8_two_launch_us_per_layer": round(w8a8_sum, 1),
         "speedup_w4a4_vs_w8a8_kernel_sums": None if not w4a4_sum else round(w8a8_sum / w4a4_sum, 3),
