@@ -229,6 +229,23 @@ int ptq4vm_w8a8_linear_fused(const void *x_f16, const float *inv_m, const float 
                              int64_t ldwq, int64_t ldy, int64_t ldxq, void *stream);
 
 /*
+ * Fused activation quantizer + W4A4 linear: ptq4vm_quantize_pts_a4 followed by ptq4vm_w4a4_linear in one launch
+ * (the four stages of App. B.1 at the precision of the latency table, Sec. 6.4); the 4-bit codes stay on chip.  Same
+ * codes and accumulators as the two calls, bit for bit.  Arguments as ptq4vm_w8a8_linear_fused, except
+ *   wq4      [N, ldwq]   packed 4-bit codes in (two per byte, even index in the low nibble; ldwq in bytes >= K / 2)
+ *   s_tok    [L]         the 4-bit steps
+ *   xq_out   [B*L, ldxq] int8 out; may be NULL (parity aid: the 4-bit codes the GEMM consumed, ONE per byte)
+ * Runs on the weight-resident kernel (N <= 128, K a multiple of 64, >= 2048 rows, 16-byte aligned rows of x and
+ * wq4) and on the row-streaming kernel (K <= 128, >= 1024 rows): the shapes where fusing pays (x_proj, dt_proj).
+ * Every other shape returns PTQ4VM_ERR_SHAPE - call ptq4vm_quantize_pts_a4 and ptq4vm_w4a4_linear there.
+ * Errors otherwise as ptq4vm_w4a4_linear / ptq4vm_w8a8_linear_fused (odd K, K > PTQ4VM_MAX_K_W4 -> PTQ4VM_ERR_SHAPE).
+ */
+int ptq4vm_w4a4_linear_fused(const void *x_f16, const float *inv_m, const float *s_tok, const uint8_t *wq4,
+                             const float *s_w, const void *bias_f16, void *y_f16, int32_t *acc_out,
+                             int8_t *xq_out, int64_t B, int64_t L, int64_t K, int64_t N, int64_t ldx,
+                             int64_t ldwq, int64_t ldy, int64_t ldxq, void *stream);
+
+/*
  * Debug validator of the device-resident scale vectors (Sec. 5.1: per-token steps Delta_X and
  * per-output-channel steps Delta_W; Sec. 2.4: smoothing vector s).  An entry is bad unless it is a
  * finite number > 0 (zero, negative, +-Inf and NaN are bad).  The hot path never looks at these

@@ -5,6 +5,7 @@ seeded Vim-shaped inputs; `build` compiles the library.  Nothing is loaded at im
 """
 from . import binding, synth  # noqa: F401
 from .binding import (  # noqa: F401
+    Ptq4vmError,
     f16_linear,
     fold_smoothing,
     fold_smoothing_w4,
@@ -14,6 +15,7 @@ from .binding import (  # noqa: F401
     fold_smoothing_w4_e2m3,
     quantize_pts_a4_e2m3,
     w4a4_linear_e2m3,
+    w4a4_linear_fused,
     quantize_dynamic,
     quantize_pts,
     quantize_pts_offset,

@@ -30,6 +30,7 @@ EXPORTS = (
     "ptq4vm_fold_smoothing_w4_e2m3",
     "ptq4vm_quantize_pts_a4_e2m3",
     "ptq4vm_w4a4_linear_e2m3",
+    "ptq4vm_w4a4_linear_fused",
     "ptq4vm_w8a8_linear",
     "ptq4vm_w8a8_linear_fused",
     "ptq4vm_f16_linear",
@@ -84,6 +85,8 @@ def load() -> ctypes.CDLL:
     lib.ptq4vm_quantize_pts_a4_e2m3.argtypes = [vp, vp, vp, vp, i64, i64, i64, i64, i64, vp]
     lib.ptq4vm_w4a4_linear_e2m3.restype = ci
     lib.ptq4vm_w4a4_linear_e2m3.argtypes = [vp, vp, vp, vp, vp, vp, vp, i64, i64, i64, i64, i64, i64, i64, vp]
+    lib.ptq4vm_w4a4_linear_fused.restype = ci
+    lib.ptq4vm_w4a4_linear_fused.argtypes = [vp, vp, vp, vp, vp, vp, vp, vp, vp, i64, i64, i64, i64, i64, i64, i64, i64, vp]
     lib.ptq4vm_w8a8_linear.restype = ci
     lib.ptq4vm_w8a8_linear.argtypes = [vp, vp, vp, vp, vp, vp, vp, i64, i64, i64, i64, i64, i64, i64, vp]
     lib.ptq4vm_w8a8_linear_fused.restype = ci
@@ -402,6 +405,35 @@ def w8a8_linear_fused(x: torch.Tensor, inv_m: Optional[torch.Tensor], s_tok: tor
                                           _ptr(acc_out), _ptr(xq_out), B, L, K, N, ldx, ldwq, ldy, ldxq, _stream()))
     return y
 
+
+def w4a4_linear_fused(x: torch.Tensor, inv_m: Optional[torch.Tensor], s_tok: torch.Tensor, wq4: torch.Tensor,
+                      s_w: torch.Tensor, bias: Optional[torch.Tensor], B: int, L: int,
+                      y: Optional[torch.Tensor] = None, acc_out: Optional[torch.Tensor] = None,
+                      xq_out: Optional[torch.Tensor] = None) -> torch.Tensor:
+    """ptq4vm_w4a4_linear_fused: y fp16 [B*L, N] from fp16 activations and a packed 4-bit weight [N, K/2];
+    acc_out / xq_out (int8, one 4-bit code per byte) are filled if given."""
+    M, K, ldx = _matrix(x, torch.float16, "x")
+    N, K2, ldwq = _matrix(wq4, torch.uint8, "wq4")
+    if K != 2 * K2 or M != B * L:
+        raise ValueError("shape mismatch")
+    _vector(inv_m, torch.float32, K, "inv_m", optional=True)
+    _vector(s_tok, torch.float32, L, "s_tok")
+    _vector(s_w, torch.float32, N, "s_w")
+    _vector(bias, torch.float16, N, "bias", optional=True)
+    if y is None:
+        y = torch.empty((M, N), dtype=torch.float16, device=x.device)
+    _, _, ldy = _matrix(y, torch.float16, "y")
+    if acc_out is not None and (acc_out.dtype != torch.int32 or tuple(acc_out.shape) != (M, N)
+                                or not acc_out.is_contiguous() or not acc_out.is_cuda):
+        raise TypeError("acc_out: expected a dense CUDA int32 [M, N] tensor")
+    ldxq = 0
+    if xq_out is not None:
+        Mq, Kq, ldxq = _matrix(xq_out, torch.int8, "xq_out")
+        if (Mq, Kq) != (M, K):
+            raise ValueError("xq_out must be [B*L, K]")
+    check(load().ptq4vm_w4a4_linear_fused(_ptr(x), _ptr(inv_m), _ptr(s_tok), _ptr(wq4), _ptr(s_w), _ptr(bias), _ptr(y),
+                                          _ptr(acc_out), _ptr(xq_out), B, L, K, N, ldx, ldwq, ldy, ldxq, _stream()))
+    return y
 
 def f16_linear(x: torch.Tensor, w: torch.Tensor, bias: Optional[torch.Tensor],
                y: Optional[torch.Tensor] = None) -> torch.Tensor:

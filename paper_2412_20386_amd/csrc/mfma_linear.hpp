@@ -456,7 +456,8 @@ __device__ __forceinline__ void lds_write_b128(uint32_t addr, v4f v) {
 // quantize: x holds fp16 activations and inv_m / xq_out are honoured; otherwise x holds int8 codes.
 // Returns PTQ4VM_OK after a launch, a negative status on error, or 1 if the shape does not fit
 // this kernel (nothing was launched; the caller picks another one).
-// packed4: x and w hold two 4-bit codes per byte (k_bytes = K / 2), expanded on chip; not with `quantize`.
+// packed4: x and w hold two 4-bit codes per byte (k_bytes = K / 2), expanded on chip; with `quantize` (the fused
+// 4-bit form) x holds fp16 activations, only w is packed and k_bytes = K.
 // offset: z_tok / rowsum are honoured (per-token zero offset); not with `quantize` or `packed4`.
 int launch_stream_smallk(const LinearArgs &a, bool quantize, hipStream_t stream, bool packed4 = false, bool offset = false);
 

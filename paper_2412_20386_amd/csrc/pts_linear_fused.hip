@@ -27,11 +27,31 @@ using namespace ptq4vm::mfma;
 
 // One PTS code (Sec. 5.1): smoothing multiply, step multiply, round half to even, clip.  Two
 // separate fp32 multiplies in this order: the codes must equal the stand-alone quantizer's.
+// BITS4: clip to +-7 (Sec. 2.3 with b = 4) instead of +-127.
+template <bool BITS4 = false>
 __device__ __forceinline__ int quantize_one(float x, float inv_m, float inv_s) {
     float v = x * inv_m;
     v = v * inv_s;
     const int q = cvt_i32_f32(__builtin_rintf(v));
-    return min(max(q, -127), 127);
+    return BITS4 ? min(max(q, -7), 7) : min(max(q, -127), 127);
+}
+
+// Four int8 bytes holding 4-bit codes -> the same codes times 16 (what the int8 MFMA is fed on the 4-bit path:
+// the accumulator is then 256 times the sum, undone exactly in the channel steps).
+__device__ __forceinline__ uint32_t times16(uint32_t packed_codes) { return (packed_codes << 4) & 0xF0F0F0F0u; }
+
+// 32 packed 4-bit codes (16 bytes, even index in the low nibble) -> 32 int8 bytes, codes times 16, in index order.
+__device__ __forceinline__ void expand_nibbles_in_order(const v4i &packed, v4i &first16, v4i &last16) {
+    uint32_t out[8];
+#pragma unroll
+    for (int e = 0; e < 4; e++) {
+        const uint32_t p = (uint32_t)packed[e];
+        const uint32_t even = (p << 4) & 0xF0F0F0F0u, odd = p & 0xF0F0F0F0u;  // codes 0, 2, 4, 6 / 1, 3, 5, 7 of this dword, times 16
+        out[2 * e] = __builtin_amdgcn_perm(odd, even, 0x05010400u);      // even.b0, odd.b0, even.b1, odd.b1
+        out[2 * e + 1] = __builtin_amdgcn_perm(odd, even, 0x07030602u);  // even.b2, odd.b2, even.b3, odd.b3
+    }
+    first16 = v4i{(int)out[0], (int)out[1], (int)out[2], (int)out[3]};
+    last16 = v4i{(int)out[4], (int)out[5], (int)out[6], (int)out[7]};
 }
 
 // f32(fp16 half of `pair`) * m in one instruction: v_fma_mix_f32 converts the selected half exactly,
@@ -46,21 +66,24 @@ __device__ __forceinline__ float half_times(int pair, float m) {
     return d;
 }
 
+template <bool BITS4>
 __device__ __forceinline__ int code_of_smoothed(float v, float inv_s) {
     const int q = cvt_i32_f32(__builtin_rintf(v * inv_s));
-    return min(max(q, -127), 127);
+    return BITS4 ? min(max(q, -7), 7) : min(max(q, -127), 127);
 }
 
-// Eight fp16 values (one 16-byte load) -> eight int8 codes.
+// Eight fp16 values (one 16-byte load) -> eight int8 codes (BITS4: 4-bit codes times 16).
+template <bool BITS4>
 __device__ __forceinline__ u32x2 quantize_8(v4i raw, const float (&im)[8], float inv_s) {
     int q[8];
 #pragma unroll
     for (int e = 0; e < 4; e++) {
         const int word = raw[e];  // (a bit_cast applied directly to a vector element reads element 0 with this compiler)
-        q[2 * e] = code_of_smoothed(half_times<false>(word, im[2 * e]), inv_s);
-        q[2 * e + 1] = code_of_smoothed(half_times<true>(word, im[2 * e + 1]), inv_s);
+        q[2 * e] = code_of_smoothed<BITS4>(half_times<false>(word, im[2 * e]), inv_s);
+        q[2 * e + 1] = code_of_smoothed<BITS4>(half_times<true>(word, im[2 * e + 1]), inv_s);
     }
     u32x2 out = {pack4(q[0], q[1], q[2], q[3]), pack4(q[4], q[5], q[6], q[7])};
+    if constexpr (BITS4) out = u32x2{times16(out[0]), times16(out[1])};
     return out;
 }
 
@@ -111,7 +134,9 @@ __host__ __device__ __forceinline__ FusedLayout fused_layout(int N, int K, int L
 
 // DUMP: also write the int8 codes (xq_out) and the int32 accumulators (acc_out), the parity aids; without it
 // their address arithmetic (a third of the VALU instructions of the k loop) is not even compiled in.
-template <int NB, int D, bool DUMP>
+// BITS4: the weight arrives as packed 4-bit codes ([N, K / 2] bytes) and is expanded once into LDS (codes times 16, in
+// index order); activations are clipped to +-7 and also fed times 16; the factor 256 is undone in the channel steps.
+template <int NB, int D, bool DUMP, bool BITS4 = false>
 __global__ __launch_bounds__(kFusedWaves * 64) void pts_linear_wres(const LinearArgs p) {
     using Acc = v4i;
 
@@ -207,6 +232,17 @@ __global__ __launch_bounds__(kFusedWaves * 64) void pts_linear_wres(const Linear
     // side; the lane picks the global chunk that belongs at its LDS position (pad chunks and pad
     // rows re-read a valid neighbour).
     {
+        if constexpr (BITS4) {
+            const int packed_chunks = K >> 5;  // 16-byte chunks of 32 packed codes per weight row (K is a multiple of 64)
+            for (int idx = tid; idx < NB * 16 * packed_chunks; idx += kFusedWaves * 64) {
+                const int row = idx / packed_chunks, c = idx - row * packed_chunks;
+                const v4i packed = *reinterpret_cast<const v4i *>(p.w + (int64_t)min(row, N - 1) * p.ldw_bytes + c * 16);  // pad rows re-read a valid one
+                v4i first16, last16;
+                expand_nibbles_in_order(packed, first16, last16);
+                *reinterpret_cast<v4i *>(w_lds + row * pw + c * 32) = first16;
+                *reinterpret_cast<v4i *>(w_lds + row * pw + c * 32 + 16) = last16;
+            }
+        } else {
         const int chunks_per_row = pw >> 4;
         for (int c = wave; c < (lay.w_bytes >> 10); c += kFusedWaves) {
             const int chunk = c * 64 + lane;
@@ -215,10 +251,12 @@ __global__ __launch_bounds__(kFusedWaves * 64) void pts_linear_wres(const Linear
             __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void *)src,
                                              (__attribute__((address_space(3))) void *)(w_lds + c * 1024), 16, 0, 0);
         }
+        }
         for (int k = tid; k < K; k += kFusedWaves * 64) inv_m_lds[k] = p.inv_m ? p.inv_m[k] : 1.0f;
         for (int t = tid; t < L; t += kFusedWaves * 64) inv_s_lds[t] = 1.0f / p.s_tok[t];  // IEEE division
         for (int o = tid; o < NB * 16; o += kFusedWaves * 64) {
-            cs_lds[o] = o < N ? p.s_w[o] : 0.0f;
+            // 4-bit path: operands are codes times 16, the accumulator 256 times the sum; undone here (a power of two: exact)
+            cs_lds[o] = o < N ? (BITS4 ? p.s_w[o] * (1.0f / 256.0f) : p.s_w[o]) : 0.0f;
             cb_lds[o] = (o < N && p.bias) ? __half2float(p.bias[o]) : 0.0f;
         }
     }
@@ -269,11 +307,21 @@ __global__ __launch_bounds__(kFusedWaves * 64) void pts_linear_wres(const Linear
                 for (int e = 0; e < 4; e++) im[e] = im_lo[e], im[4 + e] = im_hi[e];
 #pragma unroll
                 for (int i = 0; i < G; i++) {  // tile rows of further groups keep stale codes: results of rows nobody stores
-                    const u32x2 codes = quantize_8(raw[d][i], im, inv_s[i]);
+                    const u32x2 codes = quantize_8<BITS4>(raw[d][i], im, inv_s[i]);
                     *reinterpret_cast<u32x2 *>(tile + tile_wr[i]) = codes;
-                    if (DUMP && p.xq_out) {  // parity aid: the codes exactly as the MFMA will see them
+                    if (DUMP && p.xq_out) {  // parity aid: the codes that the MFMA will see (4-bit path: divided by 16 again)
                         const int64_t r = r_unit + i * 8 + rr;
-                        if (r < p.M) *reinterpret_cast<u32x2 *>(p.xq_out + r * p.ldxq_out + ks * 64 + pc * 8) = codes;
+                        u32x2 plain = codes;
+                        if constexpr (BITS4) {
+#pragma unroll
+                            for (int h = 0; h < 2; h++) {
+                                uint32_t w = 0;
+#pragma unroll
+                                for (int b = 0; b < 4; b++) w |= (uint32_t)(uint8_t)((int8_t)(codes[h] >> (8 * b)) >> 4) << (8 * b);
+                                plain[h] = w;
+                            }
+                        }
+                        if (r < p.M) *reinterpret_cast<u32x2 *>(p.xq_out + r * p.ldxq_out + ks * 64 + pc * 8) = plain;
                     }
                     __builtin_amdgcn_sched_barrier(0);  // one load's eight codes at a time: bounds the live registers
                 }
@@ -338,7 +386,7 @@ __global__ __launch_bounds__(kFusedWaves * 64) void pts_linear_wres(const Linear
 #pragma unroll
                     for (int c = 0; c < 4; c++) {
                         const int a = acc[j][i][c];
-                        if (DUMP && p.acc_out && prow < rows_valid && col + c < N) p.acc_out[(r0 + prow) * p.N + col + c] = a;
+                        if (DUMP && p.acc_out && prow < rows_valid && col + c < N) p.acc_out[(r0 + prow) * p.N + col + c] = BITS4 ? a >> 8 : a;
                         out[c] = (float)a * (rs[j] * cs[c]) + cb[c];
                     }
                     __half2 lo = __floats2half2_rn(out[0], out[1]);
@@ -389,7 +437,7 @@ __global__ __launch_bounds__(kFusedWaves * 64) void pts_linear_wres(const Linear
 
 // Sixteen codes of row `row_ptr` (fp16) starting at code index k0; codes at or beyond K are 0.
 // im[j] is the smoothing factor of code k0 + j (any value for codes at or beyond K).
-template <int X_ALIGN>
+template <int X_ALIGN, bool BITS4 = false>
 __device__ __forceinline__ v4i load_quantized_chunk(const char *row_ptr, int64_t k0, int64_t K, bool row_ok,
                                                     const float (&im)[16], float inv_s) {
     v4i out = {0, 0, 0, 0};
@@ -420,10 +468,13 @@ __device__ __forceinline__ v4i load_quantized_chunk(const char *row_ptr, int64_t
 #pragma unroll
     for (int j = 0; j < 16; j++) {
         const __half h = __builtin_bit_cast(__half, (uint16_t)(h2[j >> 1] >> (16 * (j & 1))));
-        q[j] = j < valid ? quantize_one(__half2float(h), im[j], inv_s) : 0;
+        q[j] = j < valid ? quantize_one<BITS4>(__half2float(h), im[j], inv_s) : 0;
     }
 #pragma unroll
-    for (int j = 0; j < 4; j++) out[j] = (int)pack4(q[4 * j], q[4 * j + 1], q[4 * j + 2], q[4 * j + 3]);
+    for (int j = 0; j < 4; j++) {
+        const uint32_t packed = pack4(q[4 * j], q[4 * j + 1], q[4 * j + 2], q[4 * j + 3]);
+        out[j] = (int)(BITS4 ? times16(packed) : packed);  // 4-bit path: codes times 16
+    }
     return out;
 }
 
@@ -472,7 +523,9 @@ __host__ __device__ __forceinline__ StreamLayout stream_layout(int N, int ksteps
 
 template <int KSTEPS, bool QUANT, int X_ALIGN, int W_ALIGN, bool PACKED4 = false, bool OFFSET = false>
 __global__ __launch_bounds__(kStreamWaves * 64) void linear_stream_smallk(const LinearArgs p) {
-    static_assert(!(QUANT && PACKED4) && !(OFFSET && (QUANT || PACKED4)), "one variant at a time");
+    // QUANT && PACKED4: the fused 4-bit form - fp16 activations clipped to +-7, packed 4-bit weight; both fed times 16
+    static_assert(!(OFFSET && (QUANT || PACKED4)), "the zero-offset form is two-launch and 8-bit");
+    constexpr bool BITS4 = QUANT && PACKED4;
     const int tid = threadIdx.x, lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);  // scalar: unit numbers and row bounds stay in SGPRs
     const int l16 = lane & 15, lq = lane >> 4;
@@ -494,11 +547,16 @@ __global__ __launch_bounds__(kStreamWaves * 64) void linear_stream_smallk(const 
         constexpr int CPR = 4 * KSTEPS;  // 16-byte chunks per weight row in LDS
         if constexpr (PACKED4) {
             // a packed chunk (32 codes) becomes two int8 chunks, codes times 16: even reduction indices, then odd ones
+            // (two-launch form: the activations are split the same way) or in index order (fused form)
+            const int packed_bytes = BITS4 ? K / 2 : K;
             for (int idx = tid; idx < lay.rows * (CPR / 2); idx += kStreamWaves * 64) {
                 const int row = idx / (CPR / 2), c = idx - row * (CPR / 2);
-                const v4i v = load_chunk<W_ALIGN, 1>(p.w + (int64_t)min(row, N - 1) * p.ldw_bytes, c * 16, K, row < N);
-                *reinterpret_cast<v4i *>(w_lds + row * lay.pitch + (((2 * c) ^ swz(row)) << 4)) = Int4Path::even_codes(v);
-                *reinterpret_cast<v4i *>(w_lds + row * lay.pitch + (((2 * c + 1) ^ swz(row)) << 4)) = Int4Path::odd_codes(v);
+                const v4i v = load_chunk<W_ALIGN, 1>(p.w + (int64_t)min(row, N - 1) * p.ldw_bytes, c * 16, packed_bytes, row < N);
+                v4i first, second;
+                if constexpr (BITS4) expand_nibbles_in_order(v, first, second);
+                else first = Int4Path::even_codes(v), second = Int4Path::odd_codes(v);
+                *reinterpret_cast<v4i *>(w_lds + row * lay.pitch + (((2 * c) ^ swz(row)) << 4)) = first;
+                *reinterpret_cast<v4i *>(w_lds + row * lay.pitch + (((2 * c + 1) ^ swz(row)) << 4)) = second;
             }
         } else
         for (int idx = tid; idx < lay.rows * CPR; idx += kStreamWaves * 64) {
@@ -558,11 +616,14 @@ __global__ __launch_bounds__(kStreamWaves * 64) void linear_stream_smallk(const 
                         const v4f f = *reinterpret_cast<const v4f *>(inv_m_lds + k0 + 4 * e);
                         im[4 * e] = f.x, im[4 * e + 1] = f.y, im[4 * e + 2] = f.z, im[4 * e + 3] = f.w;
                     }
-                    const v4i codes = load_quantized_chunk<X_ALIGN>(xrow, k0, K, true, im, inv_s);
-                    if (p.xq_out && part == 0 && r_unit + jb * 16 + l16 < p.M) {  // parity aid
+                    const v4i codes = load_quantized_chunk<X_ALIGN, BITS4>(xrow, k0, K, true, im, inv_s);
+                    if (p.xq_out && part == 0 && r_unit + jb * 16 + l16 < p.M) {  // parity aid (4-bit form: the codes, not times 16)
 #pragma unroll
                         for (int b = 0; b < 16; b++)
-                            if (k0 + b < K) p.xq_out[r * p.ldxq_out + k0 + b] = (int8_t)((uint32_t)codes[b >> 2] >> (8 * (b & 3)));
+                            if (k0 + b < K) {
+                                const int8_t fed = (int8_t)((uint32_t)codes[b >> 2] >> (8 * (b & 3)));
+                                p.xq_out[r * p.ldxq_out + k0 + b] = BITS4 ? (int8_t)(fed >> 4) : fed;
+                            }
                     }
                     fx[jb][ks] = codes;
                 } else if constexpr (PACKED4) {
@@ -612,7 +673,7 @@ __global__ __launch_bounds__(kStreamWaves * 64) void linear_stream_smallk(const 
                         for (int c = 0; c < 4; c++) {
                             const int64_t r = r_unit + jb * 16 + l16;
                             const int col = i * 16 + lq * 4 + c;
-                            if (r < p.M && col < cols_valid) p.acc_out[r * p.N + g * 64 + col] = PACKED4 ? acc[jb][i][c] >> 8 : acc[jb][i][c];
+                            if (r < p.M && col < cols_valid) p.acc_out[r * p.N + g * 64 + col] = PACKED4 ? acc[jb][i][c] >> 8 : acc[jb][i][c];  // 4-bit forms: 256 times the sum
                         }
             }
 #pragma unroll
@@ -792,7 +853,7 @@ int launch_stream_aligned(const LinearArgs &a, int xa, int wa, const StreamLayou
     return ptq4vm::check_launch("linear_stream_smallk");
 }
 
-int launch_wres(const LinearArgs &a, hipStream_t stream) {
+int launch_wres(const LinearArgs &a, hipStream_t stream, bool bits4) {
     const FusedLayout lay = fused_layout((int)a.N, (int)a.k_bytes, (int)a.L);
     int device = 0, cus = 0;
     hipError_t err = hipGetDevice(&device);
@@ -803,13 +864,15 @@ int launch_wres(const LinearArgs &a, hipStream_t stream) {
     int64_t wgs = ptq4vm::ceil_div(units, kFusedWaves);
     if (wgs > cus) wgs = cus;  // one workgroup per CU: the resident tables take most of its LDS
     using Kernel = void (*)(const LinearArgs);
-#define PTQ4VM_WRES_ROW(D, DUMP) \
-    {pts_linear_wres<1, D, DUMP>, pts_linear_wres<2, D, DUMP>, pts_linear_wres<3, D, DUMP>, pts_linear_wres<4, D, DUMP>, \
-     pts_linear_wres<5, D, DUMP>, pts_linear_wres<6, D, DUMP>, pts_linear_wres<7, D, DUMP>, pts_linear_wres<8, D, DUMP>}
-    // [parity aids][k-steps in flight: 4, 2, 1][number of 16-channel blocks - 1]
-    static const Kernel kernels[2][3][kFusedMaxBlocks] = {
-        {PTQ4VM_WRES_ROW(4, false), PTQ4VM_WRES_ROW(2, false), PTQ4VM_WRES_ROW(1, false)},
-        {PTQ4VM_WRES_ROW(4, true), PTQ4VM_WRES_ROW(2, true), PTQ4VM_WRES_ROW(1, true)}};
+#define PTQ4VM_WRES_ROW(D, DUMP, B4) \
+    {pts_linear_wres<1, D, DUMP, B4>, pts_linear_wres<2, D, DUMP, B4>, pts_linear_wres<3, D, DUMP, B4>, pts_linear_wres<4, D, DUMP, B4>, \
+     pts_linear_wres<5, D, DUMP, B4>, pts_linear_wres<6, D, DUMP, B4>, pts_linear_wres<7, D, DUMP, B4>, pts_linear_wres<8, D, DUMP, B4>}
+    // [4-bit][parity aids][k-steps in flight: 4, 2, 1][number of 16-channel blocks - 1]
+    static const Kernel kernels[2][2][3][kFusedMaxBlocks] = {
+        {{PTQ4VM_WRES_ROW(4, false, false), PTQ4VM_WRES_ROW(2, false, false), PTQ4VM_WRES_ROW(1, false, false)},
+         {PTQ4VM_WRES_ROW(4, true, false), PTQ4VM_WRES_ROW(2, true, false), PTQ4VM_WRES_ROW(1, true, false)}},
+        {{PTQ4VM_WRES_ROW(4, false, true), PTQ4VM_WRES_ROW(2, false, true), PTQ4VM_WRES_ROW(1, false, true)},
+         {PTQ4VM_WRES_ROW(4, true, true), PTQ4VM_WRES_ROW(2, true, true), PTQ4VM_WRES_ROW(1, true, true)}}};
 #undef PTQ4VM_WRES_ROW
     const int n_ksteps = (int)(a.k_bytes / 64);
     // four k-steps in flight need too many registers next to the accumulators of 7 or 8 channel blocks
@@ -817,7 +880,7 @@ int launch_wres(const LinearArgs &a, hipStream_t stream) {
 #define PTQ4VM_FUSED_MAXD (PTQ4VM_FUSED_RB == 1 ? 2 : 4)  // 16 wavefronts of 128 registers: two k-steps in flight (measured best)
 #endif
     const int depth_row = (PTQ4VM_FUSED_MAXD >= 4 && n_ksteps % 4 == 0 && lay.nb <= 6) ? 0 : (n_ksteps % 2 == 0 ? 1 : 2);
-    const Kernel kernel = kernels[(a.xq_out || a.acc_out) ? 1 : 0][depth_row][lay.nb - 1];
+    const Kernel kernel = kernels[bits4 ? 1 : 0][(a.xq_out || a.acc_out) ? 1 : 0][depth_row][lay.nb - 1];
     if (int rc = ptq4vm::set_lds_limit(reinterpret_cast<const void *>(kernel), kLdsBytes, "hipFuncSetAttribute(pts_linear_wres)")) return rc;
     kernel<<<dim3((unsigned)wgs), dim3(kFusedWaves * 64), lay.total, stream>>>(a);
     return ptq4vm::check_launch("pts_linear_wres");
@@ -842,7 +905,9 @@ int launch_generic(LinearArgs a, int x_align, int w_align, hipStream_t stream) {
     return ptq4vm::check_launch("pts_linear_generic");
 }
 
-int dispatch(LinearArgs a, hipStream_t stream) {
+// bits4: the 4-bit form (weight packed two codes per byte, activations clipped to +-7).  It runs on the weight-resident
+// and the row-streaming kernel only; other shapes return PTQ4VM_ERR_SHAPE (the two-call form covers them).
+int dispatch(LinearArgs a, hipStream_t stream, bool bits4 = false) {
     auto align_of = [](const void *base, int64_t pitch_bytes) {
         if (ptq4vm::aligned_to(base, 16) && pitch_bytes % 16 == 0) return 16;
         if (ptq4vm::aligned_to(base, 4) && pitch_bytes % 4 == 0) return 4;
@@ -856,11 +921,12 @@ int dispatch(LinearArgs a, hipStream_t stream) {
                          a.M >= kFusedMinRows && a.L <= 65536 &&
                          (!a.xq_out || (ptq4vm::aligned_to(a.xq_out, 8) && a.ldxq_out % 8 == 0)) &&
                          fused_layout((int)a.N, (int)a.k_bytes, (int)a.L).total <= kLdsBytes;
-    if (wres_ok) return launch_wres(a, stream);
+    if (wres_ok) return launch_wres(a, stream, bits4);
     if (a.k_bytes <= 128) {
-        const int rc = launch_stream_smallk(a, true, stream);
+        const int rc = launch_stream_smallk(a, true, stream, bits4);
         if (rc <= 0) return rc;
     }
+    if (bits4) return PTQ4VM_ERR_SHAPE;
     if (a.N > 64) return launch_generic<256, 128, 2, 2>(a, xa, wa, stream);
     return launch_generic<256, 64, 4, 1>(a, xa, wa, stream);
 }
@@ -874,8 +940,9 @@ int ptq4vm::mfma::launch_stream_smallk(const LinearArgs &a, bool quantize, hipSt
         return 0;
     };
     const int xa = align_of(a.x, a.ldx_bytes), wa = align_of(a.w, a.ldw_bytes);
-    const int64_t k_codes = packed4 ? 2 * a.k_bytes : a.k_bytes;  // bytes of K per row once the operands are int8
-    if (k_codes > 128 || (packed4 && quantize) || (offset && (quantize || packed4)) || a.M < (quantize ? kStreamMinRowsFused : kStreamMinRows) || a.M >= (1LL << 31) || a.L >= (1LL << 31) || a.N > 8192) return 1;
+    // bytes of K per row once the operands are int8 (two-launch 4-bit form: k_bytes counts packed bytes; fused 4-bit form: codes)
+    const int64_t k_codes = (packed4 && !quantize) ? 2 * a.k_bytes : a.k_bytes;
+    if (k_codes > 128 || (offset && (quantize || packed4)) || a.M < (quantize ? kStreamMinRowsFused : kStreamMinRows) || a.M >= (1LL << 31) || a.L >= (1LL << 31) || a.N > 8192) return 1;
     const int ksteps = k_codes <= 64 ? 1 : 2;
     const StreamLayout lay = stream_layout((int)a.N, ksteps);
     if (lay.total > kLdsBytes) return 1;
@@ -890,6 +957,9 @@ int ptq4vm::mfma::launch_stream_smallk(const LinearArgs &a, bool quantize, hipSt
     if (offset)
         return ksteps == 1 ? launch_stream_aligned<1, false, false, true>(a, xa, wa, lay, (unsigned)wgs, stream)
                            : launch_stream_aligned<2, false, false, true>(a, xa, wa, lay, (unsigned)wgs, stream);
+    if (packed4 && quantize)
+        return ksteps == 1 ? launch_stream_aligned<1, true, true>(a, xa, wa, lay, (unsigned)wgs, stream)
+                           : launch_stream_aligned<2, true, true>(a, xa, wa, lay, (unsigned)wgs, stream);
     if (packed4)
         return ksteps == 1 ? launch_stream_aligned<1, false, true>(a, xa, wa, lay, (unsigned)wgs, stream)
                            : launch_stream_aligned<2, false, true>(a, xa, wa, lay, (unsigned)wgs, stream);
@@ -898,6 +968,41 @@ int ptq4vm::mfma::launch_stream_smallk(const LinearArgs &a, bool quantize, hipSt
                            : launch_stream_aligned<2, true>(a, xa, wa, lay, (unsigned)wgs, stream);
     return ksteps == 1 ? launch_stream_aligned<1, false>(a, xa, wa, lay, (unsigned)wgs, stream)
                        : launch_stream_aligned<2, false>(a, xa, wa, lay, (unsigned)wgs, stream);
+}
+
+extern "C" int ptq4vm_w4a4_linear_fused(const void *x_f16, const float *inv_m, const float *s_tok, const uint8_t *wq4,
+                                        const float *s_w, const void *bias_f16, void *y_f16, int32_t *acc_out,
+                                        int8_t *xq_out, int64_t B, int64_t L, int64_t K, int64_t N, int64_t ldx,
+                                        int64_t ldwq, int64_t ldy, int64_t ldxq, void *stream_) {
+    if (!x_f16 || !s_tok || !wq4 || !s_w || !y_f16) return PTQ4VM_ERR_NULL;
+    if (B < 0 || N < 0 || L <= 0 || K <= 0 || K > PTQ4VM_MAX_K_W4 || K % 2 != 0) return PTQ4VM_ERR_SHAPE;
+    if (B > 0 && L > INT64_MAX / B) return PTQ4VM_ERR_SHAPE;
+    if (ldx < K || ldwq < K / 2 || ldy < N || (xq_out && ldxq < K)) return PTQ4VM_ERR_STRIDE;
+    if (!ptq4vm::aligned_to(x_f16, 16) || !ptq4vm::aligned_to(wq4, 16) || !ptq4vm::aligned_to(y_f16, 2) ||
+        !ptq4vm::aligned_to(inv_m, 4) || !ptq4vm::aligned_to(s_tok, 4) || !ptq4vm::aligned_to(s_w, 4) ||
+        !ptq4vm::aligned_to(bias_f16, 2) || !ptq4vm::aligned_to(acc_out, 4))
+        return PTQ4VM_ERR_ALIGN;
+    const int64_t M = B * L;
+    if (M == 0 || N == 0) return PTQ4VM_OK;
+    LinearArgs a{};
+    a.x = static_cast<const char *>(x_f16);
+    a.w = reinterpret_cast<const char *>(wq4);
+    a.s_tok = s_tok;
+    a.s_w = s_w;
+    a.bias = static_cast<const __half *>(bias_f16);
+    a.y = static_cast<__half *>(y_f16);
+    a.acc_out = acc_out;
+    a.M = M;
+    a.N = N;
+    a.k_bytes = K;  // codes per row
+    a.ldx_bytes = ldx * 2;
+    a.ldw_bytes = ldwq;  // packed bytes
+    a.ldy = ldy;
+    a.L = L;
+    a.inv_m = inv_m;
+    a.xq_out = xq_out;
+    a.ldxq_out = ldxq;
+    return dispatch(a, static_cast<hipStream_t>(stream_), true);
 }
 
 extern "C" int ptq4vm_w8a8_linear_fused(const void *x_f16, const float *inv_m, const float *s_tok, const int8_t *wq,

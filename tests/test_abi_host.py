@@ -218,6 +218,30 @@ def test_w8a8_linear_fused_argument_checks(lib):
     assert call(a9=0) == 0 and call(a12=0, a15=0) == 0       # empty problem
 
 
+def test_w4a4_linear_fused_argument_checks(lib):
+    f = lib.ptq4vm_w4a4_linear_fused
+    #     x  inv_m s_tok wq4 s_w bias y acc  xq   B  L  K   N   ldx ldwq ldy ldxq stream
+    ok = [P, P, P, P, P, P, P, NULL, NULL, 1, 1, 16, 16, 16, 8, 16, 0, None]
+
+    def call(**kw):
+        a = list(ok)
+        for i, v in kw.items():
+            a[int(i[1:])] = v
+        return f(*a)
+
+    assert call(a0=NULL) == -1 and call(a2=NULL) == -1 and call(a3=NULL) == -1
+    assert call(a4=NULL) == -1 and call(a6=NULL) == -1
+    assert call(a9=-1) == -2 and call(a10=0) == -2 and call(a11=0) == -2 and call(a12=-1) == -2
+    assert call(a11=15, a13=15) == -2                        # odd K
+    assert call(a11=131072, a13=131072, a14=65536) == -2     # int32 accumulator (256 times the sum) could overflow
+    assert call(a13=15) == -3 and call(a14=7) == -3 and call(a15=15) == -3
+    assert call(a8=P, a16=15) == -3                          # copy of the codes requested with too small a pitch
+    assert call(a0=ODD) == -4 and call(a3=ODD) == -4 and call(a1=ctypes.c_void_p(0x1002)) == -4
+    assert call(a6=ctypes.c_void_p(0x1001)) == -4
+    assert call(a9=0) == 0 and call(a12=0, a15=0) == 0       # empty problem
+    # (a valid problem outside the two kernels' shapes is refused with -2 only after a device query: GPU tests)
+
+
 def test_validate_scales_argument_checks(lib):
     f = lib.ptq4vm_validate_scales
     f.restype = ctypes.c_int

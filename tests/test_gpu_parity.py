@@ -806,6 +806,115 @@ def test_w4a4_large_ragged_shapes_sampled(B, L, K, N):
     _check_w4a4_on_sampled_rows(c, "ragged")
 
 
+def _run_fused_w4a4_case(c, use_bias=True, use_m=True, ldy=None, what=""):
+    """ptq4vm_w4a4_linear_fused on the GPU vs the oracle's 4-bit quantizer -> GEMM -> dequantization chain."""
+    print(f"fused w4a4 {what} B={c.B} L={c.L} K={c.K} N={c.N} bias={use_bias} m={use_m} ldy={ldy}", flush=True)
+    M = c.B * c.L
+    s4 = _steps_4bit(c)
+    m = c.m if use_m else torch.ones_like(c.m)
+    wq4, s_w, inv_m = ptq.fold_smoothing_w4(c.w, m)
+    bias = c.bias if use_bias else None
+    acc = torch.full((M, c.N), -1, dtype=torch.int32, device=DEV)
+    xq = torch.full((M, c.K), 0x55, dtype=torch.int8, device=DEV)
+    ybuf = None
+    if ldy is None:
+        y = ptq.w4a4_linear_fused(c.x, inv_m if use_m else None, s4, wq4, s_w, bias, c.B, c.L, acc_out=acc, xq_out=xq)
+    else:
+        ybuf, yv = _padded(M, c.N, ldy, torch.float16, 12345.0)
+        y = ptq.w4a4_linear_fused(c.x, inv_m if use_m else None, s4, wq4, s_w, bias, c.B, c.L, y=yv, acc_out=acc, xq_out=xq)
+    y2 = ptq.w4a4_linear_fused(c.x, inv_m if use_m else None, s4, wq4, s_w, bias, c.B, c.L)  # timed configuration
+    torch.cuda.synchronize()
+
+    wq_o, s_w_o, inv_m_o = oracle.fold_smoothing_bits(_np(c.w), _np(m), 4)
+    xq_o = oracle.quantize_pts_bits(_np(c.x), inv_m_o if use_m else None, _np(s4), c.B, c.L, 4)
+    b_o = _np(c.bias) if use_bias else None
+    y_o, y64, acc_o = oracle.w8a8_linear(xq_o, wq_o, _np(s4), s_w_o, b_o, c.B, c.L)
+    assert np.array_equal(_np(wq4), oracle.pack_int4(wq_o))
+    assert np.array_equal(_np(xq), xq_o), "4-bit codes differ"
+    assert np.array_equal(_np(acc), acc_o), "int32 accumulators differ"
+    st = np.tile(_np(s4).astype(np.float64), c.B)[:, None]
+    prod_abs = np.abs(acc_o.astype(np.float64) * st * s_w_o.astype(np.float64)[None, :])
+    bias_abs = np.broadcast_to(np.abs(b_o.astype(np.float64))[None, :] if use_bias else 0.0, prod_abs.shape)
+    check_dequantized_output(_np(y), y_o, y64, prod_abs, bias_abs, what)
+    assert np.array_equal(_np(y).view(np.uint16), _np(y2).view(np.uint16)), "the parity outputs change the result"
+    if ybuf is not None:
+        assert np.all(_np(ybuf[:, c.N:]) == np.float16(12345.0))
+    # the two-launch form gives the same bits
+    xq4 = ptq.quantize_pts_a4(c.x, inv_m if use_m else None, s4, c.B, c.L)
+    y_two = ptq.w4a4_linear(xq4, wq4, s4, s_w, bias, c.B, c.L)
+    torch.cuda.synchronize()
+    assert np.array_equal(_np(y).view(np.uint16), _np(y_two).view(np.uint16)), "fused and two-launch forms differ"
+
+
+FUSED_W4A4_SHAPES = [  # B, L, K, N, ldy, bias, m
+    # weight-resident kernel (N <= 128, K a multiple of 64, >= 2048 rows)
+    (83, 199, 128, 44, None, True, True),     # 2 k-steps; M mod 32 = 5
+    (64, 257, 320, 80, None, False, True),    # 5 k-steps (depth 1)
+    (70, 241, 1024, 96, None, True, True),    # 16 k-steps, 6 channel blocks
+    (70, 241, 512, 128, None, True, True),    # 8 channel blocks
+    (83, 199, 768, 50, None, True, False),    # N not a multiple of 4; no smoothing
+    (83, 199, 1536, 72, 80, True, True),      # x_proj-like, padded output rows
+    (66, 250, 1600, 16, None, True, True),    # 25 k-steps; one channel block
+    (13, 163, 192, 33, None, False, True),    # 2119 rows, M mod 8 = 7: the last group is ragged
+    # row-streaming kernel (K <= 128, >= 1024 rows)
+    (105, 197, 40, 100, 104, True, True),     # 20-byte packed weight rows, padded output rows
+    (21, 199, 12, 130, None, True, True),     # 6 packed bytes per weight row: element-wise weight loads
+    (35, 120, 128, 200, None, True, True),    # two k-steps (N > 128: not the weight-resident kernel)
+    (33, 127, 100, 33, 40, True, False),      # odd N with padding; M mod 16 = 15; K a multiple of 4 only
+    (30, 197, 48, 1536, None, True, True),    # dt_proj (Vim-B) shape on fewer rows
+    (30, 197, 24, 576, None, False, True),    # 9 channel groups in 4 parts of 3: the last part is empty
+    (11, 100, 14, 5, None, True, True),       # K even only
+]
+
+
+@pytest.mark.parametrize("B,L,K,N,ldy,bias,use_m", FUSED_W4A4_SHAPES)
+def test_fused_w4a4_whole_result(B, L, K, N, ldy, bias, use_m):
+    """Every code, accumulator and output of the one-launch W4A4 form against the oracle, and against the two launches."""
+    c = synth.random_problem(4321 + K + N, B, L, K, N, device=DEV)
+    _run_fused_w4a4_case(c, use_bias=bias, use_m=use_m, ldy=ldy, what="fused-w4a4")
+
+
+@pytest.mark.parametrize("linear", [1, 2])
+def test_fused_w4a4_vim_b_full_size_sampled(linear):
+    """x_proj and dt_proj of Vim-B at the timed size: the one-launch W4A4 form on sampled rows against the oracle."""
+    c = synth.make_linear_case(3, 0, linear, device=DEV)
+    M = c.B * c.L
+    print(f"fused w4a4 full-size {c.name}: M={M} K={c.K} N={c.N}", flush=True)
+    s4 = _steps_4bit(c)
+    wq4, s_w, inv_m = ptq.fold_smoothing_w4(c.w, c.m)
+    y = ptq.w4a4_linear_fused(c.x, inv_m, s4, wq4, s_w, c.bias, c.B, c.L)
+    acc = torch.full((M, c.N), -1, dtype=torch.int32, device=DEV)
+    xq = torch.full((M, c.K), 0x55, dtype=torch.int8, device=DEV)
+    y_dump = ptq.w4a4_linear_fused(c.x, inv_m, s4, wq4, s_w, c.bias, c.B, c.L, acc_out=acc, xq_out=xq)
+    torch.cuda.synchronize()
+    assert torch.equal(y.view(torch.int16), y_dump.view(torch.int16))
+    rows = _sampled_rows(M, 97, c.L)
+    ridx = torch.from_numpy(rows).to(DEV)
+    wq_o, s_w_o, inv_m_o = oracle.fold_smoothing_bits(_np(c.w), _np(c.m), 4)
+    st_rows = _np(s4)[rows % c.L]
+    xq_o = oracle.quantize_pts_bits(_np(c.x[ridx]), inv_m_o, st_rows, 1, len(rows), 4)
+    assert np.array_equal(_np(xq[ridx]), xq_o)
+    y_o, y64, acc_o = oracle.w8a8_linear(xq_o, wq_o, st_rows, s_w_o, _np(c.bias), 1, len(rows))
+    assert np.array_equal(_np(acc[ridx]), acc_o), "int32 accumulators differ"
+    prod_abs = np.abs(acc_o.astype(np.float64) * st_rows.astype(np.float64)[:, None] * s_w_o.astype(np.float64)[None, :])
+    bias_abs = np.broadcast_to(np.abs(_np(c.bias).astype(np.float64))[None, :], prod_abs.shape)
+    check_dequantized_output(_np(y[ridx]), y_o, y64, prod_abs, bias_abs, f"fused w4a4 {c.name}")
+
+
+def test_fused_w4a4_shapes_outside_its_kernels_are_refused():
+    """Fewer rows than either kernel takes, or a long reduction with many channels: PTQ4VM_ERR_SHAPE, nothing written."""
+    for B, L, K, N in [(1, 50, 64, 32), (20, 197, 768, 3072), (70, 241, 1024, 128)]:  # the last: tables beyond the LDS
+        c = synth.random_problem(77, B, L, K, N, device=DEV)
+        s4 = _steps_4bit(c)
+        wq4, s_w, inv_m = ptq.fold_smoothing_w4(c.w, c.m)
+        y = torch.full((B * L, N), 3.0, dtype=torch.float16, device=DEV)
+        with pytest.raises(ptq.Ptq4vmError) as e:
+            ptq.w4a4_linear_fused(c.x, inv_m, s4, wq4, s_w, c.bias, B, L, y=y)
+        assert e.value.status == -2  # PTQ4VM_ERR_SHAPE
+        torch.cuda.synchronize()
+        assert bool((y == 3.0).all())
+
+
 def test_fused_linear_every_fp16_value():
     """All 65 536 fp16 bit patterns (subnormals, infinities, NaNs) through the fused weight-resident kernel's
     quantizer, with steps from 1e-8 to 10 so that subnormal inputs reach non-zero codes: the codes it feeds
