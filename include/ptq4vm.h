@@ -246,6 +246,23 @@ int ptq4vm_w4a4_linear_fused(const void *x_f16, const float *inv_m, const float 
                              int64_t ldwq, int64_t ldy, int64_t ldxq, void *stream);
 
 /*
+ * Fused zero-offset form: ptq4vm_quantize_pts_offset followed by ptq4vm_w8a8_linear_offset in one launch (Sec. 5.1: a
+ * zero offset per token position next to its step; the quantizer of Sec. 2.3 in the loader of the linear).  Same codes,
+ * accumulators and outputs as the two calls, bit for bit.  Arguments as ptq4vm_w8a8_linear_fused plus z_tok [L] int32
+ * and rowsum [N] int32 as in ptq4vm_w8a8_linear_offset; acc_out receives the raw accumulators (before the correction),
+ * xq_out the codes with the offset in them.
+ * Runs on the weight-resident kernel (N <= 128, K a multiple of 64, >= 2048 rows, 16-byte aligned rows of x and wq)
+ * and on the row-streaming kernel (K <= 128, >= 1024 rows): the shapes where fusing pays (x_proj, dt_proj).  Every
+ * other shape returns PTQ4VM_ERR_SHAPE - call the two entry points there.
+ * Errors otherwise as ptq4vm_w8a8_linear_fused, with NULL z_tok / rowsum -> PTQ4VM_ERR_NULL and
+ * K > PTQ4VM_MAX_K_OFFSET -> PTQ4VM_ERR_SHAPE.
+ */
+int ptq4vm_w8a8_linear_offset_fused(const void *x_f16, const float *inv_m, const float *s_tok, const int32_t *z_tok,
+                                    const int8_t *wq, const int32_t *rowsum, const float *s_w, const void *bias_f16,
+                                    void *y_f16, int32_t *acc_out, int8_t *xq_out, int64_t B, int64_t L, int64_t K,
+                                    int64_t N, int64_t ldx, int64_t ldwq, int64_t ldy, int64_t ldxq, void *stream);
+
+/*
  * Debug validator of the device-resident scale vectors (Sec. 5.1: per-token steps Delta_X and
  * per-output-channel steps Delta_W; Sec. 2.4: smoothing vector s).  An entry is bad unless it is a
  * finite number > 0 (zero, negative, +-Inf and NaN are bad).  The hot path never looks at these

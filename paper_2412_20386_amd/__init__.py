@@ -21,6 +21,7 @@ from .binding import (  # noqa: F401
     quantize_pts_offset,
     weight_rowsum,
     w8a8_linear_offset,
+    w8a8_linear_offset_fused,
     w8a8_linear,
     w8a8_linear_fused,
     validate_scales,

@@ -31,6 +31,7 @@ EXPORTS = (
     "ptq4vm_quantize_pts_a4_e2m3",
     "ptq4vm_w4a4_linear_e2m3",
     "ptq4vm_w4a4_linear_fused",
+    "ptq4vm_w8a8_linear_offset_fused",
     "ptq4vm_w8a8_linear",
     "ptq4vm_w8a8_linear_fused",
     "ptq4vm_f16_linear",
@@ -85,6 +86,8 @@ def load() -> ctypes.CDLL:
     lib.ptq4vm_quantize_pts_a4_e2m3.argtypes = [vp, vp, vp, vp, i64, i64, i64, i64, i64, vp]
     lib.ptq4vm_w4a4_linear_e2m3.restype = ci
     lib.ptq4vm_w4a4_linear_e2m3.argtypes = [vp, vp, vp, vp, vp, vp, vp, i64, i64, i64, i64, i64, i64, i64, vp]
+    lib.ptq4vm_w8a8_linear_offset_fused.restype = ci
+    lib.ptq4vm_w8a8_linear_offset_fused.argtypes = [vp] * 11 + [i64] * 8 + [vp]
     lib.ptq4vm_w4a4_linear_fused.restype = ci
     lib.ptq4vm_w4a4_linear_fused.argtypes = [vp, vp, vp, vp, vp, vp, vp, vp, vp, i64, i64, i64, i64, i64, i64, i64, i64, vp]
     lib.ptq4vm_w8a8_linear.restype = ci
@@ -403,6 +406,39 @@ def w8a8_linear_fused(x: torch.Tensor, inv_m: Optional[torch.Tensor], s_tok: tor
             raise ValueError("xq_out must be [B*L, K]")
     check(load().ptq4vm_w8a8_linear_fused(_ptr(x), _ptr(inv_m), _ptr(s_tok), _ptr(wq), _ptr(s_w), _ptr(bias), _ptr(y),
                                           _ptr(acc_out), _ptr(xq_out), B, L, K, N, ldx, ldwq, ldy, ldxq, _stream()))
+    return y
+
+
+def w8a8_linear_offset_fused(x: torch.Tensor, inv_m: Optional[torch.Tensor], s_tok: torch.Tensor, z_tok: torch.Tensor,
+                             wq: torch.Tensor, rowsum: torch.Tensor, s_w: torch.Tensor, bias: Optional[torch.Tensor],
+                             B: int, L: int, y: Optional[torch.Tensor] = None, acc_out: Optional[torch.Tensor] = None,
+                             xq_out: Optional[torch.Tensor] = None) -> torch.Tensor:
+    """ptq4vm_w8a8_linear_offset_fused: y fp16 [B*L, N] from fp16 activations, per-token steps and zero offsets;
+    acc_out (raw accumulators) / xq_out (codes with the offset in them) are filled if given."""
+    M, K, ldx = _matrix(x, torch.float16, "x")
+    N, K2, ldwq = _matrix(wq, torch.int8, "wq")
+    if K != K2 or M != B * L:
+        raise ValueError("shape mismatch")
+    _vector(inv_m, torch.float32, K, "inv_m", optional=True)
+    _vector(s_tok, torch.float32, L, "s_tok")
+    _vector(z_tok, torch.int32, L, "z_tok")
+    _vector(rowsum, torch.int32, N, "rowsum")
+    _vector(s_w, torch.float32, N, "s_w")
+    _vector(bias, torch.float16, N, "bias", optional=True)
+    if y is None:
+        y = torch.empty((M, N), dtype=torch.float16, device=x.device)
+    _, _, ldy = _matrix(y, torch.float16, "y")
+    if acc_out is not None and (acc_out.dtype != torch.int32 or tuple(acc_out.shape) != (M, N)
+                                or not acc_out.is_contiguous() or not acc_out.is_cuda):
+        raise TypeError("acc_out: expected a dense CUDA int32 [M, N] tensor")
+    ldxq = 0
+    if xq_out is not None:
+        Mq, Kq, ldxq = _matrix(xq_out, torch.int8, "xq_out")
+        if (Mq, Kq) != (M, K):
+            raise ValueError("xq_out must be [B*L, K]")
+    check(load().ptq4vm_w8a8_linear_offset_fused(_ptr(x), _ptr(inv_m), _ptr(s_tok), _ptr(z_tok), _ptr(wq), _ptr(rowsum),
+                                                 _ptr(s_w), _ptr(bias), _ptr(y), _ptr(acc_out), _ptr(xq_out), B, L, K, N,
+                                                 ldx, ldwq, ldy, ldxq, _stream()))
     return y
 
 

@@ -458,7 +458,7 @@ __device__ __forceinline__ void lds_write_b128(uint32_t addr, v4f v) {
 // this kernel (nothing was launched; the caller picks another one).
 // packed4: x and w hold two 4-bit codes per byte (k_bytes = K / 2), expanded on chip; with `quantize` (the fused
 // 4-bit form) x holds fp16 activations, only w is packed and k_bytes = K.
-// offset: z_tok / rowsum are honoured (per-token zero offset); not with `quantize` or `packed4`.
+// offset: z_tok / rowsum are honoured (per-token zero offset; with `quantize` the codes carry the offset); not with `packed4`.
 int launch_stream_smallk(const LinearArgs &a, bool quantize, hipStream_t stream, bool packed4 = false, bool offset = false);
 
 // Weights-in-registers kernel for wide int8 linears with a short reduction (K = 384 or 768, e.g. the

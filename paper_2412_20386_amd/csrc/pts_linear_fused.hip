@@ -28,12 +28,19 @@ using namespace ptq4vm::mfma;
 // One PTS code (Sec. 5.1): smoothing multiply, step multiply, round half to even, clip.  Two
 // separate fp32 multiplies in this order: the codes must equal the stand-alone quantizer's.
 // BITS4: clip to +-7 (Sec. 2.3 with b = 4) instead of +-127.
-template <bool BITS4 = false>
-__device__ __forceinline__ int quantize_one(float x, float inv_m, float inv_s) {
+// OFFSET: per-token zero offset z (Sec. 5.1; the quantizer of Sec. 2.3 with its code range shifted into int8):
+// clip(q + z, -128, 127), formed as clip(q, -128 - z, 127 - z) + z so that a saturated q cannot overflow.
+template <bool BITS4, bool OFFSET>
+__device__ __forceinline__ int clip_code(int q, int z) {
+    if constexpr (OFFSET) return min(max(q, -128 - z), 127 - z) + z;
+    return BITS4 ? min(max(q, -7), 7) : min(max(q, -127), 127);
+}
+
+template <bool BITS4 = false, bool OFFSET = false>
+__device__ __forceinline__ int quantize_one(float x, float inv_m, float inv_s, int z = 0) {
     float v = x * inv_m;
     v = v * inv_s;
-    const int q = cvt_i32_f32(__builtin_rintf(v));
-    return BITS4 ? min(max(q, -7), 7) : min(max(q, -127), 127);
+    return clip_code<BITS4, OFFSET>(cvt_i32_f32(__builtin_rintf(v)), z);
 }
 
 // Four int8 bytes holding 4-bit codes -> the same codes times 16 (what the int8 MFMA is fed on the 4-bit path:
@@ -66,21 +73,20 @@ __device__ __forceinline__ float half_times(int pair, float m) {
     return d;
 }
 
-template <bool BITS4>
-__device__ __forceinline__ int code_of_smoothed(float v, float inv_s) {
-    const int q = cvt_i32_f32(__builtin_rintf(v * inv_s));
-    return BITS4 ? min(max(q, -7), 7) : min(max(q, -127), 127);
+template <bool BITS4, bool OFFSET>
+__device__ __forceinline__ int code_of_smoothed(float v, float inv_s, int z) {
+    return clip_code<BITS4, OFFSET>(cvt_i32_f32(__builtin_rintf(v * inv_s)), z);
 }
 
 // Eight fp16 values (one 16-byte load) -> eight int8 codes (BITS4: 4-bit codes times 16).
-template <bool BITS4>
-__device__ __forceinline__ u32x2 quantize_8(v4i raw, const float (&im)[8], float inv_s) {
+template <bool BITS4, bool OFFSET>
+__device__ __forceinline__ u32x2 quantize_8(v4i raw, const float (&im)[8], float inv_s, int z) {
     int q[8];
 #pragma unroll
     for (int e = 0; e < 4; e++) {
         const int word = raw[e];  // (a bit_cast applied directly to a vector element reads element 0 with this compiler)
-        q[2 * e] = code_of_smoothed<BITS4>(half_times<false>(word, im[2 * e]), inv_s);
-        q[2 * e + 1] = code_of_smoothed<BITS4>(half_times<true>(word, im[2 * e + 1]), inv_s);
+        q[2 * e] = code_of_smoothed<BITS4, OFFSET>(half_times<false>(word, im[2 * e]), inv_s, z);
+        q[2 * e + 1] = code_of_smoothed<BITS4, OFFSET>(half_times<true>(word, im[2 * e + 1]), inv_s, z);
     }
     u32x2 out = {pack4(q[0], q[1], q[2], q[3]), pack4(q[4], q[5], q[6], q[7])};
     if constexpr (BITS4) out = u32x2{times16(out[0]), times16(out[1])};
@@ -113,9 +119,10 @@ constexpr int kLdsBytes = 160 * 1024;
 constexpr int64_t kFusedMinRows = 2048;   // below this the one-off table copies per workgroup do not pay (4 k rows: 11 us against 48 us for the tiled fused kernel at 384 -> 44)
 
 struct FusedLayout {
-    int nb, n4, pw, w_bytes, inv_m_off, inv_s_off, scale_off, tile_off, tile_bytes, total;
+    int nb, n4, pw, w_bytes, inv_m_off, inv_s_off, z_off, scale_off, tile_off, tile_bytes, total;
 };
-__host__ __device__ __forceinline__ FusedLayout fused_layout(int N, int K, int L) {
+// offset: room for the per-token zero offsets [L] and the weight row sums (zero-offset form)
+__host__ __device__ __forceinline__ FusedLayout fused_layout(int N, int K, int L, bool offset = false) {
     FusedLayout l;
     l.nb = (N + 15) >> 4;
     l.n4 = (N + 3) & ~3;
@@ -123,8 +130,9 @@ __host__ __device__ __forceinline__ FusedLayout fused_layout(int N, int K, int L
     l.w_bytes = (l.nb * 16 * l.pw + 1023) & ~1023;  // whole 1 KiB wavefront copies
     l.inv_m_off = l.w_bytes;
     l.inv_s_off = l.inv_m_off + K * 4;
-    l.scale_off = l.inv_s_off + ((L * 4 + 15) & ~15);
-    l.tile_off = l.scale_off + l.nb * 16 * 4 * 2;
+    l.z_off = l.inv_s_off + ((L * 4 + 15) & ~15);
+    l.scale_off = l.z_off + (offset ? ((L * 4 + 15) & ~15) : 0);
+    l.tile_off = l.scale_off + l.nb * 16 * 4 * (offset ? 3 : 2);
     const int patch = kFusedPatchRows * l.n4 * 2;    // one pass of fp16 results
     const int codes = 1024 * kFusedRB;               // or the (16 RB) x 64-byte tile of codes
     l.tile_bytes = patch > codes ? patch : codes;
@@ -136,8 +144,10 @@ __host__ __device__ __forceinline__ FusedLayout fused_layout(int N, int K, int L
 // their address arithmetic (a third of the VALU instructions of the k loop) is not even compiled in.
 // BITS4: the weight arrives as packed 4-bit codes ([N, K / 2] bytes) and is expanded once into LDS (codes times 16, in
 // index order); activations are clipped to +-7 and also fed times 16; the factor 256 is undone in the channel steps.
-template <int NB, int D, bool DUMP, bool BITS4 = false>
+// OFFSET: the zero-offset form (8 bits): codes carry z_tok[t], the epilogue takes z_tok[t] * rowsum[o] off the accumulator.
+template <int NB, int D, bool DUMP, bool BITS4 = false, bool OFFSET = false>
 __global__ __launch_bounds__(kFusedWaves * 64) void pts_linear_wres(const LinearArgs p) {
+    static_assert(!(BITS4 && OFFSET), "the zero-offset form is 8-bit");
     using Acc = v4i;
 
     const int tid = threadIdx.x, lane = tid & 63;
@@ -145,13 +155,15 @@ __global__ __launch_bounds__(kFusedWaves * 64) void pts_linear_wres(const Linear
     const int l16 = lane & 15, lq = lane >> 4;  // MFMA operand position: row, 16-code chunk
     const int rr = lane >> 3, pc = lane & 7;    // load position: row within a group of 8, 16-byte piece
     const int N = (int)p.N, K = (int)p.k_bytes, L = (int)p.L, n_ksteps = K >> 6;
-    const FusedLayout lay = fused_layout(N, K, L);
+    const FusedLayout lay = fused_layout(N, K, L, OFFSET);
     const int n4 = lay.n4, pw = lay.pw;
     char *const w_lds = lds_dyn;
     float *const inv_m_lds = reinterpret_cast<float *>(lds_dyn + lay.inv_m_off);
     float *const inv_s_lds = reinterpret_cast<float *>(lds_dyn + lay.inv_s_off);
     float *const cs_lds = reinterpret_cast<float *>(lds_dyn + lay.scale_off);
     float *const cb_lds = cs_lds + NB * 16;
+    int *const z_lds = reinterpret_cast<int *>(lds_dyn + lay.z_off);   // zero-offset form only
+    int *const cz_lds = reinterpret_cast<int *>(cb_lds + NB * 16);     // weight row sums (zero-offset form only)
     char *const tile = lds_dyn + lay.tile_off + wave * lay.tile_bytes;  // codes in the K loop, results after it
 
     // Work items.  A wavefront handles units of up to UNIT rows, one per pass over the matrix; in a pass the
@@ -258,6 +270,10 @@ __global__ __launch_bounds__(kFusedWaves * 64) void pts_linear_wres(const Linear
             // 4-bit path: operands are codes times 16, the accumulator 256 times the sum; undone here (a power of two: exact)
             cs_lds[o] = o < N ? (BITS4 ? p.s_w[o] * (1.0f / 256.0f) : p.s_w[o]) : 0.0f;
             cb_lds[o] = (o < N && p.bias) ? __half2float(p.bias[o]) : 0.0f;
+            if constexpr (OFFSET) cz_lds[o] = o < N ? p.rowsum[o] : 0;
+        }
+        if constexpr (OFFSET) {
+            for (int t = tid; t < L; t += kFusedWaves * 64) z_lds[t] = p.z_tok[t];
         }
     }
     __builtin_amdgcn_s_waitcnt(0);  // vmcnt(0) expcnt(0) lgkmcnt(0): this wavefront's copies have landed
@@ -288,6 +304,9 @@ __global__ __launch_bounds__(kFusedWaves * 64) void pts_linear_wres(const Linear
         float inv_s[NL];
 #pragma unroll
         for (int i = 0; i < NL; i++) inv_s[i] = inv_s_lds[tok[i]];
+        int zq[NL];  // zero offsets of the rows this lane quantizes
+#pragma unroll
+        for (int i = 0; i < NL; i++) zq[i] = OFFSET ? z_lds[tok[i]] : 0;
         const int64_t r_unit = unit_r0;
         const int64_t r_end = min(p.M, unit_r0 + unit_rows);  // rows at or beyond it are not this unit's
         const int unit_groups = groups;                        // (`groups` moves on to the next unit before the epilogue)
@@ -307,7 +326,7 @@ __global__ __launch_bounds__(kFusedWaves * 64) void pts_linear_wres(const Linear
                 for (int e = 0; e < 4; e++) im[e] = im_lo[e], im[4 + e] = im_hi[e];
 #pragma unroll
                 for (int i = 0; i < G; i++) {  // tile rows of further groups keep stale codes: results of rows nobody stores
-                    const u32x2 codes = quantize_8<BITS4>(raw[d][i], im, inv_s[i]);
+                    const u32x2 codes = quantize_8<BITS4, OFFSET>(raw[d][i], im, inv_s[i], zq[i]);
                     *reinterpret_cast<u32x2 *>(tile + tile_wr[i]) = codes;
                     if (DUMP && p.xq_out) {  // parity aid: the codes that the MFMA will see (4-bit path: divided by 16 again)
                         const int64_t r = r_unit + i * 8 + rr;
@@ -364,6 +383,9 @@ __global__ __launch_bounds__(kFusedWaves * 64) void pts_linear_wres(const Linear
         float rs[RB];
 #pragma unroll
         for (int j = 0; j < RB; j++) rs[j] = p.s_tok[(uint32_t)min(r_unit + j * 16 + l16, p.M - 1) % (uint32_t)L];
+        int rz[RB];  // zero offset of the lane's result row
+#pragma unroll
+        for (int j = 0; j < RB; j++) rz[j] = OFFSET ? z_lds[(uint32_t)min(r_unit + j * 16 + l16, p.M - 1) % (uint32_t)L] : 0;
         item_k++;
         next_have = item(item_k, next_r0, next_rows);
         if (next_have) start_unit(next_r0, next_rows);  // in flight while this unit's results are written
@@ -382,11 +404,14 @@ __global__ __launch_bounds__(kFusedWaves * 64) void pts_linear_wres(const Linear
                 if (col < n4 && mine) {
                     const v4f cs = *reinterpret_cast<const v4f *>(cs_lds + col);
                     const v4f cb = *reinterpret_cast<const v4f *>(cb_lds + col);
+                    v4i cz = {0, 0, 0, 0};
+                    if constexpr (OFFSET) cz = *reinterpret_cast<const v4i *>(cz_lds + col);
                     float out[4];
 #pragma unroll
                     for (int c = 0; c < 4; c++) {
-                        const int a = acc[j][i][c];
+                        int a = acc[j][i][c];
                         if (DUMP && p.acc_out && prow < rows_valid && col + c < N) p.acc_out[(r0 + prow) * p.N + col + c] = BITS4 ? a >> 8 : a;
+                        if constexpr (OFFSET) a -= __mul24(rz[j], cz[c]);  // |z| < 2^8, |rowsum| < 2^23
                         out[c] = (float)a * (rs[j] * cs[c]) + cb[c];
                     }
                     __half2 lo = __floats2half2_rn(out[0], out[1]);
@@ -437,9 +462,9 @@ __global__ __launch_bounds__(kFusedWaves * 64) void pts_linear_wres(const Linear
 
 // Sixteen codes of row `row_ptr` (fp16) starting at code index k0; codes at or beyond K are 0.
 // im[j] is the smoothing factor of code k0 + j (any value for codes at or beyond K).
-template <int X_ALIGN, bool BITS4 = false>
+template <int X_ALIGN, bool BITS4 = false, bool OFFSET = false>
 __device__ __forceinline__ v4i load_quantized_chunk(const char *row_ptr, int64_t k0, int64_t K, bool row_ok,
-                                                    const float (&im)[16], float inv_s) {
+                                                    const float (&im)[16], float inv_s, int z = 0) {
     v4i out = {0, 0, 0, 0};
     if (!row_ok || k0 >= K) return out;
     const int valid = (int)min((int64_t)16, K - k0);
@@ -468,7 +493,7 @@ __device__ __forceinline__ v4i load_quantized_chunk(const char *row_ptr, int64_t
 #pragma unroll
     for (int j = 0; j < 16; j++) {
         const __half h = __builtin_bit_cast(__half, (uint16_t)(h2[j >> 1] >> (16 * (j & 1))));
-        q[j] = j < valid ? quantize_one<BITS4>(__half2float(h), im[j], inv_s) : 0;
+        q[j] = j < valid ? quantize_one<BITS4, OFFSET>(__half2float(h), im[j], inv_s, z) : 0;
     }
 #pragma unroll
     for (int j = 0; j < 4; j++) {
@@ -524,7 +549,7 @@ __host__ __device__ __forceinline__ StreamLayout stream_layout(int N, int ksteps
 template <int KSTEPS, bool QUANT, int X_ALIGN, int W_ALIGN, bool PACKED4 = false, bool OFFSET = false>
 __global__ __launch_bounds__(kStreamWaves * 64) void linear_stream_smallk(const LinearArgs p) {
     // QUANT && PACKED4: the fused 4-bit form - fp16 activations clipped to +-7, packed 4-bit weight; both fed times 16
-    static_assert(!(OFFSET && (QUANT || PACKED4)), "the zero-offset form is two-launch and 8-bit");
+    static_assert(!(OFFSET && PACKED4), "the zero-offset form is 8-bit");
     constexpr bool BITS4 = QUANT && PACKED4;
     const int tid = threadIdx.x, lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);  // scalar: unit numbers and row bounds stay in SGPRs
@@ -616,7 +641,7 @@ __global__ __launch_bounds__(kStreamWaves * 64) void linear_stream_smallk(const 
                         const v4f f = *reinterpret_cast<const v4f *>(inv_m_lds + k0 + 4 * e);
                         im[4 * e] = f.x, im[4 * e + 1] = f.y, im[4 * e + 2] = f.z, im[4 * e + 3] = f.w;
                     }
-                    const v4i codes = load_quantized_chunk<X_ALIGN, BITS4>(xrow, k0, K, true, im, inv_s);
+                    const v4i codes = load_quantized_chunk<X_ALIGN, BITS4, OFFSET>(xrow, k0, K, true, im, inv_s, rz[jb]);
                     if (p.xq_out && part == 0 && r_unit + jb * 16 + l16 < p.M) {  // parity aid (4-bit form: the codes, not times 16)
 #pragma unroll
                         for (int b = 0; b < 16; b++)
@@ -853,8 +878,11 @@ int launch_stream_aligned(const LinearArgs &a, int xa, int wa, const StreamLayou
     return ptq4vm::check_launch("linear_stream_smallk");
 }
 
-int launch_wres(const LinearArgs &a, hipStream_t stream, bool bits4) {
-    const FusedLayout lay = fused_layout((int)a.N, (int)a.k_bytes, (int)a.L);
+// Form of a fused launch: 8-bit codes, 4-bit codes (packed weight), or 8-bit codes with a per-token zero offset.
+enum class Form { kInt8 = 0, kBits4 = 1, kOffset = 2 };
+
+int launch_wres(const LinearArgs &a, hipStream_t stream, Form form) {
+    const FusedLayout lay = fused_layout((int)a.N, (int)a.k_bytes, (int)a.L, form == Form::kOffset);
     int device = 0, cus = 0;
     hipError_t err = hipGetDevice(&device);
     if (err == hipSuccess) err = hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, device);
@@ -864,23 +892,26 @@ int launch_wres(const LinearArgs &a, hipStream_t stream, bool bits4) {
     int64_t wgs = ptq4vm::ceil_div(units, kFusedWaves);
     if (wgs > cus) wgs = cus;  // one workgroup per CU: the resident tables take most of its LDS
     using Kernel = void (*)(const LinearArgs);
-#define PTQ4VM_WRES_ROW(D, DUMP, B4) \
-    {pts_linear_wres<1, D, DUMP, B4>, pts_linear_wres<2, D, DUMP, B4>, pts_linear_wres<3, D, DUMP, B4>, pts_linear_wres<4, D, DUMP, B4>, \
-     pts_linear_wres<5, D, DUMP, B4>, pts_linear_wres<6, D, DUMP, B4>, pts_linear_wres<7, D, DUMP, B4>, pts_linear_wres<8, D, DUMP, B4>}
-    // [4-bit][parity aids][k-steps in flight: 4, 2, 1][number of 16-channel blocks - 1]
-    static const Kernel kernels[2][2][3][kFusedMaxBlocks] = {
-        {{PTQ4VM_WRES_ROW(4, false, false), PTQ4VM_WRES_ROW(2, false, false), PTQ4VM_WRES_ROW(1, false, false)},
-         {PTQ4VM_WRES_ROW(4, true, false), PTQ4VM_WRES_ROW(2, true, false), PTQ4VM_WRES_ROW(1, true, false)}},
-        {{PTQ4VM_WRES_ROW(4, false, true), PTQ4VM_WRES_ROW(2, false, true), PTQ4VM_WRES_ROW(1, false, true)},
-         {PTQ4VM_WRES_ROW(4, true, true), PTQ4VM_WRES_ROW(2, true, true), PTQ4VM_WRES_ROW(1, true, true)}}};
-#undef PTQ4VM_WRES_ROW
-    const int n_ksteps = (int)(a.k_bytes / 64);
     // four k-steps in flight need too many registers next to the accumulators of 7 or 8 channel blocks
 #ifndef PTQ4VM_FUSED_MAXD
 #define PTQ4VM_FUSED_MAXD (PTQ4VM_FUSED_RB == 1 ? 2 : 4)  // 16 wavefronts of 128 registers: two k-steps in flight (measured best)
 #endif
+    constexpr int kDeepest = PTQ4VM_FUSED_MAXD >= 4 ? 4 : 2;  // (the depth-4 kernels are not even compiled when they cannot be chosen)
+#define PTQ4VM_WRES_ROW(D, DUMP, B4, OFS) \
+    {pts_linear_wres<1, D, DUMP, B4, OFS>, pts_linear_wres<2, D, DUMP, B4, OFS>, pts_linear_wres<3, D, DUMP, B4, OFS>, \
+     pts_linear_wres<4, D, DUMP, B4, OFS>, pts_linear_wres<5, D, DUMP, B4, OFS>, pts_linear_wres<6, D, DUMP, B4, OFS>, \
+     pts_linear_wres<7, D, DUMP, B4, OFS>, pts_linear_wres<8, D, DUMP, B4, OFS>}
+#define PTQ4VM_WRES_FORM(B4, OFS) \
+    {{PTQ4VM_WRES_ROW(kDeepest, false, B4, OFS), PTQ4VM_WRES_ROW(2, false, B4, OFS), PTQ4VM_WRES_ROW(1, false, B4, OFS)}, \
+     {PTQ4VM_WRES_ROW(kDeepest, true, B4, OFS), PTQ4VM_WRES_ROW(2, true, B4, OFS), PTQ4VM_WRES_ROW(1, true, B4, OFS)}}
+    // [form][parity aids][k-steps in flight: 4, 2, 1][number of 16-channel blocks - 1]
+    static const Kernel kernels[3][2][3][kFusedMaxBlocks] = {PTQ4VM_WRES_FORM(false, false), PTQ4VM_WRES_FORM(true, false),
+                                                             PTQ4VM_WRES_FORM(false, true)};
+#undef PTQ4VM_WRES_FORM
+#undef PTQ4VM_WRES_ROW
+    const int n_ksteps = (int)(a.k_bytes / 64);
     const int depth_row = (PTQ4VM_FUSED_MAXD >= 4 && n_ksteps % 4 == 0 && lay.nb <= 6) ? 0 : (n_ksteps % 2 == 0 ? 1 : 2);
-    const Kernel kernel = kernels[bits4 ? 1 : 0][(a.xq_out || a.acc_out) ? 1 : 0][depth_row][lay.nb - 1];
+    const Kernel kernel = kernels[(int)form][(a.xq_out || a.acc_out) ? 1 : 0][depth_row][lay.nb - 1];
     if (int rc = ptq4vm::set_lds_limit(reinterpret_cast<const void *>(kernel), kLdsBytes, "hipFuncSetAttribute(pts_linear_wres)")) return rc;
     kernel<<<dim3((unsigned)wgs), dim3(kFusedWaves * 64), lay.total, stream>>>(a);
     return ptq4vm::check_launch("pts_linear_wres");
@@ -905,9 +936,9 @@ int launch_generic(LinearArgs a, int x_align, int w_align, hipStream_t stream) {
     return ptq4vm::check_launch("pts_linear_generic");
 }
 
-// bits4: the 4-bit form (weight packed two codes per byte, activations clipped to +-7).  It runs on the weight-resident
-// and the row-streaming kernel only; other shapes return PTQ4VM_ERR_SHAPE (the two-call form covers them).
-int dispatch(LinearArgs a, hipStream_t stream, bool bits4 = false) {
+// The 4-bit form (weight packed two codes per byte, activations clipped to +-7) and the zero-offset form run on the
+// weight-resident and the row-streaming kernel only; other shapes return PTQ4VM_ERR_SHAPE (the two-call forms cover them).
+int dispatch(LinearArgs a, hipStream_t stream, Form form = Form::kInt8) {
     auto align_of = [](const void *base, int64_t pitch_bytes) {
         if (ptq4vm::aligned_to(base, 16) && pitch_bytes % 16 == 0) return 16;
         if (ptq4vm::aligned_to(base, 4) && pitch_bytes % 4 == 0) return 4;
@@ -920,13 +951,13 @@ int dispatch(LinearArgs a, hipStream_t stream, bool bits4 = false) {
     const bool wres_ok = small && xa == 16 && wa == 16 && a.k_bytes % 64 == 0 && a.N <= 16 * kFusedMaxBlocks &&
                          a.M >= kFusedMinRows && a.L <= 65536 &&
                          (!a.xq_out || (ptq4vm::aligned_to(a.xq_out, 8) && a.ldxq_out % 8 == 0)) &&
-                         fused_layout((int)a.N, (int)a.k_bytes, (int)a.L).total <= kLdsBytes;
-    if (wres_ok) return launch_wres(a, stream, bits4);
+                         fused_layout((int)a.N, (int)a.k_bytes, (int)a.L, form == Form::kOffset).total <= kLdsBytes;
+    if (wres_ok) return launch_wres(a, stream, form);
     if (a.k_bytes <= 128) {
-        const int rc = launch_stream_smallk(a, true, stream, bits4);
+        const int rc = launch_stream_smallk(a, true, stream, form == Form::kBits4, form == Form::kOffset);
         if (rc <= 0) return rc;
     }
-    if (bits4) return PTQ4VM_ERR_SHAPE;
+    if (form != Form::kInt8) return PTQ4VM_ERR_SHAPE;
     if (a.N > 64) return launch_generic<256, 128, 2, 2>(a, xa, wa, stream);
     return launch_generic<256, 64, 4, 1>(a, xa, wa, stream);
 }
@@ -942,7 +973,7 @@ int ptq4vm::mfma::launch_stream_smallk(const LinearArgs &a, bool quantize, hipSt
     const int xa = align_of(a.x, a.ldx_bytes), wa = align_of(a.w, a.ldw_bytes);
     // bytes of K per row once the operands are int8 (two-launch 4-bit form: k_bytes counts packed bytes; fused 4-bit form: codes)
     const int64_t k_codes = (packed4 && !quantize) ? 2 * a.k_bytes : a.k_bytes;
-    if (k_codes > 128 || (offset && (quantize || packed4)) || a.M < (quantize ? kStreamMinRowsFused : kStreamMinRows) || a.M >= (1LL << 31) || a.L >= (1LL << 31) || a.N > 8192) return 1;
+    if (k_codes > 128 || (offset && packed4) || a.M < (quantize ? kStreamMinRowsFused : kStreamMinRows) || a.M >= (1LL << 31) || a.L >= (1LL << 31) || a.N > 8192) return 1;
     const int ksteps = k_codes <= 64 ? 1 : 2;
     const StreamLayout lay = stream_layout((int)a.N, ksteps);
     if (lay.total > kLdsBytes) return 1;
@@ -954,6 +985,9 @@ int ptq4vm::mfma::launch_stream_smallk(const LinearArgs &a, bool quantize, hipSt
     const int64_t items = ptq4vm::ceil_div(a.M, 16 * kStreamRB) * (lay.groups < 4 ? lay.groups : 4);  // as the kernel counts them
     int64_t wgs = ptq4vm::ceil_div(items, kStreamWaves);
     if (wgs > cus) wgs = cus;  // one workgroup per CU: the resident weight takes most of its LDS
+    if (offset && quantize)
+        return ksteps == 1 ? launch_stream_aligned<1, true, false, true>(a, xa, wa, lay, (unsigned)wgs, stream)
+                           : launch_stream_aligned<2, true, false, true>(a, xa, wa, lay, (unsigned)wgs, stream);
     if (offset)
         return ksteps == 1 ? launch_stream_aligned<1, false, false, true>(a, xa, wa, lay, (unsigned)wgs, stream)
                            : launch_stream_aligned<2, false, false, true>(a, xa, wa, lay, (unsigned)wgs, stream);
@@ -1002,7 +1036,46 @@ extern "C" int ptq4vm_w4a4_linear_fused(const void *x_f16, const float *inv_m, c
     a.inv_m = inv_m;
     a.xq_out = xq_out;
     a.ldxq_out = ldxq;
-    return dispatch(a, static_cast<hipStream_t>(stream_), true);
+    return dispatch(a, static_cast<hipStream_t>(stream_), Form::kBits4);
+}
+
+extern "C" int ptq4vm_w8a8_linear_offset_fused(const void *x_f16, const float *inv_m, const float *s_tok, const int32_t *z_tok,
+                                               const int8_t *wq, const int32_t *rowsum, const float *s_w,
+                                               const void *bias_f16, void *y_f16, int32_t *acc_out, int8_t *xq_out,
+                                               int64_t B, int64_t L, int64_t K, int64_t N, int64_t ldx, int64_t ldwq,
+                                               int64_t ldy, int64_t ldxq, void *stream_) {
+    if (!x_f16 || !s_tok || !z_tok || !wq || !rowsum || !s_w || !y_f16) return PTQ4VM_ERR_NULL;
+    if (B < 0 || N < 0 || L <= 0 || K <= 0 || K > PTQ4VM_MAX_K_OFFSET) return PTQ4VM_ERR_SHAPE;
+    if (B > 0 && L > INT64_MAX / B) return PTQ4VM_ERR_SHAPE;
+    if (ldx < K || ldwq < K || ldy < N || (xq_out && ldxq < K)) return PTQ4VM_ERR_STRIDE;
+    if (!ptq4vm::aligned_to(x_f16, 16) || !ptq4vm::aligned_to(wq, 16) || !ptq4vm::aligned_to(y_f16, 2) ||
+        !ptq4vm::aligned_to(inv_m, 4) || !ptq4vm::aligned_to(s_tok, 4) || !ptq4vm::aligned_to(z_tok, 4) ||
+        !ptq4vm::aligned_to(rowsum, 4) || !ptq4vm::aligned_to(s_w, 4) || !ptq4vm::aligned_to(bias_f16, 2) ||
+        !ptq4vm::aligned_to(acc_out, 4))
+        return PTQ4VM_ERR_ALIGN;
+    const int64_t M = B * L;
+    if (M == 0 || N == 0) return PTQ4VM_OK;
+    LinearArgs a{};
+    a.x = static_cast<const char *>(x_f16);
+    a.w = reinterpret_cast<const char *>(wq);
+    a.s_tok = s_tok;
+    a.s_w = s_w;
+    a.bias = static_cast<const __half *>(bias_f16);
+    a.y = static_cast<__half *>(y_f16);
+    a.acc_out = acc_out;
+    a.M = M;
+    a.N = N;
+    a.k_bytes = K;
+    a.ldx_bytes = ldx * 2;
+    a.ldw_bytes = ldwq;
+    a.ldy = ldy;
+    a.L = L;
+    a.inv_m = inv_m;
+    a.xq_out = xq_out;
+    a.ldxq_out = ldxq;
+    a.z_tok = z_tok;
+    a.rowsum = rowsum;
+    return dispatch(a, static_cast<hipStream_t>(stream_), Form::kOffset);
 }
 
 extern "C" int ptq4vm_w8a8_linear_fused(const void *x_f16, const float *inv_m, const float *s_tok, const int8_t *wq,

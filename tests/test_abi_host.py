@@ -242,6 +242,28 @@ def test_w4a4_linear_fused_argument_checks(lib):
     # (a valid problem outside the two kernels' shapes is refused with -2 only after a device query: GPU tests)
 
 
+def test_w8a8_linear_offset_fused_argument_checks(lib):
+    f = lib.ptq4vm_w8a8_linear_offset_fused
+    #     x  inv_m s_tok z_tok wq rowsum s_w bias y acc  xq    B  L  K   N   ldx ldwq ldy ldxq stream
+    ok = [P, P, P, P, P, P, P, P, P, NULL, NULL, 1, 1, 16, 16, 16, 16, 16, 0, None]
+
+    def call(**kw):
+        a = list(ok)
+        for i, v in kw.items():
+            a[int(i[1:])] = v
+        return f(*a)
+
+    assert call(a0=NULL) == -1 and call(a2=NULL) == -1 and call(a3=NULL) == -1 and call(a4=NULL) == -1
+    assert call(a5=NULL) == -1 and call(a6=NULL) == -1 and call(a8=NULL) == -1
+    assert call(a11=-1) == -2 and call(a12=0) == -2 and call(a13=0) == -2 and call(a14=-1) == -2
+    assert call(a13=65537, a15=65537, a16=65537) == -2       # beyond PTQ4VM_MAX_K_OFFSET
+    assert call(a15=15) == -3 and call(a16=15) == -3 and call(a17=15) == -3
+    assert call(a10=P, a18=15) == -3                         # copy of the codes requested with too small a pitch
+    assert call(a0=ODD) == -4 and call(a4=ODD) == -4 and call(a3=ctypes.c_void_p(0x1002)) == -4
+    assert call(a5=ctypes.c_void_p(0x1002)) == -4 and call(a8=ctypes.c_void_p(0x1001)) == -4
+    assert call(a11=0) == 0 and call(a14=0, a17=0) == 0      # empty problem
+
+
 def test_validate_scales_argument_checks(lib):
     f = lib.ptq4vm_validate_scales
     f.restype = ctypes.c_int

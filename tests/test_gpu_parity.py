@@ -707,6 +707,129 @@ def test_zero_offset_quantizer_long_sequence_and_plain_kernels():
         assert np.array_equal(_np(xq), xq_o), (B, L, K)
 
 
+FUSED_OFFSET_SHAPES = [  # B, L, K, N, ldy, bias
+    # weight-resident kernel (N <= 128, K a multiple of 64, >= 2048 rows)
+    (83, 199, 128, 44, None, True),      # 2 k-steps; M mod 32 = 5
+    (64, 257, 320, 80, None, False),     # 5 k-steps (depth 1)
+    (70, 241, 1024, 96, None, True),     # 16 k-steps, 6 channel blocks
+    (70, 241, 512, 128, None, True),     # 8 channel blocks
+    (83, 199, 1536, 72, 80, True),       # x_proj-like, padded output rows
+    (13, 163, 192, 33, None, False),     # 2119 rows, M mod 8 = 7: the last group is ragged
+    # row-streaming kernel (K <= 128, >= 1024 rows)
+    (105, 197, 40, 100, 104, True),      # padded output rows
+    (21, 199, 12, 130, None, True),      # 24-byte fp16 rows
+    (35, 120, 128, 200, None, True),     # two k-steps (N > 128: not the weight-resident kernel)
+    (33, 127, 100, 33, 40, True),        # odd N with padding; M mod 16 = 15
+    (30, 197, 48, 1536, None, True),     # dt_proj (Vim-B) shape on fewer rows
+    (11, 100, 13, 5, None, True),        # nothing aligned
+]
+
+
+@pytest.mark.parametrize("B,L,K,N,ldy,bias", FUSED_OFFSET_SHAPES)
+def test_fused_zero_offset_whole_result(B, L, K, N, ldy, bias):
+    """Every code, accumulator and output of the one-launch zero-offset form against the oracle and the two launches."""
+    print(f"fused offset B={B} L={L} K={K} N={N} ldy={ldy} bias={bias}", flush=True)
+    c, x, s_off, z_off = _offset_case(8100 + K + N, B, L, K, N)
+    M = B * L
+    wq, s_w, inv_m = ptq.fold_smoothing(c.w, c.m)
+    rowsum = ptq.weight_rowsum(wq)
+    b = c.bias if bias else None
+    acc = torch.full((M, N), -1, dtype=torch.int32, device=DEV)
+    xq = torch.full((M, K), 0x55, dtype=torch.int8, device=DEV)
+    ybuf = None
+    if ldy is None:
+        y = ptq.w8a8_linear_offset_fused(x, inv_m, s_off, z_off, wq, rowsum, s_w, b, B, L, acc_out=acc, xq_out=xq)
+    else:
+        ybuf, yv = _padded(M, N, ldy, torch.float16, 12345.0)
+        y = ptq.w8a8_linear_offset_fused(x, inv_m, s_off, z_off, wq, rowsum, s_w, b, B, L, y=yv, acc_out=acc, xq_out=xq)
+    y2 = ptq.w8a8_linear_offset_fused(x, inv_m, s_off, z_off, wq, rowsum, s_w, b, B, L)  # timed configuration
+    xq_two = ptq.quantize_pts_offset(x, inv_m, s_off, z_off, B, L)
+    y_two = ptq.w8a8_linear_offset(xq_two, wq, s_off, z_off, rowsum, s_w, b, B, L)
+    torch.cuda.synchronize()
+
+    wq_o, s_w_o, inv_m_o = oracle.fold_smoothing(_np(c.w), _np(c.m))
+    rowsum_o = oracle.weight_rowsum(wq_o)
+    xq_o = oracle.quantize_pts_offset(_np(x), inv_m_o, _np(s_off), _np(z_off), B, L)
+    acc_o = oracle.int8_gemm(xq_o, wq_o)
+    b_o = _np(c.bias) if bias else None
+    y_o, y64 = oracle.dequant_offset(acc_o, _np(s_off), _np(z_off), rowsum_o, s_w_o, b_o, B, L)
+    assert np.array_equal(_np(xq), xq_o), "int8 codes differ"
+    assert xq_o.min() == -128 or xq_o.max() == 127                    # the clip is exercised
+    assert np.array_equal(_np(acc), acc_o), "int32 accumulators differ"
+    st = np.tile(_np(s_off).astype(np.float64), B)[:, None]
+    zt = np.tile(_np(z_off).astype(np.float64), B)[:, None]
+    corrected = acc_o.astype(np.float64) - zt * rowsum_o.astype(np.float64)[None, :]
+    prod_abs = np.abs(corrected * st * s_w_o.astype(np.float64)[None, :])
+    bias_abs = np.broadcast_to(np.abs(b_o.astype(np.float64))[None, :] if bias else 0.0, prod_abs.shape)
+    check_dequantized_output(_np(y), y_o, y64, prod_abs, bias_abs, "fused offset")
+    assert torch.equal(y.view(torch.int16), y2.view(torch.int16)), "the parity outputs change the result"
+    assert torch.equal(y.view(torch.int16), y_two.view(torch.int16)), "fused and two-launch forms differ"
+    if ybuf is not None:
+        assert np.all(_np(ybuf[:, N:]) == np.float16(12345.0))
+
+
+@pytest.mark.parametrize("linear", [1, 2])
+def test_fused_zero_offset_vim_b_full_size_sampled(linear):
+    """x_proj and dt_proj of Vim-B at the timed size: the one-launch zero-offset form on sampled rows."""
+    c = synth.make_linear_case(3, 0, linear, device=DEV)
+    M = c.B * c.L
+    print(f"fused offset full-size {c.name}: M={M} K={c.K} N={c.N}", flush=True)
+    shift = synth.token_shift(c.L, 77 + linear, device=DEV)
+    x = (c.x.view(c.B, c.L, c.K) + shift.view(1, c.L, 1).to(c.x.dtype)).reshape(M, c.K).contiguous()
+    s_off, z_off = synth.calibrate_offset(x[: 16 * c.L], c.m, c.L)
+    wq, s_w, inv_m = ptq.fold_smoothing(c.w, c.m)
+    rowsum = ptq.weight_rowsum(wq)
+    y = ptq.w8a8_linear_offset_fused(x, inv_m, s_off, z_off, wq, rowsum, s_w, c.bias, c.B, c.L)
+    acc = torch.full((M, c.N), -1, dtype=torch.int32, device=DEV)
+    xq = torch.full((M, c.K), 0x55, dtype=torch.int8, device=DEV)
+    y_dump = ptq.w8a8_linear_offset_fused(x, inv_m, s_off, z_off, wq, rowsum, s_w, c.bias, c.B, c.L, acc_out=acc, xq_out=xq)
+    torch.cuda.synchronize()
+    assert torch.equal(y.view(torch.int16), y_dump.view(torch.int16))
+    rows = _sampled_rows(M, 97, c.L)
+    ridx = torch.from_numpy(rows).to(DEV)
+    wq_o, s_w_o, inv_m_o = oracle.fold_smoothing(_np(c.w), _np(c.m))
+    rowsum_o = oracle.weight_rowsum(wq_o)
+    st_rows, z_rows = _np(s_off)[rows % c.L], _np(z_off)[rows % c.L]
+    n = len(rows)
+    xq_o = oracle.quantize_pts_offset(_np(x[ridx]), inv_m_o, st_rows, z_rows, 1, n)
+    assert np.array_equal(_np(xq[ridx]), xq_o), "int8 codes differ"
+    acc_o = oracle.int8_gemm(xq_o, wq_o)
+    assert np.array_equal(_np(acc[ridx]), acc_o), "int32 accumulators differ"
+    y_o, y64 = oracle.dequant_offset(acc_o, st_rows, z_rows, rowsum_o, s_w_o, _np(c.bias), 1, n)
+    corrected = acc_o.astype(np.float64) - z_rows.astype(np.float64)[:, None] * rowsum_o.astype(np.float64)[None, :]
+    prod_abs = np.abs(corrected * st_rows.astype(np.float64)[:, None] * s_w_o.astype(np.float64)[None, :])
+    bias_abs = np.broadcast_to(np.abs(_np(c.bias).astype(np.float64))[None, :], prod_abs.shape)
+    check_dequantized_output(_np(y[ridx]), y_o, y64, prod_abs, bias_abs, f"fused offset {c.name}")
+
+
+def test_fused_zero_offset_specials_and_refused_shapes():
+    """Infinities and NaN with offsets at both ends of the int8 range (the saturated conversion must not wrap when the
+    offset is added); shapes outside the two kernels return PTQ4VM_ERR_SHAPE."""
+    B, L, K, N = 8, 256, 64, 32
+    c = synth.random_problem(31, B, L, K, N, device=DEV)
+    x = c.x.clone()
+    x[::3, 0] = float("inf")
+    x[1::3, 1] = float("-inf")
+    x[2::3, 2] = float("nan")
+    x[::5, 3] = 65504.0
+    z = torch.randint(-128, 128, (L,), dtype=torch.int32, device=DEV)
+    z[0], z[1] = 127, -128
+    wq, s_w, inv_m = ptq.fold_smoothing(c.w, c.m)
+    rowsum = ptq.weight_rowsum(wq)
+    xq = torch.empty((B * L, K), dtype=torch.int8, device=DEV)
+    ptq.w8a8_linear_offset_fused(x, inv_m, c.s_tok, z, wq, rowsum, s_w, c.bias, B, L, xq_out=xq)
+    torch.cuda.synchronize()
+    xq_o = oracle.quantize_pts_offset(_np(x), _np(inv_m), _np(c.s_tok), _np(z), B, L)
+    assert np.array_equal(_np(xq), xq_o)
+    for Bs, Ls, Ks, Ns in [(1, 50, 64, 32), (20, 197, 768, 3072)]:
+        cs = synth.random_problem(78, Bs, Ls, Ks, Ns, device=DEV)
+        wq, s_w, inv_m = ptq.fold_smoothing(cs.w, cs.m)
+        zz = torch.zeros(Ls, dtype=torch.int32, device=DEV)
+        with pytest.raises(ptq.Ptq4vmError) as e:
+            ptq.w8a8_linear_offset_fused(cs.x, inv_m, cs.s_tok, zz, wq, ptq.weight_rowsum(wq), s_w, cs.bias, Bs, Ls)
+        assert e.value.status == -2  # PTQ4VM_ERR_SHAPE
+
+
 # ---------------------------------------------------------------------------------- W4A4 (packed 4-bit codes)
 def _steps_4bit(c):
     """The calibrated +-127 steps rescaled to the +-7 range (input preparation, fp32)."""
