@@ -78,6 +78,11 @@ constexpr int kAhead = kSlots - 1;  // slots copied ahead of the one being consu
 constexpr int kStagePitch = 528;  // bytes per staged row: 256 channels of fp16 + 16 (bank spread)
 constexpr int kStageBytes = kUnitRows * kStagePitch;
 constexpr int kRowScaleBufs = 4;  // per-row step vectors of the units in flight
+#ifndef PTQ4VM_WREG_PREFETCH
+#define PTQ4VM_WREG_PREFETCH 3
+#endif
+constexpr int kPrefetchAhead = PTQ4VM_WREG_PREFETCH;  // units between a row tile's L2 prefetch and its first copy (0: none)
+constexpr int kPrefetchSinkBytes = 4 * 256;           // where the prefetch loads land: 256 bytes per storing wavefront
 
 template <int KSTEPS, bool HAS_BIAS, bool DUMP_ACC>
 __global__ __launch_bounds__(512, 1) void linear_mfma_wreg(const LinearArgs p) {
@@ -95,6 +100,7 @@ __global__ __launch_bounds__(512, 1) void linear_mfma_wreg(const LinearArgs p) {
     float *const rs_lds = reinterpret_cast<float *>(stage + kStageBytes);  // [kRowScaleBufs][kUnitRows]
     // steps and biases of the strip's channels, 48 bytes per group of 8 channels: 8 fp32 steps, 8 fp16 biases
     char *const cs_lds = reinterpret_cast<char *>(rs_lds + kRowScaleBufs * kUnitRows);
+    char *const pf_sink = cs_lds + 32 * 48 + 16;  // never read
 
     const int tid = threadIdx.x, lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
@@ -302,6 +308,29 @@ __global__ __launch_bounds__(512, 1) void linear_mfma_wreg(const LinearArgs p) {
         }
     };
 
+    // ---- L2 prefetch (wavefronts 4-7): one 4-byte load per 128-byte line of a unit's codes, kPrefetchAhead units
+    // before the unit is worked on.  At K = 384 a step is 16 MFMAs per wavefront and the ring's three slots of
+    // lookahead are shorter than the latency of a row tile that comes from memory: measured 63 -> 59 us at
+    // M = 50 240 and 32.8 -> 31.5 us at M = 25 216 (at K = 768 the steps are twice as long and nothing changes).
+    // The ring cannot grow: LDS is full.  The loads land in an LDS sink that nobody reads (no destination register
+    // to keep alive), and they are issued by the wavefronts that never wait for a load: loads return in order, so in
+    // a copying wavefront every later copy would wait for them.
+    auto prefetch_unit = [&](const UnitCursor &c) {
+        const uint32_t ln = (threadIdx.x + opaque_zero()) & 63;
+        const int64_t r0 = unit_row0(c);
+        const int rows_valid = (int)min((int64_t)kUnitRows, p.M - r0);
+        constexpr int LINES_PER_ROW = KSTEPS / 2, LINES = kUnitRows * LINES_PER_ROW, PER_WAVE = LINES / 4;
+        const char *base = p.x + r0 * p.ldx_bytes;
+#pragma unroll
+        for (int c2 = 0; c2 < (PER_WAVE + 63) / 64; c2++) {
+            const int idx = min(gw * PER_WAVE + c2 * 64 + (int)ln, LINES - 1);
+            const int row = idx / LINES_PER_ROW, line = idx - row * LINES_PER_ROW;
+            const uint32_t off = (uint32_t)min(row, rows_valid - 1) * (uint32_t)p.ldx_bytes + line * 128;
+            __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void *)(base + off),
+                                             (__attribute__((address_space(3))) void *)(pf_sink + gw * 256), 4, 0, 0);
+        }
+    };
+
     // One source for both roles; COPIER is a compile-time flag so that neither role's code has branches
     // on the other's duties.
     auto run = [&](auto copier_tag) {
@@ -315,6 +344,14 @@ __global__ __launch_bounds__(512, 1) void linear_mfma_wreg(const LinearArgs p) {
         int g = 0, slot = 0, u = 0;
         int64_t prev_r0 = 0, prev_o0 = 0;
         bool first_run = true;
+        UnitCursor qc = wr.start;  // the unit kPrefetchAhead after the current one
+        if constexpr (!COPIER && kPrefetchAhead > 0) {
+#pragma unroll 1
+            for (int a = 0; a < kPrefetchAhead; a++) {
+                advance(qc, wr);
+                if (a + 1 < kPrefetchAhead && a + 1 < wr.count) prefetch_unit(qc);  // units 1 .. kPrefetchAhead - 1
+            }
+        }
 #pragma unroll 1
         while (u < wr.count) {
             // A run of units of one strip: the weight rows stay in registers for all of it.
@@ -328,6 +365,10 @@ __global__ __launch_bounds__(512, 1) void linear_mfma_wreg(const LinearArgs p) {
 #pragma unroll 1
             do {
                 const int64_t r0 = unit_row0(cc);
+                if constexpr (!COPIER && kPrefetchAhead > 0) {
+                    if (u + kPrefetchAhead < wr.count) prefetch_unit(qc);
+                    advance(qc, wr);
+                }
 #pragma unroll
                 for (int j = 0; j < 8; j++) fx[j] = operand(j, slot, 0);  // the unit's first operands (its slot has landed)
 #pragma unroll
@@ -411,7 +452,7 @@ int launch_wreg(const LinearArgs &a_in, hipStream_t stream) {
          {linear_mfma_wreg<12, true, false>, linear_mfma_wreg<12, true, true>}}};
     const Kernel kernel = kernels[a.k_bytes == 768 ? 1 : 0][a.bias ? 1 : 0][a.acc_out ? 1 : 0];
     const int slab = a.k_bytes == 768 ? 128 : 64;
-    const int lds_bytes = kSlots * kUnitRows * slab + kStageBytes + kRowScaleBufs * kUnitRows * 4 + 32 * 48 + 16;
+    const int lds_bytes = kSlots * kUnitRows * slab + kStageBytes + kRowScaleBufs * kUnitRows * 4 + 32 * 48 + 16 + kPrefetchSinkBytes;
     if (int rc = ptq4vm::set_lds_limit(reinterpret_cast<const void *>(kernel), lds_bytes, "hipFuncSetAttribute(linear_mfma_wreg)")) return rc;
     kernel<<<dim3(wgs), dim3(512), lds_bytes, stream>>>(a);
     return ptq4vm::check_launch("linear_mfma_wreg");
