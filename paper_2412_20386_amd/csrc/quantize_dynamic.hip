@@ -96,7 +96,7 @@ __global__ __launch_bounds__(kThreads) void quantize_dynamic_rows(const __half *
 #pragma unroll
                     for (int e = 0; e < 8; e++) q[e] = code_of(v[c][e], inv_s);
                     const u32x2 out = {pack4(q[0], q[1], q[2], q[3]), pack4(q[4], q[5], q[6], q[7])};
-                    __builtin_nontemporal_store(out, reinterpret_cast<u32x2 *>(xq + row * ldxq + (in_row + c * lanes_per_row) * 8));
+                    ptq4vm::store_for_next_kernel(reinterpret_cast<u32x2 *>(xq + row * ldxq + (in_row + c * lanes_per_row) * 8), out);
                 }
         }
 #pragma unroll

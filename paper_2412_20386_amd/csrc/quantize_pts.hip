@@ -133,7 +133,7 @@ __global__ __launch_bounds__(kMaxThreads) void quantize_pts_stream(
         }
 #pragma unroll
         for (int u = 0; u < UNROLL; u++)
-            __builtin_nontemporal_store(quantize_chunk<HAS_Z>(v[u], im, is[u], zs[u]), reinterpret_cast<Out *>(qp + u * q_step));
+            ptq4vm::store_for_next_kernel(reinterpret_cast<Out *>(qp + u * q_step), quantize_chunk<HAS_Z>(v[u], im, is[u], zs[u]));
         xp += UNROLL * x_step;
         qp += UNROLL * q_step;
     }
@@ -143,7 +143,7 @@ __global__ __launch_bounds__(kMaxThreads) void quantize_pts_stream(
         const int z = offset(t);
         t += t_step;
         if (t >= L) t -= L;
-        __builtin_nontemporal_store(quantize_chunk<HAS_Z>(v, im, is, z), reinterpret_cast<Out *>(qp));
+        ptq4vm::store_for_next_kernel(reinterpret_cast<Out *>(qp), quantize_chunk<HAS_Z>(v, im, is, z));
         xp += x_step;
         qp += q_step;
     }

@@ -80,7 +80,7 @@ __global__ __launch_bounds__(kThreads) void quantize_pts_a4_stream(const __half 
         t += t_step;
         if (t >= L) t -= L;
         const u32x2 out = {quantize8(lo, im, inv_s), quantize8(hi, im + 8, inv_s)};
-        __builtin_nontemporal_store(out, reinterpret_cast<u32x2 *>(qp));
+        ptq4vm::store_for_next_kernel(reinterpret_cast<u32x2 *>(qp), out);
         xp += x_step;
         qp += q_step;
     }

@@ -56,8 +56,8 @@ __device__ __forceinline__ void store_group(uint8_t *base, int64_t row, int grou
     const int g = group & 3;
     const u32x4 lo = {s[0], s[1], s[2], s[3]};
     const u32x2 hi = {s[4], s[5]};
-    __builtin_nontemporal_store(lo, reinterpret_cast<u32x4 *>(block + 16 * g));
-    __builtin_nontemporal_store(hi, reinterpret_cast<u32x2 *>(block + 64 + 8 * g));
+    ptq4vm::store_for_next_kernel(reinterpret_cast<u32x4 *>(block + 16 * g), lo);
+    ptq4vm::store_for_next_kernel(reinterpret_cast<u32x2 *>(block + 64 + 8 * g), hi);
 }
 
 // Column-stationary stream (K % 32 == 0, 16-byte aligned rows): gridDim.x * 256 is a multiple of `groups_padded`
@@ -194,7 +194,7 @@ __global__ __launch_bounds__(kThreads) void quantize_pts_a4_e2m3_blocks(const __
             const int off = (h * 64 + lane) * 16;
             if (off < valid && (h == 0 || lane < 32)) {
                 const u32x4 data = *reinterpret_cast<const u32x4 *>(out + off);
-                __builtin_nontemporal_store(data, reinterpret_cast<u32x4 *>(dst + off));
+                ptq4vm::store_for_next_kernel(reinterpret_cast<u32x4 *>(dst + off), data);
             }
         }
         asm volatile("" ::: "memory");
