@@ -42,10 +42,22 @@ def short(name: str) -> str:
         if t in name:
             tag = label
             break
-    if base == "linear_stream_smallk":  # template arguments: k-steps, fused quantizer, two alignments, packed 4-bit operands
-        m = re.search(r"smallkILi\d+ELb([01])ELi\d+ELi\d+ELb([01])E", name) or re.search(r"smallk<\d+, (true|false), \d+, \d+, (true|false)>", name)
-        fused, packed = (m.group(1) in ("1", "true"), m.group(2) in ("1", "true")) if m else (False, False)
-        tag = "<fused>" if fused else ("<int4>" if packed else "<int8>")
+    def flags(mangled, demangled):  # boolean template arguments, in order
+        m = re.search(mangled, name)
+        if m:
+            return [g == "1" for g in m.groups()]
+        m = re.search(demangled, name)
+        return [g == "true" for g in m.groups()] if m else None
+    if base == "linear_stream_smallk":  # <k-steps, fused quantizer, two alignments, packed 4-bit operands, zero offset>
+        f = flags(r"smallkILi\d+ELb([01])ELi\d+ELi\d+ELb([01])ELb([01])E",
+                  r"smallk<\d+, (true|false), \d+, \d+, (true|false), (true|false)>") or [False, False, False]
+        fused, packed, offset = f
+        tag = "<" + ("fused " if fused else "") + ("int4" if packed else ("int8+offset" if offset else "int8")) + ">"
+        if tag == "<fused int8>":
+            tag = "<fused>"
+    if base == "pts_linear_wres":  # <channel blocks, depth, parity aids, 4-bit, zero offset>
+        f = flags(r"wresILi\d+ELi\d+ELb[01]ELb([01])ELb([01])E", r"wres<\d+, \d+, (?:true|false), (true|false), (true|false)>") or [False, False]
+        tag = "<int4>" if f[0] else ("<int8+offset>" if f[1] else "")
     if base == "linear_mfma_wreg":
         tag = "<K=768>" if ("ILi12E" in name or "<12," in name) else "<K=384>"
     return base + tag
@@ -133,7 +145,7 @@ def dominant_median(agg, substr: str):
 
 
 def counter_table(directories, kernels, out: list) -> None:
-    """Per kernel (short-name substring) the median over dispatches of every counter found in the given
+    """Per kernel (short name) the median over dispatches of every counter found in the given
     rocprofv3 --pmc output directories (values of one dispatch are summed over its rows: one per XCD / SE)."""
     for directory in directories:
         f = first(os.path.join(directory, "**", "*counter_collection.csv")) or first(os.path.join(directory, "*counter_collection.csv"))
@@ -147,7 +159,7 @@ def counter_table(directories, kernels, out: list) -> None:
                 names[r["Dispatch_Id"]] = short(r["Kernel_Name"])
         out.append(f"counters of {directory} (median per dispatch, summed over the device):")
         for want in kernels:
-            rows = [c for d, c in per_dispatch.items() if want in names[d]]
+            rows = [c for d, c in per_dispatch.items() if want == names[d]]
             if not rows:
                 continue
             # a kernel used for two problem shapes: keep the cluster with the larger first counter
