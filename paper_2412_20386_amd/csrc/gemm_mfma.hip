@@ -1214,6 +1214,17 @@ int dispatch(LinearArgs a, hipStream_t stream) {
     // per CU instantiation balances few-tile problems better but moves 1.5x the bytes through L2; it
     // measured 3 % slower on out_proj and 10 % slower on in_proj of the Vim-B stack.)
     if (persistent_ok) return launch_persistent<Path, PTQ4VM_PERSISTENT_BO, PTQ4VM_PERSISTENT_PHYS_SLAB, PTQ4VM_PERSISTENT_STAGES>(a, stream);
+    if constexpr (Path::kElemBytes == 1 && !Path::kOffset && !Path::kPacked4 && PTQ4VM_PERSISTENT_BO == 256) {
+        // Too few 256 x 256 tiles for the kernel above, and the second of two column tiles at most half full (N = 384 at
+        // 25 216 rows: the out_proj of the Vim-S stack, batch 128): 256 x 128 tiles of the same kernel.  Measured there
+        // 26.2 us against 29.3 us on the tiled kernel below.  (With enough 256 x 256 tiles - 50 240 rows - the wide tiles
+        // are faster in spite of the half-empty column: 33.3 against 36.9 us.)
+        const bool narrow_ok = dma_ok && a.N % 8 == 0 && a.y_vec == 8 && ptq4vm::aligned_to(a.bias, 4) &&
+                               a.ldy * 512 < (1LL << 31) && a.L < (1LL << 31) && a.N > 256 && a.N <= 384 &&
+                               a.k_bytes % PTQ4VM_PERSISTENT_SLAB == 0 && a.k_bytes >= 2 * PTQ4VM_PERSISTENT_SLAB &&
+                               ptq4vm::ceil_div(a.M, 256) * ptq4vm::ceil_div(a.N, 128) >= 256;
+        if (narrow_ok) return launch_persistent<Path, 128, PTQ4VM_PERSISTENT_PHYS_SLAB, PTQ4VM_PERSISTENT_STAGES>(a, stream);
+    }
     // Few output channels over many rows: weight resident in LDS, activations streamed once.
     const bool wres_ok = dma_ok && a.N <= 16 * kWresMaxBlocks && a.M >= kWresMinRows &&
                          4 * a.M >= ptq4vm::ceil_div(a.N, 16) * 16 * a.k_bytes && a.M < (1LL << 31) &&

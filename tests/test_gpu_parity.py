@@ -405,13 +405,15 @@ def test_vim_b_other_layers_sampled(layer, linear):
 
 @pytest.mark.parametrize("B,L,K,N", [(41, 251, 192, 1544), (33, 300, 64, 2056), (20, 517, 128, 6400),
                                      (41, 251, 256, 1544), (20, 517, 384, 3400), (45, 229, 640, 1800),
-                                     (41, 251, 768, 1280), (67, 193, 768, 256), (53, 211, 384, 768), (20, 517, 384, 3328)])
+                                     (41, 251, 768, 1280), (67, 193, 768, 256), (53, 211, 384, 768), (20, 517, 384, 3328),
+                                     (129, 199, 512, 376), (105, 251, 256, 264)])
 def test_large_ragged_shapes_sampled(B, L, K, N):
     """Many 256 x 256 tiles with ragged last tiles in both directions; shapes 4 and 6 have a reduction
     length the persistent kernel takes (2 and 5 slabs of 128 bytes), with and without a partial last
     round of tiles that is cut into half tiles.  K = 384 and K = 768 with at least 8192 rows and N a
     multiple of 256 run on the weights-in-registers kernel: ragged last row tile, a single strip, more
-    workgroups than units in an XCD's last band."""
+    workgroups than units in an XCD's last band.  The last two (fewer than 256 tiles of 256 x 256, 256 < N <= 384)
+    run on 256 x 128 tiles of the persistent kernel: ragged rows and a ragged third / nearly empty third column tile."""
     c = synth.random_problem(4242 + N, B, L, K, N, device=DEV)
     _check_case_on_sampled_rows(c, _sampled_rows(B * L, 61, L), "ragged")
 
