@@ -756,8 +756,8 @@ __global__ __launch_bounds__(kThreads) void linear_mfma_smallk(const LinearArgs 
 // ------------------------------------------------------------------------------------------
 // Skinny-N path (N <= 128 over very many rows, e.g. x_proj 1536 -> 80): the activation is read
 // exactly once from HBM and is almost all of the traffic, the weight is small.  One workgroup of 8
-// wavefronts per CU keeps the WHOLE weight in LDS (row pitch K bytes + 16, so the 16 rows of an
-// MFMA operand read start 4 banks apart and never conflict) together with s_w and the bias as
+// wavefronts per CU keeps the WHOLE weight in LDS (row pitch K bytes + 32: measured in a read loop, operand
+// reads of 16 rows run at 235-240 bytes per clock and CU, at pitch K + 16 at half of that) together with s_w and the bias as
 // fp32.  A wavefront owns units of 32 token rows (two 16 x 16 MFMA row blocks against all
 // ceil(N / 16) channel blocks): its activation fragments go from global memory straight into
 // registers in MFMA operand layout (16 rows x 64 contiguous bytes per load instruction),

@@ -94,14 +94,15 @@ __device__ __forceinline__ u32x2 quantize_8(v4i raw, const float (&im)[8], float
 }
 
 // ------------------------------------------------------------------------------------------
-// Skinny-N fused kernel.  One workgroup of 8 wavefronts per CU; LDS holds, for the whole kernel,
-//   the int8 weight (row pitch K + 16 bytes: the 16 rows of an MFMA operand read start 4 banks apart),
+// Skinny-N fused kernel.  One workgroup of 16 wavefronts per CU (PTQ4VM_FUSED_RB = 1; 8 with 32-row units); LDS
+// holds, for the whole kernel,
+//   the int8 weight (row pitch K + 32 bytes, see fused_layout),
 //   inv_m[K], 1 / s_tok[L] (the only place the IEEE division appears), s_w[N] and the bias as fp32.
-// A wavefront owns units of 32 token rows.  Per k-step (64 codes = one 128-byte line of fp16 per
-// row) it fetches the unit's 32 lines with four loads (lane s: row 8 i + s / 8, 16-byte piece s mod 8,
-// so every request is a whole cache line), D k-steps ahead (D = 4, 2 or 1, the largest that divides K / 64); at consumption the eight fp16 of a
-// lane become eight codes, go through a wavefront-private 32 x 64-byte LDS tile (chunks XOR-swizzled
-// by the row) and come back as two MFMA operands (lane t: row t mod 16, 16 codes t / 16), which
+// A wavefront owns units of 16 RB token rows.  Per k-step (64 codes = one 128-byte line of fp16 per
+// row) it fetches the unit's lines with 2 RB loads (lane s: row 8 i + s / 8, 16-byte piece s mod 8,
+// so every request is a whole cache line), D k-steps ahead (D = 4, 2 or 1); at consumption the eight fp16 of a
+// lane become eight codes, go through a wavefront-private (16 RB) x 64-byte LDS tile (chunks XOR-swizzled
+// by the row) and come back as RB MFMA operands (lane t: row t mod 16, 16 codes t / 16), which
 // meet the weight fragments of all ceil(N / 16) channel blocks in v_mfma_i32_16x16x64_i8.
 // There is no barrier after the set-up.  The epilogue is the dequantization of the PTS equation,
 // staged through the same private LDS region and written as whole contiguous row segments.
@@ -505,14 +506,15 @@ __device__ __forceinline__ v4i load_quantized_chunk(const char *row_ptr, int64_t
 
 // ------------------------------------------------------------------------------------------
 // Short-reduction kernel (K <= 128, e.g. dt_proj 48 -> 1536): almost all traffic is the fp16
-// output, so the kernel is arranged around the stores.  One workgroup of 8 wavefronts per CU; LDS
+// output, so the kernel is arranged around the stores.  One workgroup of 16 wavefronts per CU; LDS
 // holds the whole int8 weight (64 or 128 bytes per channel, 16-byte chunks XOR-swizzled by the row),
 // s_w and the bias as fp32.  A wavefront owns units of 16 token rows and ALL output channels of
 // them: it reads (and, fused, quantizes) the unit's activations once into two MFMA operands, then
 // walks over the channels 64 at a time - weight fragments and scales from LDS, v_mfma_i32_16x16x64_i8,
 // dequantization, transposition through a private 4 KiB LDS patch, 16-byte non-temporal stores of
-// whole 128-byte lines.  A unit's output is one contiguous 32-row span of y written by one
-// wavefront within a few microseconds.  No barrier after the set-up.
+// whole 128-byte lines.  A unit's output is one contiguous 16-row span of y written by at most four
+// wavefronts (the channel groups of a unit are dealt in up to four parts) within a few microseconds.  No barrier
+// after the set-up.
 // QUANT: activations are fp16 and pass through the PTS quantizer; otherwise they are int8 codes.
 // Any pitch and alignment (X_ALIGN / W_ALIGN: 16, 4 or 0 = element-wise loads).
 // ------------------------------------------------------------------------------------------
