@@ -18,7 +18,7 @@ After the timed configuration the other four configurations of the benchmark spec are
 way (they take 0.04-4 ms per step) and reported under "configs"; for the two launch-bound ones
 (configs 0 and 1) the headline of their record is the step replayed as one HIP graph.
 
-Prints ONE JSON line (see README for the fields).
+Prints ONE JSON line.
 """
 from __future__ import annotations
 
@@ -439,7 +439,7 @@ def main() -> int:
     args = ap.parse_args()
     if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
         print("bench.py: this build runs on one GPU only (the path shards data-parallel over the batch "
-              "with no collectives, see DESIGN.md); run with --gpus 1", file=sys.stderr)
+              "with no collectives); run with --gpus 1", file=sys.stderr)
         return 2
 
     import torch

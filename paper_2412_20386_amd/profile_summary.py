@@ -3,8 +3,8 @@ profiles/dominant_kernel_traffic.json, the file from which bench.py takes `roofl
 
 Usage (from the repository root, after the rocprofv3 runs named in the summary's header):
 
-  python3 -m paper_2412_20386_amd.profile_summary --kernel-trace gpurun_out/prof/kt --fetch gpurun_out/prof/fetch \
-      --write gpurun_out/prof/write --bench-json gpurun_out/prof/bench_kt.json --config 3 \
+  python3 -m paper_2412_20386_amd.profile_summary --kernel-trace out/prof/kt --fetch out/prof/fetch \
+      --write out/prof/write --bench-json out/prof/bench_kt.json --config 3 \
       --dominant linear_mfma_wreg --out profiles/bench_vim_b_stack_kernel_trace_and_traffic.txt
 
 Every input is optional; what is missing is left out of the summary.  HBM traffic of a kernel = the counter's
